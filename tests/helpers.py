@@ -1,0 +1,61 @@
+"""Arena plumbing shared by the CPU-oracle tests and the GPU parity tests.
+
+No swap arithmetic here: only buffers, red zones, poison and comparisons.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+import workloads as W
+
+RED = 0xC3          # red-zone byte, both sides
+POISON_DEV = 0xA5   # incoming device ranges before the switch
+POISON_HOST = 0x5A  # outgoing host ranges before the switch
+
+
+class HostSet:
+    """One application's working set on the CPU: a 'device' stand-in arena and a
+    pageable host arena, same layout, red zones between allocations."""
+
+    def __init__(self, sizes, seed: int, resident: str, skew_dev: int = 0, skew_host: int = 0,
+                 redzone: int = 256):
+        self.sizes = [s if isinstance(s, int) else s[1] for s in sizes]
+        self.seed = seed
+        self.resident = resident  # 'dev' (to be evicted) or 'host' (to be brought in)
+        self.ldev = W.make_layout(self.sizes, redzone=redzone, skew=skew_dev)
+        self.lhost = W.make_layout(self.sizes, redzone=redzone, skew=skew_host)
+        self.dev = np.full(self.ldev.total, RED, dtype=np.uint8)
+        self.host = np.full(self.lhost.total, RED, dtype=np.uint8)
+        src, lsrc = (self.dev, self.ldev) if resident == "dev" else (self.host, self.lhost)
+        dst, ldst, poison = ((self.host, self.lhost, POISON_HOST) if resident == "dev"
+                             else (self.dev, self.ldev, POISON_DEV))
+        W.fill_content(src, lsrc, seed)
+        for o, b in zip(ldst.offsets, ldst.sizes):
+            dst[o:o + b] = poison
+
+    def pairs(self):
+        return [(self.dev[od:od + b], self.host[oh:oh + b])
+                for od, oh, b in zip(self.ldev.offsets, self.lhost.offsets, self.sizes)]
+
+    def expected(self, i: int) -> np.ndarray:
+        return W.content_bytes(self.seed, i, self.sizes[i])
+
+    def check_moved(self):
+        """Destination side holds the generated content; red zones untouched."""
+        dst, ldst = (self.host, self.lhost) if self.resident == "dev" else (self.dev, self.ldev)
+        for i, (o, b) in enumerate(zip(ldst.offsets, ldst.sizes)):
+            got = dst[o:o + b]
+            exp = self.expected(i)
+            if not np.array_equal(got, exp):
+                bad = int(np.flatnonzero(got != exp)[0])
+                raise AssertionError(f"allocation {i} ({b} B) differs first at byte {bad}")
+        self.check_redzones()
+
+    def check_redzones(self):
+        for arena, lay in ((self.dev, self.ldev), (self.host, self.lhost)):
+            mask = np.ones(arena.size, dtype=bool)
+            for o, b in zip(lay.offsets, lay.sizes):
+                mask[o:o + b] = False
+            if not (arena[mask] == RED).all():
+                bad = int(np.flatnonzero(mask & (arena != RED))[0])
+                raise AssertionError(f"red zone overwritten at arena byte {bad}")

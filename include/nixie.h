@@ -1,0 +1,237 @@
+/*
+ * nixie.h -- C ABI of the MI355X context-switch swap library (libnixie.so).
+ *
+ * One operation: when application A yields the GPU and application B is
+ * scheduled, A's working set (a table of device allocations) is evicted to
+ * pageable host memory while B's working set is brought back into HBM at the
+ * same time, both directions of the host link busy, through a pinned staging
+ * ring of bounded size.  (Paper: "Overview" step 4 of the architecture figure;
+ * "Hierarchical Memory" -- every chunk has exactly one copy and GPU-resident
+ * data needs no pinned backing; "Speeding Up Context Switches" -- bidirectional
+ * migration, global plan, orchestrated order, reserved window for the evicted
+ * application, multi-threaded pageable<->pinned copies.)
+ *
+ * Conventions
+ *  - Plain C types only.  Every pointer is labelled HOST or DEVICE below.
+ *  - All functions return 0 (NIXIE_OK) or a negative nixie_err code; nothing
+ *    throws or aborts across this boundary; outputs are untouched on failure
+ *    unless stated.
+ *  - The library never allocates device memory for payload.  It owns the pinned
+ *    ring, a small pinned control block, descriptor arrays and its host threads.
+ *  - A plan is bound to the HIP device that is current when it is created.
+ */
+#ifndef NIXIE_H
+#define NIXIE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum nixie_err {
+    NIXIE_OK = 0,
+    NIXIE_EINVAL = -1,    /* NULL where data is required, bad ring / slot geometry, bad option */
+    NIXIE_EOVERLAP = -2,  /* two listed ranges intersect (device side or host side)           */
+    NIXIE_ENOMEM = -3,    /* pinned / descriptor allocation failed; the budget is never exceeded silently */
+    NIXIE_EHIP = -4,      /* a HIP runtime call failed; see nixie_last_hip_error()             */
+    NIXIE_ETIMEOUT = -5,  /* a credit wait exceeded its bound; the kernel was told to stop     */
+    NIXIE_EMISMATCH = -6, /* nixie_verify found a hash that differs                            */
+    NIXIE_EBUSY = -7      /* the plan is already running a switch                              */
+};
+
+/* One allocation of a working set.  Memory is caller-owned on both sides.
+ * dev_ptr:  DEVICE address of the allocation (any alignment).
+ * host_ptr: HOST address of its pageable backing (any alignment, >= bytes long).
+ * bytes:    length; 0 is legal and the entry is skipped. */
+typedef struct {
+    void *dev_ptr;
+    void *host_ptr;
+    uint64_t bytes;
+} nixie_alloc_t;
+
+/* HOST array of count entries, borrowed for the duration of the call and copied. */
+typedef struct {
+    const nixie_alloc_t *allocs;
+    uint64_t count;
+} nixie_table_t;
+
+/* Order in which the planner walks a table (paper, "Speeding Up Context
+ * Switches": the orchestrator manages migration order).  The result of a switch
+ * does not depend on it. */
+enum nixie_order {
+    NIXIE_ORDER_TABLE = 0,       /* as listed                           */
+    NIXIE_ORDER_LARGE_FIRST = 1, /* by size, descending                 */
+    NIXIE_ORDER_ADDRESS = 2,     /* by device address, ascending        */
+    NIXIE_ORDER_REVERSE = 3      /* as listed, backwards                */
+};
+
+enum nixie_flags {
+    NIXIE_SPLIT_BY_BYTES = 1u << 0,   /* divide the ring's slots between the directions by byte ratio, not 50/50 */
+    NIXIE_SERIALIZE = 1u << 1,        /* self-baseline: evict completely, then restore (one link direction at a time) */
+    NIXIE_DIAG_RING_ONLY = 1u << 2,   /* measurement only: host threads recycle credits without touching pageable
+                                         memory, so destinations on the host side are NOT written */
+    NIXIE_DIAG_STALL_DRAIN = 1u << 3, /* failure-path test: drain threads never return credits, so the switch must
+                                         end with NIXIE_ETIMEOUT after timeout_ms */
+    NIXIE_HOST_PLAIN_MEMCPY = 1u << 4 /* host threads use libc memcpy instead of streaming stores */
+};
+
+/* Every field 0 = library default. */
+typedef struct {
+    uint64_t slot_bytes;     /* ring slot size; multiple of 4096, <= 1 GiB.  Default 2 MiB, halved until each
+                                active direction has at least 4 slots (never below 64 KiB)                  */
+    uint32_t out_slots;      /* slots reserved for the outgoing direction (the evicted application's
+                                streaming window); default half, or all when the other table is empty      */
+    uint32_t order;          /* enum nixie_order                                                            */
+    uint32_t gather_wgs;     /* workgroups copying HBM -> ring                                              */
+    uint32_t scatter_wgs;    /* workgroups copying ring -> HBM                                              */
+    uint32_t team;           /* workgroups that share one chunk                                             */
+    uint32_t drain_threads;  /* host threads moving ring -> pageable                                        */
+    uint32_t fill_threads;   /* host threads moving pageable -> ring                                        */
+    uint32_t timeout_ms;     /* bound on any single credit wait, host or GPU side; default 30000            */
+    uint32_t flags;          /* enum nixie_flags                                                            */
+} nixie_opts_t;
+
+typedef struct nixie_plan nixie_plan_t;     /* opaque; owns ring, flags, descriptors, host threads */
+typedef struct nixie_layout nixie_layout_t; /* opaque; the planner's output alone, host memory only */
+
+/* What the planner decided; also the pinned-memory account. */
+typedef struct {
+    uint64_t ring_bytes;        /* as requested                                    */
+    uint64_t slot_bytes;
+    uint32_t out_slots, in_slots;
+    uint64_t chunks_out, chunks_in;
+    uint64_t segments_out, segments_in;
+    uint64_t bytes_out, bytes_in;
+    uint64_t pinned_ring_bytes; /* payload slots actually allocated, <= ring_bytes  */
+    uint64_t pinned_ctrl_bytes; /* flag block, reported separately                  */
+    uint32_t gather_wgs, scatter_wgs, team_out, team_in;
+    uint32_t drain_threads, fill_threads;
+} nixie_plan_info_t;
+
+/* One contiguous piece of one allocation inside one chunk. */
+typedef struct {
+    uint64_t dev_addr;   /* DEVICE address of the piece                     */
+    uint64_t host_addr;  /* HOST address of the piece                       */
+    uint32_t slot_off;   /* offset inside the ring slot; == dev_addr mod 16 */
+    uint32_t len;
+} nixie_segment_t;
+
+/* One ring-slot's worth of work: segments [seg_begin, seg_begin + seg_count). */
+typedef struct {
+    uint64_t seg_begin;
+    uint32_t seg_count;
+    uint32_t used_bytes; /* extent of the slot image, <= slot_bytes */
+} nixie_chunk_t;
+
+/* Timers and counters of one switch.  Times are nanoseconds since nixie_switch was entered. */
+typedef struct {
+    uint64_t bytes_out, bytes_in;
+    uint64_t ns_total;        /* entry -> return: kernel done and last drain in pageable memory */
+    uint64_t ns_out_done;     /* entry -> last outgoing byte written to pageable memory         */
+    uint64_t ns_in_done;      /* entry -> last incoming byte written to HBM ("B ready")         */
+    uint64_t ns_kernel;       /* duration of the swap kernel(s) by HIP events                   */
+    uint64_t ns_launch;       /* entry -> kernel launch call returned                           */
+    uint64_t drain_wait_ns;   /* summed over drain threads: time waiting for ready flags        */
+    uint64_t fill_wait_ns;    /* summed over fill threads: time waiting for free flags          */
+    uint64_t gather_stall_ticks;  /* summed over gather workgroups, 100 MHz ticks waiting for credits */
+    uint64_t scatter_stall_ticks; /* summed over scatter workgroups, ticks waiting for filled slots   */
+    uint32_t kernels;         /* swap kernels launched (2 when serialised)                      */
+    uint32_t gpu_status;      /* 0, or the reason the kernel stopped early                      */
+} nixie_stats_t;
+
+typedef struct {
+    uint64_t checked_out, checked_in;
+    uint64_t mismatched_out, mismatched_in;
+    int64_t first_bad_out, first_bad_in; /* table index, -1 if none */
+} nixie_verify_report_t;
+
+/* Host-link rates measured on this machine, GB/s (1e9 B/s) per direction.  d2h = GPU to host. */
+typedef struct {
+    double sdma_d2h, sdma_h2d;             /* hipMemcpyAsync, one direction at a time  */
+    double sdma_d2h_both, sdma_h2d_both;   /* hipMemcpyAsync, both at once             */
+    double kernel_d2h, kernel_h2d;         /* plain 16 B/lane copy kernel, one at a time */
+    double kernel_d2h_both, kernel_h2d_both;
+} nixie_link_peak_t;
+
+/* ---- planner (paper, "Speeding Up Context Switches": global plan + orchestrated order;
+ *      "Granularity of Memory Management": large allocations are subdivided into
+ *      fixed-size units, which avoids fragmentation of the staging tier) ------------------
+ * Pure host work, no GPU needed.  Splits allocations larger than a slot, packs smaller ones
+ * into shared slots (each segment's slot offset is congruent to its device address mod 16),
+ * orders the chunks, and divides the ring's slots between the two directions.
+ * out_table: allocations that hold data at dev_ptr and must end up at host_ptr.
+ * in_table:  allocations that hold data at host_ptr and must end up at dev_ptr.
+ * Either table may be NULL or empty.  All device ranges must be pairwise disjoint, and all
+ * host ranges too (no aliasing), else NIXIE_EOVERLAP.
+ * ring_bytes must hold at least 2 slots per active direction, else NIXIE_EINVAL.
+ * *layout is library-owned; release with nixie_layout_destroy. */
+int nixie_layout_create(const nixie_table_t *out_table, const nixie_table_t *in_table,
+                        uint64_t ring_bytes, const nixie_opts_t *opts /* NULL = defaults */,
+                        nixie_layout_t **layout);
+int nixie_layout_info(const nixie_layout_t *layout, nixie_plan_info_t *info);
+/* dir: 0 = outgoing, 1 = incoming.  Copies up to cap entries into a HOST array; returns the
+ * total number of entries (>= 0) or a negative error. */
+int64_t nixie_layout_chunks(const nixie_layout_t *layout, int dir, nixie_chunk_t *chunks, uint64_t cap);
+int64_t nixie_layout_segments(const nixie_layout_t *layout, int dir, nixie_segment_t *segs, uint64_t cap);
+void nixie_layout_destroy(nixie_layout_t *layout);
+
+/* ---- plan: layout + pinned ring + flags + device descriptors + parked host threads --------
+ * Same arguments and checks as nixie_layout_create.  Allocates exactly
+ * (out_slots + in_slots) * slot_bytes <= ring_bytes of mapped pinned memory for payload and a
+ * separately reported control block for the slot flags (paper, "Hierarchical Memory": the
+ * pinned tier is the scarce one; "Speeding Up Context Switches": a window of it is reserved
+ * for the evicted application).  A plan may be switched any number of times; a second plan
+ * with the tables exchanged gives the way back. */
+int nixie_plan(const nixie_table_t *out_table, const nixie_table_t *in_table,
+               uint64_t ring_bytes, const nixie_opts_t *opts /* NULL = defaults */,
+               nixie_plan_t **plan);
+int nixie_plan_info(const nixie_plan_t *plan, nixie_plan_info_t *info);
+void nixie_plan_destroy(nixie_plan_t *plan);
+
+/* ---- the switch (paper, "Overview" step 4; "Speeding Up Context Switches") ----------------
+ * Stream-ordered after everything already queued on hip_stream (a hipStream_t, NULL = the
+ * default stream); this stands in for the paper's quiesce ("Valid memory access during
+ * migration").  Launches one persistent kernel whose workgroups gather outgoing chunks from
+ * HBM into ring slots and scatter incoming chunks from ring slots into HBM, paced by per-slot
+ * credits; host drain threads move filled slots to the outgoing allocations' host_ptr and
+ * host fill threads load slots from the incoming allocations' host_ptr.
+ * BLOCKS the calling thread until both directions are complete, the last drain included.
+ * On return 0: host_ptr[0..bytes) of every outgoing allocation equals its device bytes from
+ * before the call, dev_ptr[0..bytes) of every incoming allocation equals its host bytes from
+ * before the call, no byte outside a listed range was written, the ring holds nothing live.
+ * Sources are unspecified afterwards.  stats may be NULL. */
+int nixie_switch(nixie_plan_t *plan, void *hip_stream, nixie_stats_t *stats);
+
+/* ---- verification: per-allocation 64-bit hash ---------------------------------------------
+ * H(b[0..n)) = mix64(n) + sum_k mix64(w_k + G*(k+1)) mod 2^64, w_k the k-th little-endian
+ * 8-byte word (last one zero padded), G = 0x9E3779B97F4A7C15, mix64 the splitmix64 output
+ * function.  Position keyed and additive, so partial sums combine in any order.
+ *
+ * nixie_hash_tables: BEFORE a switch.  out_hash[i] from DEVICE memory of the outgoing
+ * table, in_hash[j] from HOST memory of the incoming table.  HOST output arrays of
+ * table length (may be NULL when that table is empty).
+ * nixie_verify: AFTER a switch.  Hashes the outgoing table at host_ptr and the incoming
+ * table at dev_ptr and compares with the expected arrays; returns NIXIE_EMISMATCH and fills
+ * report if any differs.  Either expected array may be NULL to skip that side. */
+int nixie_hash_tables(const nixie_plan_t *plan, void *hip_stream, uint64_t *out_hash, uint64_t *in_hash);
+int nixie_verify(const nixie_plan_t *plan, void *hip_stream, const uint64_t *expect_out_hash,
+                 const uint64_t *expect_in_hash, nixie_verify_report_t *report);
+/* Hash n buffers.  ptrs, bytes, hashes: HOST arrays of n.  on_device != 0: ptrs[i] are DEVICE
+ * addresses hashed by the GPU kernel; else HOST addresses hashed by host threads. */
+int nixie_hash_buffers(const void *const *ptrs, const uint64_t *bytes, uint64_t n, int on_device,
+                       void *hip_stream, uint64_t *hashes);
+
+/* ---- host-link probe (paper, "Microbenchmarks": throughput is judged against the link's
+ *      measured maximum) ---------------------------------------------------------------------
+ * Allocates 2 device + 2 pinned buffers of `bytes` each for the duration of the call, times
+ * best-of-reps transfers, frees them.  out: HOST. */
+int nixie_link_peak(uint64_t bytes, int reps, nixie_link_peak_t *out);
+
+const char *nixie_strerror(int err);
+int nixie_last_hip_error(void); /* hipError_t of the last NIXIE_EHIP on this thread */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NIXIE_H */

@@ -1,0 +1,12 @@
+"""MI355X-native context-switch swap (bidirectional evict/restore through a bounded pinned ring).
+
+The work is done by ``libnixie.so`` (hand-written HIP for gfx950 behind a C ABI, declared in
+``include/nixie.h``); this package only marshals arguments.  There is no CPU fallback: if the
+library has not been built, loading it raises.
+"""
+from .nixie import (  # noqa: F401
+    NixieError, Opts, Plan, Layout, lib, lib_path, link_peak, hash_buffers, strerror,
+    ORDER_TABLE, ORDER_LARGE_FIRST, ORDER_ADDRESS, ORDER_REVERSE,
+    SPLIT_BY_BYTES, SERIALIZE, DIAG_RING_ONLY, DIAG_STALL_DRAIN, HOST_PLAIN_MEMCPY,
+    EINVAL, EOVERLAP, ENOMEM, EHIP, ETIMEOUT, EMISMATCH, EBUSY, DECLARED_SYMBOLS,
+)

@@ -1,0 +1,81 @@
+// Internal declarations of libnixie: planner output, device descriptor ABI, launchers.
+#pragma once
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "nixie.h"
+
+namespace nixie {
+
+// ---- planner output (host) ---------------------------------------------------------------
+struct DirLayout {
+    std::vector<nixie_segment_t> segs;   // sorted by slot_off inside each chunk
+    std::vector<nixie_chunk_t> chunks;   // in execution order
+    uint64_t bytes = 0;
+    uint32_t slots = 0;
+};
+
+struct Layout {
+    uint64_t ring_bytes = 0, slot_bytes = 0;
+    nixie_opts_t opts{};
+    DirLayout dir[2];                     // 0 = outgoing (GPU -> host), 1 = incoming
+    std::vector<nixie_alloc_t> table[2];  // copies of the caller's tables, table order
+};
+
+int build_layout(const nixie_table_t *out_table, const nixie_table_t *in_table, uint64_t ring_bytes,
+                 const nixie_opts_t *opts, Layout &L);
+void fill_info(const Layout &L, nixie_plan_info_t *info);
+
+// ---- host copies and hashing ---------------------------------------------------------------
+void copy_stream(void *dst, const void *src, size_t n);   // non-temporal stores, any alignment
+uint64_t mix64(uint64_t z);
+uint64_t hash_host_range(const uint8_t *base, uint64_t n, uint64_t word_begin, uint64_t word_end);
+int hash_host_buffers(const void *const *ptrs, const uint64_t *bytes, uint64_t n, uint64_t *hashes,
+                      unsigned threads);
+
+// ---- device descriptor ABI (shared by runtime.cpp and kernels.hip) ------------------------
+struct DevSeg { uint64_t dev; uint32_t slot_off; uint32_t len; };
+struct DevChunk { uint32_t seg_begin, seg_count, used, pad; };
+
+constexpr uint32_t kFlagStride = 8;        // u64 per flag line (64 B)
+constexpr uint32_t kWgThreads = 256;
+constexpr uint32_t kTileBytes = 8192;
+
+// gpu_status values (host-visible word written by the kernel when it stops early)
+enum : uint32_t { kGpuOk = 0, kGpuSawAbort = 1, kGpuTimeout = 2 };
+
+struct DevDir {
+    const DevSeg *segs;
+    const DevChunk *chunks;
+    uint8_t *ring;          // device-visible address of this direction's first slot
+    uint64_t *wait_flags;   // host-written, pinned: out: free[s]  in: ready[s]
+    uint64_t *post_flags;   // GPU-written,  pinned: out: ready[s] in: free[s]
+    uint32_t *ticket;       // device memory, one counter
+    uint32_t *arrive;       // device memory, one counter per chunk
+    uint64_t *stall_ticks;  // device memory, summed wait time
+    uint32_t n_chunks, n_slots, team, wgs;
+};
+
+struct SwapArgs {
+    DevDir d[2];
+    uint64_t slot_bytes;
+    const uint32_t *host_abort;  // pinned, host-written
+    uint32_t *gpu_status;        // pinned, GPU-written
+    uint32_t *dev_abort;         // device memory
+    uint64_t timeout_ticks;      // 100 MHz wall clock
+};
+
+struct HashDesc { uint64_t ptr; uint64_t bytes; uint64_t first_tile; };
+constexpr uint32_t kHashTileWords = 4096;   // 32 KiB per tile
+
+}  // namespace nixie
+
+// launchers implemented in kernels.hip (hipStream_t passed as void* to keep this header HIP-free)
+extern "C++" {
+int nixie_launch_swap(const nixie::SwapArgs &a, void *stream);
+int nixie_launch_zero32(uint32_t *p, uint64_t n, void *stream);
+int nixie_launch_hash(const nixie::HashDesc *descs, uint64_t n, uint64_t total_tiles, uint64_t *hashes,
+                      void *stream);
+int nixie_launch_copy16(const void *src, void *dst, uint64_t bytes, uint32_t wgs, void *stream);
+}

@@ -1,0 +1,261 @@
+// HIP kernels of libnixie for gfx950: the persistent gather/scatter swap kernel, the
+// per-allocation hash kernel, a counter-clearing kernel and the plain copy kernel used by the
+// link probe.
+//
+// Paper, "Speeding Up Context Switches": while application B's data moves into GPU memory,
+// application A's data moves out, so both directions of the full-duplex host link carry
+// payload at once ("Existing Approach #3" explains why one direction at a time wastes half the
+// link).  The paper issues the device leg as asynchronous 2 MB block copies; here one kernel
+// drives both directions itself: workgroups with blockIdx below d[0].wgs gather outgoing
+// chunks from HBM into pinned ring slots, the rest scatter incoming chunks from ring slots
+// into HBM, 16 bytes per lane, each wave instruction moving 1 KiB of contiguous bytes.
+//
+// Slot credits.  Slot s of a direction carries chunks s, s+n, s+2n, ... (round r = k / n).
+//   producer of round r waits   free[s]  >= r      (r = 0 needs no wait)
+//   consumer of round r waits   ready[s] >= r + 1
+// Outgoing: the GPU produces, host drain threads consume.  Incoming: host fill threads
+// produce, the GPU consumes.  Flags the host writes are polled with system-scope acquire
+// loads; flags the GPU writes are stored with system-scope release after the workgroups
+// sharing a chunk have met on a device-scope counter.
+//
+// Forward progress: work units are handed out in order by an atomic ticket, so the unit a
+// workgroup waits behind always belongs to a workgroup that is already running.  Every wait is
+// bounded (abort word from the host, abort word in device memory, 100 MHz wall-clock limit),
+// so the grid always drains.
+#include <hip/hip_runtime.h>
+
+#include "internal.hpp"
+
+using namespace nixie;
+
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr uint32_t kUnroll = 8;                       // 16 B x 64 lanes x 8 = one 8 KiB tile per wave pass
+static_assert(kTileBytes == 16 * 64 * kUnroll, "tile = one unrolled wave pass");
+
+__device__ __forceinline__ uint64_t mix64_dev(uint64_t z) {
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+// Copy n bytes between a device range and its image in a ring slot.  The two addresses are
+// congruent modulo 16 (the planner guarantees it), so one head/tail peel serves both sides.
+template <bool TO_RING>
+__device__ __forceinline__ void copy_span(uint8_t *dev, uint8_t *ring, uint32_t n, uint32_t lane) {
+    const uint8_t *src = TO_RING ? dev : ring;
+    uint8_t *dst = TO_RING ? ring : dev;
+    uint32_t head = (16u - ((uint32_t)(uintptr_t)ring & 15u)) & 15u;
+    if (head > n) head = n;
+    if (lane < head) dst[lane] = src[lane];
+    const uint32_t nvec = (n - head) >> 4;
+    const u32x4 *s4 = (const u32x4 *)(src + head);
+    u32x4 *d4 = (u32x4 *)(dst + head);
+    for (uint32_t j = lane; j < nvec; j += 64 * kUnroll) {
+        u32x4 v[kUnroll];
+#pragma unroll
+        for (uint32_t u = 0; u < kUnroll; u++)
+            if (j + 64 * u < nvec) v[u] = s4[j + 64 * u];
+#pragma unroll
+        for (uint32_t u = 0; u < kUnroll; u++)
+            if (j + 64 * u < nvec) d4[j + 64 * u] = v[u];
+    }
+    const uint32_t done = head + (nvec << 4);
+    if (lane < n - done) dst[done + lane] = src[done + lane];
+}
+
+// One wave copies the part of the slot image [t0, t1) that the chunk's segments cover.
+template <bool TO_RING>
+__device__ __forceinline__ void copy_tile(const DevSeg *segs, uint32_t nseg, uint8_t *slot, uint32_t t0,
+                                          uint32_t t1, uint32_t lane) {
+    uint32_t lo = 0, hi = nseg;   // first segment that ends after t0
+    while (lo < hi) {
+        uint32_t mid = (lo + hi) >> 1;
+        DevSeg s = segs[mid];
+        if (s.slot_off + s.len <= t0) lo = mid + 1; else hi = mid;
+    }
+    for (uint32_t i = lo; i < nseg; i++) {
+        DevSeg s = segs[i];
+        if (s.slot_off >= t1) break;
+        uint32_t x0 = s.slot_off > t0 ? s.slot_off : t0;
+        uint32_t x1 = s.slot_off + s.len < t1 ? s.slot_off + s.len : t1;
+        if (x0 >= x1) continue;
+        copy_span<TO_RING>((uint8_t *)(uintptr_t)(s.dev + (x0 - s.slot_off)), slot + x0, x1 - x0, lane);
+    }
+}
+
+template <int DIR>
+__device__ void run_direction(const SwapArgs &a) {
+    const DevDir &D = a.d[DIR];
+    __shared__ uint32_t s_unit;
+    __shared__ uint32_t s_stop;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const uint32_t waves_per_wg = kWgThreads / 64;
+    const uint32_t total_units = D.n_chunks * D.team;
+    uint64_t stall = 0;
+
+    for (;;) {
+        if (tid == 0) {
+            uint32_t stop = 0;
+            uint32_t u = __hip_atomic_fetch_add(D.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (u < total_units) {
+                if (__hip_atomic_load(a.dev_abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) stop = 1;
+                const uint32_t k = u / D.team;
+                const uint32_t slot = k % D.n_slots;
+                const uint64_t need = (uint64_t)(k / D.n_slots) + (DIR == 0 ? 0u : 1u);
+                const uint64_t *flag = D.wait_flags + (size_t)slot * kFlagStride;
+                if (!stop && need > 0 &&
+                    __hip_atomic_load(flag, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_SYSTEM) < need) {
+                    const uint64_t t0 = wall_clock64();
+                    uint32_t it = 0;
+                    while (__hip_atomic_load(flag, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_SYSTEM) < need) {
+                        if ((++it & 7u) == 0) {
+                            uint32_t why = 0;
+                            if (__hip_atomic_load(a.dev_abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) stop = 1;
+                            else if (__hip_atomic_load(a.host_abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM)) why = kGpuSawAbort;
+                            else if (wall_clock64() - t0 > a.timeout_ticks) why = kGpuTimeout;
+                            if (why) {
+                                stop = 1;
+                                __hip_atomic_store(a.dev_abort, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                                __hip_atomic_store(a.gpu_status, why, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+                            }
+                            if (stop) break;
+                        }
+                        __builtin_amdgcn_s_sleep(32);
+                    }
+                    stall += wall_clock64() - t0;
+                }
+            }
+            s_unit = u;
+            s_stop = stop;
+        }
+        __syncthreads();
+        const uint32_t u = s_unit;
+        if (u >= total_units || s_stop) break;
+        const uint32_t k = u / D.team, part = u % D.team;
+        const uint32_t slot = k % D.n_slots;
+        const DevChunk ch = D.chunks[k];
+        uint8_t *slot_base = D.ring + (size_t)slot * a.slot_bytes;
+        if (DIR == 1) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "");  // the slot was just rewritten by the host
+
+        const uint32_t n_tiles = (ch.used + kTileBytes - 1) / kTileBytes;
+        for (uint32_t t = part * waves_per_wg + wave; t < n_tiles; t += D.team * waves_per_wg) {
+            const uint32_t t0 = t * kTileBytes;
+            const uint32_t t1 = t0 + kTileBytes < ch.used ? t0 + kTileBytes : ch.used;
+            copy_tile<DIR == 0>(D.segs + ch.seg_begin, ch.seg_count, slot_base, t0, t1, lane);
+        }
+        if (DIR == 0) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "");  // payload reaches host memory before the flag
+        __syncthreads();   // also: every thread has read s_unit before thread 0 overwrites it
+        if (tid == 0) {
+            bool last = true;
+            if (D.team > 1) {
+                uint32_t old = __hip_atomic_fetch_add(D.arrive + k, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+                last = (old == D.team - 1);
+            }
+            if (last)
+                __hip_atomic_store(D.post_flags + (size_t)slot * kFlagStride, (uint64_t)(k / D.n_slots) + 1u,
+                                   __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+    }
+    if (tid == 0 && stall)
+        __hip_atomic_fetch_add(D.stall_ticks, stall, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__global__ void __launch_bounds__(kWgThreads) nixie_swap_kernel(SwapArgs a) {
+    if (blockIdx.x < a.d[0].wgs) run_direction<0>(a);
+    else run_direction<1>(a);
+}
+
+__global__ void __launch_bounds__(256) nixie_zero32_kernel(uint32_t *p, uint64_t n) {
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (uint64_t)gridDim.x * blockDim.x)
+        p[i] = 0;
+}
+
+// H = mix64(bytes) + sum_k mix64(w_k + G (k+1)); each workgroup sums one tile of words and adds
+// its partial to the allocation's slot (hashes must be zero on entry).
+__global__ void __launch_bounds__(256) nixie_hash_kernel(const HashDesc *descs, uint64_t n, uint64_t total_tiles,
+                                                         uint64_t *hashes) {
+    constexpr uint64_t G = 0x9E3779B97F4A7C15ull;
+    __shared__ uint64_t s_part[4];
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    for (uint64_t t = blockIdx.x; t < total_tiles; t += gridDim.x) {
+        uint64_t lo = 0, hi = n;   // last descriptor whose first tile is <= t
+        while (lo < hi) {
+            uint64_t mid = (lo + hi) >> 1;
+            if (descs[mid].first_tile <= t) lo = mid + 1; else hi = mid;
+        }
+        const uint64_t i = lo - 1;
+        const HashDesc d = descs[i];
+        const uint64_t words = (d.bytes + 7) / 8, full = d.bytes / 8;
+        const uint64_t w0 = (t - d.first_tile) * kHashTileWords;
+        const uint64_t w1 = w0 + kHashTileWords < words ? w0 + kHashTileWords : words;
+        const uint8_t *p = (const uint8_t *)(uintptr_t)d.ptr;
+        const bool aligned = (d.ptr & 7u) == 0;
+        uint64_t acc = 0;
+        for (uint64_t k = w0 + tid; k < w1; k += 256) {
+            uint64_t w = 0;
+            if (k < full && aligned) {
+                w = *(const uint64_t *)(p + 8 * k);
+            } else {
+                const uint32_t nb = k < full ? 8u : (uint32_t)(d.bytes - 8 * k);
+                for (uint32_t b = 0; b < nb; b++) w |= (uint64_t)p[8 * k + b] << (8 * b);
+            }
+            acc += mix64_dev(w + G * (k + 1));
+        }
+        if (t == d.first_tile && tid == 0) acc += mix64_dev(d.bytes);
+        for (int off = 32; off > 0; off >>= 1) acc += __shfl_down((unsigned long long)acc, off, 64);
+        if (lane == 0) s_part[wave] = acc;
+        __syncthreads();
+        if (tid == 0)
+            atomicAdd((unsigned long long *)&hashes[i], (unsigned long long)(s_part[0] + s_part[1] + s_part[2] + s_part[3]));
+        __syncthreads();
+    }
+}
+
+// Plain copy for the link probe: each workgroup moves contiguous 64 KiB tiles, 16 B per lane.
+__global__ void __launch_bounds__(256) nixie_copy16_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst,
+                                                           uint64_t n16) {
+    constexpr uint64_t kTile = 4096;
+    const uint64_t ntiles = (n16 + kTile - 1) / kTile;
+    for (uint64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        const uint64_t base = t * kTile, end = base + kTile < n16 ? base + kTile : n16;
+        for (uint64_t i = base + threadIdx.x; i < end; i += 256 * 4) {
+            u32x4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; u++) if (i + 256ull * u < end) v[u] = src[i + 256ull * u];
+#pragma unroll
+            for (int u = 0; u < 4; u++) if (i + 256ull * u < end) dst[i + 256ull * u] = v[u];
+        }
+    }
+}
+
+}  // namespace
+
+int nixie_launch_swap(const SwapArgs &a, void *stream) {
+    const uint32_t grid = a.d[0].wgs + a.d[1].wgs;
+    if (grid == 0) return (int)hipSuccess;
+    nixie_swap_kernel<<<grid, kWgThreads, 0, (hipStream_t)stream>>>(a);
+    return (int)hipGetLastError();
+}
+
+int nixie_launch_zero32(uint32_t *p, uint64_t n, void *stream) {
+    if (n == 0) return (int)hipSuccess;
+    uint32_t grid = (uint32_t)((n + 255) / 256 < 1024 ? (n + 255) / 256 : 1024);
+    nixie_zero32_kernel<<<grid, 256, 0, (hipStream_t)stream>>>(p, n);
+    return (int)hipGetLastError();
+}
+
+int nixie_launch_hash(const HashDesc *descs, uint64_t n, uint64_t total_tiles, uint64_t *hashes, void *stream) {
+    if (total_tiles == 0) return (int)hipSuccess;
+    uint32_t grid = (uint32_t)(total_tiles < 8192 ? total_tiles : 8192);
+    nixie_hash_kernel<<<grid, 256, 0, (hipStream_t)stream>>>(descs, n, total_tiles, hashes);
+    return (int)hipGetLastError();
+}
+
+int nixie_launch_copy16(const void *src, void *dst, uint64_t bytes, uint32_t wgs, void *stream) {
+    if (bytes < 16) return (int)hipSuccess;
+    nixie_copy16_kernel<<<wgs, 256, 0, (hipStream_t)stream>>>((const u32x4 *)src, (u32x4 *)dst, bytes / 16);
+    return (int)hipGetLastError();
+}

@@ -1,0 +1,198 @@
+// Chunk planner: split, pack, order, divide the ring.  Pure host code.
+//
+// Paper, "Speeding Up Context Switches": a global plan decides what moves where before any
+// transfer starts, and an orchestrator fixes the order under limited staging space; a window
+// of the pinned tier is reserved for the evicted application so neither direction can starve
+// the other.  "Granularity of Memory Management": large allocations are subdivided and moved
+// in fixed-size units so that mixed tensor sizes do not fragment the staging tier.
+// Here the fixed unit is the ring slot: an allocation larger than a slot becomes several
+// chunks, allocations smaller than a slot share one.
+#include <algorithm>
+#include <cstring>
+#include <numeric>
+
+#include "internal.hpp"
+
+namespace nixie {
+
+namespace {
+
+constexpr uint64_t kDefaultSlot = 2ull << 20;
+constexpr uint64_t kMinAutoSlot = 64ull << 10;
+constexpr uint64_t kMaxSlot = 1ull << 30;
+
+struct Range { uint64_t lo, hi; };
+
+bool any_overlap(std::vector<Range> &r) {
+    std::sort(r.begin(), r.end(), [](const Range &a, const Range &b) { return a.lo < b.lo; });
+    for (size_t i = 1; i < r.size(); i++)
+        if (r[i].lo < r[i - 1].hi) return true;
+    return false;
+}
+
+int copy_table(const nixie_table_t *t, std::vector<nixie_alloc_t> &dst) {
+    dst.clear();
+    if (!t || t->count == 0) return NIXIE_OK;
+    if (!t->allocs) return NIXIE_EINVAL;
+    dst.assign(t->allocs, t->allocs + t->count);
+    for (const auto &a : dst) {
+        if (a.bytes == 0) continue;
+        if (!a.dev_ptr || !a.host_ptr) return NIXIE_EINVAL;
+        uint64_t d = (uint64_t)(uintptr_t)a.dev_ptr, h = (uint64_t)(uintptr_t)a.host_ptr;
+        if (d + a.bytes < d || h + a.bytes < h) return NIXIE_EINVAL;  // wraps the address space
+    }
+    return NIXIE_OK;
+}
+
+std::vector<uint64_t> walk_order(const std::vector<nixie_alloc_t> &t, uint32_t order) {
+    std::vector<uint64_t> idx(t.size());
+    std::iota(idx.begin(), idx.end(), 0);
+    switch (order) {
+    case NIXIE_ORDER_LARGE_FIRST:
+        std::stable_sort(idx.begin(), idx.end(), [&](uint64_t a, uint64_t b) { return t[a].bytes > t[b].bytes; });
+        break;
+    case NIXIE_ORDER_ADDRESS:
+        std::stable_sort(idx.begin(), idx.end(), [&](uint64_t a, uint64_t b) {
+            return (uintptr_t)t[a].dev_ptr < (uintptr_t)t[b].dev_ptr;
+        });
+        break;
+    case NIXIE_ORDER_REVERSE:
+        std::reverse(idx.begin(), idx.end());
+        break;
+    default:
+        break;
+    }
+    return idx;
+}
+
+// Greedy sequential packing.  A segment's slot offset is congruent to its device address
+// modulo 16, so the 16-byte lanes of the copy kernels are aligned on both sides at once.
+void cut(const std::vector<nixie_alloc_t> &t, uint32_t order, uint64_t S, DirLayout &D) {
+    D.segs.clear();
+    D.chunks.clear();
+    D.bytes = 0;
+    uint64_t fill = 0;
+    bool open = false;
+    for (uint64_t i : walk_order(t, order)) {
+        const nixie_alloc_t &a = t[i];
+        uint64_t off = 0;
+        while (off < a.bytes) {
+            uint64_t dev = (uint64_t)(uintptr_t)a.dev_ptr + off;
+            uint64_t pos = open ? fill + ((dev - fill) & 15) : S;
+            if (!open || pos >= S) {
+                D.chunks.push_back(nixie_chunk_t{(uint64_t)D.segs.size(), 0, 0});
+                open = true;
+                pos = dev & 15;
+            }
+            uint64_t take = std::min(S - pos, a.bytes - off);
+            D.segs.push_back(nixie_segment_t{dev, (uint64_t)(uintptr_t)a.host_ptr + off, (uint32_t)pos, (uint32_t)take});
+            nixie_chunk_t &c = D.chunks.back();
+            c.seg_count++;
+            c.used_bytes = (uint32_t)(pos + take);
+            fill = pos + take;
+            off += take;
+            D.bytes += take;
+        }
+    }
+}
+
+}  // namespace
+
+int build_layout(const nixie_table_t *out_table, const nixie_table_t *in_table, uint64_t ring_bytes,
+                 const nixie_opts_t *opts, Layout &L) {
+    L = Layout{};
+    if (opts) L.opts = *opts;
+    if (L.opts.order > NIXIE_ORDER_REVERSE) return NIXIE_EINVAL;
+    int rc = copy_table(out_table, L.table[0]);
+    if (rc) return rc;
+    rc = copy_table(in_table, L.table[1]);
+    if (rc) return rc;
+
+    // no aliasing: device ranges pairwise disjoint across both tables, host ranges likewise
+    std::vector<Range> dev, host;
+    uint64_t tot[2] = {0, 0};
+    for (int x = 0; x < 2; x++)
+        for (const auto &a : L.table[x]) {
+            if (a.bytes == 0) continue;
+            uint64_t d = (uint64_t)(uintptr_t)a.dev_ptr, h = (uint64_t)(uintptr_t)a.host_ptr;
+            dev.push_back({d, d + a.bytes});
+            host.push_back({h, h + a.bytes});
+            tot[x] += a.bytes;
+        }
+    if (any_overlap(dev) || any_overlap(host)) return NIXIE_EOVERLAP;
+
+    const int active = (tot[0] > 0) + (tot[1] > 0);
+    uint64_t S = L.opts.slot_bytes;
+    if (S == 0) {
+        S = kDefaultSlot;
+        while (S > kMinAutoSlot && ring_bytes / S < 4ull * (uint64_t)std::max(active, 1)) S >>= 1;
+    } else if (S % 4096 != 0 || S > kMaxSlot) {
+        return NIXIE_EINVAL;
+    }
+    const uint64_t n_slots = ring_bytes / S;
+    if (n_slots < 2ull * (uint64_t)std::max(active, 1) || n_slots > (1ull << 20)) return NIXIE_EINVAL;
+
+    uint64_t n_out;
+    if (tot[0] == 0) n_out = 0;
+    else if (tot[1] == 0) n_out = n_slots;
+    else if (L.opts.out_slots) n_out = L.opts.out_slots;
+    else if (L.opts.flags & NIXIE_SPLIT_BY_BYTES) {
+        long double f = (long double)tot[0] / (long double)(tot[0] + tot[1]);
+        n_out = (uint64_t)(f * (long double)n_slots + 0.5L);
+        n_out = std::min(std::max<uint64_t>(n_out, 2), n_slots - 2);
+    } else n_out = n_slots / 2;
+    if (tot[0] && tot[1] && (n_out < 2 || n_slots - n_out < 2)) return NIXIE_EINVAL;
+
+    L.ring_bytes = ring_bytes;
+    L.slot_bytes = S;
+    L.dir[0].slots = (uint32_t)n_out;
+    L.dir[1].slots = (uint32_t)(tot[1] ? n_slots - n_out : 0);
+    cut(L.table[0], L.opts.order, S, L.dir[0]);
+    cut(L.table[1], L.opts.order, S, L.dir[1]);
+    if (L.dir[0].chunks.size() > 0xFFFFFFF0ull / 64 || L.dir[1].chunks.size() > 0xFFFFFFF0ull / 64 ||
+        L.dir[0].segs.size() > 0xFFFFFFF0ull || L.dir[1].segs.size() > 0xFFFFFFF0ull)
+        return NIXIE_EINVAL;
+    return NIXIE_OK;
+}
+
+}  // namespace nixie
+
+namespace nixie {
+
+// Launch shape and thread counts the runtime will use for this layout (options override).
+void fill_info(const Layout &L, nixie_plan_info_t *info) {
+    std::memset(info, 0, sizeof(*info));
+    info->ring_bytes = L.ring_bytes;
+    info->slot_bytes = L.slot_bytes;
+    info->out_slots = L.dir[0].slots;
+    info->in_slots = L.dir[1].slots;
+    info->chunks_out = L.dir[0].chunks.size();
+    info->chunks_in = L.dir[1].chunks.size();
+    info->segments_out = L.dir[0].segs.size();
+    info->segments_in = L.dir[1].segs.size();
+    info->bytes_out = L.dir[0].bytes;
+    info->bytes_in = L.dir[1].bytes;
+    info->pinned_ring_bytes = (uint64_t)(L.dir[0].slots + L.dir[1].slots) * L.slot_bytes;
+    info->pinned_ctrl_bytes = ((uint64_t)(L.dir[0].slots + L.dir[1].slots) * 2 + 2) * kFlagStride * 8;
+    uint32_t team = L.opts.team ? L.opts.team
+                                : (uint32_t)std::min<uint64_t>(8, std::max<uint64_t>(1, L.slot_bytes / (256u << 10)));
+    team = std::min(team, 64u);
+    uint32_t wgs[2] = {L.opts.gather_wgs ? L.opts.gather_wgs : 64u, L.opts.scatter_wgs ? L.opts.scatter_wgs : 64u};
+    uint32_t thr[2] = {L.opts.drain_threads ? L.opts.drain_threads : 4u, L.opts.fill_threads ? L.opts.fill_threads : 4u};
+    for (int x = 0; x < 2; x++) {
+        if (L.dir[x].chunks.empty()) { wgs[x] = 0; thr[x] = 0; continue; }
+        // more workgroups than slots * team could only spin on credits
+        uint64_t cap = (uint64_t)L.dir[x].slots * team;
+        wgs[x] = (uint32_t)std::max<uint64_t>(1, std::min<uint64_t>(wgs[x], cap));
+        wgs[x] = std::min(wgs[x], 1024u);
+        thr[x] = std::min(std::min(thr[x], 64u), std::max(1u, L.dir[x].slots));
+    }
+    info->gather_wgs = wgs[0];
+    info->scatter_wgs = wgs[1];
+    info->team_out = L.dir[0].chunks.empty() ? 0 : team;
+    info->team_in = L.dir[1].chunks.empty() ? 0 : team;
+    info->drain_threads = thr[0];
+    info->fill_threads = thr[1];
+}
+
+}  // namespace nixie

@@ -1,0 +1,282 @@
+"""ctypes binding of libnixie.so: same names as the C ABI, argument marshalling only."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Iterable, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libnixie.so")
+
+EINVAL, EOVERLAP, ENOMEM, EHIP, ETIMEOUT, EMISMATCH, EBUSY = -1, -2, -3, -4, -5, -6, -7
+ORDER_TABLE, ORDER_LARGE_FIRST, ORDER_ADDRESS, ORDER_REVERSE = 0, 1, 2, 3
+SPLIT_BY_BYTES, SERIALIZE, DIAG_RING_ONLY, DIAG_STALL_DRAIN, HOST_PLAIN_MEMCPY = 1, 2, 4, 8, 16
+
+DECLARED_SYMBOLS = (
+    "nixie_layout_create", "nixie_layout_info", "nixie_layout_chunks", "nixie_layout_segments",
+    "nixie_layout_destroy", "nixie_plan", "nixie_plan_info", "nixie_plan_destroy", "nixie_switch",
+    "nixie_hash_tables", "nixie_verify", "nixie_hash_buffers", "nixie_link_peak",
+    "nixie_strerror", "nixie_last_hip_error",
+)
+
+
+class _Alloc(C.Structure):
+    _fields_ = [("dev_ptr", C.c_void_p), ("host_ptr", C.c_void_p), ("bytes", C.c_uint64)]
+
+
+class _Table(C.Structure):
+    _fields_ = [("allocs", C.POINTER(_Alloc)), ("count", C.c_uint64)]
+
+
+class _Opts(C.Structure):
+    _fields_ = [("slot_bytes", C.c_uint64), ("out_slots", C.c_uint32), ("order", C.c_uint32),
+                ("gather_wgs", C.c_uint32), ("scatter_wgs", C.c_uint32), ("team", C.c_uint32),
+                ("drain_threads", C.c_uint32), ("fill_threads", C.c_uint32),
+                ("timeout_ms", C.c_uint32), ("flags", C.c_uint32)]
+
+
+class _Info(C.Structure):
+    _fields_ = [("ring_bytes", C.c_uint64), ("slot_bytes", C.c_uint64),
+                ("out_slots", C.c_uint32), ("in_slots", C.c_uint32),
+                ("chunks_out", C.c_uint64), ("chunks_in", C.c_uint64),
+                ("segments_out", C.c_uint64), ("segments_in", C.c_uint64),
+                ("bytes_out", C.c_uint64), ("bytes_in", C.c_uint64),
+                ("pinned_ring_bytes", C.c_uint64), ("pinned_ctrl_bytes", C.c_uint64),
+                ("gather_wgs", C.c_uint32), ("scatter_wgs", C.c_uint32),
+                ("team_out", C.c_uint32), ("team_in", C.c_uint32),
+                ("drain_threads", C.c_uint32), ("fill_threads", C.c_uint32)]
+
+
+class _Segment(C.Structure):
+    _fields_ = [("dev_addr", C.c_uint64), ("host_addr", C.c_uint64),
+                ("slot_off", C.c_uint32), ("len", C.c_uint32)]
+
+
+class _Chunk(C.Structure):
+    _fields_ = [("seg_begin", C.c_uint64), ("seg_count", C.c_uint32), ("used_bytes", C.c_uint32)]
+
+
+class _Stats(C.Structure):
+    _fields_ = [(n, C.c_uint64) for n in (
+        "bytes_out", "bytes_in", "ns_total", "ns_out_done", "ns_in_done", "ns_kernel", "ns_launch",
+        "drain_wait_ns", "fill_wait_ns", "gather_stall_ticks", "scatter_stall_ticks")] + [
+        ("kernels", C.c_uint32), ("gpu_status", C.c_uint32)]
+
+
+class _Report(C.Structure):
+    _fields_ = [("checked_out", C.c_uint64), ("checked_in", C.c_uint64),
+                ("mismatched_out", C.c_uint64), ("mismatched_in", C.c_uint64),
+                ("first_bad_out", C.c_int64), ("first_bad_in", C.c_int64)]
+
+
+class _LinkPeak(C.Structure):
+    _fields_ = [(n, C.c_double) for n in (
+        "sdma_d2h", "sdma_h2d", "sdma_d2h_both", "sdma_h2d_both",
+        "kernel_d2h", "kernel_h2d", "kernel_d2h_both", "kernel_h2d_both")]
+
+
+def _as_dict(s: C.Structure) -> dict:
+    return {n: getattr(s, n) for n, _ in s._fields_}
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def lib() -> C.CDLL:
+    """Load libnixie.so.  Raises if it has not been built: there is no fallback path."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(f"{_LIB_PATH} is missing: run paper_2601_11743_amd/build.py "
+                           "(or __graft_entry__.build()) first; there is no CPU fallback")
+    L = C.CDLL(_LIB_PATH)
+    vp, u64, i32 = C.c_void_p, C.c_uint64, C.c_int
+    L.nixie_layout_create.argtypes = [C.POINTER(_Table), C.POINTER(_Table), u64, C.POINTER(_Opts), C.POINTER(vp)]
+    L.nixie_layout_info.argtypes = [vp, C.POINTER(_Info)]
+    L.nixie_layout_chunks.argtypes = [vp, i32, C.POINTER(_Chunk), u64]
+    L.nixie_layout_chunks.restype = C.c_int64
+    L.nixie_layout_segments.argtypes = [vp, i32, C.POINTER(_Segment), u64]
+    L.nixie_layout_segments.restype = C.c_int64
+    L.nixie_layout_destroy.argtypes = [vp]
+    L.nixie_layout_destroy.restype = None
+    L.nixie_plan.argtypes = [C.POINTER(_Table), C.POINTER(_Table), u64, C.POINTER(_Opts), C.POINTER(vp)]
+    L.nixie_plan_info.argtypes = [vp, C.POINTER(_Info)]
+    L.nixie_plan_destroy.argtypes = [vp]
+    L.nixie_plan_destroy.restype = None
+    L.nixie_switch.argtypes = [vp, vp, C.POINTER(_Stats)]
+    L.nixie_hash_tables.argtypes = [vp, vp, vp, vp]
+    L.nixie_verify.argtypes = [vp, vp, vp, vp, C.POINTER(_Report)]
+    L.nixie_hash_buffers.argtypes = [vp, vp, u64, i32, vp, vp]
+    L.nixie_link_peak.argtypes = [u64, i32, C.POINTER(_LinkPeak)]
+    L.nixie_strerror.argtypes = [i32]
+    L.nixie_strerror.restype = C.c_char_p
+    L.nixie_last_hip_error.argtypes = []
+    _lib = L
+    return L
+
+
+def strerror(code: int) -> str:
+    return lib().nixie_strerror(code).decode()
+
+
+class NixieError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        self.code = code
+        hip = lib().nixie_last_hip_error() if code == EHIP else 0
+        super().__init__(f"{what}: {strerror(code)} ({code})" + (f", hipError {hip}" if hip else ""))
+
+
+class Opts:
+    """Keyword view of nixie_opts_t; anything left out is the library default."""
+
+    def __init__(self, **kw):
+        self.c = _Opts()
+        for k, v in kw.items():
+            if not hasattr(self.c, k):
+                raise TypeError(f"unknown option {k}")
+            setattr(self.c, k, v)
+
+
+def _table(allocs: Iterable[Sequence[int]] | None):
+    """allocs: iterable of (dev_ptr, host_ptr, bytes) integers."""
+    rows = list(allocs or [])
+    arr = (_Alloc * max(1, len(rows)))()
+    for i, (d, h, b) in enumerate(rows):
+        arr[i].dev_ptr, arr[i].host_ptr, arr[i].bytes = d, h, b
+    t = _Table(arr, len(rows))
+    return t, arr
+
+
+def _opts_ptr(opts: Opts | None):
+    return C.byref(opts.c) if opts is not None else None
+
+
+class Layout:
+    """nixie_layout_*: the planner alone (host only, needs no GPU)."""
+
+    def __init__(self, out_allocs, in_allocs, ring_bytes: int, opts: Opts | None = None):
+        self._h = C.c_void_p()
+        to, self._ko = _table(out_allocs)
+        ti, self._ki = _table(in_allocs)
+        rc = lib().nixie_layout_create(C.byref(to), C.byref(ti), ring_bytes, _opts_ptr(opts), C.byref(self._h))
+        if rc:
+            self._h = None
+            raise NixieError(rc, "nixie_layout_create")
+
+    def info(self) -> dict:
+        i = _Info()
+        rc = lib().nixie_layout_info(self._h, C.byref(i))
+        if rc:
+            raise NixieError(rc, "nixie_layout_info")
+        return _as_dict(i)
+
+    def chunks(self, direction: int) -> np.ndarray:
+        n = lib().nixie_layout_chunks(self._h, direction, None, 0)
+        if n < 0:
+            raise NixieError(int(n), "nixie_layout_chunks")
+        arr = (_Chunk * max(1, n))()
+        lib().nixie_layout_chunks(self._h, direction, arr, n)
+        dt = np.dtype([("seg_begin", "<u8"), ("seg_count", "<u4"), ("used_bytes", "<u4")])
+        return np.frombuffer(arr, dtype=dt, count=n).copy()
+
+    def segments(self, direction: int) -> np.ndarray:
+        n = lib().nixie_layout_segments(self._h, direction, None, 0)
+        if n < 0:
+            raise NixieError(int(n), "nixie_layout_segments")
+        arr = (_Segment * max(1, n))()
+        lib().nixie_layout_segments(self._h, direction, arr, n)
+        dt = np.dtype([("dev_addr", "<u8"), ("host_addr", "<u8"), ("slot_off", "<u4"), ("len", "<u4")])
+        return np.frombuffer(arr, dtype=dt, count=n).copy()
+
+    def close(self):
+        if self._h:
+            lib().nixie_layout_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+
+class Plan:
+    """nixie_plan / nixie_switch / nixie_hash_tables / nixie_verify / nixie_plan_destroy."""
+
+    def __init__(self, out_allocs, in_allocs, ring_bytes: int, opts: Opts | None = None):
+        self._h = C.c_void_p()
+        to, self._ko = _table(out_allocs)
+        ti, self._ki = _table(in_allocs)
+        self.n_out, self.n_in = int(to.count), int(ti.count)
+        rc = lib().nixie_plan(C.byref(to), C.byref(ti), ring_bytes, _opts_ptr(opts), C.byref(self._h))
+        if rc:
+            self._h = None
+            raise NixieError(rc, "nixie_plan")
+
+    def info(self) -> dict:
+        i = _Info()
+        rc = lib().nixie_plan_info(self._h, C.byref(i))
+        if rc:
+            raise NixieError(rc, "nixie_plan_info")
+        return _as_dict(i)
+
+    def switch(self, stream: int = 0, check: bool = True) -> dict:
+        """stream: raw hipStream_t as an integer (torch.cuda.Stream.cuda_stream), 0 = default."""
+        st = _Stats()
+        rc = lib().nixie_switch(self._h, C.c_void_p(stream), C.byref(st))
+        d = _as_dict(st)
+        d["rc"] = rc
+        if rc and check:
+            raise NixieError(rc, "nixie_switch")
+        return d
+
+    def hash_tables(self, stream: int = 0):
+        ho = np.zeros(max(1, self.n_out), dtype=np.uint64)
+        hi = np.zeros(max(1, self.n_in), dtype=np.uint64)
+        rc = lib().nixie_hash_tables(self._h, C.c_void_p(stream), ho.ctypes.data, hi.ctypes.data)
+        if rc:
+            raise NixieError(rc, "nixie_hash_tables")
+        return ho[:self.n_out], hi[:self.n_in]
+
+    def verify(self, expect_out, expect_in, stream: int = 0, check: bool = True) -> dict:
+        eo = None if expect_out is None else np.ascontiguousarray(expect_out, dtype=np.uint64)
+        ei = None if expect_in is None else np.ascontiguousarray(expect_in, dtype=np.uint64)
+        rep = _Report()
+        rc = lib().nixie_verify(self._h, C.c_void_p(stream),
+                                None if eo is None or eo.size == 0 else eo.ctypes.data,
+                                None if ei is None or ei.size == 0 else ei.ctypes.data, C.byref(rep))
+        d = _as_dict(rep)
+        d["rc"] = rc
+        if rc and check:
+            raise NixieError(rc, f"nixie_verify {d}")
+        return d
+
+    def close(self):
+        if self._h:
+            lib().nixie_plan_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+
+def hash_buffers(ptrs: Sequence[int], sizes: Sequence[int], on_device: bool, stream: int = 0) -> np.ndarray:
+    n = len(ptrs)
+    p = np.asarray(list(ptrs), dtype=np.uint64)
+    b = np.asarray(list(sizes), dtype=np.uint64)
+    h = np.zeros(max(1, n), dtype=np.uint64)
+    if n:
+        rc = lib().nixie_hash_buffers(p.ctypes.data, b.ctypes.data, n, int(on_device), C.c_void_p(stream), h.ctypes.data)
+        if rc:
+            raise NixieError(rc, "nixie_hash_buffers")
+    return h[:n]
+
+
+def link_peak(nbytes: int = 1 << 30, reps: int = 5) -> dict:
+    out = _LinkPeak()
+    rc = lib().nixie_link_peak(nbytes, reps, C.byref(out))
+    if rc:
+        raise NixieError(rc, "nixie_link_peak")
+    return _as_dict(out)

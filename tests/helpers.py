@@ -13,6 +13,15 @@ POISON_DEV = 0xA5   # incoming device ranges before the switch
 POISON_HOST = 0x5A  # outgoing host ranges before the switch
 
 
+def aligned_full(n: int, value: int, align: int = 4096) -> np.ndarray:
+    """uint8 array of n bytes whose first byte sits on an ``align`` boundary."""
+    raw = np.empty(n + align, dtype=np.uint8)
+    off = (-raw.ctypes.data) % align
+    a = raw[off:off + n]
+    a[:] = value
+    return a
+
+
 class HostSet:
     """One application's working set on the CPU: a 'device' stand-in arena and a
     pageable host arena, same layout, red zones between allocations."""
@@ -24,8 +33,8 @@ class HostSet:
         self.resident = resident  # 'dev' (to be evicted) or 'host' (to be brought in)
         self.ldev = W.make_layout(self.sizes, redzone=redzone, skew=skew_dev)
         self.lhost = W.make_layout(self.sizes, redzone=redzone, skew=skew_host)
-        self.dev = np.full(self.ldev.total, RED, dtype=np.uint8)
-        self.host = np.full(self.lhost.total, RED, dtype=np.uint8)
+        self.dev = aligned_full(self.ldev.total, RED)
+        self.host = aligned_full(self.lhost.total, RED)
         src, lsrc = (self.dev, self.ldev) if resident == "dev" else (self.host, self.lhost)
         dst, ldst, poison = ((self.host, self.lhost, POISON_HOST) if resident == "dev"
                              else (self.dev, self.ldev, POISON_DEV))

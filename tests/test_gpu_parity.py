@@ -1,0 +1,188 @@
+"""GPU parity: libnixie (through its C ABI) against the CPU oracle, bit for bit.
+
+Every case builds the same seeded inputs twice: one copy goes through the oracle on the CPU,
+the other has its device arena uploaded to HBM and goes through nixie_switch.  Destination
+arenas are compared whole (contents and red zones); hashes are compared per allocation."""
+import numpy as np
+import pytest
+
+import workloads as W
+from tests.helpers import HostSet
+
+pytestmark = pytest.mark.gpu
+
+KiB, MiB = 1 << 10, 1 << 20
+
+
+@pytest.fixture(scope="module")
+def nx():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2601_11743_amd as nx
+    nx.lib()     # raises if the HIP library is missing: no fallback
+    return nx
+
+
+def run_case(nx, oracle, sizes_a, sizes_b, ring, opts=None, seed=7, skew=(0, 0), switches=1,
+             oracle_staged=None):
+    from tests.gpu_helpers import GpuSet, first_diff
+    kw = dict(skew_dev=skew[0], skew_host=skew[1])
+    # oracle side
+    rA, rB = HostSet(sizes_a, seed, "dev", **kw), HostSet(sizes_b, seed + 1, "host", **kw)
+    h_out_ref = oracle.hash_table(rA.pairs(), "dev")
+    h_in_ref = oracle.hash_table(rB.pairs(), "host")
+    if oracle_staged:
+        oracle.switch_staged(rA.pairs(), rB.pairs(), **oracle_staged)
+    else:
+        oracle.switch_direct(rA.pairs(), rB.pairs())
+    # GPU side
+    gA, gB = GpuSet(sizes_a, seed, "dev", **kw), GpuSet(sizes_b, seed + 1, "host", **kw)
+    plan = nx.Plan(gA.rows(), gB.rows(), ring, opts)
+    try:
+        info = plan.info()
+        assert info["pinned_ring_bytes"] <= ring
+        assert info["bytes_out"] == sum(sizes_a) and info["bytes_in"] == sum(sizes_b)
+        h_out, h_in = plan.hash_tables()
+        assert np.array_equal(h_out, h_out_ref), "pre-switch device hashes differ from the oracle"
+        assert np.array_equal(h_in, h_in_ref), "pre-switch host hashes differ from the oracle"
+        for _ in range(switches):
+            st = plan.switch()
+            assert st["bytes_out"] == sum(sizes_a) and st["bytes_in"] == sum(sizes_b)
+        dev_B = gB.download()
+        assert np.array_equal(gA.hs.host, rA.host), "evicted set: " + first_diff(gA.hs.host, rA.host)
+        assert np.array_equal(dev_B, rB.dev), "restored set: " + first_diff(dev_B, rB.dev)
+        # the source device arena of A keeps its red zones too (nothing strays on the device side)
+        dev_A = gA.download()
+        assert np.array_equal(dev_A, gA.hs.dev), "device arena of the evicted set was written"
+        rep = plan.verify(h_out_ref, h_in_ref)
+        assert rep["mismatched_out"] == 0 and rep["mismatched_in"] == 0
+        assert rep["checked_out"] == len(sizes_a) and rep["checked_in"] == len(sizes_b)
+        return info, st
+    finally:
+        plan.close()
+
+
+def test_config1_tiny(nx, oracle):
+    cf = W.config(1)
+    sa, sb = [b for _, b in cf["A"]], [b for _, b in cf["B"]]
+    info, st = run_case(nx, oracle, sa, sb, cf["ring_bytes"][0], nx.Opts(slot_bytes=cf["slot_bytes"]),
+                        seed=cf["seed_A"])
+    assert info["slot_bytes"] == 256 * KiB and info["out_slots"] == 8 and info["in_slots"] == 8
+
+
+S = 64 * KiB
+
+
+@pytest.mark.parametrize("order", [0, 1, 2, 3])
+def test_edge_sizes_every_order(nx, oracle, order):
+    sizes_a = [1, 15, 16, 17, 255, 4096, S - 1, S, S + 1, 3 * S + 5, 0, 10 * S + 333, 7]
+    sizes_b = [S + 1, 2, 7 * S - 3, 0, 31, 5 * S, 16]
+    run_case(nx, oracle, sizes_a, sizes_b, 8 * S, nx.Opts(slot_bytes=S, order=order))
+
+
+@pytest.mark.parametrize("skew", [(1, 0), (0, 7), (15, 9), (3, 3), (8, 12)])
+def test_unaligned_bases(nx, oracle, skew):
+    sizes_a = [100, 1000, S + 3, 5, 2 * S, 40000]
+    sizes_b = [999, 16, 3 * S + 1, 77777]
+    run_case(nx, oracle, sizes_a, sizes_b, 8 * S, nx.Opts(slot_bytes=S), skew=skew)
+
+
+def test_pure_evict_and_pure_restore(nx, oracle):
+    run_case(nx, oracle, [3 * S + 1, 5, 900000], [], 4 * S, nx.Opts(slot_bytes=S))
+    run_case(nx, oracle, [], [2 * S, 9, 1234567], 4 * S, nx.Opts(slot_bytes=S))
+    run_case(nx, oracle, [], [], 4 * S, nx.Opts(slot_bytes=S))
+    run_case(nx, oracle, [0, 0], [0], 4 * S, nx.Opts(slot_bytes=S))
+
+
+@pytest.mark.parametrize("team,wgs", [(1, 1), (1, 7), (2, 8), (4, 64), (8, 64), (3, 5)])
+def test_launch_shapes(nx, oracle, team, wgs):
+    sizes_a = [5 * S + 1, 300, 2 * S, 11 * S + 17]
+    sizes_b = [4 * S, 11, 6 * S + 9, 200000]
+    run_case(nx, oracle, sizes_a, sizes_b, 8 * S,
+             nx.Opts(slot_bytes=S, team=team, gather_wgs=wgs, scatter_wgs=wgs, drain_threads=2, fill_threads=3))
+
+
+def test_uneven_ring_split_and_staged_oracle(nx, oracle):
+    sizes_a = [9 * S + 1, 77, 3 * S]
+    sizes_b = [5 * S, 3, 2 * S + 2]
+    run_case(nx, oracle, sizes_a, sizes_b, 8 * S, nx.Opts(slot_bytes=S, out_slots=6),
+             oracle_staged=dict(ring_bytes=8 * S, slot_bytes=S, n_out_slots=6, seed=3, check_bytes=True))
+    run_case(nx, oracle, sizes_a, sizes_b, 8 * S, nx.Opts(slot_bytes=S, flags=nx.SPLIT_BY_BYTES))
+
+
+def test_serialized_and_plain_memcpy_modes(nx, oracle):
+    sizes_a = [9 * S + 1, 77, 3 * S]
+    sizes_b = [5 * S, 3, 2 * S + 2]
+    info, st = run_case(nx, oracle, sizes_a, sizes_b, 8 * S, nx.Opts(slot_bytes=S, flags=nx.SERIALIZE))
+    assert st["kernels"] == 2
+    run_case(nx, oracle, sizes_a, sizes_b, 8 * S, nx.Opts(slot_bytes=S, flags=nx.HOST_PLAIN_MEMCPY))
+
+
+def test_repeated_switch_same_plan(nx, oracle):
+    """A plan is reusable: flags and counters start clean every time."""
+    run_case(nx, oracle, [20 * S + 5, 999], [17 * S, 4], 4 * S, nx.Opts(slot_bytes=S), switches=3)
+
+
+def test_many_small_allocations(nx, oracle):
+    sa = W.log_uniform_sizes(5, 3000, 256, 64 * KiB, 1)
+    sb = W.log_uniform_sizes(6, 3000, 256, 64 * KiB, 1)
+    run_case(nx, oracle, sa, sb, 4 * MiB, None)   # default slot: halves down from 2 MiB
+
+
+def test_hash_buffers_device_and_host(nx, oracle):
+    import torch
+    sizes = [0, 1, 7, 8, 9, 4095, 32768, 32769, 100000, 3 * MiB + 5]
+    for skew in (0, 3, 8):
+        hs = HostSet(sizes, 99, "dev", skew_dev=skew)
+        ref = oracle.hash_table(hs.pairs(), "dev")
+        t = torch.from_numpy(hs.dev).to("cuda:0")
+        ptrs = [t.data_ptr() + o for o in hs.ldev.offsets]
+        got_d = nx.hash_buffers(ptrs, sizes, True)
+        got_h = nx.hash_buffers([hs.dev.ctypes.data + o for o in hs.ldev.offsets], sizes, False)
+        assert np.array_equal(got_d, ref) and np.array_equal(got_h, ref)
+
+
+def test_verify_reports_mismatch(nx, oracle):
+    from tests.gpu_helpers import GpuSet
+    gA, gB = GpuSet([5000, 6000], 1, "dev"), GpuSet([7000], 2, "host")
+    plan = nx.Plan(gA.rows(), gB.rows(), 4 * S, nx.Opts(slot_bytes=S))
+    ho, hi = plan.hash_tables()
+    plan.switch()
+    bad = ho.copy(); bad[1] ^= np.uint64(1)
+    rep = plan.verify(bad, hi, check=False)
+    assert rep["rc"] == nx.EMISMATCH and rep["first_bad_out"] == 1 and rep["mismatched_in"] == 0
+    plan.close()
+
+
+def test_errors(nx):
+    from tests.gpu_helpers import GpuSet
+    g = GpuSet([5000, 6000], 1, "dev")
+    rows = g.rows()
+    with pytest.raises(nx.NixieError) as e:
+        nx.Plan(rows, [], 64 * KiB, nx.Opts(slot_bytes=64 * KiB))        # one slot only
+    assert e.value.code == nx.EINVAL
+    with pytest.raises(nx.NixieError) as e:
+        nx.Plan(rows + [(rows[0][0] + 10, rows[0][1] + 100000, 100)], [], 4 * S)   # device overlap
+    assert e.value.code == nx.EOVERLAP
+    with pytest.raises(nx.NixieError) as e:
+        nx.Plan(rows, [], 4 * S, nx.Opts(slot_bytes=1000))              # slot not a multiple of 4096
+    assert e.value.code == nx.EINVAL
+
+
+def test_stalled_drain_times_out_cleanly(nx):
+    """Credits are withheld by the host on purpose: the kernel's bounded wait expires, every
+    workgroup leaves, and the switch reports a timeout instead of hanging."""
+    from tests.gpu_helpers import GpuSet
+    gA, gB = GpuSet([40 * S], 1, "dev"), GpuSet([3 * S], 2, "host")
+    plan = nx.Plan(gA.rows(), gB.rows(), 4 * S,
+                   nx.Opts(slot_bytes=S, timeout_ms=300, flags=nx.DIAG_STALL_DRAIN))
+    st = plan.switch(check=False)
+    assert st["rc"] == nx.ETIMEOUT
+    assert st["ns_total"] < 5e9
+    plan.close()
+    # the device is still healthy: a normal switch works right after
+    gA2, gB2 = GpuSet([40 * S], 1, "dev"), GpuSet([3 * S], 2, "host")
+    plan = nx.Plan(gA2.rows(), gB2.rows(), 4 * S, nx.Opts(slot_bytes=S))
+    plan.switch()
+    gA2.hs.check_moved()
+    plan.close()

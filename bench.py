@@ -1,0 +1,238 @@
+#!/usr/bin/env python3
+"""Benchmark of the context-switch swap on one MI355X.
+
+A step is one bidirectional switch of the LLM-shaped working sets (config 2): the chunk planner
+runs, then nixie_switch evicts application A (8B bf16 decoder + 2 GiB KV cache, 16.96 GiB in 355
+allocations) to pageable memory while bringing application B (same shapes, other seed) into HBM,
+through a 256 MiB pinned ring in 4 MiB slots.  Inputs are resident (A in HBM, B in pageable
+memory) before the timed region.  Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+
+def cpu_baseline(cf, sample_bytes: int) -> dict:
+    """The CPU oracle as it stands, timed on this machine's host cores on the leading allocations
+    of both tables (ordinary arrays stand in for HBM)."""
+    import numpy as np
+    import oracle
+    from workloads.device import pageable_arena
+
+    orc = oracle.Oracle()
+
+    def sample(sizes):
+        out, acc = [], 0
+        for _, b in sizes:
+            if acc + b > sample_bytes and out:
+                break
+            out.append(b)
+            acc += b
+        return out
+
+    sa, sb = sample(cf["A"]), sample(cf["B"])
+
+    def arenas(sizes, seed):
+        tot = sum(sizes)
+        src = pageable_arena(tot, fill=None)
+        rng = np.random.default_rng(seed)
+        blk = rng.integers(0, 256, size=1 << 24, dtype=np.uint8)
+        for a in range(0, tot, blk.size):
+            n = min(blk.size, tot - a)
+            src[a:a + n] = blk[:n]
+        dst = pageable_arena(tot, fill=0)
+        offs = np.concatenate([[0], np.cumsum(sizes)])
+        return src, dst, [(int(offs[i]), int(sizes[i])) for i in range(len(sizes))]
+
+    a_dev, a_host, la = arenas(sa, 1)
+    b_host, b_dev, lb = arenas(sb, 2)
+    pa = [(a_dev[o:o + b], a_host[o:o + b]) for o, b in la]
+    pb = [(b_dev[o:o + b], b_host[o:o + b]) for o, b in lb]
+    nbytes = sum(sa) + sum(sb)
+    orc.switch_direct(pa[:1], pb[:1])                      # touch code paths once
+    t_direct = min(orc.switch_direct(pa, pb) for _ in range(2))
+    cores = os.cpu_count() or 1
+    T = max(1, min(8, cores // 2))
+    slot = cf["slot_bytes"] or (2 << 20)
+    ring = max(cf["ring_bytes"][0], 2 * T * slot)
+    t_mt = min(orc.switch_staged_mt(pa, pb, ring, slot, T) for _ in range(2))
+    ok = bool(np.array_equal(a_dev, a_host) and np.array_equal(b_dev, b_host))
+    return {
+        "value": round(nbytes / t_direct / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+        "sample": f"direct definition (two memcpy loops, 1 thread) on the first {len(sa)}+{len(sb)} allocations "
+                  f"of config 2 ({sum(sa) / 2**30:.2f} GiB out + {sum(sb) / 2**30:.2f} GiB in), host arrays stand in for HBM",
+        "ms": round(t_direct * 1e3, 2),
+        "staged_mt": {"value": round(nbytes / t_mt / 1e9, 3), "unit": "GB/s", "cores": 2 * T,
+                      "ms": round(t_mt * 1e3, 2), "ring_bytes": ring, "slot_bytes": slot},
+        "result_checked": ok,
+    }
+
+
+def read_traffic(path: str):
+    """HBM bytes per launch of the swap kernel from the committed rocprofv3 --pmc summary."""
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":", 1)[1].split()[0])
+    except OSError:
+        pass
+    return None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", type=int, default=2, help="benchmark config 1..5 (2 = headline)")
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink all sizes (debug only)")
+    ap.add_argument("--ring-mib", type=int, default=0, help="override ring size")
+    ap.add_argument("--slot-kib", type=int, default=0)
+    ap.add_argument("--gather-wgs", type=int, default=0)
+    ap.add_argument("--scatter-wgs", type=int, default=0)
+    ap.add_argument("--team", type=int, default=0)
+    ap.add_argument("--drain-threads", type=int, default=0)
+    ap.add_argument("--fill-threads", type=int, default=0)
+    ap.add_argument("--flags", type=int, default=0)
+    ap.add_argument("--order", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-link-peak", action="store_true")
+    ap.add_argument("--cpu-sample-gib", type=float, default=4.0)
+    ap.add_argument("--quiet", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (the swap has no multi-GPU part: each GPU has "
+              "its own host link, ring and tables); re-run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import paper_2601_11743_amd as nx
+    import workloads as W
+    from workloads.device import BigSet
+
+    def log(*a):
+        if not args.quiet:
+            print(*a, file=sys.stderr, flush=True)
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    nx.lib()
+    torch.cuda.set_device(0)
+    cf = W.config(args.config, scale=args.scale)
+    ring = (args.ring_mib << 20) if args.ring_mib else cf["ring_bytes"][min(2, len(cf["ring_bytes"]) - 1)]
+    slot = (args.slot_kib << 10) if args.slot_kib else (cf["slot_bytes"] or 0)
+    if args.scale != 1.0 and not args.ring_mib:
+        ring = max(16 << 20, int(ring * args.scale) >> 20 << 20)
+        slot = 0 if not slot else max(64 << 10, int(slot * args.scale) >> 12 << 12)
+
+    t0 = time.perf_counter()
+    A = BigSet(cf["A"], cf["seed_A"], "dev", cf["content"])
+    B = BigSet(cf["B"], cf["seed_B"], "host", cf["content"])
+    log(f"[bench] working sets built in {time.perf_counter() - t0:.1f} s: "
+        f"A {A.total_bytes / 2**30:.2f} GiB / {len(A.sizes)} allocations, "
+        f"B {B.total_bytes / 2**30:.2f} GiB / {len(B.sizes)} allocations")
+
+    peak = None
+    if not args.no_link_peak:
+        peak = nx.link_peak(1 << 30, 3)
+        log("[bench] link peak GB/s:", {k: round(v, 2) for k, v in peak.items()})
+
+    opts = nx.Opts(slot_bytes=slot, gather_wgs=args.gather_wgs, scatter_wgs=args.scatter_wgs, team=args.team,
+                   drain_threads=args.drain_threads, fill_threads=args.fill_threads, flags=args.flags,
+                   order=args.order)
+    t0 = time.perf_counter()
+    plan = nx.Plan(A.rows(), B.rows(), ring, opts)
+    plan_ms = (time.perf_counter() - t0) * 1e3
+    info = plan.info()
+    log("[bench] plan:", info, f"nixie_plan {plan_ms:.1f} ms")
+    h_out, h_in = plan.hash_tables()
+
+    def step():
+        lay = nx.Layout(A.rows(), B.rows(), ring, opts)    # the chunk planner is part of every step
+        lay.close()
+        return plan.switch()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    stats = []
+    t_begin = time.perf_counter()
+    for _ in range(args.steps):
+        stats.append(step())
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_begin
+
+    rep = plan.verify(h_out, h_in)      # per-allocation hashes on the side that now holds the data
+    diag = bool(args.flags & nx.DIAG_RING_ONLY)
+    arenas_ok = None if diag else bool(A.arenas_equal() and B.arenas_equal())
+    if arenas_ok is False:
+        raise SystemExit("bench.py: full-buffer compare failed after the timed switches")
+    plan.close()
+
+    nbytes = info["bytes_out"] + info["bytes_in"]
+    ms = elapsed / args.steps * 1e3
+    value = nbytes * args.steps / elapsed / 1e9
+    lat = sorted(s["ns_total"] / 1e6 for s in stats)
+    kern_s = sum(s["ns_kernel"] for s in stats) / len(stats) / 1e9
+    out_gbs = sorted(s["bytes_out"] / max(1, s["ns_out_done"]) for s in stats)
+    in_gbs = sorted(s["bytes_in"] / max(1, s["ns_in_done"]) for s in stats)
+    med = lambda v: v[len(v) // 2]
+
+    roof = {"bound": "host_link", "kernel": "nixie_swap_kernel", "unit": "GB/s",
+            "achieved": round(nbytes / kern_s / 1e9, 3), "peak": None, "frac": None,
+            "traffic": read_traffic(os.path.join(ROOT, "profiles", "nixie_swap_kernel_llm_pmc.txt")),
+            "algorithmic_bytes_per_launch": nbytes, "kernel_ms": round(kern_s * 1e3, 3),
+            "hbm": {"achieved": round(nbytes / kern_s / 1e9, 3), "peak": 8000.0,
+                    "frac": round(nbytes / kern_s / 1e9 / 8000.0, 5)}}
+    if peak:
+        p_uni = peak["sdma_d2h"] + peak["sdma_h2d"]
+        roof.update(peak=round(p_uni, 3), frac=round(nbytes / kern_s / 1e9 / p_uni, 4),
+                    peak_note="sum of the two one-direction-at-a-time hipMemcpyAsync rates measured in this run",
+                    per_direction={
+                        "out_GBps": round(med(out_gbs), 3), "in_GBps": round(med(in_gbs), 3),
+                        "out_frac_of_unidirectional_peak": round(med(out_gbs) / peak["sdma_d2h"], 4),
+                        "in_frac_of_unidirectional_peak": round(med(in_gbs) / peak["sdma_h2d"], 4),
+                        "out_frac_of_simultaneous_peak": round(med(out_gbs) / peak["sdma_d2h_both"], 4),
+                        "in_frac_of_simultaneous_peak": round(med(in_gbs) / peak["sdma_h2d_both"], 4)},
+                    link_peak={k: round(v, 3) for k, v in peak.items()})
+
+    res = {
+        "metric": "bidirectional swap GB/s (switch latency in ms_per_step), 16 GiB-class out/in, 256 MiB ring",
+        "value": round(value, 3), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8", "data": "synthetic",
+        "config": {"workload": f"config {args.config} ({W.CONFIG_NAMES[args.config]}): "
+                               f"{info['bytes_out'] / 2**30:.2f} GiB out in {len(A.sizes)} allocations / "
+                               f"{info['bytes_in'] / 2**30:.2f} GiB in in {len(B.sizes)} allocations, "
+                               f"ring {ring >> 20} MiB in {info['slot_bytes'] >> 10} KiB slots",
+                   "ring_bytes": ring, "slot_bytes": info["slot_bytes"], "out_slots": info["out_slots"],
+                   "in_slots": info["in_slots"], "gather_wgs": info["gather_wgs"], "scatter_wgs": info["scatter_wgs"],
+                   "team": info["team_out"], "drain_threads": info["drain_threads"],
+                   "fill_threads": info["fill_threads"], "flags": args.flags, "scale": args.scale},
+        "switch_latency_ms": {"min": round(lat[0], 3), "median": round(med(lat), 3), "max": round(lat[-1], 3)},
+        "b_ready_ms": round(med(sorted(s["ns_in_done"] / 1e6 for s in stats)), 3),
+        "plan_ms": round(plan_ms, 2),
+        "pinned_bytes": {"ring": info["pinned_ring_bytes"], "control": info["pinned_ctrl_bytes"]},
+        "verified": {"hash_mismatches": rep["mismatched_out"] + rep["mismatched_in"], "full_buffer_equal": arenas_ok},
+        "stalls": {"drain_wait_ms": round(med(sorted(s["drain_wait_ns"] for s in stats)) / 1e6, 2),
+                   "fill_wait_ms": round(med(sorted(s["fill_wait_ns"] for s in stats)) / 1e6, 2),
+                   "gather_stall_ms_sum": round(med(sorted(s["gather_stall_ticks"] for s in stats)) / 1e5, 2),
+                   "scatter_stall_ms_sum": round(med(sorted(s["scatter_stall_ticks"] for s in stats)) / 1e5, 2)},
+        "roofline": roof,
+    }
+    del A, B
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(cf, int(args.cpu_sample_gib * 2**30))
+    print(json.dumps(res), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -14,9 +14,12 @@
 //   producer of round r waits   free[s]  >= r      (r = 0 needs no wait)
 //   consumer of round r waits   ready[s] >= r + 1
 // Outgoing: the GPU produces, host drain threads consume.  Incoming: host fill threads
-// produce, the GPU consumes.  Flags the host writes are polled with system-scope acquire
-// loads; flags the GPU writes are stored with system-scope release after the workgroups
-// sharing a chunk have met on a device-scope counter.
+// produce, the GPU consumes.  Workgroups sharing a chunk meet on a device-scope counter and the
+// last one stores the host-visible flag.  All flag traffic is relaxed system-scope atomics; the
+// ordering of payload against flags is built by hand (see the comments at the two places that
+// do it), because cache-maintaining fences at
+// device or system scope cost 5-15 % of the link rate here: payload goes into the ring with
+// write-through system-scope stores and comes out of it with system-scope loads.
 //
 // Forward progress: work units are handed out in order by an atomic ticket, so the unit a
 // workgroup waits behind always belongs to a workgroup that is already running.  Every wait is
@@ -41,6 +44,34 @@ __device__ __forceinline__ uint64_t mix64_dev(uint64_t z) {
     return z ^ (z >> 31);
 }
 
+// Eight 16-byte loads from the pinned ring, then one wait for all of them.  The loads carry
+// the system-scope bits (sc0 sc1), so they are served from host memory itself and never from
+// a cache line left over from an earlier use of the slot; no cache invalidation is needed
+// between the host's "slot ready" flag and these loads.  One asm block, because the compiler
+// does not track loads issued from inline asm: the values are only valid after the wait.
+__device__ __forceinline__ void load8_from_host(u32x4 (&v)[8], const u32x4 *const (&a)[8]) {
+    asm volatile(
+        "global_load_dwordx4 %0, %8, off sc0 sc1\n"
+        "global_load_dwordx4 %1, %9, off sc0 sc1\n"
+        "global_load_dwordx4 %2, %10, off sc0 sc1\n"
+        "global_load_dwordx4 %3, %11, off sc0 sc1\n"
+        "global_load_dwordx4 %4, %12, off sc0 sc1\n"
+        "global_load_dwordx4 %5, %13, off sc0 sc1\n"
+        "global_load_dwordx4 %6, %14, off sc0 sc1\n"
+        "global_load_dwordx4 %7, %15, off sc0 sc1\n"
+        "s_waitcnt vmcnt(0)"
+        : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3]), "=&v"(v[4]), "=&v"(v[5]), "=&v"(v[6]), "=&v"(v[7])
+        : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(a[4]), "v"(a[5]), "v"(a[6]), "v"(a[7])
+        : "memory");
+}
+
+// One 16-byte store into the pinned ring with the system-scope bits set: written through to
+// host memory instead of being held in the L2 (the driver maps pinned host memory cacheable
+// for the GPU), so that "all my stores are acknowledged" means "the payload is in host memory".
+__device__ __forceinline__ void store_to_host(u32x4 *p, u32x4 v) {
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(p), "v"(v) : "memory");
+}
+
 // Copy n bytes between a device range and its image in a ring slot.  The two addresses are
 // congruent modulo 16 (the planner guarantees it), so one head/tail peel serves both sides.
 template <bool TO_RING>
@@ -49,21 +80,38 @@ __device__ __forceinline__ void copy_span(uint8_t *dev, uint8_t *ring, uint32_t 
     uint8_t *dst = TO_RING ? ring : dev;
     uint32_t head = (16u - ((uint32_t)(uintptr_t)ring & 15u)) & 15u;
     if (head > n) head = n;
-    if (lane < head) dst[lane] = src[lane];
+    if (lane < head) {   // byte accesses to the ring are system-scope atomics: same write-through / no-cache rule
+        if (TO_RING) __hip_atomic_store(dst + lane, src[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        else dst[lane] = __hip_atomic_load(src + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
     const uint32_t nvec = (n - head) >> 4;
     const u32x4 *s4 = (const u32x4 *)(src + head);
     u32x4 *d4 = (u32x4 *)(dst + head);
-    for (uint32_t j = lane; j < nvec; j += 64 * kUnroll) {
+    for (uint32_t j = lane; j - lane < nvec; j += 64 * kUnroll) {   // wave-uniform trip count
         u32x4 v[kUnroll];
+        if (TO_RING) {
+#pragma unroll
+            for (uint32_t u = 0; u < kUnroll; u++)
+                if (j + 64 * u < nvec) v[u] = s4[j + 64 * u];
+        } else {
+            // out-of-range lanes re-read the last vector of the span (one extra line) and drop it
+            const u32x4 *a[kUnroll];
+#pragma unroll
+            for (uint32_t u = 0; u < kUnroll; u++) a[u] = s4 + (j + 64 * u < nvec ? j + 64 * u : nvec - 1);
+            load8_from_host(v, a);
+        }
 #pragma unroll
         for (uint32_t u = 0; u < kUnroll; u++)
-            if (j + 64 * u < nvec) v[u] = s4[j + 64 * u];
-#pragma unroll
-        for (uint32_t u = 0; u < kUnroll; u++)
-            if (j + 64 * u < nvec) d4[j + 64 * u] = v[u];
+            if (j + 64 * u < nvec) {
+                if (TO_RING) store_to_host(d4 + j + 64 * u, v[u]);
+                else d4[j + 64 * u] = v[u];
+            }
     }
     const uint32_t done = head + (nvec << 4);
-    if (lane < n - done) dst[done + lane] = src[done + lane];
+    if (lane < n - done) {
+        if (TO_RING) __hip_atomic_store(dst + done + lane, src[done + lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        else dst[done + lane] = __hip_atomic_load(src + done + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
 }
 
 // One wave copies the part of the slot image [t0, t1) that the chunk's segments cover.
@@ -107,10 +155,10 @@ __device__ void run_direction(const SwapArgs &a) {
                 const uint64_t need = (uint64_t)(k / D.n_slots) + (DIR == 0 ? 0u : 1u);
                 const uint64_t *flag = D.wait_flags + (size_t)slot * kFlagStride;
                 if (!stop && need > 0 &&
-                    __hip_atomic_load(flag, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_SYSTEM) < need) {
+                    __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) < need) {
                     const uint64_t t0 = wall_clock64();
                     uint32_t it = 0;
-                    while (__hip_atomic_load(flag, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_SYSTEM) < need) {
+                    while (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) < need) {
                         if ((++it & 7u) == 0) {
                             uint32_t why = 0;
                             if (__hip_atomic_load(a.dev_abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) stop = 1;
@@ -119,7 +167,7 @@ __device__ void run_direction(const SwapArgs &a) {
                             if (why) {
                                 stop = 1;
                                 __hip_atomic_store(a.dev_abort, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                                __hip_atomic_store(a.gpu_status, why, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+                                __hip_atomic_store(a.gpu_status, why, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
                             }
                             if (stop) break;
                         }
@@ -138,7 +186,6 @@ __device__ void run_direction(const SwapArgs &a) {
         const uint32_t slot = k % D.n_slots;
         const DevChunk ch = D.chunks[k];
         uint8_t *slot_base = D.ring + (size_t)slot * a.slot_bytes;
-        if (DIR == 1) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "");  // the slot was just rewritten by the host
 
         const uint32_t n_tiles = (ch.used + kTileBytes - 1) / kTileBytes;
         for (uint32_t t = part * waves_per_wg + wave; t < n_tiles; t += D.team * waves_per_wg) {
@@ -146,17 +193,24 @@ __device__ void run_direction(const SwapArgs &a) {
             const uint32_t t1 = t0 + kTileBytes < ch.used ? t0 + kTileBytes : ch.used;
             copy_tile<DIR == 0>(D.segs + ch.seg_begin, ch.seg_count, slot_base, t0, t1, lane);
         }
-        if (DIR == 0) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "");  // payload reaches host memory before the flag
+        // Payload before flag, without a release fence.  A system- or device-scope release would
+        // write back the whole L2 (which holds the scatter side's dirty HBM lines) for every work
+        // unit, and measurably slows both directions.  Every store into the ring is a write-through
+        // system-scope store, so it is enough that every wave waits until all of its stores are
+        // acknowledged (vmcnt = 0), that the workgroup then meets at the barrier, and that
+        // thread 0 only afterwards bumps the arrive counter and stores the flag.  The flag is a
+        // later posted write on the same link and cannot pass the payload.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();   // also: every thread has read s_unit before thread 0 overwrites it
         if (tid == 0) {
             bool last = true;
             if (D.team > 1) {
-                uint32_t old = __hip_atomic_fetch_add(D.arrive + k, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+                uint32_t old = __hip_atomic_fetch_add(D.arrive + k, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 last = (old == D.team - 1);
             }
             if (last)
                 __hip_atomic_store(D.post_flags + (size_t)slot * kFlagStride, (uint64_t)(k / D.n_slots) + 1u,
-                                   __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
         }
     }
     if (tid == 0 && stall)

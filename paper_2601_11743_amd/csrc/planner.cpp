@@ -174,10 +174,16 @@ void fill_info(const Layout &L, nixie_plan_info_t *info) {
     info->bytes_in = L.dir[1].bytes;
     info->pinned_ring_bytes = (uint64_t)(L.dir[0].slots + L.dir[1].slots) * L.slot_bytes;
     info->pinned_ctrl_bytes = ((uint64_t)(L.dir[0].slots + L.dir[1].slots) * 2 + 2) * kFlagStride * 8;
+    // Work unit = 64 KiB of a slot: small enough that all workgroups of a direction share the one
+    // or two oldest chunks (a chunk is published when its slowest unit is done, so units of one
+    // chunk should finish close together), large enough to hide the ticket and the flag poll.
     uint32_t team = L.opts.team ? L.opts.team
-                                : (uint32_t)std::min<uint64_t>(8, std::max<uint64_t>(1, L.slot_bytes / (256u << 10)));
+                                : (uint32_t)std::min<uint64_t>(64, std::max<uint64_t>(1, L.slot_bytes / (64u << 10)));
     team = std::min(team, 64u);
-    uint32_t wgs[2] = {L.opts.gather_wgs ? L.opts.gather_wgs : 64u, L.opts.scatter_wgs ? L.opts.scatter_wgs : 64u};
+    // Measured on MI355X with both directions active: write-through stores into the ring need
+    // about twice the workgroups that the reads out of it need; beyond 128 + 64 the surplus
+    // only waits on credits.
+    uint32_t wgs[2] = {L.opts.gather_wgs ? L.opts.gather_wgs : 128u, L.opts.scatter_wgs ? L.opts.scatter_wgs : 64u};
     uint32_t thr[2] = {L.opts.drain_threads ? L.opts.drain_threads : 4u, L.opts.fill_threads ? L.opts.fill_threads : 4u};
     for (int x = 0; x < 2; x++) {
         if (L.dir[x].chunks.empty()) { wgs[x] = 0; thr[x] = 0; continue; }

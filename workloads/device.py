@@ -1,0 +1,90 @@
+"""Large working sets built in place: HBM arenas filled by torch, pageable arenas from mmap.
+
+Input generation only.  torch is used for device memory and its random generators; nothing
+here chunks, copies or hashes a working set the way the swap does.
+"""
+from __future__ import annotations
+
+import ctypes
+import mmap
+
+import numpy as np
+
+from .sets import Layout, make_layout
+
+_MADV_HUGEPAGE = 14
+_libc = ctypes.CDLL(None, use_errno=True)
+
+
+def pageable_arena(nbytes: int, fill: int | None = 0) -> np.ndarray:
+    """Anonymous private mapping (ordinary pageable memory), huge pages requested,
+    faulted in up front so that a timed run does not measure the page allocator."""
+    nbytes = max(nbytes, mmap.PAGESIZE)
+    mm = mmap.mmap(-1, nbytes, flags=mmap.MAP_PRIVATE | mmap.MAP_ANONYMOUS)
+    arr = np.frombuffer(mm, dtype=np.uint8)
+    _libc.madvise(ctypes.c_void_p(arr.ctypes.data), ctypes.c_size_t(nbytes), _MADV_HUGEPAGE)
+    if fill is not None:
+        step = 1 << 30
+        for a in range(0, nbytes, step):
+            arr[a:a + step] = fill
+    return arr
+
+
+class BigSet:
+    """One application's working set at full size: an HBM arena (torch uint8) and a pageable
+    arena with the same layout (256 B aligned bases, red zones between allocations)."""
+
+    def __init__(self, sizes, seed: int, resident: str, content: str, device: str = "cuda:0",
+                 redzone: int = 256, red: int = 0xC3, poison_dev: int = 0xA5, poison_host: int = 0x5A):
+        import torch
+        self.sizes = [s if isinstance(s, int) else s[1] for s in sizes]
+        self.names = [("" if isinstance(s, int) else s[0]) for s in sizes]
+        self.seed, self.resident, self.red = seed, resident, red
+        self.layout: Layout = make_layout(self.sizes, redzone=redzone)
+        self.dev = torch.full((self.layout.total,), red, dtype=torch.uint8, device=device)
+        self.host = pageable_arena(self.layout.total, fill=red)
+        self.host_t = torch.from_numpy(self.host)
+        g = torch.Generator(device=device)
+        g.manual_seed(seed)
+        for o, b in zip(self.layout.offsets, self.sizes):
+            v = self.dev[o:o + b]
+            if content == "bf16_normal" and b % 2 == 0 and b > 0:
+                v.view(torch.bfloat16).normal_(0.0, 0.02, generator=g)
+            elif b > 0:
+                v.random_(0, 256, generator=g)
+        torch.cuda.synchronize()
+        if resident == "host":       # B starts in pageable memory; its HBM ranges are poisoned
+            step = 1 << 30
+            for a in range(0, self.layout.total, step):
+                self.host_t[a:a + step].copy_(self.dev[a:a + step])
+            for o, b in zip(self.layout.offsets, self.sizes):
+                self.dev[o:o + b] = poison_dev
+        else:                        # A is GPU resident; its pageable ranges are poisoned
+            for o, b in zip(self.layout.offsets, self.sizes):
+                self.host[o:o + b] = poison_host
+        torch.cuda.synchronize()
+
+    @property
+    def total_bytes(self) -> int:
+        return sum(self.sizes)
+
+    def rows(self):
+        bd, bh = self.dev.data_ptr(), self.host.ctypes.data
+        return [(bd + o, bh + o, b) for o, b in zip(self.layout.offsets, self.sizes)]
+
+    def dev_view(self, i: int):
+        o, b = self.layout.offsets[i], self.sizes[i]
+        return self.dev[o:o + b]
+
+    def host_view(self, i: int) -> np.ndarray:
+        o, b = self.layout.offsets[i], self.sizes[i]
+        return self.host[o:o + b]
+
+    def arenas_equal(self) -> bool:
+        """Whole-arena compare, HBM against pageable (contents and red zones), in 1 GiB steps."""
+        import torch
+        step = 1 << 30
+        for a in range(0, self.layout.total, step):
+            if not torch.equal(self.dev[a:a + step], self.host_t[a:a + step].to(self.dev.device)):
+                return False
+        return True

@@ -1,0 +1,142 @@
+"""Full-size parity on the GPU: the five benchmark configs at their real sizes, in the launch
+configuration bench.py times.
+
+The oracle cannot move 17-24 GiB in test time, so it is applied to a sample of allocations
+(first, last, smallest, largest and seeded random picks): for each sampled allocation the
+oracle's direct definition produces the expected destination bytes and its hash, which are
+compared bit for bit with what nixie_switch left.  On top of that every destination arena is
+compared whole against its (untouched) source arena, red zones included, and nixie_verify
+checks all per-allocation hashes against the pre-switch snapshot."""
+import numpy as np
+import pytest
+
+import workloads as W
+
+pytestmark = pytest.mark.gpu
+MiB, GiB = 1 << 20, 1 << 30
+
+
+@pytest.fixture(scope="module")
+def nx():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_2601_11743_amd as nx
+    nx.lib()
+    return nx
+
+
+def sample_indices(sizes, seed, n_random=16, cap_bytes=1200 * MiB):
+    order = np.argsort(sizes)
+    picks = {0, len(sizes) - 1, int(order[0]), int(order[-1]), int(order[len(order) // 2])}
+    rng = np.random.default_rng(seed)
+    picks.update(int(i) for i in rng.integers(0, len(sizes), size=n_random))
+    out, acc = [], 0
+    for i in sorted(picks, key=lambda i: sizes[i]):
+        if acc + sizes[i] > cap_bytes and out:
+            continue
+        out.append(i)
+        acc += sizes[i]
+    return sorted(out)
+
+
+def oracle_expectation(oracle, S, idx, src_side):
+    """Oracle's direct definition on the sampled allocations of set S: returns the destination
+    bytes it produces and the oracle hash of each."""
+    pairs, dst = [], []
+    for i in idx:
+        if src_side == "dev":
+            src = S.dev_view(i).cpu().numpy().copy()
+            d = np.zeros_like(src)
+            pairs.append((src, d))        # (dev stand-in, host stand-in)
+        else:
+            src = S.host_view(i).copy()
+            d = np.zeros_like(src)
+            pairs.append((d, src))
+        dst.append(d)
+    if src_side == "dev":
+        oracle.switch_direct(pairs, [])
+    else:
+        oracle.switch_direct([], pairs)
+    return dst, [oracle.hash64(d) for d in dst]
+
+
+def full_case(nx, oracle, cfg, ring, round_trips=0, opts_kw=None):
+    import torch
+    from workloads.device import BigSet
+    cf = W.config(cfg)
+    A = BigSet(cf["A"], cf["seed_A"], "dev", cf["content"])
+    B = BigSet(cf["B"], cf["seed_B"], "host", cf["content"])
+    ia, ib = sample_indices(A.sizes, 1), sample_indices(B.sizes, 2)
+    exp_a, hash_a = oracle_expectation(oracle, A, ia, "dev")
+    exp_b, hash_b = oracle_expectation(oracle, B, ib, "host")
+    opts = nx.Opts(slot_bytes=cf["slot_bytes"] or 0, **(opts_kw or {}))
+    plan = nx.Plan(A.rows(), B.rows(), ring, opts)
+    info = plan.info()
+    assert info["pinned_ring_bytes"] <= ring
+    assert info["bytes_out"] == A.total_bytes and info["bytes_in"] == B.total_bytes
+    h_out, h_in = plan.hash_tables()
+    assert [int(h_out[i]) for i in ia] == hash_a, "GPU hash kernel differs from the oracle hash"
+    assert [int(h_in[i]) for i in ib] == hash_b, "host hash differs from the oracle hash"
+
+    st = plan.switch()
+    for i, e in zip(ia, exp_a):
+        assert np.array_equal(A.host_view(i), e), f"evicted allocation {i} differs from the oracle"
+    for i, e in zip(ib, exp_b):
+        assert np.array_equal(B.dev_view(i).cpu().numpy(), e), f"restored allocation {i} differs from the oracle"
+    assert A.arenas_equal(), "evicted set: pageable arena differs from the HBM source arena"
+    assert B.arenas_equal(), "restored set: HBM arena differs from the pageable source arena"
+    rep = plan.verify(h_out, h_in)
+    assert rep["checked_out"] == len(A.sizes) and rep["checked_in"] == len(B.sizes)
+
+    if round_trips:
+        back = nx.Plan(B.rows(), A.rows(), ring, opts)
+        for t in range(round_trips):
+            # sources are "don't care" after a switch: overwrite them before the way back
+            for S, side in ((A, "dev"), (B, "host")):
+                for i in (0, len(S.sizes) - 1):
+                    (S.dev_view(i) if side == "dev" else S.host_view(i))[:] = 0x11
+            back.switch()                      # B out to host, A back into HBM
+            back.verify(h_in, h_out)
+            for i, e in zip(ia, exp_a):
+                assert np.array_equal(A.dev_view(i).cpu().numpy(), e)
+            for i, e in zip(ib, exp_b):
+                assert np.array_equal(B.host_view(i), e)
+            for S, side in ((A, "host"), (B, "dev")):
+                for i in (0, len(S.sizes) - 1):
+                    (S.dev_view(i) if side == "dev" else S.host_view(i))[:] = 0x22
+            plan.switch()                      # and forth again
+            plan.verify(h_out, h_in)
+        back.close()
+        for i, e in zip(ia, exp_a):
+            assert np.array_equal(A.host_view(i), e)
+        for i, e in zip(ib, exp_b):
+            assert np.array_equal(B.dev_view(i).cpu().numpy(), e)
+    plan.close()
+    del A, B
+    torch.cuda.empty_cache()
+    return info, st
+
+
+def test_config2_llm_full(nx, oracle):
+    info, st = full_case(nx, oracle, 2, 256 * MiB)
+    assert info["slot_bytes"] == 4 * MiB and info["out_slots"] == 32 and info["in_slots"] == 32
+    print(f"\nconfig 2: {st['ns_total'] / 1e6:.1f} ms, out {st['bytes_out'] / st['ns_out_done']:.1f} GB/s, "
+          f"in {st['bytes_in'] / st['ns_in_done']:.1f} GB/s")
+
+
+def test_config3_asymmetric_full(nx, oracle):
+    info, st = full_case(nx, oracle, 3, 128 * MiB)
+    assert st["ns_in_done"] < st["ns_out_done"]        # 6 GiB in is ready long before 20 GiB are out
+    info, st = full_case(nx, oracle, 3, 128 * MiB, opts_kw=dict(flags=nx.SPLIT_BY_BYTES, order=nx.ORDER_LARGE_FIRST))
+
+
+def test_config4_fragmented_full(nx, oracle):
+    info, st = full_case(nx, oracle, 4, 64 * MiB)
+    assert info["segments_out"] >= 100_000
+    print(f"\nconfig 4: {st['ns_total'] / 1e6:.1f} ms, {info['segments_out']} segments out")
+
+
+@pytest.mark.parametrize("ring_mib", [16, 1024])
+def test_config5_pingpong_full(nx, oracle, ring_mib):
+    info, st = full_case(nx, oracle, 5, ring_mib * MiB, round_trips=1)
+    assert info["pinned_ring_bytes"] <= ring_mib * MiB

@@ -1,0 +1,196 @@
+"""Host-side logic of libnixie without a GPU: the library loads and exports what the header
+declares; the chunk planner's output partitions every allocation exactly; host hashing agrees
+with the oracle.  No GPU compute is called here."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+import workloads as W
+
+KiB, MiB, GiB = 1 << 10, 1 << 20, 1 << 30
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def nx():
+    import paper_2601_11743_amd as nx
+    if not os.path.exists(nx.lib_path()):
+        from paper_2601_11743_amd import build
+        build.build()
+    nx.lib()
+    return nx
+
+
+def test_library_exports_every_declared_symbol(nx):
+    header = open(os.path.join(ROOT, "include", "nixie.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(nixie_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(nx.DECLARED_SYMBOLS)
+    L = nx.lib()
+    for name in declared:
+        assert getattr(L, name) is not None, name
+    assert nx.strerror(0) == "ok" and "overlap" in nx.strerror(nx.EOVERLAP)
+
+
+def fake_rows(sizes, dev_base=0x7F00_0000_0000, host_base=0x1000_0000_0000, skew_dev=0, skew_host=0, gap=256):
+    rows, d, h = [], dev_base, host_base
+    for b in sizes:
+        d = (d + 255) // 256 * 256 + skew_dev
+        h = (h + 255) // 256 * 256 + skew_host
+        rows.append((d, h, b))
+        d += b + gap
+        h += b + gap
+    return rows
+
+
+def check_layout(lay, rows_out, rows_in, ring):
+    info = lay.info()
+    S = info["slot_bytes"]
+    assert (info["out_slots"] + info["in_slots"]) * S == info["pinned_ring_bytes"] <= ring
+    for direction, rows in ((0, rows_out), (1, rows_in)):
+        ch, sg = lay.chunks(direction), lay.segments(direction)
+        total = sum(b for _, _, b in rows)
+        assert int(sg["len"].sum()) == total == info["bytes_out" if direction == 0 else "bytes_in"]
+        if len(sg) == 0:
+            assert len(ch) == 0
+            continue
+        assert (sg["len"] > 0).all()
+        # chunks tile the segment array in order
+        assert ch["seg_begin"][0] == 0 and (ch["seg_count"] > 0).all()
+        assert np.array_equal(ch["seg_begin"][1:], (ch["seg_begin"] + ch["seg_count"])[:-1])
+        assert int(ch["seg_begin"][-1] + ch["seg_count"][-1]) == len(sg)
+        # inside a chunk: ascending, non-overlapping slot ranges that fit the slot; alignment congruence
+        chunk_of = np.repeat(np.arange(len(ch)), ch["seg_count"])
+        end = sg["slot_off"].astype(np.int64) + sg["len"]
+        assert (end <= S).all()
+        same = chunk_of[1:] == chunk_of[:-1]
+        assert (sg["slot_off"][1:][same] >= end[:-1][same]).all()
+        assert ((sg["slot_off"].astype(np.uint64) & 15) == (sg["dev_addr"] & 15)).all()
+        used = np.zeros(len(ch), dtype=np.int64)
+        np.maximum.at(used, chunk_of, end)
+        assert np.array_equal(used, ch["used_bytes"].astype(np.int64))
+        # segments partition every allocation: sorted by device address they abut exactly
+        order = np.argsort(sg["dev_addr"], kind="stable")
+        dev, ln, host = sg["dev_addr"][order], sg["len"][order].astype(np.uint64), sg["host_addr"][order]
+        ranges = sorted((d, h, b) for d, h, b in rows if b)
+        starts = np.array([r[0] for r in ranges], dtype=np.uint64)
+        idx = np.searchsorted(starts, dev, side="right") - 1
+        a_dev = starts[idx]
+        a_host = np.array([r[1] for r in ranges], dtype=np.uint64)[idx]
+        a_len = np.array([r[2] for r in ranges], dtype=np.uint64)[idx]
+        assert ((dev - a_dev) == (host - a_host)).all()          # same offset on both sides
+        assert (dev + ln <= a_dev + a_len).all()
+        first = np.r_[True, idx[1:] != idx[:-1]]
+        assert (dev[first] == a_dev[first]).all()
+        assert (dev[1:][~first[1:]] == (dev + ln)[:-1][~first[1:]]).all()   # pieces abut
+        covered = np.zeros(len(ranges), dtype=np.uint64)
+        np.add.at(covered, idx, ln)
+        assert np.array_equal(covered, np.array([r[2] for r in ranges], dtype=np.uint64))
+    return info
+
+
+@pytest.mark.parametrize("order", [0, 1, 2, 3])
+def test_planner_partitions_exactly(nx, order):
+    S = 64 * KiB
+    sizes_a = [1, 15, 16, 17, 255, 4096, S - 1, S, S + 1, 3 * S + 5, 0, 10 * S + 333, 7]
+    sizes_b = [S + 1, 2, 7 * S - 3, 0, 31, 5 * S, 16]
+    for skew in ((0, 0), (3, 9), (15, 1)):
+        ra = fake_rows(sizes_a, skew_dev=skew[0], skew_host=skew[1])
+        rb = fake_rows(sizes_b, dev_base=0x7F80_0000_0000, host_base=0x1800_0000_0000, skew_dev=skew[1], skew_host=skew[0])
+        lay = nx.Layout(ra, rb, 8 * S, nx.Opts(slot_bytes=S, order=order))
+        info = check_layout(lay, ra, rb, 8 * S)
+        assert info["out_slots"] == 4 and info["in_slots"] == 4
+        lay.close()
+
+
+def test_planner_order_modes(nx):
+    S = 64 * KiB
+    rows = fake_rows([100, 5 * S, 300, 2 * S])
+    first_dev = {}
+    for order in range(4):
+        lay = nx.Layout(rows, [], 8 * S, nx.Opts(slot_bytes=S, order=order))
+        first_dev[order] = int(lay.segments(0)["dev_addr"][0])
+        lay.close()
+    assert first_dev[0] == rows[0][0] and first_dev[3] == rows[3][0]
+    assert first_dev[1] == rows[1][0]                 # largest first
+    assert first_dev[2] == min(r[0] for r in rows)    # lowest address first
+
+
+def test_planner_packing_is_dense(nx):
+    """Small allocations share slots: 16-byte-aligned pieces waste nothing, so the chunk count is
+    ceil(total / slot)."""
+    S = 256 * KiB
+    sizes = [16 * (1 + (i * 37) % 500) for i in range(4000)]
+    rows = fake_rows(sizes, gap=0)
+    lay = nx.Layout(rows, [], 16 * S, nx.Opts(slot_bytes=S))
+    info = check_layout(lay, rows, [], 16 * S)
+    assert info["chunks_out"] == -(-sum(sizes) // S)
+    lay.close()
+
+
+def test_planner_ring_split_and_defaults(nx):
+    ra, rb = fake_rows([20 * MiB]), fake_rows([6 * MiB], dev_base=0x7F80_0000_0000, host_base=0x1800_0000_0000)
+    lay = nx.Layout(ra, rb, 128 * MiB)
+    i = lay.info()
+    assert i["slot_bytes"] == 2 * MiB and i["out_slots"] == 32 and i["in_slots"] == 32
+    assert i["team_out"] == 32 and i["gather_wgs"] == 128 and i["scatter_wgs"] == 64
+    lay = nx.Layout(ra, rb, 128 * MiB, nx.Opts(flags=nx.SPLIT_BY_BYTES))
+    i = lay.info()
+    assert i["out_slots"] == round(64 * 20 / 26) and i["out_slots"] + i["in_slots"] == 64
+    lay = nx.Layout(ra, rb, 128 * MiB, nx.Opts(out_slots=10))
+    assert lay.info()["out_slots"] == 10 and lay.info()["in_slots"] == 54
+    lay = nx.Layout(ra, [], 128 * MiB)                 # pure evict: the whole ring serves one direction
+    assert lay.info()["out_slots"] == 64 and lay.info()["in_slots"] == 0 and lay.info()["scatter_wgs"] == 0
+    lay = nx.Layout(ra, rb, 16 * MiB)                  # small ring: slot halves until 4 per direction
+    assert lay.info()["slot_bytes"] == 2 * MiB and lay.info()["out_slots"] == 4
+    lay = nx.Layout(ra, rb, 4 * MiB)
+    assert lay.info()["slot_bytes"] == 512 * KiB
+    lay = nx.Layout(ra, rb, 256 * KiB)
+    assert lay.info()["slot_bytes"] == 64 * KiB and lay.info()["out_slots"] == 2
+
+
+def test_planner_errors(nx):
+    S = 64 * KiB
+    rows = fake_rows([5000, 6000])
+
+    def code(fn):
+        with pytest.raises(nx.NixieError) as e:
+            fn()
+        return e.value.code
+
+    assert code(lambda: nx.Layout(rows, [], S, nx.Opts(slot_bytes=S))) == nx.EINVAL          # one slot
+    assert code(lambda: nx.Layout(rows, rows, 8 * S, nx.Opts(slot_bytes=S))) == nx.EOVERLAP  # same ranges twice
+    assert code(lambda: nx.Layout(rows + [(rows[0][0] + 4999, 0x2000_0000_0000, 2)], [], 8 * S)) == nx.EOVERLAP
+    assert code(lambda: nx.Layout(rows + [(0x7F90_0000_0000, rows[1][1] + 5999, 2)], [], 8 * S)) == nx.EOVERLAP
+    assert code(lambda: nx.Layout(rows, [], 8 * S, nx.Opts(slot_bytes=1000))) == nx.EINVAL
+    assert code(lambda: nx.Layout(rows, [], 8 * S, nx.Opts(order=9))) == nx.EINVAL
+    assert code(lambda: nx.Layout([(0, 0x1000, 10)], [], 8 * S)) == nx.EINVAL               # NULL device pointer
+    assert code(lambda: nx.Layout(rows, fake_rows([10], dev_base=0x7F80_0000_0000, host_base=0x1800_0000_0000),
+                                  3 * S, nx.Opts(slot_bytes=S))) == nx.EINVAL               # < 2 slots per direction
+    nx.Layout([(0, 0, 0)], [], 8 * S).close()                                               # empty entries are legal
+    # adjacent (touching) ranges are not an overlap
+    nx.Layout([(0x7F00_0000_0000, 0x1000_0000_0000, 4096), (0x7F00_0000_1000, 0x1000_0000_1000, 4096)], [], 8 * S).close()
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_planner_on_benchmark_configs(nx, cfg):
+    cf = W.config(cfg)
+    ra = fake_rows([b for _, b in cf["A"]])
+    rb = fake_rows([b for _, b in cf["B"]], dev_base=0x7A00_0000_0000, host_base=0x1A00_0000_0000)
+    for ring in cf["ring_bytes"]:
+        lay = nx.Layout(ra, rb, ring, nx.Opts(slot_bytes=cf["slot_bytes"] or 0))
+        info = check_layout(lay, ra, rb, ring)
+        S = info["slot_bytes"]
+        # packing keeps slots full: at most one partly filled chunk beyond the dense count per direction
+        assert info["chunks_out"] <= -(-info["bytes_out"] // S) + max(1, len(ra) * 15 // S + 1)
+        lay.close()
+
+
+def test_host_hash_matches_oracle(nx, oracle):
+    sizes = [0, 1, 7, 8, 9, 4095, 32768, 32769, 100000, 3 * MiB + 5]
+    for skew in (0, 3):
+        bufs = [np.concatenate([np.zeros(skew, np.uint8), W.content_bytes(5, i, b)])[skew:] for i, b in enumerate(sizes)]
+        got = nx.hash_buffers([b.ctypes.data for b in bufs], sizes, on_device=False)
+        assert [int(x) for x in got] == [oracle.hash64(b) for b in bufs]

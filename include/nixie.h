@@ -73,7 +73,9 @@ enum nixie_flags {
                                          memory, so destinations on the host side are NOT written */
     NIXIE_DIAG_STALL_DRAIN = 1u << 3, /* failure-path test: drain threads never return credits, so the switch must
                                          end with NIXIE_ETIMEOUT after timeout_ms */
-    NIXIE_HOST_PLAIN_MEMCPY = 1u << 4 /* host threads use libc memcpy instead of streaming stores */
+    NIXIE_HOST_PLAIN_MEMCPY = 1u << 4,/* host threads use libc memcpy instead of streaming stores */
+    NIXIE_CREDIT_PUMP = 1u << 5       /* one extra wave per direction mirrors the host-written credits into device
+                                         memory and workers poll the mirror instead of pinned memory */
 };
 
 /* Every field 0 = library default. */

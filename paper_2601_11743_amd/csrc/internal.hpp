@@ -38,7 +38,10 @@ int hash_host_buffers(const void *const *ptrs, const uint64_t *bytes, uint64_t n
 struct DevSeg { uint64_t dev; uint32_t slot_off; uint32_t len; };
 struct DevChunk { uint32_t seg_begin, seg_count, used, pad; };
 
-constexpr uint32_t kFlagStride = 8;        // u64 per flag line (64 B)
+constexpr uint32_t kFlagStride = 8;        // GPU-written flags: one 64 B line (8 x u64) per flag
+// Host-written flags are packed (one u64 each, a direction's array padded to whole 64 B lines):
+// a single wave of the kernel reads a direction's credits with a few line-sized link reads.
+inline uint64_t wait_flag_words(uint32_t slots) { return ((uint64_t)slots + 7) / 8 * 8; }
 constexpr uint32_t kWgThreads = 256;
 constexpr uint32_t kTileBytes = 8192;
 
@@ -49,9 +52,11 @@ struct DevDir {
     const DevSeg *segs;
     const DevChunk *chunks;
     uint8_t *ring;          // device-visible address of this direction's first slot
-    uint64_t *wait_flags;   // host-written, pinned: out: free[s]  in: ready[s]
-    uint64_t *post_flags;   // GPU-written,  pinned: out: ready[s] in: free[s]
+    const uint64_t *wait_flags;  // host-written, pinned, packed: out: free[s]  in: ready[s]
+    uint64_t *post_flags;   // GPU-written,  pinned, one line each: out: ready[s] in: free[s]
+    uint64_t *mirror;       // device memory: copy of wait_flags kept fresh by the pump wave
     uint32_t *ticket;       // device memory, one counter
+    uint32_t *exited;       // device memory, workgroups of this direction that have left
     uint32_t *arrive;       // device memory, one counter per chunk
     uint64_t *stall_ticks;  // device memory, summed wait time
     uint32_t n_chunks, n_slots, team, wgs;
@@ -64,6 +69,7 @@ struct SwapArgs {
     uint32_t *gpu_status;        // pinned, GPU-written
     uint32_t *dev_abort;         // device memory
     uint64_t timeout_ticks;      // 100 MHz wall clock
+    uint32_t use_pump;           // 1: workers read credits from the device mirror kept by the pump wave
 };
 
 struct HashDesc { uint64_t ptr; uint64_t bytes; uint64_t first_tile; };

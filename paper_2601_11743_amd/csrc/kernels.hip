@@ -21,10 +21,13 @@
 // device or system scope cost 5-15 % of the link rate here: payload goes into the ring with
 // write-through system-scope stores and comes out of it with system-scope loads.
 //
+// Workers never poll host memory: one pump wave per direction mirrors the host-written flags into
+// device memory and relays the host's abort word.
+//
 // Forward progress: work units are handed out in order by an atomic ticket, so the unit a
-// workgroup waits behind always belongs to a workgroup that is already running.  Every wait is
-// bounded (abort word from the host, abort word in device memory, 100 MHz wall-clock limit),
-// so the grid always drains.
+// workgroup waits behind always belongs to a workgroup that is already running.  Every worker
+// wait is bounded (abort word in device memory, 100 MHz wall-clock limit) and the pump leaves
+// once all workers have, so the grid always drains.
 #include <hip/hip_runtime.h>
 
 #include "internal.hpp"
@@ -153,16 +156,22 @@ __device__ void run_direction(const SwapArgs &a) {
                 const uint32_t k = u / D.team;
                 const uint32_t slot = k % D.n_slots;
                 const uint64_t need = (uint64_t)(k / D.n_slots) + (DIR == 0 ? 0u : 1u);
-                const uint64_t *flag = D.wait_flags + (size_t)slot * kFlagStride;
-                if (!stop && need > 0 &&
-                    __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) < need) {
+                // Credits are read from the device-memory mirror that the pump wave keeps fresh, not
+                // from host memory: a poll over the link queues behind the bulk reads and would cost
+                // every work unit tens of microseconds.
+                const uint64_t *credit = a.use_pump ? D.mirror + slot : D.wait_flags + slot;
+                auto peek = [&]() {
+                    return a.use_pump ? __hip_atomic_load(credit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                      : __hip_atomic_load(credit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                };
+                if (!stop && need > 0 && peek() < need) {
                     const uint64_t t0 = wall_clock64();
                     uint32_t it = 0;
-                    while (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) < need) {
+                    while (peek() < need) {
                         if ((++it & 7u) == 0) {
                             uint32_t why = 0;
                             if (__hip_atomic_load(a.dev_abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) stop = 1;
-                            else if (__hip_atomic_load(a.host_abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM)) why = kGpuSawAbort;
+                            else if (!a.use_pump && __hip_atomic_load(a.host_abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM)) why = kGpuSawAbort;
                             else if (wall_clock64() - t0 > a.timeout_ticks) why = kGpuTimeout;
                             if (why) {
                                 stop = 1;
@@ -171,7 +180,7 @@ __device__ void run_direction(const SwapArgs &a) {
                             }
                             if (stop) break;
                         }
-                        __builtin_amdgcn_s_sleep(32);
+                        if (a.use_pump) __builtin_amdgcn_s_sleep(4); else __builtin_amdgcn_s_sleep(32);
                     }
                     stall += wall_clock64() - t0;
                 }
@@ -213,12 +222,51 @@ __device__ void run_direction(const SwapArgs &a) {
                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
         }
     }
-    if (tid == 0 && stall)
-        __hip_atomic_fetch_add(D.stall_ticks, stall, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid == 0) {
+        if (stall) __hip_atomic_fetch_add(D.stall_ticks, stall, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_fetch_add(D.exited, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // on every exit path
+    }
 }
 
+// Credit pump: one wave per direction copies the host-written flags of that direction from
+// pinned memory into the device-memory mirror, over and over, and relays the host's abort word.
+// It leaves when every worker workgroup of its direction has left; workers always leave (their
+// waits are bounded), so the pump does too.
+__device__ void run_pump(const SwapArgs &a, int dir) {
+    const DevDir &D = a.d[dir];
+    if (D.wgs == 0) return;
+    const uint32_t lane = threadIdx.x & 63u;
+    for (;;) {
+        for (uint32_t base = 0; base < D.n_slots; base += 64) {
+            const uint32_t s = base + lane;
+            if (s < D.n_slots) {
+                const uint64_t v = __hip_atomic_load(D.wait_flags + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                __hip_atomic_store(D.mirror + s, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        if (__hip_atomic_load(a.host_abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) &&
+            !__hip_atomic_load(a.dev_abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) && lane == 0) {
+            __hip_atomic_store(a.dev_abort, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(a.gpu_status, (uint32_t)kGpuSawAbort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+        if (__hip_atomic_load(D.exited, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= D.wgs) break;
+        __builtin_amdgcn_s_sleep(16);
+    }
+}
+
+// Block 0 is the credit pump (first to be dispatched, so it is resident before any worker can
+// wait on it); blocks 1..gather are gather workers, the rest scatter workers.
 __global__ void __launch_bounds__(kWgThreads) nixie_swap_kernel(SwapArgs a) {
-    if (blockIdx.x < a.d[0].wgs) run_direction<0>(a);
+    uint32_t b = blockIdx.x;
+    if (a.use_pump) {
+        if (b == 0) {
+            const uint32_t wave = threadIdx.x >> 6;
+            if (wave < 2) run_pump(a, (int)wave);
+            return;
+        }
+        b -= 1;
+    }
+    if (b < a.d[0].wgs) run_direction<0>(a);
     else run_direction<1>(a);
 }
 
@@ -288,8 +336,8 @@ __global__ void __launch_bounds__(256) nixie_copy16_kernel(const u32x4 *__restri
 }  // namespace
 
 int nixie_launch_swap(const SwapArgs &a, void *stream) {
-    const uint32_t grid = a.d[0].wgs + a.d[1].wgs;
-    if (grid == 0) return (int)hipSuccess;
+    if (a.d[0].wgs + a.d[1].wgs == 0) return (int)hipSuccess;
+    const uint32_t grid = a.d[0].wgs + a.d[1].wgs + (a.use_pump ? 1u : 0u);
     nixie_swap_kernel<<<grid, kWgThreads, 0, (hipStream_t)stream>>>(a);
     return (int)hipGetLastError();
 }

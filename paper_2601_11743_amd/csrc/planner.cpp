@@ -173,7 +173,8 @@ void fill_info(const Layout &L, nixie_plan_info_t *info) {
     info->bytes_out = L.dir[0].bytes;
     info->bytes_in = L.dir[1].bytes;
     info->pinned_ring_bytes = (uint64_t)(L.dir[0].slots + L.dir[1].slots) * L.slot_bytes;
-    info->pinned_ctrl_bytes = ((uint64_t)(L.dir[0].slots + L.dir[1].slots) * 2 + 2) * kFlagStride * 8;
+    info->pinned_ctrl_bytes = (wait_flag_words(L.dir[0].slots) + wait_flag_words(L.dir[1].slots) +
+                               ((uint64_t)(L.dir[0].slots + L.dir[1].slots) + 2) * kFlagStride) * 8;
     // Work unit = 64 KiB of a slot: small enough that all workgroups of a direction share the one
     // or two oldest chunks (a chunk is published when its slowest unit is done, so units of one
     // chunk should finish close together), large enough to hide the ticket and the flag poll.

@@ -66,7 +66,7 @@ struct nixie_plan {
     DevSeg *segs_d[2] = {nullptr, nullptr};
     DevChunk *chunks_d[2] = {nullptr, nullptr};
     uint32_t *counters_d = nullptr;
-    uint64_t n_counters = 0;
+    uint64_t n_counters = 0, mirror_off[2] = {0, 0}, arrive_off = 0;
     HashDesc *hdesc_d[2] = {nullptr, nullptr};
     uint64_t htiles[2] = {0, 0};
     uint64_t *hashes_d = nullptr;
@@ -153,7 +153,7 @@ void run_drain(nixie_plan_t *p) {
             _mm_sfence();
         }
         if (flags & NIXIE_DIAG_STALL_DRAIN) continue;   // credit withheld on purpose
-        store_rel(p->wait_h[0] + slot * kFlagStride, round + 1);
+        store_rel(p->wait_h[0] + slot, round + 1);
     }
     note_end(p, 0);
 }
@@ -179,7 +179,7 @@ void run_fill(nixie_plan_t *p, uint32_t idx) {
             }
             _mm_sfence();
         }
-        store_rel(p->wait_h[1] + slot * kFlagStride, round + 1);
+        store_rel(p->wait_h[1] + slot, round + 1);
     }
     if (idx != 0) return;
     // "B ready": every slot has been scattered for its last round
@@ -266,14 +266,14 @@ int create_plan(nixie_plan_t *p) {
         std::memset(p->ctrl_h, 0, p->ctrl_bytes);
     }
     uint64_t *c = p->ctrl_h;
-    p->wait_h[0] = c;                                   c += (size_t)L.dir[0].slots * kFlagStride;
+    p->wait_h[0] = c;                                   c += wait_flag_words(L.dir[0].slots);
+    p->wait_h[1] = c;                                   c += wait_flag_words(L.dir[1].slots);
     p->post_h[0] = c;                                   c += (size_t)L.dir[0].slots * kFlagStride;
-    p->wait_h[1] = c;                                   c += (size_t)L.dir[1].slots * kFlagStride;
     p->post_h[1] = c;                                   c += (size_t)L.dir[1].slots * kFlagStride;
     p->abort_h = (uint32_t *)c;                         c += kFlagStride;
     p->status_h = (uint32_t *)c;                        c += kFlagStride;
-    if ((size_t)(c - p->ctrl_h) * 8 != p->ctrl_bytes || ((uint64_t)n_slots * 2 + 2) * kFlagStride * 8 != p->ctrl_bytes)
-        return NIXIE_EINVAL;
+    if ((size_t)(c - p->ctrl_h) * 8 != p->ctrl_bytes) return NIXIE_EINVAL;
+    (void)n_slots;
 
     // descriptors
     uint64_t n_arrive = 0;
@@ -303,8 +303,12 @@ int create_plan(nixie_plan_t *p) {
         rc = upload(hd.data(), hd.size() * sizeof(HashDesc), (void **)&p->hdesc_d[x]);
         if (rc) return rc;
     }
-    // counters: [0] ticket out, [1] ticket in, [2] abort, [3] pad, [4,5] stall out, [6,7] stall in, then arrive[]
-    p->n_counters = 8 + n_arrive;
+    // counters (u32 units): [0] ticket out, [1] ticket in, [2] abort, [3] pad, [4,5] stall out, [6,7] stall in,
+    // [8] exited out, [9] exited in, [10..15] pad, then the two credit mirrors (u64 per slot), then arrive[]
+    p->mirror_off[0] = 16;
+    p->mirror_off[1] = p->mirror_off[0] + 2 * wait_flag_words(L.dir[0].slots);
+    p->arrive_off = p->mirror_off[1] + 2 * wait_flag_words(L.dir[1].slots);
+    p->n_counters = p->arrive_off + n_arrive;
     {
         hipError_t e = hipMalloc((void **)&p->counters_d, p->n_counters * sizeof(uint32_t));
         if (e != hipSuccess) { t_last_hip_error = (int)e; return NIXIE_ENOMEM; }
@@ -334,7 +338,7 @@ int run_pass(nixie_plan_t *p, uint32_t mask, hipStream_t stream, nixie_stats_t *
     std::atomic_thread_fence(std::memory_order_seq_cst);
 
     SwapArgs a{};
-    uint64_t arrive_off = 8;
+    uint64_t arrive_off = p->arrive_off;
     for (int x = 0; x < 2; x++) {
         const DirLayout &D = L.dir[x];
         DevDir &d = a.d[x];
@@ -346,6 +350,8 @@ int run_pass(nixie_plan_t *p, uint32_t mask, hipStream_t stream, nixie_stats_t *
         d.wait_flags = p->ctrl_d + wait_off;
         d.post_flags = p->ctrl_d + post_off;
         d.ticket = p->counters_d + x;
+        d.exited = p->counters_d + 8 + x;
+        d.mirror = (uint64_t *)(p->counters_d + p->mirror_off[x]);
         d.arrive = p->counters_d + arrive_off;
         d.stall_ticks = (uint64_t *)(p->counters_d + 4 + 2 * x);
         d.n_chunks = on ? (uint32_t)D.chunks.size() : 0;
@@ -360,6 +366,7 @@ int run_pass(nixie_plan_t *p, uint32_t mask, hipStream_t stream, nixie_stats_t *
     a.gpu_status = (uint32_t *)(p->ctrl_d + (size_t)((uint64_t *)p->status_h - p->ctrl_h));
     a.dev_abort = p->counters_d + 2;
     a.timeout_ticks = p->timeout_ns / 10;   // wall clock runs at 100 MHz
+    a.use_pump = (L.opts.flags & NIXIE_CREDIT_PUMP) ? 1u : 0u;
 
     int e = nixie_launch_zero32(p->counters_d, p->n_counters, stream);
     if (e) { t_last_hip_error = e; return NIXIE_EHIP; }

@@ -105,6 +105,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-link-peak", action="store_true")
     ap.add_argument("--cpu-sample-gib", type=float, default=4.0)
+    ap.add_argument("--ring-sweep", action="store_true",
+                    help="config 5 protocol: for every ring size of the config, 10 back-to-back ping-pong "
+                         "switches A<->B; adds a 'ring_sweep' list to the JSON line")
     ap.add_argument("--quiet", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -169,6 +172,25 @@ def main() -> int:
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_begin
 
+    sweep = None
+    if args.ring_sweep:
+        sweep = []
+        for r in cf["ring_bytes"]:
+            fwd, back = nx.Plan(A.rows(), B.rows(), r, opts), nx.Plan(B.rows(), A.rows(), r, opts)
+            fwd.switch(); back.switch()                  # warm-up round trip
+            sts = []
+            for t in range(10):
+                sts.append((fwd if t % 2 == 0 else back).switch())
+            back.verify(h_in, h_out)                     # 10 switches end with A back in HBM, B in pageable memory
+            pi = fwd.info()
+            msl = sorted(x["ns_total"] / 1e6 for x in sts)
+            sweep.append({"ring_mib": r >> 20, "slot_kib": pi["slot_bytes"] >> 10,
+                          "pinned_bytes": pi["pinned_ring_bytes"] + pi["pinned_ctrl_bytes"],
+                          "latency_ms": {"min": round(msl[0], 2), "median": round(msl[5], 2), "max": round(msl[-1], 2)},
+                          "bidir_GBps": round((pi["bytes_out"] + pi["bytes_in"]) / msl[5] / 1e6, 2)})
+            fwd.close(); back.close()
+            log("[bench] ring sweep:", sweep[-1])
+
     rep = plan.verify(h_out, h_in)      # per-allocation hashes on the side that now holds the data
     diag = bool(args.flags & nx.DIAG_RING_ONLY)
     arenas_ok = None if diag else bool(A.arenas_equal() and B.arenas_equal())
@@ -227,6 +249,8 @@ def main() -> int:
                    "scatter_stall_ms_sum": round(med(sorted(s["scatter_stall_ticks"] for s in stats)) / 1e5, 2)},
         "roofline": roof,
     }
+    if sweep is not None:
+        res["ring_sweep"] = sweep
     del A, B
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(cf, int(args.cpu_sample_gib * 2**30))

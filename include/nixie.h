@@ -73,21 +73,19 @@ enum nixie_flags {
                                          memory, so destinations on the host side are NOT written */
     NIXIE_DIAG_STALL_DRAIN = 1u << 3, /* failure-path test: drain threads never return credits, so the switch must
                                          end with NIXIE_ETIMEOUT after timeout_ms */
-    NIXIE_HOST_PLAIN_MEMCPY = 1u << 4,/* host threads use libc memcpy instead of streaming stores */
-    NIXIE_CREDIT_PUMP = 1u << 5       /* one extra wave per direction mirrors the host-written credits into device
-                                         memory and workers poll the mirror instead of pinned memory */
+    NIXIE_HOST_PLAIN_MEMCPY = 1u << 4 /* host threads use libc memcpy instead of streaming stores */
 };
 
 /* Every field 0 = library default. */
 typedef struct {
     uint64_t slot_bytes;     /* ring slot size; multiple of 4096, <= 1 GiB.  Default 2 MiB, halved until each
-                                active direction has at least 4 slots (never below 64 KiB)                  */
+                                active direction has about 128 slots (never below 64 KiB)                  */
     uint32_t out_slots;      /* slots reserved for the outgoing direction (the evicted application's
                                 streaming window); default half, or all when the other table is empty      */
     uint32_t order;          /* enum nixie_order                                                            */
     uint32_t gather_wgs;     /* workgroups copying HBM -> ring                                              */
     uint32_t scatter_wgs;    /* workgroups copying ring -> HBM                                              */
-    uint32_t team;           /* workgroups that share one chunk; default one per 64 KiB of slot, at most 64   */
+    uint32_t team;           /* workgroups that share one chunk; default one per 16-64 KiB of slot, at most 256 */
     uint32_t drain_threads;  /* host threads moving ring -> pageable                                        */
     uint32_t fill_threads;   /* host threads moving pageable -> ring                                        */
     uint32_t timeout_ms;     /* bound on any single credit wait, host or GPU side; default 30000            */

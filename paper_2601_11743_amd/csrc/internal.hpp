@@ -51,14 +51,15 @@ enum : uint32_t { kGpuOk = 0, kGpuSawAbort = 1, kGpuTimeout = 2 };
 struct DevDir {
     const DevSeg *segs;
     const DevChunk *chunks;
-    uint8_t *ring;          // device-visible address of this direction's first slot
-    const uint64_t *wait_flags;  // host-written, pinned, packed: out: free[s]  in: ready[s]
-    uint64_t *post_flags;   // GPU-written,  pinned, one line each: out: ready[s] in: free[s]
-    uint64_t *mirror;       // device memory: copy of wait_flags kept fresh by the pump wave
-    uint32_t *ticket;       // device memory, one counter
-    uint32_t *exited;       // device memory, workgroups of this direction that have left
-    uint32_t *arrive;       // device memory, one counter per chunk
-    uint64_t *stall_ticks;  // device memory, summed wait time
+    uint8_t *ring;               // device-visible address of this direction's first slot
+    const uint64_t *host_flags;  // host-written, pinned, packed: out: released[s]  in: filled[s]
+    uint64_t *post_flags;        // GPU-written,  pinned, one line each: out: ready[s]  in: freed[s]
+    uint64_t *seen;              // device memory, pump only: last value of host_flags[s] acted on
+    uint32_t *chunk_slot;        // device memory, per chunk: 0 = no slot yet, else slot + 1
+    uint32_t *ticket;            // device memory, one counter
+    uint32_t *exited;            // device memory, workgroups of this direction that have left
+    uint32_t *arrive;            // device memory, one counter per chunk
+    uint64_t *stall_ticks;       // device memory, summed wait time
     uint32_t n_chunks, n_slots, team, wgs;
 };
 
@@ -69,7 +70,6 @@ struct SwapArgs {
     uint32_t *gpu_status;        // pinned, GPU-written
     uint32_t *dev_abort;         // device memory
     uint64_t timeout_ticks;      // 100 MHz wall clock
-    uint32_t use_pump;           // 1: workers read credits from the device mirror kept by the pump wave
 };
 
 struct HashDesc { uint64_t ptr; uint64_t bytes; uint64_t first_tile; };

@@ -6,28 +6,30 @@
 // application A's data moves out, so both directions of the full-duplex host link carry
 // payload at once ("Existing Approach #3" explains why one direction at a time wastes half the
 // link).  The paper issues the device leg as asynchronous 2 MB block copies; here one kernel
-// drives both directions itself: workgroups with blockIdx below d[0].wgs gather outgoing
-// chunks from HBM into pinned ring slots, the rest scatter incoming chunks from ring slots
-// into HBM, 16 bytes per lane, each wave instruction moving 1 KiB of contiguous bytes.
+// drives both directions itself: gather workgroups copy outgoing chunks from HBM into pinned
+// ring slots, scatter workgroups copy incoming chunks from ring slots into HBM, 16 bytes per
+// lane, each wave instruction moving 1 KiB of contiguous bytes.
 //
-// Slot credits.  Slot s of a direction carries chunks s, s+n, s+2n, ... (round r = k / n).
-//   producer of round r waits   free[s]  >= r      (r = 0 needs no wait)
-//   consumer of round r waits   ready[s] >= r + 1
-// Outgoing: the GPU produces, host drain threads consume.  Incoming: host fill threads
-// produce, the GPU consumes.  Workgroups sharing a chunk meet on a device-scope counter and the
-// last one stores the host-visible flag.  All flag traffic is relaxed system-scope atomics; the
-// ordering of payload against flags is built by hand (see the comments at the two places that
-// do it), because cache-maintaining fences at
-// device or system scope cost 5-15 % of the link rate here: payload goes into the ring with
-// write-through system-scope stores and comes out of it with system-scope loads.
+// Slots and flags.  A direction's slots are a free pool.  Every flag carries a chunk id, so a
+// change of value is the event:
+//   outgoing: GPU  ready[s]    = k + 1  "slot s holds chunk k"        -> a host drain thread copies it out
+//             host released[s] = k + 2  "chunk k has left slot s"     -> the pump gives s to the next chunk
+//   incoming: host filled[s]   = k + 1  "slot s holds chunk k"        -> the pump tells the scatter workers
+//             GPU  freed[s]    = k + 1  "chunk k has left slot s"     -> a host fill thread refills it
+// Workgroups sharing a chunk meet on a device-scope counter and the last one stores the
+// host-visible flag.  All flag traffic is relaxed system-scope atomics; the ordering of payload
+// against flags is built by hand (see the comments at the places that do it), because
+// cache-maintaining fences at device or system scope cost 5-15 % of the link rate here: payload
+// goes into the ring with write-through system-scope stores and comes out of it with
+// system-scope loads.
 //
-// Workers never poll host memory: one pump wave per direction mirrors the host-written flags into
-// device memory and relays the host's abort word.
+// Workers never poll host memory: one pump wave per direction reads the host-written flags and
+// publishes chunk -> slot assignments in device memory, and relays the host's abort word.
 //
-// Forward progress: work units are handed out in order by an atomic ticket, so the unit a
-// workgroup waits behind always belongs to a workgroup that is already running.  Every worker
-// wait is bounded (abort word in device memory, 100 MHz wall-clock limit) and the pump leaves
-// once all workers have, so the grid always drains.
+// Forward progress: work units are handed out in order by an atomic ticket and slots are given
+// to chunks in order, so the oldest unfinished chunk always has a slot and workgroups that are
+// already running.  Every worker wait is bounded (abort word in device memory, 100 MHz
+// wall-clock limit) and the pump leaves once all workers have, so the grid always drains.
 #include <hip/hip_runtime.h>
 
 #include "internal.hpp"
@@ -141,7 +143,7 @@ template <int DIR>
 __device__ void run_direction(const SwapArgs &a) {
     const DevDir &D = a.d[DIR];
     __shared__ uint32_t s_unit;
-    __shared__ uint32_t s_stop;
+    __shared__ uint32_t s_slot;   // slot + 1 of the unit's chunk, 0 = stop
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const uint32_t waves_per_wg = kWgThreads / 64;
     const uint32_t total_units = D.n_chunks * D.team;
@@ -149,50 +151,39 @@ __device__ void run_direction(const SwapArgs &a) {
 
     for (;;) {
         if (tid == 0) {
-            uint32_t stop = 0;
-            uint32_t u = __hip_atomic_fetch_add(D.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (u < total_units) {
-                if (__hip_atomic_load(a.dev_abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) stop = 1;
-                const uint32_t k = u / D.team;
-                const uint32_t slot = k % D.n_slots;
-                const uint64_t need = (uint64_t)(k / D.n_slots) + (DIR == 0 ? 0u : 1u);
-                // Credits are read from the device-memory mirror that the pump wave keeps fresh, not
-                // from host memory: a poll over the link queues behind the bulk reads and would cost
-                // every work unit tens of microseconds.
-                const uint64_t *credit = a.use_pump ? D.mirror + slot : D.wait_flags + slot;
-                auto peek = [&]() {
-                    return a.use_pump ? __hip_atomic_load(credit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                                      : __hip_atomic_load(credit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-                };
-                if (!stop && need > 0 && peek() < need) {
+            uint32_t cs = 0;
+            const uint32_t u = __hip_atomic_fetch_add(D.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (u < total_units && !__hip_atomic_load(a.dev_abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
+                // The pump wave writes chunk_slot[k] once chunk k has a slot: outgoing, a slot the
+                // host has released; incoming, the slot the host has filled with chunk k.  Workers
+                // only ever poll device memory: a poll over the link queues behind the bulk reads.
+                const uint32_t *where = D.chunk_slot + u / D.team;
+                cs = __hip_atomic_load(where, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (cs == 0) {
                     const uint64_t t0 = wall_clock64();
                     uint32_t it = 0;
-                    while (peek() < need) {
+                    while ((cs = __hip_atomic_load(where, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) == 0) {
                         if ((++it & 7u) == 0) {
-                            uint32_t why = 0;
-                            if (__hip_atomic_load(a.dev_abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) stop = 1;
-                            else if (!a.use_pump && __hip_atomic_load(a.host_abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM)) why = kGpuSawAbort;
-                            else if (wall_clock64() - t0 > a.timeout_ticks) why = kGpuTimeout;
-                            if (why) {
-                                stop = 1;
+                            if (__hip_atomic_load(a.dev_abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) break;
+                            if (wall_clock64() - t0 > a.timeout_ticks) {
                                 __hip_atomic_store(a.dev_abort, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                                __hip_atomic_store(a.gpu_status, why, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                                __hip_atomic_store(a.gpu_status, (uint32_t)kGpuTimeout, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                                break;
                             }
-                            if (stop) break;
                         }
-                        if (a.use_pump) __builtin_amdgcn_s_sleep(4); else __builtin_amdgcn_s_sleep(32);
+                        __builtin_amdgcn_s_sleep(4);
                     }
                     stall += wall_clock64() - t0;
                 }
             }
             s_unit = u;
-            s_stop = stop;
+            s_slot = cs;
         }
         __syncthreads();
         const uint32_t u = s_unit;
-        if (u >= total_units || s_stop) break;
+        if (u >= total_units || s_slot == 0) break;
         const uint32_t k = u / D.team, part = u % D.team;
-        const uint32_t slot = k % D.n_slots;
+        const uint32_t slot = s_slot - 1;
         const DevChunk ch = D.chunks[k];
         uint8_t *slot_base = D.ring + (size_t)slot * a.slot_bytes;
 
@@ -210,16 +201,16 @@ __device__ void run_direction(const SwapArgs &a) {
         // thread 0 only afterwards bumps the arrive counter and stores the flag.  The flag is a
         // later posted write on the same link and cannot pass the payload.
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();   // also: every thread has read s_unit before thread 0 overwrites it
+        __syncthreads();   // also: every thread has read s_unit / s_slot before thread 0 overwrites them
         if (tid == 0) {
             bool last = true;
             if (D.team > 1) {
                 uint32_t old = __hip_atomic_fetch_add(D.arrive + k, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 last = (old == D.team - 1);
             }
-            if (last)
-                __hip_atomic_store(D.post_flags + (size_t)slot * kFlagStride, (uint64_t)(k / D.n_slots) + 1u,
-                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            if (last)   // outgoing: "slot holds chunk k"; incoming: "chunk k has left the slot"
+                __hip_atomic_store(D.post_flags + (size_t)slot * kFlagStride, (uint64_t)k + 1u, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_SYSTEM);
         }
     }
     if (tid == 0) {
@@ -228,20 +219,43 @@ __device__ void run_direction(const SwapArgs &a) {
     }
 }
 
-// Credit pump: one wave per direction copies the host-written flags of that direction from
-// pinned memory into the device-memory mirror, over and over, and relays the host's abort word.
-// It leaves when every worker workgroup of its direction has left; workers always leave (their
-// waits are bounded), so the pump does too.
+// Slot pump: one wave per direction reads that direction's host-written flags from pinned
+// memory, over and over, and turns every change into a chunk -> slot assignment in device memory.
+//   outgoing: released[s] changed  -> slot s is free again -> it goes to the next chunk, in order
+//   incoming: filled[s] = k + 1    -> chunk k sits in slot s
+// Slots are therefore a free pool, not a fixed k mod n rotation: a chunk whose workgroups run on
+// a slow XCD (they differ by 2x on the way to the host link) holds only its own slot instead of
+// stalling every chunk behind it.  The pump also relays the host's abort word.  It leaves when
+// every worker workgroup of its direction has left; workers always leave (bounded waits).
 __device__ void run_pump(const SwapArgs &a, int dir) {
     const DevDir &D = a.d[dir];
     if (D.wgs == 0) return;
     const uint32_t lane = threadIdx.x & 63u;
+    uint32_t next = 0;   // outgoing: next chunk without a slot (wave-uniform)
     for (;;) {
         for (uint32_t base = 0; base < D.n_slots; base += 64) {
             const uint32_t s = base + lane;
+            uint64_t v = 0, old = 0;
             if (s < D.n_slots) {
-                const uint64_t v = __hip_atomic_load(D.wait_flags + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-                __hip_atomic_store(D.mirror + s, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                v = __hip_atomic_load(D.host_flags + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                old = D.seen[s];
+            }
+            const bool changed = v != old;
+            if (dir == 0) {
+                const uint64_t mask = __ballot(changed);
+                const uint32_t rank = __popcll(mask & ((1ull << lane) - 1ull));
+                if (changed) {
+                    const uint32_t k = next + rank;
+                    if (k < D.n_chunks)
+                        __hip_atomic_store(D.chunk_slot + k, s + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    D.seen[s] = v;
+                }
+                next += (uint32_t)__popcll(mask);
+            } else if (changed) {
+                const uint64_t k = v - 1;
+                if (k < D.n_chunks)
+                    __hip_atomic_store(D.chunk_slot + k, s + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                D.seen[s] = v;
             }
         }
         if (__hip_atomic_load(a.host_abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) &&
@@ -250,23 +264,19 @@ __device__ void run_pump(const SwapArgs &a, int dir) {
             __hip_atomic_store(a.gpu_status, (uint32_t)kGpuSawAbort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
         }
         if (__hip_atomic_load(D.exited, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= D.wgs) break;
-        __builtin_amdgcn_s_sleep(16);
+        __builtin_amdgcn_s_sleep(8);
     }
 }
 
-// Block 0 is the credit pump (first to be dispatched, so it is resident before any worker can
-// wait on it); blocks 1..gather are gather workers, the rest scatter workers.
+// Block 0 is the pump (first to be dispatched, so it is resident before any worker can wait on
+// it); blocks 1..gather_wgs are gather workers, the rest scatter workers.
 __global__ void __launch_bounds__(kWgThreads) nixie_swap_kernel(SwapArgs a) {
-    uint32_t b = blockIdx.x;
-    if (a.use_pump) {
-        if (b == 0) {
-            const uint32_t wave = threadIdx.x >> 6;
-            if (wave < 2) run_pump(a, (int)wave);
-            return;
-        }
-        b -= 1;
+    if (blockIdx.x == 0) {
+        const uint32_t wave = threadIdx.x >> 6;
+        if (wave < 2) run_pump(a, (int)wave);
+        return;
     }
-    if (b < a.d[0].wgs) run_direction<0>(a);
+    if (blockIdx.x - 1 < a.d[0].wgs) run_direction<0>(a);
     else run_direction<1>(a);
 }
 
@@ -337,7 +347,7 @@ __global__ void __launch_bounds__(256) nixie_copy16_kernel(const u32x4 *__restri
 
 int nixie_launch_swap(const SwapArgs &a, void *stream) {
     if (a.d[0].wgs + a.d[1].wgs == 0) return (int)hipSuccess;
-    const uint32_t grid = a.d[0].wgs + a.d[1].wgs + (a.use_pump ? 1u : 0u);
+    const uint32_t grid = a.d[0].wgs + a.d[1].wgs + 1;   // + the pump
     nixie_swap_kernel<<<grid, kWgThreads, 0, (hipStream_t)stream>>>(a);
     return (int)hipGetLastError();
 }

@@ -124,8 +124,12 @@ int build_layout(const nixie_table_t *out_table, const nixie_table_t *in_table, 
     const int active = (tot[0] > 0) + (tot[1] > 0);
     uint64_t S = L.opts.slot_bytes;
     if (S == 0) {
+        // About 128 slots per active direction, between 64 KiB and 2 MiB.  Slots are a free pool,
+        // so what counts is how finely the ring is recycled: on a 64 MiB ring 2 MiB slots lose
+        // 15 % against 256 KiB slots, on a 16 MiB ring 256 KiB slots lose 20 % against 64 KiB ones,
+        // while beyond ~128 slots per direction nothing more is gained.
         S = kDefaultSlot;
-        while (S > kMinAutoSlot && ring_bytes / S < 4ull * (uint64_t)std::max(active, 1)) S >>= 1;
+        while (S > kMinAutoSlot && ring_bytes / S < 128ull * (uint64_t)std::max(active, 1)) S >>= 1;
     } else if (S % 4096 != 0 || S > kMaxSlot) {
         return NIXIE_EINVAL;
     }
@@ -149,7 +153,7 @@ int build_layout(const nixie_table_t *out_table, const nixie_table_t *in_table, 
     L.dir[1].slots = (uint32_t)(tot[1] ? n_slots - n_out : 0);
     cut(L.table[0], L.opts.order, S, L.dir[0]);
     cut(L.table[1], L.opts.order, S, L.dir[1]);
-    if (L.dir[0].chunks.size() > 0xFFFFFFF0ull / 64 || L.dir[1].chunks.size() > 0xFFFFFFF0ull / 64 ||
+    if (L.dir[0].chunks.size() > 0xFFFFFFF0ull / 256 || L.dir[1].chunks.size() > 0xFFFFFFF0ull / 256 ||
         L.dir[0].segs.size() > 0xFFFFFFF0ull || L.dir[1].segs.size() > 0xFFFFFFF0ull)
         return NIXIE_EINVAL;
     return NIXIE_OK;
@@ -175,16 +179,22 @@ void fill_info(const Layout &L, nixie_plan_info_t *info) {
     info->pinned_ring_bytes = (uint64_t)(L.dir[0].slots + L.dir[1].slots) * L.slot_bytes;
     info->pinned_ctrl_bytes = (wait_flag_words(L.dir[0].slots) + wait_flag_words(L.dir[1].slots) +
                                ((uint64_t)(L.dir[0].slots + L.dir[1].slots) + 2) * kFlagStride) * 8;
-    // Work unit = 64 KiB of a slot: small enough that all workgroups of a direction share the one
-    // or two oldest chunks (a chunk is published when its slowest unit is done, so units of one
-    // chunk should finish close together), large enough to hide the ticket and the flag poll.
-    uint32_t team = L.opts.team ? L.opts.team
-                                : (uint32_t)std::min<uint64_t>(64, std::max<uint64_t>(1, L.slot_bytes / (64u << 10)));
-    team = std::min(team, 64u);
     // Measured on MI355X with both directions active: write-through stores into the ring need
     // about twice the workgroups that the reads out of it need; beyond 128 + 64 the surplus
-    // only waits on credits.
+    // only waits for slots.
     uint32_t wgs[2] = {L.opts.gather_wgs ? L.opts.gather_wgs : 128u, L.opts.scatter_wgs ? L.opts.scatter_wgs : 64u};
+    // Work unit: at most 64 KiB of a slot, so that all workgroups of a direction share the one or
+    // two oldest chunks (a chunk is published when its slowest unit is done), and small enough
+    // that the units in flight (one per workgroup) occupy no more than a quarter of the
+    // direction's share of the ring -- the rest is what the host threads drain or fill meanwhile.
+    uint32_t team = L.opts.team;
+    if (team == 0) {
+        const uint32_t max_slots = std::max(1u, std::max(L.dir[0].slots, L.dir[1].slots));
+        uint64_t unit = 64u << 10;
+        while (unit > (16u << 10) && unit * 4 * std::max(wgs[0], wgs[1]) > (uint64_t)max_slots * L.slot_bytes) unit >>= 1;
+        team = (uint32_t)std::max<uint64_t>(1, L.slot_bytes / unit);
+    }
+    team = std::min(team, 256u);
     uint32_t thr[2] = {L.opts.drain_threads ? L.opts.drain_threads : 4u, L.opts.fill_threads ? L.opts.fill_threads : 4u};
     for (int x = 0; x < 2; x++) {
         if (L.dir[x].chunks.empty()) { wgs[x] = 0; thr[x] = 0; continue; }

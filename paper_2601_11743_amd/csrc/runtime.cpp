@@ -66,7 +66,7 @@ struct nixie_plan {
     DevSeg *segs_d[2] = {nullptr, nullptr};
     DevChunk *chunks_d[2] = {nullptr, nullptr};
     uint32_t *counters_d = nullptr;
-    uint64_t n_counters = 0, mirror_off[2] = {0, 0}, arrive_off = 0;
+    uint64_t n_counters = 0, seen_off[2] = {0, 0}, cslot_off[2] = {0, 0}, arrive_off[2] = {0, 0};
     HashDesc *hdesc_d[2] = {nullptr, nullptr};
     uint64_t htiles[2] = {0, 0};
     uint64_t *hashes_d = nullptr;
@@ -85,6 +85,7 @@ struct nixie_plan {
     uint32_t pass_mask = 0;
     uint64_t timeout_ns = 0;
     std::atomic<uint64_t> next_chunk[2];
+    std::atomic<uint64_t> done_chunks[2];
     std::atomic<int> error{0};
     std::atomic<uint32_t> abort_local{0};
     std::atomic<uint64_t> wait_ns[2];
@@ -100,94 +101,119 @@ void raise_abort(nixie_plan_t *p, int err) {
     __atomic_store_n(p->abort_h, 1u, __ATOMIC_RELEASE);   // the kernel polls this word
 }
 
-// Spin until *flag >= need.  False if the switch was aborted or the bound expired.
-bool wait_flag(nixie_plan_t *p, const uint64_t *flag, uint64_t need, int dir) {
-    if (load_acq(flag) >= need) return true;
-    const uint64_t t0 = now_ns();
+// Idle bookkeeping of a host thread that scans its slots: aborts the switch when nothing has
+// moved for longer than the bound, or when the kernel reported that it gave up.
+struct IdleWatch {
+    nixie_plan_t *p;
+    int dir;
+    uint64_t idle_since = 0;
     uint32_t spins = 0;
-    bool ok = true;
-    while (load_acq(flag) < need) {
+    // call after a scan that made no progress; false = stop
+    bool idle() {
         _mm_pause();
-        if ((++spins & 255u) == 0) {
-            if (p->abort_local.load(std::memory_order_acquire)) { ok = false; break; }
-            if (__atomic_load_n(p->status_h, __ATOMIC_ACQUIRE) != kGpuOk) {   // the kernel gave up
-                raise_abort(p, NIXIE_ETIMEOUT);
-                ok = false;
-                break;
-            }
-            if (now_ns() - t0 > p->timeout_ns) {
-                raise_abort(p, NIXIE_ETIMEOUT);
-                ok = false;
-                break;
-            }
+        if (idle_since == 0) idle_since = now_ns();
+        if ((++spins & 63u) != 0) return true;
+        if (p->abort_local.load(std::memory_order_acquire)) return false;
+        if (__atomic_load_n(p->status_h, __ATOMIC_ACQUIRE) != kGpuOk || now_ns() - idle_since > p->timeout_ns) {
+            raise_abort(p, NIXIE_ETIMEOUT);
+            return false;
         }
+        return true;
     }
-    p->wait_ns[dir].fetch_add(now_ns() - t0, std::memory_order_relaxed);
-    return ok;
-}
+    void progressed() {
+        if (idle_since) p->wait_ns[dir].fetch_add(now_ns() - idle_since, std::memory_order_relaxed);
+        idle_since = 0;
+    }
+};
 
 void note_end(nixie_plan_t *p, int dir) {
     uint64_t t = now_ns(), cur = p->end_ns[dir].load(std::memory_order_relaxed);
     while (cur < t && !p->end_ns[dir].compare_exchange_weak(cur, t, std::memory_order_relaxed)) {}
 }
 
-// ring -> pageable.  Consumer of the outgoing direction.
-void run_drain(nixie_plan_t *p) {
+// ring -> pageable.  Consumer of the outgoing direction.  Thread idx owns slots idx, idx + T, ...
+// and drains whichever of them the GPU has marked ready (ready[s] = chunk id + 1), in any order.
+void run_drain(nixie_plan_t *p, uint32_t idx, uint32_t T) {
     const DirLayout &D = p->L.dir[0];
     const uint32_t flags = p->L.opts.flags;
     const uint64_t n = D.chunks.size(), S = p->L.slot_bytes;
     const bool plain = flags & NIXIE_HOST_PLAIN_MEMCPY;
-    for (;;) {
-        const uint64_t k = p->next_chunk[0].fetch_add(1, std::memory_order_relaxed);
-        if (k >= n) break;
-        const uint64_t slot = k % D.slots, round = k / D.slots;
-        if (!wait_flag(p, p->post_h[0] + slot * kFlagStride, round + 1, 0)) return;
-        if (!(flags & NIXIE_DIAG_RING_ONLY)) {
-            const nixie_chunk_t &c = D.chunks[k];
-            const uint8_t *src = p->ring_h + slot * S;
-            for (uint64_t q = c.seg_begin; q < c.seg_begin + c.seg_count; q++) {
-                const nixie_segment_t &s = D.segs[q];
-                if (plain) std::memcpy((void *)(uintptr_t)s.host_addr, src + s.slot_off, s.len);
-                else copy_stream((void *)(uintptr_t)s.host_addr, src + s.slot_off, s.len);
+    std::vector<uint64_t> last(D.slots, 0);
+    IdleWatch watch{p, 0};
+    while (p->done_chunks[0].load(std::memory_order_acquire) < n) {
+        bool moved = false;
+        for (uint64_t slot = idx; slot < D.slots; slot += T) {
+            const uint64_t v = load_acq(p->post_h[0] + slot * kFlagStride);
+            if (v == last[slot]) continue;
+            last[slot] = v;
+            const uint64_t k = v - 1;
+            if (k >= n) { raise_abort(p, NIXIE_EINVAL); return; }
+            if (!(flags & NIXIE_DIAG_RING_ONLY)) {
+                const nixie_chunk_t &c = D.chunks[k];
+                const uint8_t *src = p->ring_h + slot * S;
+                for (uint64_t q = c.seg_begin; q < c.seg_begin + c.seg_count; q++) {
+                    const nixie_segment_t &sg = D.segs[q];
+                    if (plain) std::memcpy((void *)(uintptr_t)sg.host_addr, src + sg.slot_off, sg.len);
+                    else copy_stream((void *)(uintptr_t)sg.host_addr, src + sg.slot_off, sg.len);
+                }
+                _mm_sfence();
             }
-            _mm_sfence();
+            if (!(flags & NIXIE_DIAG_STALL_DRAIN)) store_rel(p->wait_h[0] + slot, k + 2);   // released
+            p->done_chunks[0].fetch_add(1, std::memory_order_acq_rel);
+            moved = true;
         }
-        if (flags & NIXIE_DIAG_STALL_DRAIN) continue;   // credit withheld on purpose
-        store_rel(p->wait_h[0] + slot, round + 1);
+        if (moved) watch.progressed();
+        else if (!watch.idle()) return;
     }
+    watch.progressed();
     note_end(p, 0);
 }
 
-// pageable -> ring.  Producer of the incoming direction.
-void run_fill(nixie_plan_t *p, uint32_t idx) {
+// pageable -> ring.  Producer of the incoming direction.  Thread idx owns slots idx, idx + T, ...;
+// whenever one of them is free it claims the next chunk, loads it and publishes filled[s] = id + 1.
+// A slot is free again when the GPU has written freed[s] = id + 1 for the chunk it held.
+void run_fill(nixie_plan_t *p, uint32_t idx, uint32_t T) {
     const DirLayout &D = p->L.dir[1];
     const uint32_t flags = p->L.opts.flags;
     const uint64_t n = D.chunks.size(), S = p->L.slot_bytes;
     const bool plain = flags & NIXIE_HOST_PLAIN_MEMCPY;
+    std::vector<uint64_t> pending(D.slots, 0);
+    uint64_t outstanding = 0;
+    bool claiming = true;
+    IdleWatch watch{p, 1};
     for (;;) {
-        const uint64_t k = p->next_chunk[1].fetch_add(1, std::memory_order_relaxed);
-        if (k >= n) break;
-        const uint64_t slot = k % D.slots, round = k / D.slots;
-        if (round > 0 && !wait_flag(p, p->post_h[1] + slot * kFlagStride, round, 1)) return;
-        if (!(flags & NIXIE_DIAG_RING_ONLY)) {
-            const nixie_chunk_t &c = D.chunks[k];
-            uint8_t *dst = p->ring_h + ((uint64_t)p->L.dir[0].slots + slot) * S;
-            for (uint64_t q = c.seg_begin; q < c.seg_begin + c.seg_count; q++) {
-                const nixie_segment_t &s = D.segs[q];
-                if (plain) std::memcpy(dst + s.slot_off, (const void *)(uintptr_t)s.host_addr, s.len);
-                else copy_stream(dst + s.slot_off, (const void *)(uintptr_t)s.host_addr, s.len);
+        bool moved = false;
+        for (uint64_t slot = idx; slot < D.slots; slot += T) {
+            if (pending[slot]) {
+                if (load_acq(p->post_h[1] + slot * kFlagStride) != pending[slot]) continue;
+                pending[slot] = 0;
+                outstanding--;
+                moved = true;
             }
-            _mm_sfence();
+            if (!claiming) continue;
+            const uint64_t k = p->next_chunk[1].fetch_add(1, std::memory_order_relaxed);
+            if (k >= n) { claiming = false; continue; }
+            if (!(flags & NIXIE_DIAG_RING_ONLY)) {
+                const nixie_chunk_t &c = D.chunks[k];
+                uint8_t *dst = p->ring_h + ((uint64_t)p->L.dir[0].slots + slot) * S;
+                for (uint64_t q = c.seg_begin; q < c.seg_begin + c.seg_count; q++) {
+                    const nixie_segment_t &sg = D.segs[q];
+                    if (plain) std::memcpy(dst + sg.slot_off, (const void *)(uintptr_t)sg.host_addr, sg.len);
+                    else copy_stream(dst + sg.slot_off, (const void *)(uintptr_t)sg.host_addr, sg.len);
+                }
+                _mm_sfence();
+            }
+            store_rel(p->wait_h[1] + slot, k + 1);   // filled
+            pending[slot] = k + 1;
+            outstanding++;
+            moved = true;
         }
-        store_rel(p->wait_h[1] + slot, round + 1);
+        if (!claiming && outstanding == 0) break;
+        if (moved) watch.progressed();
+        else if (!watch.idle()) return;
     }
-    if (idx != 0) return;
-    // "B ready": every slot has been scattered for its last round
-    for (uint64_t s = 0; s < D.slots && s < n; s++) {
-        const uint64_t rounds = (n - s + D.slots - 1) / D.slots;
-        if (!wait_flag(p, p->post_h[1] + s * kFlagStride, rounds, 1)) return;
-    }
-    note_end(p, 1);
+    watch.progressed();
+    note_end(p, 1);   // this thread's last chunk has reached HBM; the latest such time is "B ready"
 }
 
 void worker_main(nixie_plan_t *p, int dir, uint32_t idx) {
@@ -200,8 +226,8 @@ void worker_main(nixie_plan_t *p, int dir, uint32_t idx) {
             seen = p->epoch;
         }
         if (p->pass_mask & (1u << dir)) {
-            if (dir == 0) run_drain(p);
-            else run_fill(p, idx);
+            if (dir == 0) run_drain(p, idx, p->info.drain_threads);
+            else run_fill(p, idx, p->info.fill_threads);
         }
         {
             std::lock_guard<std::mutex> lk(p->mu);
@@ -304,11 +330,14 @@ int create_plan(nixie_plan_t *p) {
         if (rc) return rc;
     }
     // counters (u32 units): [0] ticket out, [1] ticket in, [2] abort, [3] pad, [4,5] stall out, [6,7] stall in,
-    // [8] exited out, [9] exited in, [10..15] pad, then the two credit mirrors (u64 per slot), then arrive[]
-    p->mirror_off[0] = 16;
-    p->mirror_off[1] = p->mirror_off[0] + 2 * wait_flag_words(L.dir[0].slots);
-    p->arrive_off = p->mirror_off[1] + 2 * wait_flag_words(L.dir[1].slots);
-    p->n_counters = p->arrive_off + n_arrive;
+    // [8] exited out, [9] exited in, [10..15] pad, then per direction: seen[] (u64 per slot),
+    // chunk_slot[] and arrive[] (u32 per chunk).  All of it is cleared before every launch.
+    uint64_t off = 16;
+    for (int x = 0; x < 2; x++) { p->seen_off[x] = off; off += 2 * wait_flag_words(L.dir[x].slots); }
+    for (int x = 0; x < 2; x++) { p->cslot_off[x] = off; off += L.dir[x].chunks.size(); }
+    for (int x = 0; x < 2; x++) { p->arrive_off[x] = off; off += L.dir[x].chunks.size(); }
+    p->n_counters = off;
+    (void)n_arrive;
     {
         hipError_t e = hipMalloc((void **)&p->counters_d, p->n_counters * sizeof(uint32_t));
         if (e != hipSuccess) { t_last_hip_error = (int)e; return NIXIE_ENOMEM; }
@@ -333,12 +362,13 @@ int run_pass(nixie_plan_t *p, uint32_t mask, hipStream_t stream, nixie_stats_t *
     p->abort_local.store(0);
     for (int x = 0; x < 2; x++) {
         p->next_chunk[x].store(0);
+        p->done_chunks[x].store(0);
         p->wait_ns[x].store(0);
     }
+    for (uint32_t sl = 0; sl < L.dir[0].slots; sl++) p->wait_h[0][sl] = 1;   // every outgoing slot starts released
     std::atomic_thread_fence(std::memory_order_seq_cst);
 
     SwapArgs a{};
-    uint64_t arrive_off = p->arrive_off;
     for (int x = 0; x < 2; x++) {
         const DirLayout &D = L.dir[x];
         DevDir &d = a.d[x];
@@ -347,26 +377,25 @@ int run_pass(nixie_plan_t *p, uint32_t mask, hipStream_t stream, nixie_stats_t *
         d.chunks = p->chunks_d[x];
         d.ring = p->ring_d + (x ? (uint64_t)L.dir[0].slots * L.slot_bytes : 0);
         const size_t wait_off = (size_t)(p->wait_h[x] - p->ctrl_h), post_off = (size_t)(p->post_h[x] - p->ctrl_h);
-        d.wait_flags = p->ctrl_d + wait_off;
+        d.host_flags = p->ctrl_d + wait_off;
         d.post_flags = p->ctrl_d + post_off;
         d.ticket = p->counters_d + x;
         d.exited = p->counters_d + 8 + x;
-        d.mirror = (uint64_t *)(p->counters_d + p->mirror_off[x]);
-        d.arrive = p->counters_d + arrive_off;
+        d.seen = (uint64_t *)(p->counters_d + p->seen_off[x]);
+        d.chunk_slot = p->counters_d + p->cslot_off[x];
+        d.arrive = p->counters_d + p->arrive_off[x];
         d.stall_ticks = (uint64_t *)(p->counters_d + 4 + 2 * x);
         d.n_chunks = on ? (uint32_t)D.chunks.size() : 0;
         d.n_slots = D.slots ? D.slots : 1;
         d.team = x ? p->info.team_in : p->info.team_out;
         if (d.team == 0) d.team = 1;
         d.wgs = on ? (x ? p->info.scatter_wgs : p->info.gather_wgs) : 0;
-        arrive_off += D.chunks.size();
     }
     a.slot_bytes = L.slot_bytes;
     a.host_abort = (const uint32_t *)(p->ctrl_d + (size_t)((uint64_t *)p->abort_h - p->ctrl_h));
     a.gpu_status = (uint32_t *)(p->ctrl_d + (size_t)((uint64_t *)p->status_h - p->ctrl_h));
     a.dev_abort = p->counters_d + 2;
     a.timeout_ticks = p->timeout_ns / 10;   // wall clock runs at 100 MHz
-    a.use_pump = (L.opts.flags & NIXIE_CREDIT_PUMP) ? 1u : 0u;
 
     int e = nixie_launch_zero32(p->counters_d, p->n_counters, stream);
     if (e) { t_last_hip_error = e; return NIXIE_EHIP; }

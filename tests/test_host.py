@@ -132,23 +132,32 @@ def test_planner_packing_is_dense(nx):
 
 def test_planner_ring_split_and_defaults(nx):
     ra, rb = fake_rows([20 * MiB]), fake_rows([6 * MiB], dev_base=0x7F80_0000_0000, host_base=0x1800_0000_0000)
-    lay = nx.Layout(ra, rb, 128 * MiB)
+    lay = nx.Layout(ra, rb, 512 * MiB)
     i = lay.info()
-    assert i["slot_bytes"] == 2 * MiB and i["out_slots"] == 32 and i["in_slots"] == 32
-    assert i["team_out"] == 32 and i["gather_wgs"] == 128 and i["scatter_wgs"] == 64
+    assert i["slot_bytes"] == 2 * MiB and i["out_slots"] == 128 and i["in_slots"] == 128
+    assert i["team_out"] == 32 and i["gather_wgs"] == 128 and i["scatter_wgs"] == 64   # 64 KiB work units
+    lay = nx.Layout(ra, rb, 128 * MiB)                 # about 128 slots per direction
+    i = lay.info()
+    assert i["slot_bytes"] == 512 * KiB and i["out_slots"] == 128 and i["in_slots"] == 128 and i["team_out"] == 8
     lay = nx.Layout(ra, rb, 128 * MiB, nx.Opts(flags=nx.SPLIT_BY_BYTES))
     i = lay.info()
-    assert i["out_slots"] == round(64 * 20 / 26) and i["out_slots"] + i["in_slots"] == 64
+    assert i["out_slots"] == round(256 * 20 / 26) and i["out_slots"] + i["in_slots"] == 256
     lay = nx.Layout(ra, rb, 128 * MiB, nx.Opts(out_slots=10))
-    assert lay.info()["out_slots"] == 10 and lay.info()["in_slots"] == 54
+    assert lay.info()["out_slots"] == 10 and lay.info()["in_slots"] == 246
     lay = nx.Layout(ra, [], 128 * MiB)                 # pure evict: the whole ring serves one direction
-    assert lay.info()["out_slots"] == 64 and lay.info()["in_slots"] == 0 and lay.info()["scatter_wgs"] == 0
-    lay = nx.Layout(ra, rb, 16 * MiB)                  # small ring: slot halves until 4 per direction
-    assert lay.info()["slot_bytes"] == 2 * MiB and lay.info()["out_slots"] == 4
+    i = lay.info()
+    assert i["slot_bytes"] == 1 * MiB and i["out_slots"] == 128 and i["in_slots"] == 0 and i["scatter_wgs"] == 0
+    lay = nx.Layout(ra, rb, 16 * MiB)                  # small ring: smaller slots and smaller work units
+    i = lay.info()
+    assert i["slot_bytes"] == 64 * KiB and i["out_slots"] == 128
+    assert i["team_out"] == 4                          # 16 KiB units: 128 units in flight = a quarter of 8 MiB
     lay = nx.Layout(ra, rb, 4 * MiB)
-    assert lay.info()["slot_bytes"] == 512 * KiB
+    assert lay.info()["slot_bytes"] == 64 * KiB and lay.info()["out_slots"] == 32
     lay = nx.Layout(ra, rb, 256 * KiB)
     assert lay.info()["slot_bytes"] == 64 * KiB and lay.info()["out_slots"] == 2
+    lay = nx.Layout(ra, rb, 256 * MiB, nx.Opts(slot_bytes=4 * MiB))   # the headline geometry
+    i = lay.info()
+    assert i["out_slots"] == 32 and i["team_out"] == 64
 
 
 def test_planner_errors(nx):

@@ -151,14 +151,15 @@ def main() -> int:
                    drain_threads=args.drain_threads, fill_threads=args.fill_threads, flags=args.flags,
                    order=args.order)
     t0 = time.perf_counter()
-    plan = nx.Plan(A.rows(), B.rows(), ring, opts)
+    rows_a, rows_b = A.rows_np(), B.rows_np()
+    plan = nx.Plan(rows_a, rows_b, ring, opts)
     plan_ms = (time.perf_counter() - t0) * 1e3
     info = plan.info()
     log("[bench] plan:", info, f"nixie_plan {plan_ms:.1f} ms")
     h_out, h_in = plan.hash_tables()
 
     def step():
-        lay = nx.Layout(A.rows(), B.rows(), ring, opts)    # the chunk planner is part of every step
+        lay = nx.Layout(rows_a, rows_b, ring, opts)    # the chunk planner is part of every step
         lay.close()
         return plan.switch()
 
@@ -176,7 +177,7 @@ def main() -> int:
     if args.ring_sweep:
         sweep = []
         for r in cf["ring_bytes"]:
-            fwd, back = nx.Plan(A.rows(), B.rows(), r, opts), nx.Plan(B.rows(), A.rows(), r, opts)
+            fwd, back = nx.Plan(rows_a, rows_b, r, opts), nx.Plan(rows_b, rows_a, r, opts)
             fwd.switch(); back.switch()                  # warm-up round trip
             sts = []
             for t in range(10):

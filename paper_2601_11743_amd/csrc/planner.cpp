@@ -10,6 +10,7 @@
 #include <algorithm>
 #include <cstring>
 #include <numeric>
+#include <thread>
 
 #include "internal.hpp"
 
@@ -23,8 +24,14 @@ constexpr uint64_t kMaxSlot = 1ull << 30;
 
 struct Range { uint64_t lo, hi; };
 
-bool any_overlap(std::vector<Range> &r) {
-    std::sort(r.begin(), r.end(), [](const Range &a, const Range &b) { return a.lo < b.lo; });
+// r holds the ranges of the outgoing table in [0, mid) and of the incoming table in [mid, end).
+// Allocation tables usually come in address order, so try a linear merge before a full sort.
+bool any_overlap(std::vector<Range> &r, size_t mid) {
+    auto less = [](const Range &a, const Range &b) { return a.lo < b.lo; };
+    if (std::is_sorted(r.begin(), r.begin() + (ptrdiff_t)mid, less) && std::is_sorted(r.begin() + (ptrdiff_t)mid, r.end(), less))
+        std::inplace_merge(r.begin(), r.begin() + (ptrdiff_t)mid, r.end(), less);
+    else
+        std::sort(r.begin(), r.end(), less);
     for (size_t i = 1; i < r.size(); i++)
         if (r[i].lo < r[i - 1].hi) return true;
     return false;
@@ -71,6 +78,10 @@ void cut(const std::vector<nixie_alloc_t> &t, uint32_t order, uint64_t S, DirLay
     D.segs.clear();
     D.chunks.clear();
     D.bytes = 0;
+    uint64_t total = 0;
+    for (const auto &a : t) total += a.bytes;
+    D.segs.reserve(t.size() + total / S + 8);     // every allocation once, plus one cut per slot boundary
+    D.chunks.reserve(total / (S - 16) + 8);       // at most 15 padding bytes per segment start
     uint64_t fill = 0;
     bool open = false;
     for (uint64_t i : walk_order(t, order)) {
@@ -111,7 +122,11 @@ int build_layout(const nixie_table_t *out_table, const nixie_table_t *in_table, 
     // no aliasing: device ranges pairwise disjoint across both tables, host ranges likewise
     std::vector<Range> dev, host;
     uint64_t tot[2] = {0, 0};
-    for (int x = 0; x < 2; x++)
+    size_t mid = 0;
+    dev.reserve(L.table[0].size() + L.table[1].size());
+    host.reserve(L.table[0].size() + L.table[1].size());
+    for (int x = 0; x < 2; x++) {
+        if (x == 1) mid = dev.size();
         for (const auto &a : L.table[x]) {
             if (a.bytes == 0) continue;
             uint64_t d = (uint64_t)(uintptr_t)a.dev_ptr, h = (uint64_t)(uintptr_t)a.host_ptr;
@@ -119,7 +134,8 @@ int build_layout(const nixie_table_t *out_table, const nixie_table_t *in_table, 
             host.push_back({h, h + a.bytes});
             tot[x] += a.bytes;
         }
-    if (any_overlap(dev) || any_overlap(host)) return NIXIE_EOVERLAP;
+    }
+    if (any_overlap(dev, mid) || any_overlap(host, mid)) return NIXIE_EOVERLAP;
 
     const int active = (tot[0] > 0) + (tot[1] > 0);
     uint64_t S = L.opts.slot_bytes;
@@ -151,8 +167,14 @@ int build_layout(const nixie_table_t *out_table, const nixie_table_t *in_table, 
     L.slot_bytes = S;
     L.dir[0].slots = (uint32_t)n_out;
     L.dir[1].slots = (uint32_t)(tot[1] ? n_slots - n_out : 0);
-    cut(L.table[0], L.opts.order, S, L.dir[0]);
-    cut(L.table[1], L.opts.order, S, L.dir[1]);
+    if (L.table[0].size() + L.table[1].size() > 20000) {   // large tables: one direction per thread
+        std::thread other([&] { cut(L.table[1], L.opts.order, S, L.dir[1]); });
+        cut(L.table[0], L.opts.order, S, L.dir[0]);
+        other.join();
+    } else {
+        cut(L.table[0], L.opts.order, S, L.dir[0]);
+        cut(L.table[1], L.opts.order, S, L.dir[1]);
+    }
     if (L.dir[0].chunks.size() > 0xFFFFFFF0ull / 256 || L.dir[1].chunks.size() > 0xFFFFFFF0ull / 256 ||
         L.dir[0].segs.size() > 0xFFFFFFF0ull || L.dir[1].segs.size() > 0xFFFFFFF0ull)
         return NIXIE_EINVAL;

@@ -144,8 +144,16 @@ class Opts:
             setattr(self.c, k, v)
 
 
-def _table(allocs: Iterable[Sequence[int]] | None):
-    """allocs: iterable of (dev_ptr, host_ptr, bytes) integers."""
+def _table(allocs):
+    """allocs: iterable of (dev_ptr, host_ptr, bytes) integers, or a C-contiguous uint64 numpy
+    array of shape (n, 3) with the same columns (used as is, no copy)."""
+    if isinstance(allocs, np.ndarray):
+        a = np.ascontiguousarray(allocs, dtype=np.uint64)
+        if a.ndim != 2 or a.shape[1] != 3:
+            raise TypeError("allocation table array must have shape (n, 3)")
+        n = a.shape[0]
+        ptr = C.cast(a.ctypes.data, C.POINTER(_Alloc)) if n else C.cast(None, C.POINTER(_Alloc))
+        return _Table(ptr, n), a
     rows = list(allocs or [])
     arr = (_Alloc * max(1, len(rows)))()
     for i, (d, h, b) in enumerate(rows):

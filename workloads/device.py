@@ -72,6 +72,15 @@ class BigSet:
         bd, bh = self.dev.data_ptr(), self.host.ctypes.data
         return [(bd + o, bh + o, b) for o, b in zip(self.layout.offsets, self.sizes)]
 
+    def rows_np(self) -> np.ndarray:
+        """The allocation table as a (n, 3) uint64 array: device address, host address, bytes."""
+        offs = np.asarray(self.layout.offsets, dtype=np.uint64)
+        out = np.empty((len(self.sizes), 3), dtype=np.uint64)
+        out[:, 0] = np.uint64(self.dev.data_ptr()) + offs
+        out[:, 1] = np.uint64(self.host.ctypes.data) + offs
+        out[:, 2] = np.asarray(self.sizes, dtype=np.uint64)
+        return out
+
     def dev_view(self, i: int):
         o, b = self.layout.offsets[i], self.sizes[i]
         return self.dev[o:o + b]

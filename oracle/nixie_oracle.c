@@ -20,6 +20,11 @@
  * goes (every byte moved exactly once, nothing written outside an allocation,
  * staged bytes never above the ring size, ring empty at the end).
  *
+ * o_switch_staged with in_place = 1 is the in-place switch: the incoming
+ * allocations may reuse GPU memory of the outgoing ones, and a GPU byte is
+ * only overwritten after its old content has been staged out.  The direct
+ * definition covers it unchanged because it evicts everything first.
+ *
  * Pins: final state against numpy slicing (a library copy), per-byte copy
  * counts on tiny inputs, red zones checked by the caller, order independence
  * over seeds, planted faults that each check must catch.  The 64-bit hash
@@ -174,7 +179,7 @@ enum {
 enum {
     O_FAULT_NONE = 0, O_FAULT_DROP_CHUNK = 1, O_FAULT_SHORT_PIECE = 2,
     O_FAULT_SLOT_SHIFT = 3, O_FAULT_DOUBLE_COPY = 4, O_FAULT_OVERRUN = 5,
-    O_FAULT_WRONG_DIRECTION = 6
+    O_FAULT_WRONG_DIRECTION = 6, O_FAULT_IGNORE_ALIAS = 7
 };
 
 typedef struct {
@@ -183,6 +188,7 @@ typedef struct {
     int64_t *slot_chunk; uint64_t n_slots;   /* -1 = free, else staged chunk */
     uint8_t *ring;                           /* this direction's sub-ring   */
     uint8_t **stage_cnt, **dest_cnt;         /* per-byte copy counts or NULL */
+    uint8_t **gone;                          /* out only, in-place mode: byte has left the GPU */
     int to_host;                             /* 1 = out (dev->host)          */
     uint64_t done;
 } o_dir;
@@ -223,6 +229,9 @@ static void dir_free(o_dir *d)
 {
     if (d->stage_cnt)
         for (uint64_t i = 0; i < d->n; i++) { free(d->stage_cnt[i]); free(d->dest_cnt[i]); }
+    if (d->gone)
+        for (uint64_t i = 0; i < d->n; i++) free(d->gone[i]);
+    free(d->gone);
     free(d->stage_cnt); free(d->dest_cnt);
     free(d->order); free(d->slot_chunk);
     free(d->cut.pieces); free(d->cut.chunks);
@@ -249,6 +258,26 @@ static uint64_t pick_slot(const o_dir *d, int want_free, uint64_t *rng)
     return cand;
 }
 
+/* In-place switch (the incoming application reuses GPU memory the outgoing one gives up; paper,
+ * "Maintaining consistent virtual memory addresses" and the premise that both sets do not fit):
+ * a GPU byte may only be overwritten once its old content has been staged out.  True if every
+ * byte that chunk k of the incoming direction would write has already left the GPU. */
+static int scatter_allowed(const o_dir *in, const o_dir *out, uint64_t k)
+{
+    const o_chunk *ch = &in->cut.chunks[k];
+    for (uint64_t q = ch->first; q < ch->first + ch->count; q++) {
+        const o_piece *p = &in->cut.pieces[q];
+        uintptr_t a = (uintptr_t)in->t[p->alloc].dev + p->off, b = a + p->len;
+        for (uint64_t i = 0; i < out->n; i++) {
+            uintptr_t lo = (uintptr_t)out->t[i].dev, hi = lo + out->t[i].bytes;
+            uintptr_t x0 = a > lo ? a : lo, x1 = b < hi ? b : hi;
+            for (uintptr_t x = x0; x < x1; x++)
+                if (!out->gone[i][x - lo]) return 0;
+        }
+    }
+    return 1;
+}
+
 /*
  * One bidirectional switch through a ring of ring_bytes cut into slots of
  * slot_bytes; the first n_out_slots slots serve the outgoing direction (the
@@ -259,7 +288,7 @@ static uint64_t pick_slot(const o_dir *d, int want_free, uint64_t *rng)
 int o_switch_staged(const o_alloc *out, uint64_t n_out,
                     const o_alloc *in, uint64_t n_in,
                     uint64_t ring_bytes, uint64_t slot_bytes, uint64_t n_out_slots,
-                    int pack, uint64_t seed, int check_bytes, int fault,
+                    int pack, uint64_t seed, int check_bytes, int fault, int in_place,
                     o_report *rep)
 {
     o_report local;
@@ -287,6 +316,12 @@ int o_switch_staged(const o_alloc *out, uint64_t n_out,
                       ring + n_out_slots * slot_bytes, 0, check_bytes, &rng);
     rep->n_out_chunks = d[0].cut.n_chunks;
     rep->n_in_chunks = d[1].cut.n_chunks;
+    if (rc == O_OK && in_place) {
+        d[0].gone = (uint8_t **)calloc(n_out + 1, sizeof(uint8_t *));
+        if (!d[0].gone) rc = O_ENOMEM;
+        for (uint64_t i = 0; rc == O_OK && i < n_out; i++)
+            if (!(d[0].gone[i] = (uint8_t *)calloc(out[i].bytes + 1, 1))) rc = O_ENOMEM;
+    }
     uint64_t staged = 0;
     int fault_armed = fault;
 
@@ -294,9 +329,18 @@ int o_switch_staged(const o_alloc *out, uint64_t n_out,
         /* feasible steps: 0 stage-out (GPU->ring), 1 drain (ring->host),
          *                 2 fill (host->ring),     3 scatter (ring->GPU) */
         int feas[4], nf = 0;
+        int64_t ok_slot[4096];   /* staged incoming slots whose chunk may be scattered now */
+        uint64_t n_ok = 0;
         for (int x = 0; x < 2; x++) {
             if (d[x].next < d[x].cut.n_chunks && count_free(&d[x]) > 0) feas[nf++] = 2 * x;
-            if ((uint64_t)count_free(&d[x]) < d[x].n_slots) feas[nf++] = 2 * x + 1;
+            if (x == 0 || !in_place || fault == O_FAULT_IGNORE_ALIAS) {
+                if ((uint64_t)count_free(&d[x]) < d[x].n_slots) feas[nf++] = 2 * x + 1;
+            } else {
+                for (uint64_t s = 0; s < d[1].n_slots && n_ok < 4096; s++)
+                    if (d[1].slot_chunk[s] >= 0 && scatter_allowed(&d[1], &d[0], (uint64_t)d[1].slot_chunk[s]))
+                        ok_slot[n_ok++] = (int64_t)s;
+                if (n_ok) feas[nf++] = 3;
+            }
         }
         if (nf == 0) break;
         int step = feas[rng_next(&rng) % (uint64_t)nf];
@@ -317,6 +361,8 @@ int o_switch_staged(const o_alloc *out, uint64_t n_out,
                 memcpy(D->ring + s * slot_bytes + p->slot_off, src, p->len);
                 if (D->stage_cnt)
                     for (uint64_t b = 0; b < p->len; b++) D->stage_cnt[p->alloc][p->off + b]++;
+                if (D->gone)
+                    for (uint64_t b = 0; b < p->len; b++) D->gone[p->alloc][p->off + b] = 1;
             }
             if (fault_armed == O_FAULT_WRONG_DIRECTION) fault_armed = 0;
             D->slot_chunk[s] = (int64_t)k;
@@ -324,7 +370,7 @@ int o_switch_staged(const o_alloc *out, uint64_t n_out,
             if (staged > rep->hwm_staged_bytes) rep->hwm_staged_bytes = staged;
             if (staged > ring_bytes) { rc = O_EBUDGET; break; }
         } else {
-            uint64_t s = pick_slot(D, 0, &rng);
+            uint64_t s = n_ok && step == 3 ? (uint64_t)ok_slot[rng_next(&rng) % n_ok] : pick_slot(D, 0, &rng);
             uint64_t k = (uint64_t)D->slot_chunk[s];
             const o_chunk *ch = &D->cut.chunks[k];
             int drop = 0;

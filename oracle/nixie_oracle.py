@@ -43,7 +43,7 @@ class OracleError(RuntimeError):
 _CODES = {0: "OK", -1: "EINVAL", -2: "ENOMEM", -3: "ESLOT_BUSY", -4: "EBUDGET",
           -5: "ECOUNT", -6: "ERANGE", -7: "ELEFTOVER"}
 FAULTS = {"none": 0, "drop_chunk": 1, "short_piece": 2, "slot_shift": 3,
-          "double_copy": 4, "overrun": 5, "wrong_direction": 6}
+          "double_copy": 4, "overrun": 5, "wrong_direction": 6, "ignore_alias": 7}
 
 
 class _Alloc(C.Structure):
@@ -82,7 +82,7 @@ class Oracle:
         L.o_hash_table.restype = None
         L.o_switch_staged.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64,
                                       C.c_uint64, C.c_uint64, C.c_uint64, C.c_int,
-                                      C.c_uint64, C.c_int, C.c_int, C.c_void_p]
+                                      C.c_uint64, C.c_int, C.c_int, C.c_int, C.c_void_p]
         L.o_switch_staged.restype = C.c_int
         L.o_switch_staged_mt.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64,
                                          C.c_uint64, C.c_uint64, C.c_int, C.c_void_p]
@@ -101,7 +101,9 @@ class Oracle:
     # -- staged form with invariant checks --------------------------------
     def switch_staged(self, out_pairs, in_pairs, ring_bytes: int, slot_bytes: int,
                       n_out_slots: int | None = None, pack: bool = True, seed: int = 0,
-                      check_bytes: bool = False, fault: str = "none") -> dict:
+                      check_bytes: bool = False, fault: str = "none", in_place: bool = False) -> dict:
+        """in_place: incoming device ranges may overlap outgoing ones; a chunk is only scattered
+        once every GPU byte it overwrites has been staged out."""
         o, no = _table(out_pairs)
         i, ni = _table(in_pairs)
         if n_out_slots is None:
@@ -109,7 +111,7 @@ class Oracle:
         rep = _Report()
         rc = self._L.o_switch_staged(o, no, i, ni, ring_bytes, slot_bytes, n_out_slots,
                                      int(pack), seed & (2**64 - 1), int(check_bytes),
-                                     FAULTS[fault], C.byref(rep))
+                                     FAULTS[fault], int(in_place), C.byref(rep))
         d = {n: int(getattr(rep, n)) for n, _ in _Report._fields_}
         if rc != 0:
             raise OracleError(rc, d)

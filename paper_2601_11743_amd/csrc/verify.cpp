@@ -143,11 +143,14 @@ int nixie_link_peak(uint64_t bytes, int reps, nixie_link_peak_t *out) {
     if (!out || bytes < (1u << 20) || bytes % 16 || reps < 1) return NIXIE_EINVAL;
     std::memset(out, 0, sizeof(*out));
     void *d0 = nullptr, *d1 = nullptr, *h0 = nullptr, *h1 = nullptr;
-    hipStream_t s0 = nullptr, s1 = nullptr;
+    // The HIP runtime maps streams onto a few hardware queues; two copies that land on the same
+    // queue run one after the other.  Several streams are created and the "both at once" case
+    // is timed on every pair (first stream with each of the others), keeping the best.
+    constexpr int kStreams = 4;
+    hipStream_t st[kStreams] = {nullptr, nullptr, nullptr, nullptr};
     int rc = NIXIE_OK;
     auto cleanup = [&]() {
-        if (s0) (void)hipStreamDestroy(s0);
-        if (s1) (void)hipStreamDestroy(s1);
+        for (auto &x : st) if (x) (void)hipStreamDestroy(x);
         if (d0) (void)hipFree(d0);
         if (d1) (void)hipFree(d1);
         if (h0) (void)hipHostFree(h0);
@@ -162,30 +165,31 @@ int nixie_link_peak(uint64_t bytes, int reps, nixie_link_peak_t *out) {
     LP(hipMemset(d1, 2, bytes));
     std::memset(h0, 3, bytes);
     std::memset(h1, 4, bytes);
-    LP(hipStreamCreateWithFlags(&s0, hipStreamNonBlocking));
-    LP(hipStreamCreateWithFlags(&s1, hipStreamNonBlocking));
+    for (auto &x : st) LP(hipStreamCreateWithFlags(&x, hipStreamNonBlocking));
     LP(hipDeviceSynchronize());
     const uint32_t wgs = 128;
     // mode: bit0 = d2h active, bit1 = h2d active; engine 0 = SDMA, 1 = kernel
     for (int engine = 0; engine < 2; engine++)
         for (int mode = 1; mode <= 3; mode++) {
             double best = 1e30;
-            for (int r = 0; r < reps + 1; r++) {   // first repetition is a warm-up
-                LP(hipDeviceSynchronize());
-                const double t0 = now_s();
-                if (mode & 1) {
-                    if (engine == 0) LP(hipMemcpyAsync(h0, d0, bytes, hipMemcpyDeviceToHost, s0));
-                    else { int e = nixie_launch_copy16(d0, h0, bytes, wgs, s0); if (e) { set_last_hip_error(e); cleanup(); return NIXIE_EHIP; } }
+            for (int pair = 1; pair < (mode == 3 ? kStreams : 2); pair++)
+                for (int r = 0; r < reps + 1; r++) {   // first repetition is a warm-up
+                    hipStream_t s0 = st[0], s1 = st[pair];
+                    LP(hipDeviceSynchronize());
+                    const double t0 = now_s();
+                    if (mode & 1) {
+                        if (engine == 0) LP(hipMemcpyAsync(h0, d0, bytes, hipMemcpyDeviceToHost, s0));
+                        else { int e = nixie_launch_copy16(d0, h0, bytes, wgs, s0); if (e) { set_last_hip_error(e); cleanup(); return NIXIE_EHIP; } }
+                    }
+                    if (mode & 2) {
+                        if (engine == 0) LP(hipMemcpyAsync(d1, h1, bytes, hipMemcpyHostToDevice, s1));
+                        else { int e = nixie_launch_copy16(h1, d1, bytes, wgs, s1); if (e) { set_last_hip_error(e); cleanup(); return NIXIE_EHIP; } }
+                    }
+                    LP(hipStreamSynchronize(s0));
+                    LP(hipStreamSynchronize(s1));
+                    const double dt = now_s() - t0;
+                    if (r > 0 && dt < best) best = dt;
                 }
-                if (mode & 2) {
-                    if (engine == 0) LP(hipMemcpyAsync(d1, h1, bytes, hipMemcpyHostToDevice, s1));
-                    else { int e = nixie_launch_copy16(h1, d1, bytes, wgs, s1); if (e) { set_last_hip_error(e); cleanup(); return NIXIE_EHIP; } }
-                }
-                LP(hipStreamSynchronize(s0));
-                LP(hipStreamSynchronize(s1));
-                const double dt = now_s() - t0;
-                if (r > 0 && dt < best) best = dt;
-            }
             const double gbs = (double)bytes / best / 1e9;
             if (engine == 0) {
                 if (mode == 1) out->sdma_d2h = gbs;

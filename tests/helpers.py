@@ -68,3 +68,60 @@ class HostSet:
             if not (arena[mask] == RED).all():
                 bad = int(np.flatnonzero(mask & (arena != RED))[0])
                 raise AssertionError(f"red zone overwritten at arena byte {bad}")
+
+
+class AliasedPair:
+    """In-place switch inputs: application A (GPU resident) and application B (in pageable memory)
+    whose device ranges lie in ONE shared device arena, so B's allocations partly or wholly reuse
+    the GPU memory A gives up.  Host arenas are separate.  expected_dev() is the arena a correct
+    switch leaves: B's content written over the initial arena (numpy slicing, no swap code)."""
+
+    def __init__(self, sizes_a, sizes_b, seed: int, skew_a: int = 0, skew_b: int = 0, shift_b: int = 0,
+                 redzone: int = 256):
+        self.sizes_a, self.sizes_b, self.seed = list(sizes_a), list(sizes_b), seed
+        self.la = W.make_layout(self.sizes_a, redzone=redzone, skew=skew_a)
+        lb = W.make_layout(self.sizes_b, redzone=redzone, skew=skew_b)
+        self.lb = W.Layout([o + shift_b for o in lb.offsets], lb.sizes, lb.total + shift_b, redzone)
+        total = max(self.la.total, self.lb.total)
+        self.dev = aligned_full(total, RED)
+        W.fill_content(self.dev, self.la, seed)                 # A is resident
+        self.dev0 = self.dev.copy()
+        self.lha = W.make_layout(self.sizes_a, redzone=redzone)
+        self.lhb = W.make_layout(self.sizes_b, redzone=redzone)
+        self.host_a = aligned_full(self.lha.total, RED)
+        self.host_b = aligned_full(self.lhb.total, RED)
+        for o, b in zip(self.lha.offsets, self.sizes_a):
+            self.host_a[o:o + b] = POISON_HOST
+        W.fill_content(self.host_b, self.lhb, seed + 1)         # B waits in pageable memory
+
+    def pairs_a(self, dev=None):
+        dev = self.dev if dev is None else dev
+        return [(dev[od:od + b], self.host_a[oh:oh + b])
+                for od, oh, b in zip(self.la.offsets, self.lha.offsets, self.sizes_a)]
+
+    def pairs_b(self, dev=None):
+        dev = self.dev if dev is None else dev
+        return [(dev[od:od + b], self.host_b[oh:oh + b])
+                for od, oh, b in zip(self.lb.offsets, self.lhb.offsets, self.sizes_b)]
+
+    def expected_dev(self) -> np.ndarray:
+        e = self.dev0.copy()
+        for i, (o, b) in enumerate(zip(self.lb.offsets, self.sizes_b)):
+            e[o:o + b] = W.content_bytes(self.seed + 1, i, b)
+        return e
+
+    def expected_host_a(self) -> np.ndarray:
+        e = aligned_full(self.lha.total, RED)
+        for i, (o, b) in enumerate(zip(self.lha.offsets, self.sizes_a)):
+            e[o:o + b] = W.content_bytes(self.seed, i, b)
+        return e
+
+    def check(self, dev=None):
+        dev = self.dev if dev is None else dev
+        exp_h, exp_d = self.expected_host_a(), self.expected_dev()
+        if not np.array_equal(self.host_a, exp_h):
+            bad = int(np.flatnonzero(self.host_a != exp_h)[0])
+            raise AssertionError(f"evicted set differs first at host arena byte {bad}")
+        if not np.array_equal(dev, exp_d):
+            bad = int(np.flatnonzero(dev != exp_d)[0])
+            raise AssertionError(f"device arena differs first at byte {bad}")

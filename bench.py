@@ -105,6 +105,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-link-peak", action="store_true")
     ap.add_argument("--cpu-sample-gib", type=float, default=4.0)
+    ap.add_argument("--in-place", action="store_true",
+                    help="in-place switch: B is restored into the HBM that A is evicted from (one device arena); "
+                         "every step is a switch in the opposite direction of the one before")
     ap.add_argument("--ring-sweep", action="store_true",
                     help="config 5 protocol: for every ring size of the config, 10 back-to-back ping-pong "
                          "switches A<->B; adds a 'ring_sweep' list to the JSON line")
@@ -137,7 +140,10 @@ def main() -> int:
 
     t0 = time.perf_counter()
     A = BigSet(cf["A"], cf["seed_A"], "dev", cf["content"])
-    B = BigSet(cf["B"], cf["seed_B"], "host", cf["content"])
+    B = BigSet(cf["B"], cf["seed_B"], "host", cf["content"], share_dev=A if args.in_place else None)
+    if args.in_place:
+        args.flags |= nx.IN_PLACE
+        torch.cuda.empty_cache()
     log(f"[bench] working sets built in {time.perf_counter() - t0:.1f} s: "
         f"A {A.total_bytes / 2**30:.2f} GiB / {len(A.sizes)} allocations, "
         f"B {B.total_bytes / 2**30:.2f} GiB / {len(B.sizes)} allocations")
@@ -158,10 +164,15 @@ def main() -> int:
     log("[bench] plan:", info, f"nixie_plan {plan_ms:.1f} ms")
     h_out, h_in = plan.hash_tables()
 
+    back = nx.Plan(rows_b, rows_a, ring, opts) if args.in_place else None
+    n_switches = [0]
+
     def step():
-        lay = nx.Layout(rows_a, rows_b, ring, opts)    # the chunk planner is part of every step
-        lay.close()
-        return plan.switch()
+        fwd_turn = (n_switches[0] % 2 == 0) or back is None
+        lay = nx.Layout(rows_a if fwd_turn else rows_b, rows_b if fwd_turn else rows_a, ring, opts)
+        lay.close()                                    # the chunk planner is part of every step
+        n_switches[0] += 1
+        return (plan if fwd_turn else back).switch()
 
     for _ in range(args.warmup):
         step()
@@ -192,9 +203,15 @@ def main() -> int:
             fwd.close(); back.close()
             log("[bench] ring sweep:", sweep[-1])
 
-    rep = plan.verify(h_out, h_in)      # per-allocation hashes on the side that now holds the data
     diag = bool(args.flags & nx.DIAG_RING_ONLY)
-    arenas_ok = None if diag else bool(A.arenas_equal() and B.arenas_equal())
+    if back is not None:                # in place: where the sets are depends on the number of switches so far
+        b_in_hbm = n_switches[0] % 2 == 1
+        rep = plan.verify(h_out, h_in) if b_in_hbm else back.verify(h_in, h_out)
+        arenas_ok = None if diag else bool((B if b_in_hbm else A).arenas_equal())
+        back.close()
+    else:
+        rep = plan.verify(h_out, h_in)  # per-allocation hashes on the side that now holds the data
+        arenas_ok = None if diag else bool(A.arenas_equal() and B.arenas_equal())
     if arenas_ok is False:
         raise SystemExit("bench.py: full-buffer compare failed after the timed switches")
     plan.close()
@@ -238,7 +255,8 @@ def main() -> int:
                    "ring_bytes": ring, "slot_bytes": info["slot_bytes"], "out_slots": info["out_slots"],
                    "in_slots": info["in_slots"], "gather_wgs": info["gather_wgs"], "scatter_wgs": info["scatter_wgs"],
                    "team": info["team_out"], "drain_threads": info["drain_threads"],
-                   "fill_threads": info["fill_threads"], "flags": args.flags, "scale": args.scale},
+                   "fill_threads": info["fill_threads"], "flags": args.flags, "scale": args.scale,
+                   "in_place": bool(args.in_place)},
         "switch_latency_ms": {"min": round(lat[0], 3), "median": round(med(lat), 3), "max": round(lat[-1], 3)},
         "b_ready_ms": round(med(sorted(s["ns_in_done"] / 1e6 for s in stats)), 3),
         "plan_ms": round(plan_ms, 2),

@@ -73,7 +73,13 @@ enum nixie_flags {
                                          memory, so destinations on the host side are NOT written */
     NIXIE_DIAG_STALL_DRAIN = 1u << 3, /* failure-path test: drain threads never return credits, so the switch must
                                          end with NIXIE_ETIMEOUT after timeout_ms */
-    NIXIE_HOST_PLAIN_MEMCPY = 1u << 4 /* host threads use libc memcpy instead of streaming stores */
+    NIXIE_HOST_PLAIN_MEMCPY = 1u << 4,/* host threads use libc memcpy instead of streaming stores */
+    NIXIE_IN_PLACE = 1u << 5          /* in-place switch: device ranges of the incoming table may overlap device ranges
+                                         of the outgoing table (the incoming application reuses the GPU memory the
+                                         outgoing one gives up; paper, "Maintaining consistent virtual memory
+                                         addresses").  A chunk is scattered only after every outgoing chunk that
+                                         covers GPU bytes it overwrites has left HBM.  Ranges inside one table must
+                                         still be disjoint, and so must all host ranges. */
 };
 
 /* Every field 0 = library default. */
@@ -122,6 +128,8 @@ typedef struct {
     uint64_t seg_begin;
     uint32_t seg_count;
     uint32_t used_bytes; /* extent of the slot image, <= slot_bytes */
+    uint64_t dep_out;    /* incoming chunks of an in-place switch: number of leading outgoing chunks that must
+                            have left HBM before this chunk may be written there; otherwise 0 */
 } nixie_chunk_t;
 
 /* Timers and counters of one switch.  Times are nanoseconds since nixie_switch was entered. */
@@ -163,7 +171,9 @@ typedef struct {
  * out_table: allocations that hold data at dev_ptr and must end up at host_ptr.
  * in_table:  allocations that hold data at host_ptr and must end up at dev_ptr.
  * Either table may be NULL or empty.  All device ranges must be pairwise disjoint, and all
- * host ranges too (no aliasing), else NIXIE_EOVERLAP.
+ * host ranges too (no aliasing), else NIXIE_EOVERLAP; NIXIE_IN_PLACE lifts this for device
+ * ranges of different tables and makes the planner walk the incoming table in the order in
+ * which its GPU memory becomes free.
  * ring_bytes must hold at least 2 slots per active direction, else NIXIE_EINVAL.
  * *layout is library-owned; release with nixie_layout_destroy. */
 int nixie_layout_create(const nixie_table_t *out_table, const nixie_table_t *in_table,

@@ -36,7 +36,7 @@ int hash_host_buffers(const void *const *ptrs, const uint64_t *bytes, uint64_t n
 
 // ---- device descriptor ABI (shared by runtime.cpp and kernels.hip) ------------------------
 struct DevSeg { uint64_t dev; uint32_t slot_off; uint32_t len; };
-struct DevChunk { uint32_t seg_begin, seg_count, used, pad; };
+struct DevChunk { uint32_t seg_begin, seg_count, used, dep; };   // dep: see nixie_chunk_t::dep_out
 
 constexpr uint32_t kFlagStride = 8;        // GPU-written flags: one 64 B line (8 x u64) per flag
 // Host-written flags are packed (one u64 each, a direction's array padded to whole 64 B lines):
@@ -70,6 +70,8 @@ struct SwapArgs {
     uint32_t *gpu_status;        // pinned, GPU-written
     uint32_t *dev_abort;         // device memory
     uint64_t timeout_ticks;      // 100 MHz wall clock
+    uint32_t *gathered_prefix;   // device memory: number of leading outgoing chunks that have left HBM
+    uint32_t track_prefix;       // 1: in-place switch with both directions running in this launch
 };
 
 struct HashDesc { uint64_t ptr; uint64_t bytes; uint64_t first_tile; };

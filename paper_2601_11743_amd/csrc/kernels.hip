@@ -16,6 +16,9 @@
 //             host released[s] = k + 2  "chunk k has left slot s"     -> the pump gives s to the next chunk
 //   incoming: host filled[s]   = k + 1  "slot s holds chunk k"        -> the pump tells the scatter workers
 //             GPU  freed[s]    = k + 1  "chunk k has left slot s"     -> a host fill thread refills it
+// In-place switch (incoming ranges reuse GPU memory of outgoing ones): the outgoing pump also
+// publishes how many leading outgoing chunks have left HBM, and a scatter unit waits until that
+// count reaches its chunk's dependency before it overwrites anything.
 // Workgroups sharing a chunk meet on a device-scope counter and the last one stores the
 // host-visible flag.  All flag traffic is relaxed system-scope atomics; the ordering of payload
 // against flags is built by hand (see the comments at the places that do it), because
@@ -175,6 +178,27 @@ __device__ void run_direction(const SwapArgs &a) {
                     }
                     stall += wall_clock64() - t0;
                 }
+                // In-place switch: the GPU bytes this chunk overwrites must have been gathered.
+                if (DIR == 1 && cs != 0 && a.track_prefix) {
+                    const uint32_t dep = D.chunks[u / D.team].dep;
+                    if (__hip_atomic_load(a.gathered_prefix, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < dep) {
+                        const uint64_t t0 = wall_clock64();
+                        uint32_t it = 0;
+                        while (__hip_atomic_load(a.gathered_prefix, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < dep) {
+                            if ((++it & 7u) == 0) {
+                                if (__hip_atomic_load(a.dev_abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) { cs = 0; break; }
+                                if (wall_clock64() - t0 > a.timeout_ticks) {
+                                    __hip_atomic_store(a.dev_abort, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                                    __hip_atomic_store(a.gpu_status, (uint32_t)kGpuTimeout, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                                    cs = 0;
+                                    break;
+                                }
+                            }
+                            __builtin_amdgcn_s_sleep(4);
+                        }
+                        stall += wall_clock64() - t0;
+                    }
+                }
             }
             s_unit = u;
             s_slot = cs;
@@ -203,11 +227,10 @@ __device__ void run_direction(const SwapArgs &a) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();   // also: every thread has read s_unit / s_slot before thread 0 overwrites them
         if (tid == 0) {
-            bool last = true;
-            if (D.team > 1) {
-                uint32_t old = __hip_atomic_fetch_add(D.arrive + k, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                last = (old == D.team - 1);
-            }
+            // (for the outgoing direction the counter also tells the pump that the chunk has left HBM:
+            //  every load of this unit completed before the barrier above)
+            const uint32_t old = __hip_atomic_fetch_add(D.arrive + k, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const bool last = (old == D.team - 1);
             if (last)   // outgoing: "slot holds chunk k"; incoming: "chunk k has left the slot"
                 __hip_atomic_store(D.post_flags + (size_t)slot * kFlagStride, (uint64_t)k + 1u, __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_SYSTEM);
@@ -231,7 +254,20 @@ __device__ void run_pump(const SwapArgs &a, int dir) {
     const DevDir &D = a.d[dir];
     if (D.wgs == 0) return;
     const uint32_t lane = threadIdx.x & 63u;
-    uint32_t next = 0;   // outgoing: next chunk without a slot (wave-uniform)
+    uint32_t next = 0;     // outgoing: next chunk without a slot (wave-uniform)
+    uint32_t prefix = 0;   // outgoing, in-place switch: leading chunks that have left HBM (wave-uniform)
+    const bool track = dir == 0 && a.track_prefix;
+    auto advance_prefix = [&]() {   // up to 64 chunks per call; true if it moved
+        const uint32_t k = prefix + lane;
+        const bool done = k < D.n_chunks &&
+                          __hip_atomic_load(D.arrive + k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= D.team;
+        const uint64_t pending = ~__ballot(done);                         // first zero bit = first unfinished chunk
+        const uint32_t step = pending ? (uint32_t)__builtin_ctzll(pending) : 64u;
+        if (step == 0) return false;
+        prefix += step;
+        if (lane == 0) __hip_atomic_store(a.gathered_prefix, prefix, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return true;
+    };
     for (;;) {
         for (uint32_t base = 0; base < D.n_slots; base += 64) {
             const uint32_t s = base + lane;
@@ -263,7 +299,13 @@ __device__ void run_pump(const SwapArgs &a, int dir) {
             __hip_atomic_store(a.dev_abort, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __hip_atomic_store(a.gpu_status, (uint32_t)kGpuSawAbort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
         }
-        if (__hip_atomic_load(D.exited, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= D.wgs) break;
+        if (track) advance_prefix();
+        if (__hip_atomic_load(D.exited, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= D.wgs) {
+            // every gather workgroup has left, so every arrive counter is final: publish the rest
+            // (bounded: at most n_chunks / 64 + 1 rounds)
+            if (track) while (prefix < D.n_chunks && advance_prefix()) {}
+            break;
+        }
         __builtin_amdgcn_s_sleep(8);
     }
 }

@@ -51,6 +51,18 @@ int copy_table(const nixie_table_t *t, std::vector<nixie_alloc_t> &dst) {
     return NIXIE_OK;
 }
 
+// In-place switch.  osegs: outgoing segments sorted by device address (they are disjoint), with the
+// chunk each belongs to.  Returns 1 + the highest outgoing chunk index that covers a byte of
+// [a, b), or 0: that many leading outgoing chunks must have left HBM before [a, b) is written.
+struct OutSpan { uint64_t lo, hi, chunk; };
+uint64_t dep_of_range(const std::vector<OutSpan> &osegs, uint64_t a, uint64_t b) {
+    if (a >= b) return 0;
+    auto it = std::upper_bound(osegs.begin(), osegs.end(), a, [](uint64_t v, const OutSpan &s) { return v < s.hi; });
+    uint64_t dep = 0;
+    for (; it != osegs.end() && it->lo < b; ++it) dep = std::max(dep, it->chunk + 1);
+    return dep;
+}
+
 std::vector<uint64_t> walk_order(const std::vector<nixie_alloc_t> &t, uint32_t order) {
     std::vector<uint64_t> idx(t.size());
     std::iota(idx.begin(), idx.end(), 0);
@@ -74,7 +86,7 @@ std::vector<uint64_t> walk_order(const std::vector<nixie_alloc_t> &t, uint32_t o
 
 // Greedy sequential packing.  A segment's slot offset is congruent to its device address
 // modulo 16, so the 16-byte lanes of the copy kernels are aligned on both sides at once.
-void cut(const std::vector<nixie_alloc_t> &t, uint32_t order, uint64_t S, DirLayout &D) {
+void cut(const std::vector<nixie_alloc_t> &t, const std::vector<uint64_t> &walk, uint64_t S, DirLayout &D) {
     D.segs.clear();
     D.chunks.clear();
     D.bytes = 0;
@@ -84,14 +96,14 @@ void cut(const std::vector<nixie_alloc_t> &t, uint32_t order, uint64_t S, DirLay
     D.chunks.reserve(total / (S - 16) + 8);       // at most 15 padding bytes per segment start
     uint64_t fill = 0;
     bool open = false;
-    for (uint64_t i : walk_order(t, order)) {
+    for (uint64_t i : walk) {
         const nixie_alloc_t &a = t[i];
         uint64_t off = 0;
         while (off < a.bytes) {
             uint64_t dev = (uint64_t)(uintptr_t)a.dev_ptr + off;
             uint64_t pos = open ? fill + ((dev - fill) & 15) : S;
             if (!open || pos >= S) {
-                D.chunks.push_back(nixie_chunk_t{(uint64_t)D.segs.size(), 0, 0});
+                D.chunks.push_back(nixie_chunk_t{(uint64_t)D.segs.size(), 0, 0, 0});
                 open = true;
                 pos = dev & 15;
             }
@@ -135,7 +147,14 @@ int build_layout(const nixie_table_t *out_table, const nixie_table_t *in_table, 
             tot[x] += a.bytes;
         }
     }
-    if (any_overlap(dev, mid) || any_overlap(host, mid)) return NIXIE_EOVERLAP;
+    const bool in_place = (L.opts.flags & NIXIE_IN_PLACE) != 0;
+    if (in_place) {   // device ranges may overlap across the tables, not inside one
+        std::vector<Range> d0(dev.begin(), dev.begin() + (ptrdiff_t)mid), d1(dev.begin() + (ptrdiff_t)mid, dev.end());
+        if (any_overlap(d0, d0.size()) || any_overlap(d1, d1.size())) return NIXIE_EOVERLAP;
+    } else if (any_overlap(dev, mid)) {
+        return NIXIE_EOVERLAP;
+    }
+    if (any_overlap(host, mid)) return NIXIE_EOVERLAP;
 
     const int active = (tot[0] > 0) + (tot[1] > 0);
     uint64_t S = L.opts.slot_bytes;
@@ -167,13 +186,39 @@ int build_layout(const nixie_table_t *out_table, const nixie_table_t *in_table, 
     L.slot_bytes = S;
     L.dir[0].slots = (uint32_t)n_out;
     L.dir[1].slots = (uint32_t)(tot[1] ? n_slots - n_out : 0);
-    if (L.table[0].size() + L.table[1].size() > 20000) {   // large tables: one direction per thread
-        std::thread other([&] { cut(L.table[1], L.opts.order, S, L.dir[1]); });
-        cut(L.table[0], L.opts.order, S, L.dir[0]);
+    const std::vector<uint64_t> walk0 = walk_order(L.table[0], L.opts.order);
+    std::vector<uint64_t> walk1 = walk_order(L.table[1], L.opts.order);
+    if (in_place && tot[0] && tot[1]) {
+        cut(L.table[0], walk0, S, L.dir[0]);
+        std::vector<OutSpan> osegs;
+        osegs.reserve(L.dir[0].segs.size());
+        for (uint64_t k = 0; k < L.dir[0].chunks.size(); k++) {
+            const nixie_chunk_t &c = L.dir[0].chunks[k];
+            for (uint64_t q = c.seg_begin; q < c.seg_begin + c.seg_count; q++)
+                osegs.push_back({L.dir[0].segs[q].dev_addr, L.dir[0].segs[q].dev_addr + L.dir[0].segs[q].len, k});
+        }
+        std::sort(osegs.begin(), osegs.end(), [](const OutSpan &a, const OutSpan &b) { return a.lo < b.lo; });
+        // Walk the incoming table in the order in which its GPU memory becomes free, so that the
+        // scatter side follows right behind the gather side instead of waiting for its end.
+        std::vector<uint64_t> adep(L.table[1].size());
+        for (size_t i = 0; i < adep.size(); i++) {
+            const uint64_t d = (uint64_t)(uintptr_t)L.table[1][i].dev_ptr;
+            adep[i] = dep_of_range(osegs, d, d + L.table[1][i].bytes);
+        }
+        std::stable_sort(walk1.begin(), walk1.end(), [&](uint64_t a, uint64_t b) { return adep[a] < adep[b]; });
+        cut(L.table[1], walk1, S, L.dir[1]);
+        for (nixie_chunk_t &c : L.dir[1].chunks)
+            for (uint64_t q = c.seg_begin; q < c.seg_begin + c.seg_count; q++) {
+                const nixie_segment_t &sg = L.dir[1].segs[q];
+                c.dep_out = std::max(c.dep_out, dep_of_range(osegs, sg.dev_addr, sg.dev_addr + sg.len));
+            }
+    } else if (L.table[0].size() + L.table[1].size() > 20000) {   // large tables: one direction per thread
+        std::thread other([&] { cut(L.table[1], walk1, S, L.dir[1]); });
+        cut(L.table[0], walk0, S, L.dir[0]);
         other.join();
     } else {
-        cut(L.table[0], L.opts.order, S, L.dir[0]);
-        cut(L.table[1], L.opts.order, S, L.dir[1]);
+        cut(L.table[0], walk0, S, L.dir[0]);
+        cut(L.table[1], walk1, S, L.dir[1]);
     }
     if (L.dir[0].chunks.size() > 0xFFFFFFF0ull / 256 || L.dir[1].chunks.size() > 0xFFFFFFF0ull / 256 ||
         L.dir[0].segs.size() > 0xFFFFFFF0ull || L.dir[1].segs.size() > 0xFFFFFFF0ull)

@@ -309,7 +309,8 @@ int create_plan(nixie_plan_t *p) {
         for (size_t i = 0; i < segs.size(); i++) segs[i] = DevSeg{D.segs[i].dev_addr, D.segs[i].slot_off, D.segs[i].len};
         std::vector<DevChunk> chunks(D.chunks.size());
         for (size_t i = 0; i < chunks.size(); i++)
-            chunks[i] = DevChunk{(uint32_t)D.chunks[i].seg_begin, D.chunks[i].seg_count, D.chunks[i].used_bytes, 0};
+            chunks[i] = DevChunk{(uint32_t)D.chunks[i].seg_begin, D.chunks[i].seg_count, D.chunks[i].used_bytes,
+                                 (uint32_t)D.chunks[i].dep_out};
         int rc = upload(segs.data(), segs.size() * sizeof(DevSeg), (void **)&p->segs_d[x]);
         if (rc) return rc;
         rc = upload(chunks.data(), chunks.size() * sizeof(DevChunk), (void **)&p->chunks_d[x]);
@@ -330,7 +331,7 @@ int create_plan(nixie_plan_t *p) {
         if (rc) return rc;
     }
     // counters (u32 units): [0] ticket out, [1] ticket in, [2] abort, [3] pad, [4,5] stall out, [6,7] stall in,
-    // [8] exited out, [9] exited in, [10..15] pad, then per direction: seen[] (u64 per slot),
+    // [8] exited out, [9] exited in, [10] gathered prefix, [11..15] pad, then per direction: seen[] (u64 per slot),
     // chunk_slot[] and arrive[] (u32 per chunk).  All of it is cleared before every launch.
     uint64_t off = 16;
     for (int x = 0; x < 2; x++) { p->seen_off[x] = off; off += 2 * wait_flag_words(L.dir[x].slots); }
@@ -396,6 +397,9 @@ int run_pass(nixie_plan_t *p, uint32_t mask, hipStream_t stream, nixie_stats_t *
     a.gpu_status = (uint32_t *)(p->ctrl_d + (size_t)((uint64_t *)p->status_h - p->ctrl_h));
     a.dev_abort = p->counters_d + 2;
     a.timeout_ticks = p->timeout_ns / 10;   // wall clock runs at 100 MHz
+    a.gathered_prefix = p->counters_d + 10;
+    // when the directions run one after the other, everything has left HBM before the restore starts
+    a.track_prefix = ((L.opts.flags & NIXIE_IN_PLACE) && a.d[0].wgs && a.d[1].wgs) ? 1u : 0u;
 
     int e = nixie_launch_zero32(p->counters_d, p->n_counters, stream);
     if (e) { t_last_hip_error = e; return NIXIE_EHIP; }

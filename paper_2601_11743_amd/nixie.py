@@ -12,7 +12,7 @@ _LIB_PATH = os.path.join(_HERE, "libnixie.so")
 
 EINVAL, EOVERLAP, ENOMEM, EHIP, ETIMEOUT, EMISMATCH, EBUSY = -1, -2, -3, -4, -5, -6, -7
 ORDER_TABLE, ORDER_LARGE_FIRST, ORDER_ADDRESS, ORDER_REVERSE = 0, 1, 2, 3
-SPLIT_BY_BYTES, SERIALIZE, DIAG_RING_ONLY, DIAG_STALL_DRAIN, HOST_PLAIN_MEMCPY = 1, 2, 4, 8, 16
+SPLIT_BY_BYTES, SERIALIZE, DIAG_RING_ONLY, DIAG_STALL_DRAIN, HOST_PLAIN_MEMCPY, IN_PLACE = 1, 2, 4, 8, 16, 32
 
 DECLARED_SYMBOLS = (
     "nixie_layout_create", "nixie_layout_info", "nixie_layout_chunks", "nixie_layout_segments",
@@ -55,7 +55,8 @@ class _Segment(C.Structure):
 
 
 class _Chunk(C.Structure):
-    _fields_ = [("seg_begin", C.c_uint64), ("seg_count", C.c_uint32), ("used_bytes", C.c_uint32)]
+    _fields_ = [("seg_begin", C.c_uint64), ("seg_count", C.c_uint32), ("used_bytes", C.c_uint32),
+                ("dep_out", C.c_uint64)]
 
 
 class _Stats(C.Structure):
@@ -191,7 +192,7 @@ class Layout:
             raise NixieError(int(n), "nixie_layout_chunks")
         arr = (_Chunk * max(1, n))()
         lib().nixie_layout_chunks(self._h, direction, arr, n)
-        dt = np.dtype([("seg_begin", "<u8"), ("seg_count", "<u4"), ("used_bytes", "<u4")])
+        dt = np.dtype([("seg_begin", "<u8"), ("seg_count", "<u4"), ("used_bytes", "<u4"), ("dep_out", "<u8")])
         return np.frombuffer(arr, dtype=dt, count=n).copy()
 
     def segments(self, direction: int) -> np.ndarray:

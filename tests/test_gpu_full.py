@@ -140,3 +140,42 @@ def test_config4_fragmented_full(nx, oracle):
 def test_config5_pingpong_full(nx, oracle, ring_mib):
     info, st = full_case(nx, oracle, 5, ring_mib * MiB, round_trips=1)
     assert info["pinned_ring_bytes"] <= ring_mib * MiB
+
+
+def test_config2_in_place_full(nx, oracle):
+    """In-place switch at full size: B is restored into the very HBM that A is evicted from (one
+    17 GiB arena instead of two), then A comes back the same way."""
+    import torch
+    from workloads.device import BigSet
+    cf = W.config(2)
+    A = BigSet(cf["A"], cf["seed_A"], "dev", cf["content"])
+    B = BigSet(cf["B"], cf["seed_B"], "host", cf["content"], share_dev=A)
+    torch.cuda.empty_cache()
+    ia, ib = sample_indices(A.sizes, 1), sample_indices(B.sizes, 2)
+    exp_a, hash_a = oracle_expectation(oracle, A, ia, "dev")
+    exp_b, hash_b = oracle_expectation(oracle, B, ib, "host")
+    opts = nx.Opts(slot_bytes=cf["slot_bytes"], flags=nx.IN_PLACE)
+    with pytest.raises(nx.NixieError):
+        nx.Plan(A.rows_np(), B.rows_np(), 256 * MiB, nx.Opts(slot_bytes=cf["slot_bytes"]))
+    fwd = nx.Plan(A.rows_np(), B.rows_np(), 256 * MiB, opts)
+    back = nx.Plan(B.rows_np(), A.rows_np(), 256 * MiB, opts)
+    h_a, h_b = fwd.hash_tables()
+    assert [int(h_a[i]) for i in ia] == hash_a and [int(h_b[i]) for i in ib] == hash_b
+    st = fwd.switch()
+    for i, e in zip(ia, exp_a):
+        assert np.array_equal(A.host_view(i), e), f"evicted allocation {i} differs from the oracle"
+    for i, e in zip(ib, exp_b):
+        assert np.array_equal(B.dev_view(i).cpu().numpy(), e), f"restored allocation {i} differs from the oracle"
+    assert B.arenas_equal(), "HBM arena differs from B's pageable arena"
+    fwd.verify(h_a, h_b)
+    print(f"\nin-place config 2: {st['ns_total'] / 1e6:.1f} ms, out {st['bytes_out'] / st['ns_out_done']:.1f} GB/s, "
+          f"in {st['bytes_in'] / st['ns_in_done']:.1f} GB/s")
+    for i in (0, len(B.sizes) - 1):
+        B.host_view(i)[:] = 0x33                      # sources are don't-care
+    back.switch()                                     # B out, A back in, same HBM
+    back.verify(h_b, h_a)
+    for i, e in zip(ia, exp_a):
+        assert np.array_equal(A.dev_view(i).cpu().numpy(), e)
+    for i, e in zip(ib, exp_b):
+        assert np.array_equal(B.host_view(i), e)
+    fwd.close(); back.close()

@@ -186,3 +186,49 @@ def test_stalled_drain_times_out_cleanly(nx):
     plan.switch()
     gA2.hs.check_moved()
     plan.close()
+
+
+# ---- in-place switch: B's device ranges reuse the GPU memory A gives up -----------------------
+
+ALIAS_CASES = [
+    ([5 * S + 1, 300, 2 * S, 9 * S + 77], [4 * S, 11, 3 * S + 9, 7 * S], 0),
+    ([3 * S, 3 * S, 3 * S, 3 * S], [3 * S, 3 * S, 3 * S, 3 * S], 0),
+    ([2 * S + 7, 900, 5 * S], [S, S, 500, 4 * S + 3], 1000),
+    ([4 * S], [100, 200, 6 * S], 3 * S),
+    ([20 * S + 5, 999, 13 * S], [17 * S, 4, 15 * S + 1], 256),
+]
+
+
+@pytest.mark.parametrize("case", range(len(ALIAS_CASES)))
+@pytest.mark.parametrize("mode", ["default", "small_units", "serialized"])
+def test_in_place_switch(nx, oracle, case, mode):
+    import torch
+    from tests.helpers import AliasedPair
+    from tests.gpu_helpers import first_diff
+    sa, sb, shift = ALIAS_CASES[case]
+    ref = AliasedPair(sa, sb, 31, shift_b=shift, skew_a=case % 3, skew_b=(case * 5) % 16)
+    h_out_ref = oracle.hash_table(ref.pairs_a(), "dev")
+    h_in_ref = oracle.hash_table(ref.pairs_b(), "host")
+    oracle.switch_direct(ref.pairs_a(), ref.pairs_b())           # the definition: evict all, then restore
+    ref.check()
+
+    g = AliasedPair(sa, sb, 31, shift_b=shift, skew_a=case % 3, skew_b=(case * 5) % 16)
+    dev_t = torch.from_numpy(g.dev).to("cuda:0")
+    base = dev_t.data_ptr()
+    rows_a = [(base + od, g.host_a.ctypes.data + oh, b) for od, oh, b in zip(g.la.offsets, g.lha.offsets, g.sizes_a)]
+    rows_b = [(base + od, g.host_b.ctypes.data + oh, b) for od, oh, b in zip(g.lb.offsets, g.lhb.offsets, g.sizes_b)]
+    kw = dict(default={}, small_units=dict(team=8, gather_wgs=16, scatter_wgs=24, drain_threads=2, fill_threads=2),
+              serialized={})[mode]
+    flags = nx.IN_PLACE | (nx.SERIALIZE if mode == "serialized" else 0)
+    with pytest.raises(nx.NixieError):
+        nx.Plan(rows_a, rows_b, 8 * S, nx.Opts(slot_bytes=S))     # without the flag aliasing is an error
+    plan = nx.Plan(rows_a, rows_b, 8 * S, nx.Opts(slot_bytes=S, flags=flags, **kw))
+    h_out, h_in = plan.hash_tables()
+    assert np.array_equal(h_out, h_out_ref) and np.array_equal(h_in, h_in_ref)
+    plan.switch()
+    torch.cuda.synchronize()
+    dev_after = dev_t.cpu().numpy()
+    assert np.array_equal(g.host_a, ref.host_a), "evicted set: " + first_diff(g.host_a, ref.host_a)
+    assert np.array_equal(dev_after, ref.dev), "device arena: " + first_diff(dev_after, ref.dev)
+    plan.verify(h_out_ref, h_in_ref)
+    plan.close()

@@ -203,3 +203,47 @@ def test_host_hash_matches_oracle(nx, oracle):
         bufs = [np.concatenate([np.zeros(skew, np.uint8), W.content_bytes(5, i, b)])[skew:] for i, b in enumerate(sizes)]
         got = nx.hash_buffers([b.ctypes.data for b in bufs], sizes, on_device=False)
         assert [int(x) for x in got] == [oracle.hash64(b) for b in bufs]
+
+
+def test_in_place_dependencies(nx):
+    """NIXIE_IN_PLACE: every incoming chunk depends on exactly the outgoing chunks whose device
+    bytes it overwrites (as a prefix length), and the incoming table is walked in the order its
+    GPU memory becomes free."""
+    S = 64 * KiB
+    rng = np.random.default_rng(4)
+    sizes_a = [int(x) for x in rng.integers(1, 5 * S, size=40)]
+    sizes_b = [int(x) for x in rng.integers(1, 7 * S, size=25)]
+    ra = fake_rows(sizes_a, gap=64)
+    rb = fake_rows(sizes_b, host_base=0x1800_0000_0000, gap=192)     # same device base: overlaps A's ranges
+    with pytest.raises(nx.NixieError) as e:
+        nx.Layout(ra, rb, 16 * S, nx.Opts(slot_bytes=S))
+    assert e.value.code == nx.EOVERLAP                                 # aliasing needs the flag
+    lay = nx.Layout(ra, rb, 16 * S, nx.Opts(slot_bytes=S, flags=nx.IN_PLACE))
+    check_layout(lay, ra, rb, 16 * S)
+    co, so, ci, si = lay.chunks(0), lay.segments(0), lay.chunks(1), lay.segments(1)
+    assert (co["dep_out"] == 0).all()
+    out_chunk_of = np.repeat(np.arange(len(co)), co["seg_count"])
+    in_chunk_of = np.repeat(np.arange(len(ci)), ci["seg_count"])
+    want = np.zeros(len(ci), dtype=np.int64)
+    for q in range(len(si)):                                           # brute force over all segment pairs
+        a, b = int(si["dev_addr"][q]), int(si["dev_addr"][q]) + int(si["len"][q])
+        hit = (so["dev_addr"].astype(np.int64) < b) & (so["dev_addr"].astype(np.int64) + so["len"] > a)
+        if hit.any():
+            want[in_chunk_of[q]] = max(want[in_chunk_of[q]], int(out_chunk_of[hit].max()) + 1)
+    assert np.array_equal(ci["dep_out"].astype(np.int64), want)
+    assert want.max() > 0
+    # walked in the order the memory becomes free: dependencies never decrease by more than one allocation's span
+    first_dep = [int(want[in_chunk_of[np.flatnonzero(si["dev_addr"] == r[0])[0]]]) for r in rb if r[2]]
+    order = np.argsort([int(np.flatnonzero(si["dev_addr"] == r[0])[0]) for r in rb if r[2]])
+    alloc_dep = []
+    for r in rb:
+        a, b = r[0], r[0] + r[2]
+        hit = (so["dev_addr"].astype(np.int64) < b) & (so["dev_addr"].astype(np.int64) + so["len"] > a)
+        alloc_dep.append(int(out_chunk_of[hit].max()) + 1 if hit.any() else 0)
+    walked = [alloc_dep[i] for i in order]
+    assert walked == sorted(walked)
+    # overlap inside one table is still refused, and so is any host overlap
+    with pytest.raises(nx.NixieError):
+        nx.Layout(ra + [(ra[0][0] + 1, 0x2000_0000_0000, 2)], rb, 16 * S, nx.Opts(slot_bytes=S, flags=nx.IN_PLACE))
+    with pytest.raises(nx.NixieError):
+        nx.Layout(ra, [(r[0], ra[0][1], r[2]) for r in rb[:1]], 16 * S, nx.Opts(slot_bytes=S, flags=nx.IN_PLACE))

@@ -35,7 +35,10 @@ class BigSet:
     arena with the same layout (256 B aligned bases, red zones between allocations)."""
 
     def __init__(self, sizes, seed: int, resident: str, content: str, device: str = "cuda:0",
-                 redzone: int = 256, red: int = 0xC3, poison_dev: int = 0xA5, poison_host: int = 0x5A):
+                 redzone: int = 256, red: int = 0xC3, poison_dev: int = 0xA5, poison_host: int = 0x5A,
+                 share_dev: "BigSet | None" = None):
+        """share_dev: for an in-place switch -- this (host-resident) set gets no HBM of its own; its
+        device ranges lie in the other set's arena, which must have the same layout."""
         import torch
         self.sizes = [s if isinstance(s, int) else s[1] for s in sizes]
         self.names = [("" if isinstance(s, int) else s[0]) for s in sizes]
@@ -57,8 +60,13 @@ class BigSet:
             step = 1 << 30
             for a in range(0, self.layout.total, step):
                 self.host_t[a:a + step].copy_(self.dev[a:a + step])
-            for o, b in zip(self.layout.offsets, self.sizes):
-                self.dev[o:o + b] = poison_dev
+            if share_dev is not None:
+                assert resident == "host" and share_dev.layout.offsets == self.layout.offsets \
+                    and share_dev.sizes == self.sizes, "in-place sets must share one layout"
+                self.dev = share_dev.dev          # the generator's scratch arena is dropped here
+            else:
+                for o, b in zip(self.layout.offsets, self.sizes):
+                    self.dev[o:o + b] = poison_dev
         else:                        # A is GPU resident; its pageable ranges are poisoned
             for o, b in zip(self.layout.offsets, self.sizes):
                 self.host[o:o + b] = poison_host

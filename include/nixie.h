@@ -96,6 +96,9 @@ typedef struct {
     uint32_t fill_threads;   /* host threads moving pageable -> ring                                        */
     uint32_t timeout_ms;     /* bound on any single credit wait, host or GPU side; default 30000            */
     uint32_t flags;          /* enum nixie_flags                                                            */
+    uint32_t xcd_mask;       /* tuning: bit i set = workgroups that land on XCD i take part, the others leave at
+                                once (workgroups are dealt round-robin over the 8 XCDs, so raise gather_wgs /
+                                scatter_wgs accordingly); 0 = all XCDs                                       */
 } nixie_opts_t;
 
 typedef struct nixie_plan nixie_plan_t;     /* opaque; owns ring, flags, descriptors, host threads */

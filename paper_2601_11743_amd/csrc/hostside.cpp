@@ -1,0 +1,220 @@
+// Host half of the slot protocol: drain and fill threads, their watchdog, and the crew that
+// parks them between switches.
+//
+// Paper, "Speeding Up Context Switches": the pinned tier is run as a stream with back-pressure
+// -- a slot is refilled as soon as the stage below has emptied it -- and the pageable<->pinned
+// leg is copied by several threads.  Each thread owns a fixed subset of the slots and serves
+// whichever of them has work, so a slot that is slow to come back delays nothing else.
+#include "hostside.hpp"
+
+#include <immintrin.h>
+#include <time.h>
+
+#include <cstring>
+
+namespace nixie {
+
+namespace {
+
+inline uint64_t now_ns() {
+    timespec ts;
+    clock_gettime(CLOCK_MONOTONIC, &ts);
+    return (uint64_t)ts.tv_sec * 1000000000ull + (uint64_t)ts.tv_nsec;
+}
+inline uint64_t load_acq(const uint64_t *p) { return __atomic_load_n(p, __ATOMIC_ACQUIRE); }
+inline void store_rel(uint64_t *p, uint64_t v) { __atomic_store_n(p, v, __ATOMIC_RELEASE); }
+
+}  // namespace
+
+void HostSide::begin_pass() {
+    abort_local.store(0);
+    for (int x = 0; x < 2; x++) {
+        next_chunk[x].store(0);
+        done_chunks[x].store(0);
+        wait_ns[x].store(0);
+    }
+    for (uint32_t s = 0; s < L->dir[0].slots; s++) wait[0][s] = 1;   // every outgoing slot starts released
+    std::atomic_thread_fence(std::memory_order_seq_cst);
+}
+
+void HostSide::raise_abort(int err) {
+    int expected = 0;
+    error.compare_exchange_strong(expected, err);
+    abort_local.store(1, std::memory_order_release);
+    __atomic_store_n(abort_word, 1u, __ATOMIC_RELEASE);   // the kernel's pump polls this word
+}
+
+namespace {
+
+// Idle bookkeeping of a host thread that scans its slots: aborts the switch when nothing has
+// moved for longer than the bound, or when the kernel reported that it gave up.
+struct IdleWatch {
+    HostSide *p;
+    int dir;
+    uint64_t idle_since = 0;
+    uint32_t spins = 0;
+    // call after a scan that made no progress; false = stop
+    bool idle() {
+        _mm_pause();
+        if (idle_since == 0) idle_since = now_ns();
+        if ((++spins & 63u) != 0) return true;
+        if (p->abort_local.load(std::memory_order_acquire)) return false;
+        if (__atomic_load_n(p->status_word, __ATOMIC_ACQUIRE) != kGpuOk || now_ns() - idle_since > p->timeout_ns) {
+            p->raise_abort(NIXIE_ETIMEOUT);
+            return false;
+        }
+        return true;
+    }
+    void progressed() {
+        if (idle_since) p->wait_ns[dir].fetch_add(now_ns() - idle_since, std::memory_order_relaxed);
+        idle_since = 0;
+    }
+};
+
+void note_end(HostSide *p, int dir) {
+    uint64_t t = now_ns(), cur = p->end_ns[dir].load(std::memory_order_relaxed);
+    while (cur < t && !p->end_ns[dir].compare_exchange_weak(cur, t, std::memory_order_relaxed)) {}
+}
+
+}  // namespace
+
+// ring -> pageable.  Consumer of the outgoing direction.  Thread idx owns slots idx, idx + T, ...
+// and drains whichever of them the GPU has marked ready (ready[s] = chunk id + 1), in any order.
+void HostSide::run_drain(uint32_t idx) {
+    HostSide *p = this;
+    const uint32_t T = threads[0];
+    const DirLayout &D = L->dir[0];
+    const uint32_t flags = L->opts.flags;
+    const uint64_t n = D.chunks.size(), S = L->slot_bytes;
+    const bool plain = flags & NIXIE_HOST_PLAIN_MEMCPY;
+    std::vector<uint64_t> last(D.slots, 0);
+    IdleWatch watch{p, 0};
+    while (p->done_chunks[0].load(std::memory_order_acquire) < n) {
+        bool moved = false;
+        for (uint64_t slot = idx; slot < D.slots; slot += T) {
+            const uint64_t v = load_acq(p->post[0] + slot * kFlagStride);
+            if (v == last[slot]) continue;
+            last[slot] = v;
+            const uint64_t k = v - 1;
+            if (k >= n) { p->raise_abort(NIXIE_EINVAL); return; }
+            if (!(flags & NIXIE_DIAG_RING_ONLY)) {
+                const nixie_chunk_t &c = D.chunks[k];
+                const uint8_t *src = p->ring + slot * S;
+                for (uint64_t q = c.seg_begin; q < c.seg_begin + c.seg_count; q++) {
+                    const nixie_segment_t &sg = D.segs[q];
+                    if (plain) std::memcpy((void *)(uintptr_t)sg.host_addr, src + sg.slot_off, sg.len);
+                    else copy_stream((void *)(uintptr_t)sg.host_addr, src + sg.slot_off, sg.len);
+                }
+                _mm_sfence();
+            }
+            if (!(flags & NIXIE_DIAG_STALL_DRAIN)) store_rel(p->wait[0] + slot, k + 2);   // released
+            p->done_chunks[0].fetch_add(1, std::memory_order_acq_rel);
+            moved = true;
+        }
+        if (moved) watch.progressed();
+        else if (!watch.idle()) return;
+    }
+    watch.progressed();
+    note_end(p, 0);
+}
+
+// pageable -> ring.  Producer of the incoming direction.  Thread idx owns slots idx, idx + T, ...;
+// whenever one of them is free it claims the next chunk, loads it and publishes filled[s] = id + 1.
+// A slot is free again when the GPU has written freed[s] = id + 1 for the chunk it held.
+void HostSide::run_fill(uint32_t idx) {
+    HostSide *p = this;
+    const uint32_t T = threads[1];
+    const DirLayout &D = L->dir[1];
+    const uint32_t flags = L->opts.flags;
+    const uint64_t n = D.chunks.size(), S = L->slot_bytes;
+    const bool plain = flags & NIXIE_HOST_PLAIN_MEMCPY;
+    std::vector<uint64_t> pending(D.slots, 0);
+    uint64_t outstanding = 0;
+    bool claiming = true;
+    IdleWatch watch{p, 1};
+    for (;;) {
+        bool moved = false;
+        for (uint64_t slot = idx; slot < D.slots; slot += T) {
+            if (pending[slot]) {
+                if (load_acq(p->post[1] + slot * kFlagStride) != pending[slot]) continue;
+                pending[slot] = 0;
+                outstanding--;
+                moved = true;
+            }
+            if (!claiming) continue;
+            const uint64_t k = p->next_chunk[1].fetch_add(1, std::memory_order_relaxed);
+            if (k >= n) { claiming = false; continue; }
+            if (!(flags & NIXIE_DIAG_RING_ONLY)) {
+                const nixie_chunk_t &c = D.chunks[k];
+                uint8_t *dst = p->ring + ((uint64_t)p->L->dir[0].slots + slot) * S;
+                for (uint64_t q = c.seg_begin; q < c.seg_begin + c.seg_count; q++) {
+                    const nixie_segment_t &sg = D.segs[q];
+                    if (plain) std::memcpy(dst + sg.slot_off, (const void *)(uintptr_t)sg.host_addr, sg.len);
+                    else copy_stream(dst + sg.slot_off, (const void *)(uintptr_t)sg.host_addr, sg.len);
+                }
+                _mm_sfence();
+            }
+            store_rel(p->wait[1] + slot, k + 1);   // filled
+            pending[slot] = k + 1;
+            outstanding++;
+            moved = true;
+        }
+        if (!claiming && outstanding == 0) break;
+        if (moved) watch.progressed();
+        else if (!watch.idle()) return;
+    }
+    watch.progressed();
+    note_end(p, 1);   // this thread's last chunk has reached HBM; the latest such time is "B ready"
+}
+
+void HostCrew::worker(int dir, uint32_t idx) {
+    uint64_t seen = 0;
+    for (;;) {
+        uint32_t mask;
+        {
+            std::unique_lock<std::mutex> lk(mu_);
+            cv_go_.wait(lk, [&] { return quit_ || epoch_ != seen; });
+            if (quit_) return;
+            seen = epoch_;
+            mask = mask_;
+        }
+        if (mask & (1u << dir)) {
+            if (dir == 0) hs_->run_drain(idx);
+            else hs_->run_fill(idx);
+        }
+        {
+            std::lock_guard<std::mutex> lk(mu_);
+            if (--running_ == 0) cv_done_.notify_all();
+        }
+    }
+}
+
+void HostCrew::start(HostSide *hs) {
+    hs_ = hs;
+    for (uint32_t t = 0; t < hs->threads[0]; t++) threads_.emplace_back(&HostCrew::worker, this, 0, t);
+    for (uint32_t t = 0; t < hs->threads[1]; t++) threads_.emplace_back(&HostCrew::worker, this, 1, t);
+}
+
+void HostCrew::run_pass(uint32_t mask) {
+    {
+        std::lock_guard<std::mutex> lk(mu_);
+        mask_ = mask;
+        running_ = (uint32_t)threads_.size();
+        epoch_++;
+    }
+    cv_go_.notify_all();
+    std::unique_lock<std::mutex> lk(mu_);
+    cv_done_.wait(lk, [&] { return running_ == 0; });
+}
+
+void HostCrew::stop() {
+    {
+        std::lock_guard<std::mutex> lk(mu_);
+        quit_ = true;
+    }
+    cv_go_.notify_all();
+    for (auto &t : threads_) t.join();
+    threads_.clear();
+}
+
+}  // namespace nixie

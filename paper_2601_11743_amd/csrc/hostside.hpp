@@ -1,0 +1,58 @@
+// Host half of the slot protocol: what the drain / fill threads see and do.  No HIP types here,
+// so this half can be built and run (and raced under a thread sanitizer) without a GPU.
+#pragma once
+#include <atomic>
+#include <condition_variable>
+#include <cstdint>
+#include <mutex>
+#include <thread>
+#include <vector>
+
+#include "internal.hpp"
+
+namespace nixie {
+
+struct HostSide {
+    const Layout *L = nullptr;
+    uint8_t *ring = nullptr;                          // host view of the pinned ring, outgoing sub-ring first
+    uint64_t *wait[2] = {nullptr, nullptr};           // host-written, packed: out released[s], in filled[s]
+    const uint64_t *post[2] = {nullptr, nullptr};     // GPU-written, kFlagStride apart: out ready[s], in freed[s]
+    uint32_t *abort_word = nullptr;                   // host-written, the kernel's pump relays it
+    const uint32_t *status_word = nullptr;            // GPU-written: kGpuOk or why the kernel gave up
+    uint64_t timeout_ns = 0;
+    uint32_t threads[2] = {0, 0};                     // drain, fill
+
+    std::atomic<uint64_t> next_chunk[2];              // incoming: next chunk to claim
+    std::atomic<uint64_t> done_chunks[2];             // outgoing: chunks that reached pageable memory
+    std::atomic<uint64_t> wait_ns[2];                 // summed idle time per direction
+    std::atomic<uint64_t> end_ns[2];                  // latest completion time seen per direction
+    std::atomic<int> error{0};
+    std::atomic<uint32_t> abort_local{0};
+
+    void begin_pass();                                // flags must already be cleared
+    void raise_abort(int err);
+    void run_drain(uint32_t idx);                     // ring -> pageable, thread idx of threads[0]
+    void run_fill(uint32_t idx);                      // pageable -> ring, thread idx of threads[1]
+};
+
+// The parked threads.  run_pass wakes them for the directions in mask and returns when all of
+// them are done (finished, aborted or timed out).
+class HostCrew {
+public:
+    void start(HostSide *hs);
+    void run_pass(uint32_t mask);
+    void stop();
+    ~HostCrew() { stop(); }
+
+private:
+    void worker(int dir, uint32_t idx);
+    HostSide *hs_ = nullptr;
+    std::vector<std::thread> threads_;
+    std::mutex mu_;
+    std::condition_variable cv_go_, cv_done_;
+    uint64_t epoch_ = 0;
+    uint32_t running_ = 0, mask_ = 0;
+    bool quit_ = false;
+};
+
+}  // namespace nixie

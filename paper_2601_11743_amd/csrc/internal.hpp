@@ -72,6 +72,7 @@ struct SwapArgs {
     uint64_t timeout_ticks;      // 100 MHz wall clock
     uint32_t *gathered_prefix;   // device memory: number of leading outgoing chunks that have left HBM
     uint32_t track_prefix;       // 1: in-place switch with both directions running in this launch
+    uint32_t xcd_mask;           // 0 = every XCD takes part
 };
 
 struct HashDesc { uint64_t ptr; uint64_t bytes; uint64_t first_tile; };

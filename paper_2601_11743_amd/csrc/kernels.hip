@@ -151,8 +151,10 @@ __device__ void run_direction(const SwapArgs &a) {
     const uint32_t waves_per_wg = kWgThreads / 64;
     const uint32_t total_units = D.n_chunks * D.team;
     uint64_t stall = 0;
+    // XCC_ID hardware register, bits 3:0 = the XCD this workgroup runs on
+    const bool sit_out = a.xcd_mask && !((a.xcd_mask >> (__builtin_amdgcn_s_getreg((3 << 11) | 20) & 7u)) & 1u);
 
-    for (;;) {
+    for (; !sit_out;) {
         if (tid == 0) {
             uint32_t cs = 0;
             const uint32_t u = __hip_atomic_fetch_add(D.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -8,7 +8,6 @@
 // copied by several threads.  "Hierarchical Memory": after the switch each working set has
 // exactly one copy -- A in pageable memory, B in HBM -- and the pinned ring holds nothing.
 #include <hip/hip_runtime.h>
-#include <immintrin.h>
 #include <time.h>
 
 #include <atomic>
@@ -19,6 +18,7 @@
 #include <thread>
 
 #include "internal.hpp"
+#include "hostside.hpp"
 
 using namespace nixie;
 
@@ -41,8 +41,6 @@ inline uint64_t now_ns() {
         }                                                \
     } while (0)
 
-inline uint64_t load_acq(const uint64_t *p) { return __atomic_load_n(p, __ATOMIC_ACQUIRE); }
-inline void store_rel(uint64_t *p, uint64_t v) { __atomic_store_n(p, v, __ATOMIC_RELEASE); }
 
 }  // namespace
 
@@ -59,8 +57,6 @@ struct nixie_plan {
     uint8_t *ring_h = nullptr, *ring_d = nullptr;
     uint64_t *ctrl_h = nullptr, *ctrl_d = nullptr;
     size_t ctrl_bytes = 0;
-    uint64_t *wait_h[2] = {nullptr, nullptr}, *post_h[2] = {nullptr, nullptr};  // host views of the flag arrays
-    uint32_t *abort_h = nullptr, *status_h = nullptr;
 
     // device memory (descriptors and counters only, never payload)
     DevSeg *segs_d[2] = {nullptr, nullptr};
@@ -72,178 +68,16 @@ struct nixie_plan {
     uint64_t *hashes_d = nullptr;
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
 
-    // workers
-    std::vector<std::thread> threads;
-    std::mutex mu;
-    std::condition_variable cv_go, cv_done;
-    uint64_t epoch = 0;
-    bool quit = false;
-    uint32_t running = 0;
-
-    // state of the switch in flight
-    std::mutex switch_mu;
-    uint32_t pass_mask = 0;
-    uint64_t timeout_ns = 0;
-    std::atomic<uint64_t> next_chunk[2];
-    std::atomic<uint64_t> done_chunks[2];
-    std::atomic<int> error{0};
-    std::atomic<uint32_t> abort_local{0};
-    std::atomic<uint64_t> wait_ns[2];
-    std::atomic<uint64_t> end_ns[2];   // latest completion time seen per direction
+    HostSide hs;           // flags, ring and counters as the host threads see them
+    HostCrew crew;         // the parked drain / fill threads
+    std::mutex switch_mu;  // one switch at a time
 };
 
 namespace {
 
-void raise_abort(nixie_plan_t *p, int err) {
-    int expected = 0;
-    p->error.compare_exchange_strong(expected, err);
-    p->abort_local.store(1, std::memory_order_release);
-    __atomic_store_n(p->abort_h, 1u, __ATOMIC_RELEASE);   // the kernel polls this word
-}
-
-// Idle bookkeeping of a host thread that scans its slots: aborts the switch when nothing has
-// moved for longer than the bound, or when the kernel reported that it gave up.
-struct IdleWatch {
-    nixie_plan_t *p;
-    int dir;
-    uint64_t idle_since = 0;
-    uint32_t spins = 0;
-    // call after a scan that made no progress; false = stop
-    bool idle() {
-        _mm_pause();
-        if (idle_since == 0) idle_since = now_ns();
-        if ((++spins & 63u) != 0) return true;
-        if (p->abort_local.load(std::memory_order_acquire)) return false;
-        if (__atomic_load_n(p->status_h, __ATOMIC_ACQUIRE) != kGpuOk || now_ns() - idle_since > p->timeout_ns) {
-            raise_abort(p, NIXIE_ETIMEOUT);
-            return false;
-        }
-        return true;
-    }
-    void progressed() {
-        if (idle_since) p->wait_ns[dir].fetch_add(now_ns() - idle_since, std::memory_order_relaxed);
-        idle_since = 0;
-    }
-};
-
-void note_end(nixie_plan_t *p, int dir) {
-    uint64_t t = now_ns(), cur = p->end_ns[dir].load(std::memory_order_relaxed);
-    while (cur < t && !p->end_ns[dir].compare_exchange_weak(cur, t, std::memory_order_relaxed)) {}
-}
-
-// ring -> pageable.  Consumer of the outgoing direction.  Thread idx owns slots idx, idx + T, ...
-// and drains whichever of them the GPU has marked ready (ready[s] = chunk id + 1), in any order.
-void run_drain(nixie_plan_t *p, uint32_t idx, uint32_t T) {
-    const DirLayout &D = p->L.dir[0];
-    const uint32_t flags = p->L.opts.flags;
-    const uint64_t n = D.chunks.size(), S = p->L.slot_bytes;
-    const bool plain = flags & NIXIE_HOST_PLAIN_MEMCPY;
-    std::vector<uint64_t> last(D.slots, 0);
-    IdleWatch watch{p, 0};
-    while (p->done_chunks[0].load(std::memory_order_acquire) < n) {
-        bool moved = false;
-        for (uint64_t slot = idx; slot < D.slots; slot += T) {
-            const uint64_t v = load_acq(p->post_h[0] + slot * kFlagStride);
-            if (v == last[slot]) continue;
-            last[slot] = v;
-            const uint64_t k = v - 1;
-            if (k >= n) { raise_abort(p, NIXIE_EINVAL); return; }
-            if (!(flags & NIXIE_DIAG_RING_ONLY)) {
-                const nixie_chunk_t &c = D.chunks[k];
-                const uint8_t *src = p->ring_h + slot * S;
-                for (uint64_t q = c.seg_begin; q < c.seg_begin + c.seg_count; q++) {
-                    const nixie_segment_t &sg = D.segs[q];
-                    if (plain) std::memcpy((void *)(uintptr_t)sg.host_addr, src + sg.slot_off, sg.len);
-                    else copy_stream((void *)(uintptr_t)sg.host_addr, src + sg.slot_off, sg.len);
-                }
-                _mm_sfence();
-            }
-            if (!(flags & NIXIE_DIAG_STALL_DRAIN)) store_rel(p->wait_h[0] + slot, k + 2);   // released
-            p->done_chunks[0].fetch_add(1, std::memory_order_acq_rel);
-            moved = true;
-        }
-        if (moved) watch.progressed();
-        else if (!watch.idle()) return;
-    }
-    watch.progressed();
-    note_end(p, 0);
-}
-
-// pageable -> ring.  Producer of the incoming direction.  Thread idx owns slots idx, idx + T, ...;
-// whenever one of them is free it claims the next chunk, loads it and publishes filled[s] = id + 1.
-// A slot is free again when the GPU has written freed[s] = id + 1 for the chunk it held.
-void run_fill(nixie_plan_t *p, uint32_t idx, uint32_t T) {
-    const DirLayout &D = p->L.dir[1];
-    const uint32_t flags = p->L.opts.flags;
-    const uint64_t n = D.chunks.size(), S = p->L.slot_bytes;
-    const bool plain = flags & NIXIE_HOST_PLAIN_MEMCPY;
-    std::vector<uint64_t> pending(D.slots, 0);
-    uint64_t outstanding = 0;
-    bool claiming = true;
-    IdleWatch watch{p, 1};
-    for (;;) {
-        bool moved = false;
-        for (uint64_t slot = idx; slot < D.slots; slot += T) {
-            if (pending[slot]) {
-                if (load_acq(p->post_h[1] + slot * kFlagStride) != pending[slot]) continue;
-                pending[slot] = 0;
-                outstanding--;
-                moved = true;
-            }
-            if (!claiming) continue;
-            const uint64_t k = p->next_chunk[1].fetch_add(1, std::memory_order_relaxed);
-            if (k >= n) { claiming = false; continue; }
-            if (!(flags & NIXIE_DIAG_RING_ONLY)) {
-                const nixie_chunk_t &c = D.chunks[k];
-                uint8_t *dst = p->ring_h + ((uint64_t)p->L.dir[0].slots + slot) * S;
-                for (uint64_t q = c.seg_begin; q < c.seg_begin + c.seg_count; q++) {
-                    const nixie_segment_t &sg = D.segs[q];
-                    if (plain) std::memcpy(dst + sg.slot_off, (const void *)(uintptr_t)sg.host_addr, sg.len);
-                    else copy_stream(dst + sg.slot_off, (const void *)(uintptr_t)sg.host_addr, sg.len);
-                }
-                _mm_sfence();
-            }
-            store_rel(p->wait_h[1] + slot, k + 1);   // filled
-            pending[slot] = k + 1;
-            outstanding++;
-            moved = true;
-        }
-        if (!claiming && outstanding == 0) break;
-        if (moved) watch.progressed();
-        else if (!watch.idle()) return;
-    }
-    watch.progressed();
-    note_end(p, 1);   // this thread's last chunk has reached HBM; the latest such time is "B ready"
-}
-
-void worker_main(nixie_plan_t *p, int dir, uint32_t idx) {
-    uint64_t seen = 0;
-    for (;;) {
-        {
-            std::unique_lock<std::mutex> lk(p->mu);
-            p->cv_go.wait(lk, [&] { return p->quit || p->epoch != seen; });
-            if (p->quit) return;
-            seen = p->epoch;
-        }
-        if (p->pass_mask & (1u << dir)) {
-            if (dir == 0) run_drain(p, idx, p->info.drain_threads);
-            else run_fill(p, idx, p->info.fill_threads);
-        }
-        {
-            std::lock_guard<std::mutex> lk(p->mu);
-            if (--p->running == 0) p->cv_done.notify_all();
-        }
-    }
-}
-
 void destroy_plan(nixie_plan_t *p) {
     if (!p) return;
-    {
-        std::lock_guard<std::mutex> lk(p->mu);
-        p->quit = true;
-    }
-    p->cv_go.notify_all();
-    for (auto &t : p->threads) t.join();
+    p->crew.stop();
     int prev = -1;
     if (hipGetDevice(&prev) == hipSuccess && p->device >= 0 && prev != p->device) (void)hipSetDevice(p->device);
     if (p->ev0) (void)hipEventDestroy(p->ev0);
@@ -292,12 +126,12 @@ int create_plan(nixie_plan_t *p) {
         std::memset(p->ctrl_h, 0, p->ctrl_bytes);
     }
     uint64_t *c = p->ctrl_h;
-    p->wait_h[0] = c;                                   c += wait_flag_words(L.dir[0].slots);
-    p->wait_h[1] = c;                                   c += wait_flag_words(L.dir[1].slots);
-    p->post_h[0] = c;                                   c += (size_t)L.dir[0].slots * kFlagStride;
-    p->post_h[1] = c;                                   c += (size_t)L.dir[1].slots * kFlagStride;
-    p->abort_h = (uint32_t *)c;                         c += kFlagStride;
-    p->status_h = (uint32_t *)c;                        c += kFlagStride;
+    p->hs.wait[0] = c;                                   c += wait_flag_words(L.dir[0].slots);
+    p->hs.wait[1] = c;                                   c += wait_flag_words(L.dir[1].slots);
+    p->hs.post[0] = c;                                   c += (size_t)L.dir[0].slots * kFlagStride;
+    p->hs.post[1] = c;                                   c += (size_t)L.dir[1].slots * kFlagStride;
+    p->hs.abort_word = (uint32_t *)c;                         c += kFlagStride;
+    p->hs.status_word = (uint32_t *)c;                        c += kFlagStride;
     if ((size_t)(c - p->ctrl_h) * 8 != p->ctrl_bytes) return NIXIE_EINVAL;
     (void)n_slots;
 
@@ -351,8 +185,11 @@ int create_plan(nixie_plan_t *p) {
     NIXIE_HIP(hipEventCreate(&p->ev0));
     NIXIE_HIP(hipEventCreate(&p->ev1));
 
-    for (uint32_t t = 0; t < p->info.drain_threads; t++) p->threads.emplace_back(worker_main, p, 0, t);
-    for (uint32_t t = 0; t < p->info.fill_threads; t++) p->threads.emplace_back(worker_main, p, 1, t);
+    p->hs.L = &p->L;
+    p->hs.ring = p->ring_h;
+    p->hs.threads[0] = p->info.drain_threads;
+    p->hs.threads[1] = p->info.fill_threads;
+    p->crew.start(&p->hs);
     return NIXIE_OK;
 }
 
@@ -360,14 +197,7 @@ int create_plan(nixie_plan_t *p) {
 int run_pass(nixie_plan_t *p, uint32_t mask, hipStream_t stream, nixie_stats_t *st, uint64_t t_entry) {
     const Layout &L = p->L;
     std::memset(p->ctrl_h, 0, p->ctrl_bytes);
-    p->abort_local.store(0);
-    for (int x = 0; x < 2; x++) {
-        p->next_chunk[x].store(0);
-        p->done_chunks[x].store(0);
-        p->wait_ns[x].store(0);
-    }
-    for (uint32_t sl = 0; sl < L.dir[0].slots; sl++) p->wait_h[0][sl] = 1;   // every outgoing slot starts released
-    std::atomic_thread_fence(std::memory_order_seq_cst);
+    p->hs.begin_pass();   // counters to zero, every outgoing slot marked released
 
     SwapArgs a{};
     for (int x = 0; x < 2; x++) {
@@ -377,7 +207,7 @@ int run_pass(nixie_plan_t *p, uint32_t mask, hipStream_t stream, nixie_stats_t *
         d.segs = p->segs_d[x];
         d.chunks = p->chunks_d[x];
         d.ring = p->ring_d + (x ? (uint64_t)L.dir[0].slots * L.slot_bytes : 0);
-        const size_t wait_off = (size_t)(p->wait_h[x] - p->ctrl_h), post_off = (size_t)(p->post_h[x] - p->ctrl_h);
+        const size_t wait_off = (size_t)(p->hs.wait[x] - p->ctrl_h), post_off = (size_t)(p->hs.post[x] - p->ctrl_h);
         d.host_flags = p->ctrl_d + wait_off;
         d.post_flags = p->ctrl_d + post_off;
         d.ticket = p->counters_d + x;
@@ -393,11 +223,12 @@ int run_pass(nixie_plan_t *p, uint32_t mask, hipStream_t stream, nixie_stats_t *
         d.wgs = on ? (x ? p->info.scatter_wgs : p->info.gather_wgs) : 0;
     }
     a.slot_bytes = L.slot_bytes;
-    a.host_abort = (const uint32_t *)(p->ctrl_d + (size_t)((uint64_t *)p->abort_h - p->ctrl_h));
-    a.gpu_status = (uint32_t *)(p->ctrl_d + (size_t)((uint64_t *)p->status_h - p->ctrl_h));
+    a.host_abort = (const uint32_t *)(p->ctrl_d + (size_t)((uint64_t *)p->hs.abort_word - p->ctrl_h));
+    a.gpu_status = (uint32_t *)(p->ctrl_d + (size_t)((uint64_t *)p->hs.status_word - p->ctrl_h));
     a.dev_abort = p->counters_d + 2;
-    a.timeout_ticks = p->timeout_ns / 10;   // wall clock runs at 100 MHz
+    a.timeout_ticks = p->hs.timeout_ns / 10;   // wall clock runs at 100 MHz
     a.gathered_prefix = p->counters_d + 10;
+    a.xcd_mask = L.opts.xcd_mask & 0xFFu;
     // when the directions run one after the other, everything has left HBM before the restore starts
     a.track_prefix = ((L.opts.flags & NIXIE_IN_PLACE) && a.d[0].wgs && a.d[1].wgs) ? 1u : 0u;
 
@@ -406,20 +237,19 @@ int run_pass(nixie_plan_t *p, uint32_t mask, hipStream_t stream, nixie_stats_t *
     NIXIE_HIP(hipEventRecord(p->ev0, stream));
     e = nixie_launch_swap(a, stream);
     if (e) { t_last_hip_error = e; return NIXIE_EHIP; }
-    NIXIE_HIP(hipEventRecord(p->ev1, stream));
+    {   // From here on the kernel may be running: never return before it has drained, or the caller
+        // could destroy the plan (ring, flags, descriptors) underneath it.
+        hipError_t re = hipEventRecord(p->ev1, stream);
+        if (re != hipSuccess) {
+            t_last_hip_error = (int)re;
+            p->hs.raise_abort(NIXIE_EHIP);         // the pump relays the abort word to every workgroup
+            (void)hipStreamSynchronize(stream);
+            return NIXIE_EHIP;
+        }
+    }
     if (st && st->ns_launch == 0) st->ns_launch = now_ns() - t_entry;
 
-    {
-        std::lock_guard<std::mutex> lk(p->mu);
-        p->pass_mask = mask;
-        p->running = (uint32_t)p->threads.size();
-        p->epoch++;
-    }
-    p->cv_go.notify_all();
-    {
-        std::unique_lock<std::mutex> lk(p->mu);
-        p->cv_done.wait(lk, [&] { return p->running == 0; });
-    }
+    p->crew.run_pass(mask);   // wake the drain / fill threads and wait until they are done
     hipError_t se = hipStreamSynchronize(stream);
     if (se != hipSuccess) { t_last_hip_error = (int)se; return NIXIE_EHIP; }
 
@@ -430,14 +260,14 @@ int run_pass(nixie_plan_t *p, uint32_t mask, hipStream_t stream, nixie_stats_t *
         NIXIE_HIP(hipMemcpy(stall, p->counters_d + 4, sizeof(stall), hipMemcpyDeviceToHost));
         st->gather_stall_ticks += stall[0];
         st->scatter_stall_ticks += stall[1];
-        st->drain_wait_ns += p->wait_ns[0].load();
-        st->fill_wait_ns += p->wait_ns[1].load();
+        st->drain_wait_ns += p->hs.wait_ns[0].load();
+        st->fill_wait_ns += p->hs.wait_ns[1].load();
         st->kernels++;
-        const uint32_t gs = __atomic_load_n(p->status_h, __ATOMIC_ACQUIRE);
+        const uint32_t gs = __atomic_load_n(p->hs.status_word, __ATOMIC_ACQUIRE);
         if (gs) st->gpu_status = gs;
     }
-    int err = p->error.load();
-    if (!err && __atomic_load_n(p->status_h, __ATOMIC_ACQUIRE) != kGpuOk) err = NIXIE_ETIMEOUT;
+    int err = p->hs.error.load();
+    if (!err && __atomic_load_n(p->hs.status_word, __ATOMIC_ACQUIRE) != kGpuOk) err = NIXIE_ETIMEOUT;
     return err;
 }
 
@@ -526,10 +356,10 @@ int nixie_switch(nixie_plan_t *p, void *hip_stream, nixie_stats_t *stats) {
     nixie_stats_t st{};
     st.bytes_out = p->L.dir[0].bytes;
     st.bytes_in = p->L.dir[1].bytes;
-    p->timeout_ns = (uint64_t)(p->L.opts.timeout_ms ? p->L.opts.timeout_ms : 30000u) * 1000000ull;
-    p->error.store(0);
-    p->end_ns[0].store(0);
-    p->end_ns[1].store(0);
+    p->hs.timeout_ns = (uint64_t)(p->L.opts.timeout_ms ? p->L.opts.timeout_ms : 30000u) * 1000000ull;
+    p->hs.error.store(0);
+    p->hs.end_ns[0].store(0);
+    p->hs.end_ns[1].store(0);
 
     int rc = NIXIE_OK;
     const bool both = !p->L.dir[0].chunks.empty() && !p->L.dir[1].chunks.empty();
@@ -541,8 +371,8 @@ int nixie_switch(nixie_plan_t *p, void *hip_stream, nixie_stats_t *stats) {
     }
     const uint64_t t_end = now_ns();
     st.ns_total = t_end - t_entry;
-    st.ns_out_done = p->end_ns[0].load() > t_entry ? p->end_ns[0].load() - t_entry : 0;
-    st.ns_in_done = p->end_ns[1].load() > t_entry ? p->end_ns[1].load() - t_entry : 0;
+    st.ns_out_done = p->hs.end_ns[0].load() > t_entry ? p->hs.end_ns[0].load() - t_entry : 0;
+    st.ns_in_done = p->hs.end_ns[1].load() > t_entry ? p->hs.end_ns[1].load() - t_entry : 0;
     if (stats) *stats = st;
     return rc;
 }

@@ -34,7 +34,7 @@ class _Opts(C.Structure):
     _fields_ = [("slot_bytes", C.c_uint64), ("out_slots", C.c_uint32), ("order", C.c_uint32),
                 ("gather_wgs", C.c_uint32), ("scatter_wgs", C.c_uint32), ("team", C.c_uint32),
                 ("drain_threads", C.c_uint32), ("fill_threads", C.c_uint32),
-                ("timeout_ms", C.c_uint32), ("flags", C.c_uint32)]
+                ("timeout_ms", C.c_uint32), ("flags", C.c_uint32), ("xcd_mask", C.c_uint32)]
 
 
 class _Info(C.Structure):

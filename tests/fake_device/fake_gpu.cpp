@@ -1,0 +1,279 @@
+// CPU stand-in for the device half of the slot protocol, for tests only.
+//
+// Builds the library's planner, streaming copies and host half (drain / fill threads, watchdog,
+// crew) for the CPU, and drives them against a model of what the swap kernel does: one pump
+// thread per direction that turns host-written flags into chunk -> slot assignments, and worker
+// threads that take tickets, wait for their chunk's slot, copy, meet on the arrive counter and
+// publish the GPU-written flag.  "Device memory" is ordinary memory.  Meant to run under a
+// thread sanitizer: every hand-over that the real hardware orders physically is an
+// acquire/release pair here, so a missing hand-over in the host half shows up as a data race.
+//
+// usage: fake_gpu <scenario> [seed]
+//   swap        bidirectional switch, mixed sizes, small ring; result must equal memcpy
+//   in_place    incoming ranges reuse the outgoing "device" memory; evict-before-overwrite
+//   stall       the host withholds credits (NIXIE_DIAG_STALL_DRAIN): must end with NIXIE_ETIMEOUT
+//   gpu_quits   the device reports that it gave up: the host must stop with NIXIE_ETIMEOUT
+//   dead_gpu    the device never starts: the host watchdog must fire
+#include <atomic>
+#include <chrono>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <string>
+#include <thread>
+#include <vector>
+
+#include "hostside.hpp"
+
+using namespace nixie;
+
+namespace {
+
+uint64_t rng_state = 1;
+uint64_t rnd() {
+    rng_state += 0x9E3779B97F4A7C15ull;
+    uint64_t z = rng_state;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+struct FakeGpu {
+    const Layout *L;
+    uint8_t *ring;
+    const uint64_t *host_flags[2];   // host-written (packed)
+    uint64_t *post[2];               // "GPU"-written (kFlagStride apart)
+    const uint32_t *host_abort;
+    uint32_t *status;
+    uint32_t team[2], wgs[2];
+    bool in_place = false;
+    bool never_start = false, quit_early = false;
+
+    std::vector<std::atomic<uint32_t>> chunk_slot[2], arrive[2];
+    std::atomic<uint32_t> ticket[2], exited[2], dev_abort{0}, gathered_prefix{0};
+    std::vector<std::thread> threads;
+
+    void copy_unit(int dir, uint32_t k, uint32_t part, uint32_t slot) {
+        const DirLayout &D = L->dir[dir];
+        const nixie_chunk_t &c = D.chunks[k];
+        uint8_t *base = ring + ((dir ? L->dir[0].slots : 0) + (uint64_t)slot) * L->slot_bytes;
+        const uint32_t n_tiles = (c.used_bytes + kTileBytes - 1) / kTileBytes;
+        for (uint32_t t = part; t < n_tiles; t += team[dir]) {
+            const uint32_t t0 = t * kTileBytes, t1 = std::min(t0 + kTileBytes, c.used_bytes);
+            for (uint64_t q = c.seg_begin; q < c.seg_begin + c.seg_count; q++) {
+                const nixie_segment_t &s = D.segs[q];
+                const uint32_t x0 = std::max(s.slot_off, t0), x1 = std::min(s.slot_off + s.len, t1);
+                if (x0 >= x1) continue;
+                uint8_t *dev = (uint8_t *)(uintptr_t)(s.dev_addr + (x0 - s.slot_off));
+                if (dir == 0) std::memcpy(base + x0, dev, x1 - x0);
+                else std::memcpy(dev, base + x0, x1 - x0);
+            }
+        }
+    }
+
+    void worker(int dir) {
+        const DirLayout &D = L->dir[dir];
+        const uint32_t total = (uint32_t)D.chunks.size() * team[dir];
+        for (;;) {
+            const uint32_t u = ticket[dir].fetch_add(1, std::memory_order_relaxed);
+            if (u >= total || dev_abort.load(std::memory_order_acquire)) break;
+            const uint32_t k = u / team[dir], part = u % team[dir];
+            uint32_t cs;
+            while ((cs = chunk_slot[dir][k].load(std::memory_order_acquire)) == 0) {
+                if (dev_abort.load(std::memory_order_acquire)) break;
+                std::this_thread::yield();
+            }
+            if (cs == 0) break;
+            if (dir == 1 && in_place) {
+                bool stop = false;
+                while (gathered_prefix.load(std::memory_order_acquire) < D.chunks[k].dep_out) {
+                    if (dev_abort.load(std::memory_order_acquire)) { stop = true; break; }
+                    std::this_thread::yield();
+                }
+                if (stop) break;
+            }
+            copy_unit(dir, k, part, cs - 1);
+            const uint32_t old = arrive[dir][k].fetch_add(1, std::memory_order_acq_rel);
+            if (old == team[dir] - 1)
+                __atomic_store_n(post[dir] + (size_t)(cs - 1) * kFlagStride, (uint64_t)k + 1, __ATOMIC_RELEASE);
+        }
+        exited[dir].fetch_add(1, std::memory_order_release);
+    }
+
+    void pump(int dir) {
+        const DirLayout &D = L->dir[dir];
+        if (wgs[dir] == 0) return;
+        std::vector<uint64_t> seen(D.slots, 0);
+        uint32_t next = 0, prefix = 0;
+        for (;;) {
+            for (uint32_t s = 0; s < D.slots; s++) {
+                const uint64_t v = __atomic_load_n(host_flags[dir] + s, __ATOMIC_ACQUIRE);
+                if (v == seen[s]) continue;
+                seen[s] = v;
+                const uint64_t k = dir == 0 ? next++ : v - 1;
+                if (k < D.chunks.size()) chunk_slot[dir][k].store(s + 1, std::memory_order_release);
+            }
+            if (dir == 0 && in_place) {
+                while (prefix < D.chunks.size() && arrive[0][prefix].load(std::memory_order_acquire) >= team[0]) prefix++;
+                gathered_prefix.store(prefix, std::memory_order_release);
+            }
+            if (__atomic_load_n(host_abort, __ATOMIC_ACQUIRE) && !dev_abort.load()) {
+                dev_abort.store(1, std::memory_order_release);
+                __atomic_store_n(status, (uint32_t)kGpuSawAbort, __ATOMIC_RELEASE);
+            }
+            if (exited[dir].load(std::memory_order_acquire) >= wgs[dir]) break;
+            std::this_thread::yield();
+        }
+    }
+
+    void launch() {
+        for (int x = 0; x < 2; x++) {
+            const size_t n = L->dir[x].chunks.size();
+            chunk_slot[x] = std::vector<std::atomic<uint32_t>>(n);
+            arrive[x] = std::vector<std::atomic<uint32_t>>(n);
+            for (size_t i = 0; i < n; i++) { chunk_slot[x][i].store(0); arrive[x][i].store(0); }
+            ticket[x].store(0);
+            exited[x].store(0);
+            if (n == 0) wgs[x] = 0;
+        }
+        if (never_start) return;
+        if (quit_early) {   // the kernel hit its own wait bound
+            __atomic_store_n(status, (uint32_t)kGpuTimeout, __ATOMIC_RELEASE);
+            return;
+        }
+        for (int x = 0; x < 2; x++) {
+            if (wgs[x]) threads.emplace_back(&FakeGpu::pump, this, x);
+            for (uint32_t w = 0; w < wgs[x]; w++) threads.emplace_back(&FakeGpu::worker, this, x);
+        }
+    }
+    void join() { for (auto &t : threads) t.join(); threads.clear(); }
+};
+
+struct Arena {
+    std::vector<uint8_t> host;
+    std::vector<nixie_alloc_t> rows;
+};
+
+uint64_t arena_bytes(const std::vector<uint64_t> &sizes) {
+    uint64_t total = 256;
+    for (uint64_t b : sizes) total += b + 64;
+    return total;
+}
+
+// Allocations of the given sizes inside the "device" arena dev, 64 B gaps, bases skewed by `skew`
+// bytes; the resident side gets content f(seed, byte index, size).
+void build(Arena &a, const std::vector<uint64_t> &sizes, uint64_t seed, bool resident_dev, uint8_t *dev, uint64_t skew) {
+    a.host.assign(arena_bytes(sizes), 0xC3);
+    uint64_t off = 64 + skew;
+    for (uint64_t b : sizes) {
+        a.rows.push_back(nixie_alloc_t{dev + off, a.host.data() + off, b});
+        uint8_t *src = resident_dev ? dev + off : a.host.data() + off;
+        for (uint64_t i = 0; i < b; i++) src[i] = (uint8_t)((seed * 131 + i * 7 + (i >> 8) + b) & 0xFF);
+        off += b + 64;
+    }
+}
+
+int run(const std::string &scenario, uint64_t seed) {
+    rng_state = seed * 7919 + 1;
+    const uint64_t S = 64 << 10;
+    std::vector<uint64_t> sa, sb;
+    for (int i = 0; i < 14; i++) sa.push_back(1 + rnd() % (3 * S));
+    for (int i = 0; i < 11; i++) sb.push_back(1 + rnd() % (4 * S));
+    sa.push_back(0); sa.push_back(S); sa.push_back(5 * S + 1);
+    sb.push_back(S - 1); sb.push_back(15);
+    const bool in_place = scenario == "in_place";
+
+    // in place: B's device ranges lie in the same "device" arena as A's
+    std::vector<uint8_t> dev_a(std::max(arena_bytes(sa), in_place ? arena_bytes(sb) : 0) + 64, 0xC3);
+    std::vector<uint8_t> dev_b(in_place ? 0 : arena_bytes(sb) + 64, 0xC3);
+    Arena A, B;
+    build(A, sa, seed, true, dev_a.data(), seed % 16);
+    build(B, sb, seed + 1, false, in_place ? dev_a.data() : dev_b.data(), (seed * 5) % 16);
+    // expectation by plain memcpy, in definition order: all of A out, then B in
+    std::vector<std::vector<uint8_t>> want_a, want_b;
+    for (auto &r : A.rows) want_a.emplace_back((uint8_t *)r.dev_ptr, (uint8_t *)r.dev_ptr + r.bytes);
+    for (auto &r : B.rows) want_b.emplace_back((uint8_t *)r.host_ptr, (uint8_t *)r.host_ptr + r.bytes);
+
+    nixie_opts_t o{};
+    o.slot_bytes = S;
+    o.drain_threads = 3;
+    o.fill_threads = 2;
+    o.timeout_ms = (scenario == "swap" || scenario == "in_place") ? 20000 : 300;
+    if (in_place) o.flags |= NIXIE_IN_PLACE;
+    if (scenario == "stall") o.flags |= NIXIE_DIAG_STALL_DRAIN;
+    nixie_table_t ta{A.rows.data(), A.rows.size()}, tb{B.rows.data(), B.rows.size()};
+    Layout L;
+    const uint64_t ring_bytes = 12 * S;
+    int rc = build_layout(&ta, &tb, ring_bytes, &o, L);
+    if (rc) { std::printf("build_layout failed %d\n", rc); return 2; }
+    nixie_plan_info_t info;
+    fill_info(L, &info);
+
+    std::vector<uint8_t> ring(info.pinned_ring_bytes + 64);
+    std::vector<uint64_t> ctrl(info.pinned_ctrl_bytes / 8 + 8, 0);
+    HostSide hs;
+    uint64_t *c = ctrl.data();
+    hs.wait[0] = c; c += wait_flag_words(L.dir[0].slots);
+    hs.wait[1] = c; c += wait_flag_words(L.dir[1].slots);
+    uint64_t *post0 = c; c += (size_t)L.dir[0].slots * kFlagStride;
+    uint64_t *post1 = c; c += (size_t)L.dir[1].slots * kFlagStride;
+    hs.post[0] = post0; hs.post[1] = post1;
+    hs.abort_word = (uint32_t *)c; c += kFlagStride;
+    uint32_t *status = (uint32_t *)c;
+    hs.status_word = status;
+    hs.L = &L;
+    hs.ring = ring.data();
+    hs.threads[0] = info.drain_threads;
+    hs.threads[1] = info.fill_threads;
+    hs.timeout_ns = (uint64_t)o.timeout_ms * 1000000ull;
+    hs.error.store(0);
+    hs.end_ns[0].store(0); hs.end_ns[1].store(0);
+    HostCrew crew;
+    crew.start(&hs);
+
+    FakeGpu gpu;
+    gpu.L = &L; gpu.ring = ring.data();
+    gpu.host_flags[0] = hs.wait[0]; gpu.host_flags[1] = hs.wait[1];
+    gpu.post[0] = post0; gpu.post[1] = post1;
+    gpu.host_abort = hs.abort_word; gpu.status = status;
+    gpu.team[0] = info.team_out ? info.team_out : 1; gpu.team[1] = info.team_in ? info.team_in : 1;
+    gpu.wgs[0] = 5; gpu.wgs[1] = 3;
+    gpu.in_place = in_place;
+    gpu.never_start = scenario == "dead_gpu";
+    gpu.quit_early = scenario == "gpu_quits";
+
+    int fails = 0;
+    for (int round = 0; round < (scenario == "swap" ? 2 : 1); round++) {   // a plan is reusable
+        std::fill(ctrl.begin(), ctrl.end(), 0);
+        hs.begin_pass();
+        gpu.dev_abort.store(0); gpu.gathered_prefix.store(0);
+        const auto t0 = std::chrono::steady_clock::now();
+        gpu.launch();
+        crew.run_pass(3u);
+        gpu.join();
+        const double ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+        const int err = hs.error.load();
+        if (scenario == "swap" || scenario == "in_place") {
+            if (err) { std::printf("switch failed: %d\n", err); fails++; }
+            for (size_t i = 0; i < A.rows.size(); i++)
+                if (std::memcmp(A.rows[i].host_ptr, want_a[i].data(), A.rows[i].bytes)) { std::printf("evicted allocation %zu differs\n", i); fails++; }
+            for (size_t i = 0; i < B.rows.size(); i++)
+                if (std::memcmp(B.rows[i].dev_ptr, want_b[i].data(), B.rows[i].bytes)) { std::printf("restored allocation %zu differs\n", i); fails++; }
+            if (hs.done_chunks[0].load() != L.dir[0].chunks.size()) { std::printf("drained %llu of %zu chunks\n", (unsigned long long)hs.done_chunks[0].load(), L.dir[0].chunks.size()); fails++; }
+        } else {
+            if (err != NIXIE_ETIMEOUT) { std::printf("expected NIXIE_ETIMEOUT, got %d\n", err); fails++; }
+            if (ms > 5000) { std::printf("took %.0f ms to give up\n", ms); fails++; }
+        }
+        std::printf("%s seed %llu round %d: %zu + %zu chunks, %.1f ms, error %d\n", scenario.c_str(), (unsigned long long)seed, round,
+                    L.dir[0].chunks.size(), L.dir[1].chunks.size(), ms, err);
+    }
+    crew.stop();
+    return fails ? 1 : 0;
+}
+
+}  // namespace
+
+int main(int argc, char **argv) {
+    if (argc < 2) { std::printf("usage: fake_gpu <swap|in_place|stall|gpu_quits|dead_gpu> [seed]\n"); return 2; }
+    return run(argv[1], argc > 2 ? std::strtoull(argv[2], nullptr, 10) : 1);
+}

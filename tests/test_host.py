@@ -247,3 +247,18 @@ def test_in_place_dependencies(nx):
         nx.Layout(ra + [(ra[0][0] + 1, 0x2000_0000_0000, 2)], rb, 16 * S, nx.Opts(slot_bytes=S, flags=nx.IN_PLACE))
     with pytest.raises(nx.NixieError):
         nx.Layout(ra, [(r[0], ra[0][1], r[2]) for r in rb[:1]], 16 * S, nx.Opts(slot_bytes=S, flags=nx.IN_PLACE))
+
+
+def test_plan_without_gpu_fails_loudly(nx):
+    """No CPU fallback: without a GPU the product path reports a HIP error instead of doing the work."""
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("this check is for machines without a GPU")
+    a, b = np.zeros(4096, np.uint8), np.zeros(4096, np.uint8)
+    with pytest.raises(nx.NixieError) as e:
+        nx.Plan([(0x7F00_0000_0000, a.ctypes.data, 4096)], [(0x7F00_0001_0000, b.ctypes.data, 4096)], 1 << 20)
+    assert e.value.code in (nx.EHIP, nx.ENOMEM)
+    with pytest.raises(nx.NixieError):
+        nx.hash_buffers([0x7F00_0000_0000], [64], on_device=True)
+    with pytest.raises(nx.NixieError):
+        nx.link_peak(1 << 20, 1)

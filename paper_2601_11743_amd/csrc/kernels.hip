@@ -329,38 +329,60 @@ __global__ void __launch_bounds__(256) nixie_zero32_kernel(uint32_t *p, uint64_t
         p[i] = 0;
 }
 
-// H = mix64(bytes) + sum_k mix64(w_k + G (k+1)); each workgroup sums one tile of words and adds
-// its partial to the allocation's slot (hashes must be zero on entry).
+// H = mix64(bytes) + sum_k mix64(w_k + G (k+1)).  A tile is up to 4096 words (32 KiB) of one
+// allocation; each workgroup takes a contiguous run of tiles, so it finds its first allocation
+// by binary search once and then only steps forward.  Per tile: 16 B loads, eight in flight per
+// lane, wave-shuffle + LDS reduce, one 64-bit atomic add into the allocation's slot (hashes must
+// be zero on entry).  HBM-read bound: 1 B read per byte hashed.
 __global__ void __launch_bounds__(256) nixie_hash_kernel(const HashDesc *descs, uint64_t n, uint64_t total_tiles,
                                                          uint64_t *hashes) {
     constexpr uint64_t G = 0x9E3779B97F4A7C15ull;
+    typedef uint64_t u64x2 __attribute__((ext_vector_type(2)));
     __shared__ uint64_t s_part[4];
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
-    for (uint64_t t = blockIdx.x; t < total_tiles; t += gridDim.x) {
-        uint64_t lo = 0, hi = n;   // last descriptor whose first tile is <= t
-        while (lo < hi) {
-            uint64_t mid = (lo + hi) >> 1;
-            if (descs[mid].first_tile <= t) lo = mid + 1; else hi = mid;
-        }
-        const uint64_t i = lo - 1;
-        const HashDesc d = descs[i];
+    const uint64_t per = (total_tiles + gridDim.x - 1) / gridDim.x;
+    const uint64_t t_begin = (uint64_t)blockIdx.x * per;
+    const uint64_t t_end = t_begin + per < total_tiles ? t_begin + per : total_tiles;
+    if (t_begin >= t_end) return;
+    uint64_t lo = 0, hi = n;   // last descriptor whose first tile is <= t_begin
+    while (lo < hi) {
+        uint64_t mid = (lo + hi) >> 1;
+        if (descs[mid].first_tile <= t_begin) lo = mid + 1; else hi = mid;
+    }
+    uint64_t i = lo - 1;
+    HashDesc d = descs[i];
+    for (uint64_t t = t_begin; t < t_end; t++) {
+        // step to the allocation that owns tile t (allocations of zero bytes own no tile)
+        while (i + 1 < n && descs[i + 1].first_tile <= t) d = descs[++i];
         const uint64_t words = (d.bytes + 7) / 8, full = d.bytes / 8;
         const uint64_t w0 = (t - d.first_tile) * kHashTileWords;
         const uint64_t w1 = w0 + kHashTileWords < words ? w0 + kHashTileWords : words;
         const uint8_t *p = (const uint8_t *)(uintptr_t)d.ptr;
-        const bool aligned = (d.ptr & 7u) == 0;
         uint64_t acc = 0;
-        for (uint64_t k = w0 + tid; k < w1; k += 256) {
-            uint64_t w = 0;
-            if (k < full && aligned) {
-                w = *(const uint64_t *)(p + 8 * k);
-            } else {
-                const uint32_t nb = k < full ? 8u : (uint32_t)(d.bytes - 8 * k);
-                for (uint32_t b = 0; b < nb; b++) w |= (uint64_t)p[8 * k + b] << (8 * b);
+        if ((d.ptr & 15u) == 0 && w1 - w0 == kHashTileWords && w1 <= full) {   // whole aligned tile
+            const u64x2 *v = (const u64x2 *)(p + 8 * w0);
+            u64x2 r[8];
+#pragma unroll
+            for (uint32_t u = 0; u < 8; u++) r[u] = __builtin_nontemporal_load(v + tid + 256 * u);
+#pragma unroll
+            for (uint32_t u = 0; u < 8; u++) {
+                const uint64_t k = w0 + 2 * (uint64_t)(tid + 256 * u);
+                acc += mix64_dev(r[u].x + G * (k + 1)) + mix64_dev(r[u].y + G * (k + 2));
             }
-            acc += mix64_dev(w + G * (k + 1));
+        } else {
+            const bool aligned = (d.ptr & 7u) == 0;
+            for (uint64_t k = w0 + tid; k < w1; k += 256) {
+                uint64_t w = 0;
+                if (k < full && aligned) {
+                    w = *(const uint64_t *)(p + 8 * k);
+                } else {
+                    const uint32_t nb = k < full ? 8u : (uint32_t)(d.bytes - 8 * k);
+                    for (uint32_t b = 0; b < nb; b++) w |= (uint64_t)p[8 * k + b] << (8 * b);
+                }
+                acc += mix64_dev(w + G * (k + 1));
+            }
         }
-        if (t == d.first_tile && tid == 0) acc += mix64_dev(d.bytes);
+        if (w0 == 0 && tid == 0) acc += mix64_dev(d.bytes);
         for (int off = 32; off > 0; off >>= 1) acc += __shfl_down((unsigned long long)acc, off, 64);
         if (lane == 0) s_part[wave] = acc;
         __syncthreads();
@@ -405,7 +427,7 @@ int nixie_launch_zero32(uint32_t *p, uint64_t n, void *stream) {
 
 int nixie_launch_hash(const HashDesc *descs, uint64_t n, uint64_t total_tiles, uint64_t *hashes, void *stream) {
     if (total_tiles == 0) return (int)hipSuccess;
-    uint32_t grid = (uint32_t)(total_tiles < 8192 ? total_tiles : 8192);
+    uint32_t grid = (uint32_t)(total_tiles < 4096 ? total_tiles : 4096);   // 16 workgroups per CU
     nixie_hash_kernel<<<grid, 256, 0, (hipStream_t)stream>>>(descs, n, total_tiles, hashes);
     return (int)hipGetLastError();
 }

@@ -243,7 +243,7 @@ int run(const std::string &scenario, uint64_t seed) {
     gpu.quit_early = scenario == "gpu_quits";
 
     int fails = 0;
-    for (int round = 0; round < (scenario == "swap" ? 2 : 1); round++) {   // a plan is reusable
+    for (int round = 0; round < (scenario == "swap" ? 2 : 1); round++) {   // a plan is reusable: two passes
         std::fill(ctrl.begin(), ctrl.end(), 0);
         hs.begin_pass();
         gpu.dev_abort.store(0); gpu.gathered_prefix.store(0);
@@ -264,7 +264,7 @@ int run(const std::string &scenario, uint64_t seed) {
             if (err != NIXIE_ETIMEOUT) { std::printf("expected NIXIE_ETIMEOUT, got %d\n", err); fails++; }
             if (ms > 5000) { std::printf("took %.0f ms to give up\n", ms); fails++; }
         }
-        std::printf("%s seed %llu round %d: %zu + %zu chunks, %.1f ms, error %d\n", scenario.c_str(), (unsigned long long)seed, round,
+        std::printf("%s seed %llu pass %d: %zu + %zu chunks, %.1f ms, error %d\n", scenario.c_str(), (unsigned long long)seed, round,
                     L.dir[0].chunks.size(), L.dir[1].chunks.size(), ms, err);
     }
     crew.stop();

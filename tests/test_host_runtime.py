@@ -41,7 +41,7 @@ def run(binary, scenario, seed):
 @pytest.mark.parametrize("seed", [1, 2, 3])
 def test_swap_equals_memcpy_and_is_race_free(fake_gpu, seed):
     out = run(fake_gpu, "swap", seed)
-    assert "round 1" in out          # the same plan switched twice
+    assert "pass 1" in out           # the same plan switched twice
 
 
 @pytest.mark.parametrize("seed", [1, 2, 3])

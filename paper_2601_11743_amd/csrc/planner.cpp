@@ -250,14 +250,15 @@ void fill_info(const Layout &L, nixie_plan_info_t *info) {
     // about twice the workgroups that the reads out of it need; beyond 128 + 64 the surplus
     // only waits for slots.
     uint32_t wgs[2] = {L.opts.gather_wgs ? L.opts.gather_wgs : 128u, L.opts.scatter_wgs ? L.opts.scatter_wgs : 64u};
-    // Work unit: at most 64 KiB of a slot, so that all workgroups of a direction share the one or
-    // two oldest chunks (a chunk is published when its slowest unit is done), and small enough
-    // that the units in flight (one per workgroup) occupy no more than a quarter of the
-    // direction's share of the ring -- the rest is what the host threads drain or fill meanwhile.
+    // Work unit: at most 128 KiB of a slot -- per unit a workgroup pays a ticket, a slot lookup, a
+    // store drain and a barrier (4 % of the rate at 64 KiB), while at 256 KiB and more a chunk
+    // waits too long for its slowest unit -- and small enough that the units in flight (one per
+    // workgroup) occupy no more than a quarter of the direction's share of the ring: the rest is
+    // what the host threads drain or fill meanwhile.
     uint32_t team = L.opts.team;
     if (team == 0) {
         const uint32_t max_slots = std::max(1u, std::max(L.dir[0].slots, L.dir[1].slots));
-        uint64_t unit = 64u << 10;
+        uint64_t unit = 128u << 10;
         while (unit > (16u << 10) && unit * 4 * std::max(wgs[0], wgs[1]) > (uint64_t)max_slots * L.slot_bytes) unit >>= 1;
         team = (uint32_t)std::max<uint64_t>(1, L.slot_bytes / unit);
     }

@@ -6,3 +6,4 @@ package.  It shares nothing with the GPU library and never imports it.
 from .nixie_oracle import (  # noqa: F401
     Oracle, OracleError, build, FAULTS, lib_path,
 )
+from .sched_oracle import SchedOracle  # noqa: F401,E402

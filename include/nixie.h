@@ -241,6 +241,52 @@ int nixie_hash_buffers(const void *const *ptrs, const uint64_t *bytes, uint64_t 
  * best-of-reps transfers, frees them.  out: HOST. */
 int nixie_link_peak(uint64_t bytes, int reps, nixie_link_peak_t *out);
 
+/* ---- scheduler (paper, "Scheduling": Idleness Detection, Priority Inference / Algorithm 1,
+ *      MLFQ with Prefetching) ------------------------------------------------------------------
+ * Pure host logic: decides which application owns the GPU; the caller then runs the matching
+ * nixie_switch.  All times are nanoseconds on a clock of the caller's choice, non-decreasing
+ * over the calls on one scheduler, so a recorded trace replays exactly.  Not thread safe.
+ * Applications are numbered 0, 1, ... in the order they are added; levels are 1 (highest
+ * priority) .. levels.  Level p has allotment T_p = allot_ns * 2^(p-1) and preemption
+ * threshold S_p = preempt_ns * 2^(p-1). */
+typedef struct nixie_sched nixie_sched_t;
+
+typedef struct {          /* every field 0 = default */
+    uint32_t levels;      /* K, default 4, at most 16              */
+    uint64_t allot_ns;    /* T of the top level, default 8 s       */
+    uint64_t preempt_ns;  /* S of the top level, default 4 s       */
+    uint64_t idle_ns;     /* idleness threshold, default 100 ms    */
+} nixie_sched_params_t;
+
+typedef struct {
+    int32_t run;          /* application that owns the GPU after this tick, -1 = none           */
+    int32_t evict;        /* application that lost it in this tick, -1 = none                   */
+    int32_t prefetch;     /* head of the queue after the decision: worth prefetching, -1 = none */
+    uint32_t switched;    /* 1 if run changed in this tick: the caller switches evict -> run    */
+} nixie_sched_decision_t;
+
+typedef struct {
+    uint32_t priority;    /* current level                                           */
+    uint32_t idle, pending, running;
+    uint64_t exec_ns;     /* t_a: execution time accumulated at the current level    */
+} nixie_sched_app_t;
+
+int nixie_sched_create(const nixie_sched_params_t *params /* NULL = defaults */, nixie_sched_t **sched);
+void nixie_sched_destroy(nixie_sched_t *sched);
+/* Returns the new application's id (>= 0) or a negative error.  It starts at level 1. */
+int nixie_sched_add_app(nixie_sched_t *sched, uint64_t now_ns);
+/* The application entered / returned from a runtime API call.  blocking != 0: it may sit inside
+ * the call for long (a synchronisation) and is not idle meanwhile. */
+int nixie_sched_api_enter(nixie_sched_t *sched, int app, uint64_t now_ns, int blocking);
+int nixie_sched_api_return(nixie_sched_t *sched, int app, uint64_t now_ns);
+/* The application tried to launch work while it does not own the GPU: it joins the queue of its
+ * level (no effect if it already waits or owns the GPU). */
+int nixie_sched_request(nixie_sched_t *sched, int app, uint64_t now_ns);
+/* The periodic step, also to be called on an idleness notification: accounts the owner's
+ * execution time, applies the priority inference to every application, then decides. */
+int nixie_sched_tick(nixie_sched_t *sched, uint64_t now_ns, nixie_sched_decision_t *decision);
+int nixie_sched_app_info(const nixie_sched_t *sched, int app, uint64_t now_ns, nixie_sched_app_t *info);
+
 const char *nixie_strerror(int err);
 int nixie_last_hip_error(void); /* hipError_t of the last NIXIE_EHIP on this thread */
 

@@ -9,7 +9,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libnixie.so")
-SOURCES = ["kernels.hip", "runtime.cpp", "hostside.cpp", "planner.cpp", "hostcopy.cpp", "verify.cpp"]
+SOURCES = ["kernels.hip", "runtime.cpp", "hostside.cpp", "planner.cpp", "hostcopy.cpp", "verify.cpp",
+           "scheduler.cpp"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wextra",
          # packed FP32 instructions are kept out of all device code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -19,6 +19,8 @@ DECLARED_SYMBOLS = (
     "nixie_layout_destroy", "nixie_plan", "nixie_plan_info", "nixie_plan_destroy", "nixie_switch",
     "nixie_hash_tables", "nixie_verify", "nixie_hash_buffers", "nixie_link_peak",
     "nixie_strerror", "nixie_last_hip_error",
+    "nixie_sched_create", "nixie_sched_destroy", "nixie_sched_add_app", "nixie_sched_api_enter",
+    "nixie_sched_api_return", "nixie_sched_request", "nixie_sched_tick", "nixie_sched_app_info",
 )
 
 
@@ -78,6 +80,19 @@ class _LinkPeak(C.Structure):
         "kernel_d2h", "kernel_h2d", "kernel_d2h_both", "kernel_h2d_both")]
 
 
+class _SchedParams(C.Structure):
+    _fields_ = [("levels", C.c_uint32), ("allot_ns", C.c_uint64), ("preempt_ns", C.c_uint64), ("idle_ns", C.c_uint64)]
+
+
+class _SchedDecision(C.Structure):
+    _fields_ = [("run", C.c_int32), ("evict", C.c_int32), ("prefetch", C.c_int32), ("switched", C.c_uint32)]
+
+
+class _SchedApp(C.Structure):
+    _fields_ = [("priority", C.c_uint32), ("idle", C.c_uint32), ("pending", C.c_uint32), ("running", C.c_uint32),
+                ("exec_ns", C.c_uint64)]
+
+
 def _as_dict(s: C.Structure) -> dict:
     return {n: getattr(s, n) for n, _ in s._fields_}
 
@@ -116,6 +131,15 @@ def lib() -> C.CDLL:
     L.nixie_verify.argtypes = [vp, vp, vp, vp, C.POINTER(_Report)]
     L.nixie_hash_buffers.argtypes = [vp, vp, u64, i32, vp, vp]
     L.nixie_link_peak.argtypes = [u64, i32, C.POINTER(_LinkPeak)]
+    L.nixie_sched_create.argtypes = [C.POINTER(_SchedParams), C.POINTER(vp)]
+    L.nixie_sched_destroy.argtypes = [vp]
+    L.nixie_sched_destroy.restype = None
+    L.nixie_sched_add_app.argtypes = [vp, u64]
+    L.nixie_sched_api_enter.argtypes = [vp, i32, u64, i32]
+    L.nixie_sched_api_return.argtypes = [vp, i32, u64]
+    L.nixie_sched_request.argtypes = [vp, i32, u64]
+    L.nixie_sched_tick.argtypes = [vp, u64, C.POINTER(_SchedDecision)]
+    L.nixie_sched_app_info.argtypes = [vp, i32, u64, C.POINTER(_SchedApp)]
     L.nixie_strerror.argtypes = [i32]
     L.nixie_strerror.restype = C.c_char_p
     L.nixie_last_hip_error.argtypes = []
@@ -289,3 +313,50 @@ def link_peak(nbytes: int = 1 << 30, reps: int = 5) -> dict:
     if rc:
         raise NixieError(rc, "nixie_link_peak")
     return _as_dict(out)
+
+
+class Sched:
+    """nixie_sched_*: idleness detection, priority inference and MLFQ (host only, needs no GPU)."""
+
+    def __init__(self, levels: int = 0, allot_ns: int = 0, preempt_ns: int = 0, idle_ns: int = 0):
+        self._h = C.c_void_p()
+        p = _SchedParams(levels, allot_ns, preempt_ns, idle_ns)
+        rc = lib().nixie_sched_create(C.byref(p), C.byref(self._h))
+        if rc:
+            self._h = None
+            raise NixieError(rc, "nixie_sched_create")
+
+    def _ck(self, rc, what):
+        if rc < 0:
+            raise NixieError(rc, what)
+        return rc
+
+    def add_app(self, now: int) -> int:
+        return self._ck(lib().nixie_sched_add_app(self._h, now), "nixie_sched_add_app")
+
+    def api_enter(self, app: int, now: int, blocking: bool) -> None:
+        self._ck(lib().nixie_sched_api_enter(self._h, app, now, int(blocking)), "nixie_sched_api_enter")
+
+    def api_return(self, app: int, now: int) -> None:
+        self._ck(lib().nixie_sched_api_return(self._h, app, now), "nixie_sched_api_return")
+
+    def request(self, app: int, now: int) -> None:
+        self._ck(lib().nixie_sched_request(self._h, app, now), "nixie_sched_request")
+
+    def tick(self, now: int) -> dict:
+        d = _SchedDecision()
+        self._ck(lib().nixie_sched_tick(self._h, now, C.byref(d)), "nixie_sched_tick")
+        return {"run": d.run, "evict": d.evict, "prefetch": d.prefetch, "switched": bool(d.switched)}
+
+    def info(self, app: int, now: int) -> dict:
+        a = _SchedApp()
+        self._ck(lib().nixie_sched_app_info(self._h, app, now, C.byref(a)), "nixie_sched_app_info")
+        return {"priority": a.priority, "t_a": a.exec_ns, "idle": bool(a.idle), "pending": bool(a.pending),
+                "running": bool(a.running)}
+
+    def close(self):
+        if self._h:
+            lib().nixie_sched_destroy(self._h)
+            self._h = None
+
+    __del__ = close

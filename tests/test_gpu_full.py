@@ -248,3 +248,54 @@ def test_pingpong_stress_small_ring(nx, oracle):
     fwd.close(); back.close()
     del A, B
     torch.cuda.empty_cache()
+
+
+def test_scheduler_drives_the_swaps(nx, oracle):
+    """The two halves together: the scheduler's decisions (a scripted trace in simulated time:
+    one batch application, two interactive ones) select which nixie_switch runs; after every
+    switch the new owner's working set must be in HBM and the evicted one in pageable memory,
+    checked by the per-allocation hashes taken at the start."""
+    import torch
+    from workloads.device import BigSet
+    SEC, MS = 1_000_000_000, 1_000_000
+    sizes = [W.log_uniform_sizes(40 + i, 24, 256 << 10, 8 << 20, 16) for i in range(3)]
+    sets = [BigSet(sz, 50 + i, "host", "bf16_normal") for i, sz in enumerate(sizes)]
+    ref = [nx.hash_buffers([r[1] for r in s.rows()], s.sizes, on_device=False) for s in sets]   # all start in pageable memory
+    for i, s in enumerate(sets):                       # oracle hash on a sample pins the library's host hash
+        assert int(ref[i][3]) == oracle.hash64(s.host_view(3))
+    sched = nx.Sched()
+    apps = [sched.add_app(0) for _ in sets]
+    plans = {}
+
+    def do_switch(evict, run):
+        key = (evict, run)
+        if key not in plans:
+            plans[key] = nx.Plan(sets[evict].rows_np() if evict >= 0 else [], sets[run].rows_np(), 32 * MiB)
+        plans[key].switch()
+        plans[key].verify(ref[evict] if evict >= 0 else None, ref[run])
+        if evict >= 0:
+            sets[evict].dev[:] = 0xEE                    # its HBM is dead now
+
+    # script: (time, app that is active in the 250 ms before the tick, apps that ask for the GPU)
+    t, owner, log = 0, -1, []
+    script = ([(0, [0])] + [(0, [])] * 8 + [(0, [1])] + [(1, [])] + [(1, [0])] * 1 + [(-1, [])] * 2 +
+              [(0, [2])] + [(2, [])] + [(2, [0, 1])] + [(-1, [])] * 3)
+    for active, asking in script:
+        t += 250 * MS
+        if active >= 0 and active == owner:
+            for k in range(1, 26):
+                sched.api_return(active, t - 250 * MS + k * 10 * MS)
+        for a in asking:
+            sched.request(a, t - 5 * MS)
+        d = sched.tick(t)
+        if d["switched"]:
+            do_switch(d["evict"], d["run"])
+            log.append((d["evict"], d["run"]))
+        owner = d["run"]
+    assert len(log) >= 5 and log[0] == (-1, 0)
+    assert (0, 1) in log and any(e == 1 and r == 0 for e, r in log)      # the interactive one got in and the batch one came back
+    for p in plans.values():
+        p.close()
+    sched.close()
+    del sets
+    torch.cuda.empty_cache()

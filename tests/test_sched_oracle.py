@@ -8,6 +8,30 @@ from oracle import SchedOracle
 SEC, MS = 1_000_000_000, 1_000_000
 
 
+class _Product:
+    """The library's scheduler behind the oracle's method names (so every pin runs on both)."""
+
+    def __init__(self, levels=4, **kw):
+        import paper_2601_11743_amd as nx
+        self._s = nx.Sched(levels=levels, **kw)
+        self.running = -1
+        for name in ("add_app", "api_enter", "api_return", "request", "info"):
+            setattr(self, name, getattr(self._s, name))
+
+    def is_idle(self, a, now):
+        return self._s.info(a, now)["idle"]
+
+    def tick(self, now):
+        d = self._s.tick(now)
+        self.running = d["run"]
+        return d
+
+
+@pytest.fixture(params=["oracle", "library"])
+def SchedImpl(request):
+    return SchedOracle if request.param == "oracle" else _Product
+
+
 def active(o, a, t0, t1, step=10 * MS):
     """Application a returns from an API call every `step` in (t0, t1]."""
     t = t0 + step
@@ -16,8 +40,8 @@ def active(o, a, t0, t1, step=10 * MS):
         t += step
 
 
-def test_idleness_threshold_and_blocking_calls():
-    o = SchedOracle()
+def test_idleness_threshold_and_blocking_calls(SchedImpl):
+    o = SchedImpl()
     a = o.add_app(0)
     o.api_return(a, 1 * SEC)
     assert not o.is_idle(a, 1 * SEC + 100 * MS)        # exactly the threshold: not yet idle
@@ -30,10 +54,10 @@ def test_idleness_threshold_and_blocking_calls():
     assert o.is_idle(a, 11 * SEC + 200 * MS)
 
 
-def test_demotion_times_follow_the_doubling_allotments():
+def test_demotion_times_follow_the_doubling_allotments(SchedImpl):
     """One application computing without pause, ticks every second: t_a first exceeds 8 s at the
     9th accrued second, then 16 s after 17 more, then 32 s after 33 more: 9 s, 26 s, 59 s."""
-    o = SchedOracle(levels=4)
+    o = SchedImpl(levels=4)
     a = o.add_app(0)
     o.request(a, 0)
     d = o.tick(0)
@@ -50,9 +74,9 @@ def test_demotion_times_follow_the_doubling_allotments():
     assert o.info(a, 199 * SEC)["priority"] == 4
 
 
-def test_round_robin_at_the_preemption_threshold():
+def test_round_robin_at_the_preemption_threshold(SchedImpl):
     """Two applications that never pause, same level: turns of S_1 = 4 s, the longer waiter first."""
-    o = SchedOracle()
+    o = SchedImpl()
     a, b = o.add_app(0), o.add_app(0)
     o.request(a, 0); o.request(b, 1)                   # a waits longer
     owner, switches, prefetch = [], [], {}
@@ -74,8 +98,8 @@ def test_round_robin_at_the_preemption_threshold():
     assert prefetch[4] == -1                              # right after the swap nobody waits yet
 
 
-def test_higher_level_preempts_at_once_and_idle_owner_yields():
-    o = SchedOracle()
+def test_higher_level_preempts_at_once_and_idle_owner_yields(SchedImpl):
+    o = SchedImpl()
     batch, inter = o.add_app(0), o.add_app(0)
     o.request(batch, 0)
     o.tick(0)
@@ -109,10 +133,10 @@ def demote(o, a, upto_level):
     return s * SEC
 
 
-def test_soft_promotion_needs_long_idleness_and_no_jitter():
+def test_soft_promotion_needs_long_idleness_and_no_jitter(SchedImpl):
     """Level 3, t_a = 5 s there, then idle and not waiting: promoted when p_a > T_3 = 32 s and
     i_a > T_2 + t_a = 16 s + 5 s.  The first bound is the later one here."""
-    o = SchedOracle()
+    o = SchedImpl()
     a = o.add_app(0)
     t0 = demote(o, a, 3)                                # reaches level 3 at 26 s
     assert t0 == 26 * SEC
@@ -138,10 +162,10 @@ def test_soft_promotion_needs_long_idleness_and_no_jitter():
     assert o.info(a, t + 100 * SEC)["priority"] == 1
 
 
-def test_pending_time_is_discounted_with_R_below_one_over_N():
+def test_pending_time_is_discounted_with_R_below_one_over_N(SchedImpl):
     """Same as above but the application is waiting in the queue behind a busy owner: with N
     applications at its level the condition is (N+1) i_a - q_a > (N+1)(T_{p-1} + t_a)."""
-    o = SchedOracle(levels=3)
+    o = SchedImpl(levels=3)
     a, hog = o.add_app(0), o.add_app(0)
     t0 = demote(o, a, 3)                                # a alone at level 3 at 26 s, t_a = 0
     o.request(hog, t0)                                  # hog (level 1) takes the GPU and keeps it busy

@@ -195,7 +195,7 @@ void HostCrew::start(HostSide *hs) {
     for (uint32_t t = 0; t < hs->threads[1]; t++) threads_.emplace_back(&HostCrew::worker, this, 1, t);
 }
 
-void HostCrew::run_pass(uint32_t mask) {
+void HostCrew::wake(uint32_t mask) {
     {
         std::lock_guard<std::mutex> lk(mu_);
         mask_ = mask;
@@ -203,6 +203,9 @@ void HostCrew::run_pass(uint32_t mask) {
         epoch_++;
     }
     cv_go_.notify_all();
+}
+
+void HostCrew::wait() {
     std::unique_lock<std::mutex> lk(mu_);
     cv_done_.wait(lk, [&] { return running_ == 0; });
 }

@@ -35,12 +35,14 @@ struct HostSide {
     void run_fill(uint32_t idx);                      // pageable -> ring, thread idx of threads[1]
 };
 
-// The parked threads.  run_pass wakes them for the directions in mask and returns when all of
-// them are done (finished, aborted or timed out).
+// The parked threads.  wake() starts them on the directions in mask; wait() returns when all of
+// them are done (finished, aborted or timed out).  run_pass() is the two in a row.
 class HostCrew {
 public:
     void start(HostSide *hs);
-    void run_pass(uint32_t mask);
+    void wake(uint32_t mask);
+    void wait();
+    void run_pass(uint32_t mask) { wake(mask); wait(); }
     void stop();
     ~HostCrew() { stop(); }
 

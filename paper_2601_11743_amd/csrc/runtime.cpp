@@ -232,24 +232,26 @@ int run_pass(nixie_plan_t *p, uint32_t mask, hipStream_t stream, nixie_stats_t *
     // when the directions run one after the other, everything has left HBM before the restore starts
     a.track_prefix = ((L.opts.flags & NIXIE_IN_PLACE) && a.d[0].wgs && a.d[1].wgs) ? 1u : 0u;
 
+    // The host threads start first: while the launches below are in flight they are already waking
+    // up and loading the first incoming slots.
+    p->crew.wake(mask);
     int e = nixie_launch_zero32(p->counters_d, p->n_counters, stream);
-    if (e) { t_last_hip_error = e; return NIXIE_EHIP; }
-    NIXIE_HIP(hipEventRecord(p->ev0, stream));
-    e = nixie_launch_swap(a, stream);
-    if (e) { t_last_hip_error = e; return NIXIE_EHIP; }
-    {   // From here on the kernel may be running: never return before it has drained, or the caller
-        // could destroy the plan (ring, flags, descriptors) underneath it.
-        hipError_t re = hipEventRecord(p->ev1, stream);
-        if (re != hipSuccess) {
-            t_last_hip_error = (int)re;
-            p->hs.raise_abort(NIXIE_EHIP);         // the pump relays the abort word to every workgroup
-            (void)hipStreamSynchronize(stream);
-            return NIXIE_EHIP;
-        }
+    if (!e) e = (int)hipEventRecord(p->ev0, stream);
+    if (!e) e = nixie_launch_swap(a, stream);
+    if (!e) e = (int)hipEventRecord(p->ev1, stream);
+    if (e) {
+        // Something on the launch path failed.  The kernel may or may not be running: tell both
+        // halves to stop (the pump relays the abort word to every workgroup), let the threads
+        // finish, and drain the stream before returning, so that the caller can never destroy
+        // the plan (ring, flags, descriptors) underneath a live kernel.
+        t_last_hip_error = e;
+        p->hs.raise_abort(NIXIE_EHIP);
+        p->crew.wait();
+        (void)hipStreamSynchronize(stream);
+        return NIXIE_EHIP;
     }
     if (st && st->ns_launch == 0) st->ns_launch = now_ns() - t_entry;
-
-    p->crew.run_pass(mask);   // wake the drain / fill threads and wait until they are done
+    p->crew.wait();   // drain / fill threads done (finished, aborted or timed out)
     hipError_t se = hipStreamSynchronize(stream);
     if (se != hipSuccess) { t_last_hip_error = (int)se; return NIXIE_EHIP; }
 

@@ -229,6 +229,9 @@ def main() -> int:
             "achieved": round(nbytes / kern_s / 1e9, 3), "peak": None, "frac": None,
             "traffic": read_traffic(os.path.join(ROOT, "profiles", "nixie_swap_kernel_llm_pmc.txt")),
             "algorithmic_bytes_per_launch": nbytes, "kernel_ms": round(kern_s * 1e3, 3),
+            "traffic_note": "FETCH_SIZE + WRITE_SIZE count every switched byte twice (fetched once, from HBM or over "
+                            "the link, and written once, over the link or into HBM): compare with 2 x "
+                            "algorithmic_bytes_per_launch",
             "hbm": {"achieved": round(nbytes / kern_s / 1e9, 3), "peak": 8000.0,
                     "frac": round(nbytes / kern_s / 1e9 / 8000.0, 5)}}
     if peak:

@@ -91,7 +91,10 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--config", type=int, default=2, help="benchmark config 1..5 (2 = headline)")
+    ap.add_argument("--config", type=int, default=2,
+                    help="benchmark config 1..5 (2 = headline); 6 = exactly 16 GiB out / 16 GiB in as 64 x 256 MiB")
+    ap.add_argument("--no-serialized", action="store_true",
+                    help="skip the serialised self-baseline (evict completely, then restore)")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink all sizes (debug only)")
     ap.add_argument("--ring-mib", type=int, default=0, help="override ring size")
     ap.add_argument("--slot-kib", type=int, default=0)
@@ -184,6 +187,18 @@ def main() -> int:
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_begin
 
+    serialized = None
+    if not args.no_serialized and not args.in_place and not (args.flags & nx.SERIALIZE) and info["bytes_out"] and info["bytes_in"]:
+        # self-baseline: the same library with the overlap switched off (one link direction at a time)
+        so = nx.Opts(slot_bytes=slot, gather_wgs=args.gather_wgs, scatter_wgs=args.scatter_wgs, team=args.team,
+                     drain_threads=args.drain_threads, fill_threads=args.fill_threads,
+                     flags=args.flags | nx.SERIALIZE, order=args.order)
+        sp = nx.Plan(rows_a, rows_b, ring, so)
+        sp.switch()
+        sms = sorted(sp.switch()["ns_total"] / 1e6 for _ in range(2))
+        sp.close()
+        serialized = {"ms": round(sms[0], 3), "slowdown_vs_bidirectional": round(sms[0] / (elapsed / args.steps * 1e3), 3)}
+
     sweep = None
     if args.ring_sweep:
         sweep = []
@@ -271,6 +286,8 @@ def main() -> int:
                    "scatter_stall_ms_sum": round(med(sorted(s["scatter_stall_ticks"] for s in stats)) / 1e5, 2)},
         "roofline": roof,
     }
+    if serialized is not None:
+        res["serialized_self_baseline"] = serialized
     if sweep is not None:
         res["ring_sweep"] = sweep
     del A, B

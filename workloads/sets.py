@@ -111,11 +111,11 @@ def _until_total(seed, lo, hi, gran, total):
     return out
 
 
-CONFIG_NAMES = {1: "tiny", 2: "llm", 3: "asymmetric", 4: "fragmented", 5: "budget_sweep"}
+CONFIG_NAMES = {1: "tiny", 2: "llm", 3: "asymmetric", 4: "fragmented", 5: "budget_sweep", 6: "exact16"}
 
 
 def config(cfg: int, seed: int = 2601, scale: float = 1.0) -> dict:
-    """Size lists and ring parameters of benchmark config ``cfg`` (1..5).
+    """Size lists and ring parameters of benchmark config ``cfg`` (1..5; 6 = exactly 16 GiB each way).
 
     Returns {"A": [(name, bytes)...], "B": [...], "ring_bytes": [..], "slot_bytes",
     "content": "splitmix"|"bf16_normal", "seed_A", "seed_B"}.  A is GPU resident
@@ -165,6 +165,11 @@ def config(cfg: int, seed: int = 2601, scale: float = 1.0) -> dict:
         B = _named("t", _until_total(sb, lo, hi, 16, tot))
         return dict(A=A, B=B, ring_bytes=[16 * MiB, 64 * MiB, 256 * MiB, 1024 * MiB],
                     slot_bytes=None, content="bf16_normal", seed_A=sa, seed_B=sb, cfg=5)
+    if cfg == 6:   # the metric's wording taken literally: exactly 16 GiB out and 16 GiB in, 256 MiB ring
+        A = [(f"t{i}", 256 * MiB) for i in range(64)]
+        B = [(f"t{i}", 256 * MiB) for i in range(64)]
+        return dict(A=_scaled(A, scale, 16), B=_scaled(B, scale, 16), ring_bytes=[256 * MiB],
+                    slot_bytes=4 * MiB, content="bf16_normal", seed_A=sa, seed_B=sb, cfg=6)
     raise ValueError(f"no config {cfg}")
 
 

@@ -263,7 +263,11 @@ void fill_info(const Layout &L, nixie_plan_info_t *info) {
         team = (uint32_t)std::max<uint64_t>(1, L.slot_bytes / unit);
     }
     team = std::min(team, 256u);
-    uint32_t thr[2] = {L.opts.drain_threads ? L.opts.drain_threads : 4u, L.opts.fill_threads ? L.opts.fill_threads : 4u};
+    // Host threads busy-poll their slots, so the default never takes more than half the cores for
+    // the two directions together (4 + 4 on the 16-core boxes measured; 3 + 3 already saturate the link).
+    const uint32_t cores = std::max(1u, std::thread::hardware_concurrency());
+    const uint32_t dflt = std::max(1u, std::min(4u, cores / 4));
+    uint32_t thr[2] = {L.opts.drain_threads ? L.opts.drain_threads : dflt, L.opts.fill_threads ? L.opts.fill_threads : dflt};
     for (int x = 0; x < 2; x++) {
         if (L.dir[x].chunks.empty()) { wgs[x] = 0; thr[x] = 0; continue; }
         // more workgroups than slots * team could only spin on credits

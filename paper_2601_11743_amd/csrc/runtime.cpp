@@ -107,9 +107,8 @@ int upload(const void *src, size_t bytes, void **dst) {
 int create_plan(nixie_plan_t *p) {
     const Layout &L = p->L;
     NIXIE_HIP(hipGetDevice(&p->device));
-    const uint32_t n_slots = L.dir[0].slots + L.dir[1].slots;
 
-    // payload ring: exactly n_slots * slot_bytes, never more than the budget
+    // payload ring: exactly (out_slots + in_slots) * slot_bytes, never more than the budget
     if (p->info.pinned_ring_bytes > L.ring_bytes) return NIXIE_EINVAL;
     if (p->info.pinned_ring_bytes) {
         hipError_t e = hipHostMalloc((void **)&p->ring_h, p->info.pinned_ring_bytes,
@@ -117,7 +116,8 @@ int create_plan(nixie_plan_t *p) {
         if (e != hipSuccess) { t_last_hip_error = (int)e; return NIXIE_ENOMEM; }
         NIXIE_HIP(hipHostGetDevicePointer((void **)&p->ring_d, p->ring_h, 0));
     }
-    // control block: one 64 B line per flag; [out wait | out post | in wait | in post | abort | status]
+    // control block: [host-written flags out | in (8 B each, padded to lines)] [GPU-written flags out | in
+    // (one 64 B line each)] [abort word] [status word]
     p->ctrl_bytes = p->info.pinned_ctrl_bytes;
     {
         hipError_t e = hipHostMalloc((void **)&p->ctrl_h, p->ctrl_bytes, hipHostMallocMapped | hipHostMallocCoherent);
@@ -133,10 +133,8 @@ int create_plan(nixie_plan_t *p) {
     p->hs.abort_word = (uint32_t *)c;                         c += kFlagStride;
     p->hs.status_word = (uint32_t *)c;                        c += kFlagStride;
     if ((size_t)(c - p->ctrl_h) * 8 != p->ctrl_bytes) return NIXIE_EINVAL;
-    (void)n_slots;
 
     // descriptors
-    uint64_t n_arrive = 0;
     for (int x = 0; x < 2; x++) {
         const DirLayout &D = L.dir[x];
         std::vector<DevSeg> segs(D.segs.size());
@@ -149,7 +147,6 @@ int create_plan(nixie_plan_t *p) {
         if (rc) return rc;
         rc = upload(chunks.data(), chunks.size() * sizeof(DevChunk), (void **)&p->chunks_d[x]);
         if (rc) return rc;
-        n_arrive += D.chunks.size();
 
         // hash descriptors of the table (table order)
         const auto &T = L.table[x];
@@ -172,7 +169,6 @@ int create_plan(nixie_plan_t *p) {
     for (int x = 0; x < 2; x++) { p->cslot_off[x] = off; off += L.dir[x].chunks.size(); }
     for (int x = 0; x < 2; x++) { p->arrive_off[x] = off; off += L.dir[x].chunks.size(); }
     p->n_counters = off;
-    (void)n_arrive;
     {
         hipError_t e = hipMalloc((void **)&p->counters_d, p->n_counters * sizeof(uint32_t));
         if (e != hipSuccess) { t_last_hip_error = (int)e; return NIXIE_ENOMEM; }

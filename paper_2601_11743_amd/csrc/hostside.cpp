@@ -8,6 +8,7 @@
 #include "hostside.hpp"
 
 #include <immintrin.h>
+#include <sched.h>
 #include <time.h>
 
 #include <cstring>
@@ -55,7 +56,12 @@ struct IdleWatch {
     uint32_t spins = 0;
     // call after a scan that made no progress; false = stop
     bool idle() {
-        _mm_pause();
+        // Spin: a slot usually turns around in microseconds.  Only where the threads outnumber
+        // the cores does a long-idle thread give its core away between looks, so that a waiting
+        // thread cannot keep the one it waits for off the processor; with a core each, yielding
+        // costs a small ring one to two percent and buys nothing.
+        if (p->yield_when_idle && spins >= 4096) sched_yield();
+        else _mm_pause();
         if (idle_since == 0) idle_since = now_ns();
         if ((++spins & 63u) != 0) return true;
         if (p->abort_local.load(std::memory_order_acquire)) return false;
@@ -68,6 +74,7 @@ struct IdleWatch {
     void progressed() {
         if (idle_since) p->wait_ns[dir].fetch_add(now_ns() - idle_since, std::memory_order_relaxed);
         idle_since = 0;
+        spins = 0;
     }
 };
 

@@ -21,6 +21,7 @@ struct HostSide {
     const uint32_t *status_word = nullptr;            // GPU-written: kGpuOk or why the kernel gave up
     uint64_t timeout_ns = 0;
     uint32_t threads[2] = {0, 0};                     // drain, fill
+    bool yield_when_idle = false;                     // set when the threads outnumber the usable cores
 
     std::atomic<uint64_t> next_chunk[2];              // incoming: next chunk to claim
     std::atomic<uint64_t> done_chunks[2];             // outgoing: chunks that reached pageable memory

@@ -10,6 +10,7 @@
 #include <hip/hip_runtime.h>
 #include <time.h>
 
+#include <algorithm>
 #include <atomic>
 #include <condition_variable>
 #include <cstring>
@@ -185,6 +186,8 @@ int create_plan(nixie_plan_t *p) {
     p->hs.ring = p->ring_h;
     p->hs.threads[0] = p->info.drain_threads;
     p->hs.threads[1] = p->info.fill_threads;
+    // +1: the thread that calls nixie_switch also needs a core while it launches the kernel
+    p->hs.yield_when_idle = p->info.drain_threads + p->info.fill_threads + 1 > std::max(1u, std::thread::hardware_concurrency());
     p->crew.start(&p->hs);
     return NIXIE_OK;
 }

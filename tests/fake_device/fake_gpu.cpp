@@ -225,6 +225,7 @@ int run(const std::string &scenario, uint64_t seed) {
     hs.ring = ring.data();
     hs.threads[0] = info.drain_threads;
     hs.threads[1] = info.fill_threads;
+    hs.yield_when_idle = seed % 2 == 0;                // both idle policies get raced
     hs.timeout_ns = (uint64_t)o.timeout_ms * 1000000ull;
     hs.error.store(0);
     hs.end_ns[0].store(0); hs.end_ns[1].store(0);

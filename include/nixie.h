@@ -37,7 +37,8 @@ enum nixie_err {
     NIXIE_EHIP = -4,      /* a HIP runtime call failed; see nixie_last_hip_error()             */
     NIXIE_ETIMEOUT = -5,  /* a credit wait exceeded its bound; the kernel was told to stop     */
     NIXIE_EMISMATCH = -6, /* nixie_verify found a hash that differs                            */
-    NIXIE_EBUSY = -7      /* the plan is already running a switch                              */
+    NIXIE_EBUSY = -7,     /* the plan is already running a switch; the pool still has spaces   */
+    NIXIE_EUNMAPPED = -8  /* a listed device range lies in a space whose blocks are not mapped */
 };
 
 /* One allocation of a working set.  Memory is caller-owned on both sides.
@@ -234,6 +235,42 @@ int nixie_verify(const nixie_plan_t *plan, void *hip_stream, const uint64_t *exp
  * addresses hashed by the GPU kernel; else HOST addresses hashed by host threads. */
 int nixie_hash_buffers(const void *const *ptrs, const uint64_t *bytes, uint64_t n, int on_device,
                        void *hip_stream, uint64_t *hashes);
+
+/* ---- stable device addresses over shared physical memory (paper, "Maintaining consistent
+ *      virtual memory addresses": addresses are reserved once and mapped to different
+ *      physical allocations before and after a migration; "Granularity of Memory
+ *      Management": physical memory is handled in fixed-size blocks) -------------------------
+ * A pool is physical device memory of the current device, cut into equal blocks.  A space is
+ * a reserved range of device addresses as long as the pool, owned by one application, which
+ * keeps its pointers for life.  nixie_space_map puts pool block i behind offset
+ * i * block_bytes of the space; several spaces may map the same block at once, and then they
+ * share its bytes.  The planner knows this: device ranges of two spaces over one pool count
+ * as overlapping exactly where they share blocks and offsets, so a switch between two
+ * applications that take turns on one pool is an in-place switch (NIXIE_IN_PLACE), ordered
+ * by the same per-chunk dependencies as for equal addresses.  The calls around a switch:
+ *     nixie_space_map(B)  ->  nixie_switch(plan(A's table, B's table, NIXIE_IN_PLACE))
+ *     ->  nixie_space_unmap(A)           (A's pointers stay reserved, and fault if used)
+ * None of these calls runs inside the switch.  Mapping and unmapping take the library's
+ * switch lock, so they wait for a running nixie_switch; nixie_switch returns NIXIE_EUNMAPPED
+ * without touching the GPU when a listed range lies in unmapped blocks.
+ * block_bytes: multiple of the device's allocation granularity, 0 = 64 MiB (a map or unmap
+ * call costs the same for any block size, so small blocks make the remap slow).  bytes is
+ * rounded up to whole blocks.  offset and bytes of map / unmap must be multiples of the
+ * block size; mapping a mapped block or unmapping an unmapped one is not an error.
+ * Errors: NIXIE_EINVAL, NIXIE_ENOMEM (no physical memory or address range left),
+ * NIXIE_EHIP, NIXIE_EBUSY (pool destroyed while spaces exist).  Spaces are destroyed before
+ * their pool; destroying a space unmaps it. */
+typedef struct nixie_pool nixie_pool_t;
+typedef struct nixie_space nixie_space_t;
+int nixie_pool_create(uint64_t bytes, uint64_t block_bytes, nixie_pool_t **pool);
+int nixie_pool_info(const nixie_pool_t *pool, uint64_t *bytes, uint64_t *block_bytes);
+int nixie_pool_destroy(nixie_pool_t *pool);
+int nixie_space_create(nixie_pool_t *pool, nixie_space_t **space, void **base /* device address */);
+int nixie_space_map(nixie_space_t *space, uint64_t offset, uint64_t bytes);
+int nixie_space_unmap(nixie_space_t *space, uint64_t offset, uint64_t bytes);
+/* 1 = every block of [offset, offset + bytes) is mapped, 0 = not, negative = error */
+int nixie_space_mapped(const nixie_space_t *space, uint64_t offset, uint64_t bytes);
+int nixie_space_destroy(nixie_space_t *space);
 
 /* ---- host-link probe (paper, "Microbenchmarks": throughput is judged against the link's
  *      measured maximum) ---------------------------------------------------------------------

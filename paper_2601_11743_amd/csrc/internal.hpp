@@ -5,6 +5,7 @@
 #include <vector>
 
 #include "nixie.h"
+#include "spaces.hpp"
 
 namespace nixie {
 
@@ -21,6 +22,7 @@ struct Layout {
     nixie_opts_t opts{};
     DirLayout dir[2];                     // 0 = outgoing (GPU -> host), 1 = incoming
     std::vector<nixie_alloc_t> table[2];  // copies of the caller's tables, table order
+    std::vector<SpaceUse> uses[2];        // blocks of registered spaces that each table touches
 };
 
 int build_layout(const nixie_table_t *out_table, const nixie_table_t *in_table, uint64_t ring_bytes,

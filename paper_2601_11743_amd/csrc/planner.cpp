@@ -13,10 +13,20 @@
 #include <thread>
 
 #include "internal.hpp"
+#include "spaces.hpp"
 
 namespace nixie {
 
 namespace {
+
+// Device ranges are compared where they really live: a range inside a registered space is
+// translated into the coordinate of the physical pool behind it, so two spaces that map the
+// same pool are seen to share memory although their addresses differ.
+uint64_t dev_key(uint64_t addr, uint64_t len) {
+    uint64_t key = addr;
+    space_translate(addr, len, &key, nullptr);   // ranges were validated when the table was copied
+    return key;
+}
 
 constexpr uint64_t kDefaultSlot = 2ull << 20;
 constexpr uint64_t kMinAutoSlot = 64ull << 10;
@@ -142,7 +152,11 @@ int build_layout(const nixie_table_t *out_table, const nixie_table_t *in_table, 
         for (const auto &a : L.table[x]) {
             if (a.bytes == 0) continue;
             uint64_t d = (uint64_t)(uintptr_t)a.dev_ptr, h = (uint64_t)(uintptr_t)a.host_ptr;
-            dev.push_back({d, d + a.bytes});
+            uint64_t key = d;
+            SpaceUse use;
+            if (!space_translate(d, a.bytes, &key, &use)) return NIXIE_EINVAL;   // straddles the edge of a space
+            if (use.count) L.uses[x].push_back(use);
+            dev.push_back({key, key + a.bytes});
             host.push_back({h, h + a.bytes});
             tot[x] += a.bytes;
         }
@@ -194,15 +208,17 @@ int build_layout(const nixie_table_t *out_table, const nixie_table_t *in_table, 
         osegs.reserve(L.dir[0].segs.size());
         for (uint64_t k = 0; k < L.dir[0].chunks.size(); k++) {
             const nixie_chunk_t &c = L.dir[0].chunks[k];
-            for (uint64_t q = c.seg_begin; q < c.seg_begin + c.seg_count; q++)
-                osegs.push_back({L.dir[0].segs[q].dev_addr, L.dir[0].segs[q].dev_addr + L.dir[0].segs[q].len, k});
+            for (uint64_t q = c.seg_begin; q < c.seg_begin + c.seg_count; q++) {
+                const uint64_t key = dev_key(L.dir[0].segs[q].dev_addr, L.dir[0].segs[q].len);
+                osegs.push_back({key, key + L.dir[0].segs[q].len, k});
+            }
         }
         std::sort(osegs.begin(), osegs.end(), [](const OutSpan &a, const OutSpan &b) { return a.lo < b.lo; });
         // Walk the incoming table in the order in which its GPU memory becomes free, so that the
         // scatter side follows right behind the gather side instead of waiting for its end.
         std::vector<uint64_t> adep(L.table[1].size());
         for (size_t i = 0; i < adep.size(); i++) {
-            const uint64_t d = (uint64_t)(uintptr_t)L.table[1][i].dev_ptr;
+            const uint64_t d = dev_key((uint64_t)(uintptr_t)L.table[1][i].dev_ptr, L.table[1][i].bytes);
             adep[i] = dep_of_range(osegs, d, d + L.table[1][i].bytes);
         }
         std::stable_sort(walk1.begin(), walk1.end(), [&](uint64_t a, uint64_t b) { return adep[a] < adep[b]; });
@@ -210,7 +226,8 @@ int build_layout(const nixie_table_t *out_table, const nixie_table_t *in_table, 
         for (nixie_chunk_t &c : L.dir[1].chunks)
             for (uint64_t q = c.seg_begin; q < c.seg_begin + c.seg_count; q++) {
                 const nixie_segment_t &sg = L.dir[1].segs[q];
-                c.dep_out = std::max(c.dep_out, dep_of_range(osegs, sg.dev_addr, sg.dev_addr + sg.len));
+                const uint64_t key = dev_key(sg.dev_addr, sg.len);
+                c.dep_out = std::max(c.dep_out, dep_of_range(osegs, key, key + sg.len));
             }
     } else if (L.table[0].size() + L.table[1].size() > 20000) {   // large tables: one direction per thread
         std::thread other([&] { cut(L.table[1], walk1, S, L.dir[1]); });

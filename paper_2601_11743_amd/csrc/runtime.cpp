@@ -16,6 +16,7 @@
 #include <cstring>
 #include <mutex>
 #include <new>
+#include <shared_mutex>
 #include <thread>
 
 #include "internal.hpp"
@@ -350,6 +351,9 @@ int nixie_switch(nixie_plan_t *p, void *hip_stream, nixie_stats_t *stats) {
     if (!p) return NIXIE_EINVAL;
     std::unique_lock<std::mutex> lk(p->switch_mu, std::try_to_lock);
     if (!lk.owns_lock()) return NIXIE_EBUSY;
+    // no block of a registered space is mapped or unmapped while the kernel runs
+    std::shared_lock<std::shared_mutex> maps(switch_lock());
+    if (!space_uses_mapped(p->L.uses[0]) || !space_uses_mapped(p->L.uses[1])) return NIXIE_EUNMAPPED;
     const uint64_t t_entry = now_ns();
     int dev = -1;
     NIXIE_HIP(hipGetDevice(&dev));
@@ -387,7 +391,8 @@ const char *nixie_strerror(int err) {
     case NIXIE_EHIP: return "HIP runtime error";
     case NIXIE_ETIMEOUT: return "credit wait timed out; switch aborted";
     case NIXIE_EMISMATCH: return "hash mismatch";
-    case NIXIE_EBUSY: return "plan is busy";
+    case NIXIE_EBUSY: return "busy: the plan is running a switch, or the pool still has spaces";
+    case NIXIE_EUNMAPPED: return "a listed device range lies in unmapped blocks of a space";
     default: return "unknown error";
     }
 }

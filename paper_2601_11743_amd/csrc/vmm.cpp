@@ -1,0 +1,251 @@
+// Pools and spaces: physical device memory in equal blocks, and reserved address ranges that
+// map those blocks (paper, "Maintaining consistent virtual memory addresses"; "Granularity of
+// Memory Management").  All driver calls here run outside a switch: they take the switch lock
+// exclusively, nixie_switch holds it shared.
+#include <hip/hip_runtime.h>
+
+#include <mutex>
+#include <new>
+#include <shared_mutex>
+#include <vector>
+
+#include "internal.hpp"
+#include "spaces.hpp"
+
+namespace nixie {
+void set_last_hip_error(int e);
+}  // namespace nixie
+
+using namespace nixie;
+
+struct nixie_pool {
+    int device = 0;
+    uint64_t bytes = 0, block_bytes = 0, key_base = 0;
+    std::vector<hipMemGenericAllocationHandle_t> blocks;
+    uint32_t spaces = 0;
+    std::mutex mu;
+};
+
+struct nixie_space {
+    nixie_pool *pool = nullptr;
+    void *base = nullptr;
+    std::vector<uint8_t> mapped;
+};
+
+namespace {
+
+constexpr uint64_t kDefaultBlock = 64ull << 20;
+
+int fail(hipError_t e) {
+    set_last_hip_error((int)e);
+    return e == hipErrorOutOfMemory ? NIXIE_ENOMEM : NIXIE_EHIP;
+}
+
+hipMemAllocationProp device_prop(int device) {
+    hipMemAllocationProp prop{};
+    prop.type = hipMemAllocationTypePinned;          // ordinary, non-migratable device memory
+    prop.location.type = hipMemLocationTypeDevice;
+    prop.location.id = device;
+    return prop;
+}
+
+int block_range(const nixie_space *s, uint64_t offset, uint64_t bytes, uint64_t *first, uint64_t *count) {
+    const uint64_t B = s->pool->block_bytes;
+    if (offset % B || bytes % B || offset > s->pool->bytes || bytes > s->pool->bytes - offset) return NIXIE_EINVAL;
+    *first = offset / B;
+    *count = bytes / B;
+    return NIXIE_OK;
+}
+
+// caller holds the switch lock exclusively
+int unmap_blocks(nixie_space *s, uint64_t first, uint64_t count) {
+    const uint64_t B = s->pool->block_bytes;
+    for (uint64_t b = first; b < first + count; b++) {
+        if (!s->mapped[b]) continue;
+        // out of the registry first: from here on no switch may count on this block
+        space_set_mapped((uint64_t)(uintptr_t)s->base, b, 1, false);
+        s->mapped[b] = 0;
+        hipError_t e = hipMemUnmap((char *)s->base + b * B, B);
+        if (e != hipSuccess) return fail(e);
+    }
+    return NIXIE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int nixie_pool_create(uint64_t bytes, uint64_t block_bytes, nixie_pool_t **pool) {
+    if (!pool || bytes == 0) return NIXIE_EINVAL;
+    *pool = nullptr;
+    int device = 0, supported = 0;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess) return fail(e);
+    e = hipDeviceGetAttribute(&supported, hipDeviceAttributeVirtualMemoryManagementSupported, device);
+    if (e != hipSuccess) return fail(e);
+    if (!supported) { set_last_hip_error((int)hipErrorNotSupported); return NIXIE_EHIP; }
+    hipMemAllocationProp prop = device_prop(device);
+    size_t gran = 0;
+    e = hipMemGetAllocationGranularity(&gran, &prop, hipMemAllocationGranularityRecommended);
+    if (e != hipSuccess) return fail(e);
+    if (block_bytes == 0) block_bytes = kDefaultBlock;
+    if (gran == 0 || block_bytes % gran || block_bytes % 4096 || block_bytes > (1ull << 36)) return NIXIE_EINVAL;
+    const uint64_t n = (bytes + block_bytes - 1) / block_bytes;
+    if (n > (1ull << 22) || n * block_bytes > kKeyStride) return NIXIE_EINVAL;
+    nixie_pool *p = new (std::nothrow) nixie_pool;
+    if (!p) return NIXIE_ENOMEM;
+    p->device = device;
+    p->block_bytes = block_bytes;
+    p->bytes = n * block_bytes;
+    p->key_base = next_pool_key();
+    p->blocks.reserve(n);
+    for (uint64_t i = 0; i < n; i++) {
+        hipMemGenericAllocationHandle_t h;
+        e = hipMemCreate(&h, block_bytes, &prop, 0);
+        if (e != hipSuccess) {
+            for (auto &b : p->blocks) (void)hipMemRelease(b);
+            delete p;
+            return fail(e);
+        }
+        p->blocks.push_back(h);
+    }
+    *pool = p;
+    return NIXIE_OK;
+}
+
+int nixie_pool_info(const nixie_pool_t *pool, uint64_t *bytes, uint64_t *block_bytes) {
+    if (!pool) return NIXIE_EINVAL;
+    if (bytes) *bytes = pool->bytes;
+    if (block_bytes) *block_bytes = pool->block_bytes;
+    return NIXIE_OK;
+}
+
+int nixie_pool_destroy(nixie_pool_t *pool) {
+    if (!pool) return NIXIE_OK;
+    {
+        std::lock_guard<std::mutex> g(pool->mu);
+        if (pool->spaces) return NIXIE_EBUSY;
+    }
+    int rc = NIXIE_OK;
+    for (auto &b : pool->blocks) {
+        hipError_t e = hipMemRelease(b);
+        if (e != hipSuccess) rc = fail(e);
+    }
+    delete pool;
+    return rc;
+}
+
+int nixie_space_create(nixie_pool_t *pool, nixie_space_t **space, void **base) {
+    if (!pool || !space || !base) return NIXIE_EINVAL;
+    *space = nullptr;
+    *base = nullptr;
+    nixie_space *s = new (std::nothrow) nixie_space;
+    if (!s) return NIXIE_ENOMEM;
+    // aligned to the block size (a power of two is not required: alignment 0 = the driver's own)
+    hipError_t e = hipMemAddressReserve(&s->base, pool->bytes, 0, nullptr, 0);
+    if (e != hipSuccess || !s->base) {
+        delete s;
+        return e == hipSuccess ? NIXIE_ENOMEM : fail(e);
+    }
+    s->pool = pool;
+    s->mapped.assign(pool->blocks.size(), 0);
+    SpaceSpan span;
+    span.base = (uint64_t)(uintptr_t)s->base;
+    span.bytes = pool->bytes;
+    span.key_base = pool->key_base;
+    span.block_bytes = pool->block_bytes;
+    span.mapped.assign(pool->blocks.size(), 0);
+    space_register(span);
+    {
+        std::lock_guard<std::mutex> g(pool->mu);
+        pool->spaces++;
+    }
+    *space = s;
+    *base = s->base;
+    return NIXIE_OK;
+}
+
+int nixie_space_map(nixie_space_t *s, uint64_t offset, uint64_t bytes) {
+    if (!s) return NIXIE_EINVAL;
+    uint64_t first = 0, count = 0;
+    int rc = block_range(s, offset, bytes, &first, &count);
+    if (rc) return rc;
+    int device = -1;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess) return fail(e);
+    if (device != s->pool->device) return NIXIE_EINVAL;
+    std::unique_lock<std::shared_mutex> lk(switch_lock());
+    const uint64_t B = s->pool->block_bytes;
+    hipMemAccessDesc acc{};
+    acc.location.type = hipMemLocationTypeDevice;
+    acc.location.id = device;
+    acc.flags = hipMemAccessFlagsProtReadWrite;
+    // map, then open access for each run of newly mapped blocks with one call
+    uint64_t b = first;
+    while (b < first + count) {
+        if (s->mapped[b]) { b++; continue; }
+        uint64_t run = b;
+        while (run < first + count && !s->mapped[run]) {
+            e = hipMemMap((char *)s->base + run * B, B, 0, s->pool->blocks[run], 0);
+            if (e != hipSuccess) break;
+            run++;
+        }
+        hipError_t e2 = hipSuccess;
+        if (run > b) e2 = hipMemSetAccess((char *)s->base + b * B, (run - b) * B, &acc, 1);
+        if (e2 != hipSuccess) {              // mapped but not accessible: take the run back out
+            for (uint64_t q = b; q < run; q++) (void)hipMemUnmap((char *)s->base + q * B, B);
+            return fail(e2);
+        }
+        for (uint64_t q = b; q < run; q++) s->mapped[q] = 1;
+        space_set_mapped((uint64_t)(uintptr_t)s->base, b, run - b, true);
+        if (e != hipSuccess) return fail(e);
+        b = run;
+    }
+    return NIXIE_OK;
+}
+
+int nixie_space_unmap(nixie_space_t *s, uint64_t offset, uint64_t bytes) {
+    if (!s) return NIXIE_EINVAL;
+    uint64_t first = 0, count = 0;
+    int rc = block_range(s, offset, bytes, &first, &count);
+    if (rc) return rc;
+    std::unique_lock<std::shared_mutex> lk(switch_lock());
+    // work queued on any stream may still use these addresses
+    hipError_t e = hipDeviceSynchronize();
+    if (e != hipSuccess) return fail(e);
+    return unmap_blocks(s, first, count);
+}
+
+int nixie_space_mapped(const nixie_space_t *s, uint64_t offset, uint64_t bytes) {
+    if (!s) return NIXIE_EINVAL;
+    uint64_t first = 0, count = 0;
+    int rc = block_range(s, offset, bytes, &first, &count);
+    if (rc) return rc;
+    std::shared_lock<std::shared_mutex> lk(switch_lock());
+    for (uint64_t b = first; b < first + count; b++)
+        if (!s->mapped[b]) return 0;
+    return 1;
+}
+
+int nixie_space_destroy(nixie_space_t *s) {
+    if (!s) return NIXIE_OK;
+    int rc;
+    {
+        std::unique_lock<std::shared_mutex> lk(switch_lock());
+        hipError_t e = hipDeviceSynchronize();
+        if (e != hipSuccess) return fail(e);
+        rc = unmap_blocks(s, 0, s->mapped.size());
+        if (rc) return rc;
+        space_unregister((uint64_t)(uintptr_t)s->base);
+    }
+    hipError_t e = hipMemAddressFree(s->base, s->pool->bytes);
+    if (e != hipSuccess) rc = fail(e);
+    {
+        std::lock_guard<std::mutex> g(s->pool->mu);
+        s->pool->spaces--;
+    }
+    delete s;
+    return rc;
+}
+
+}  // extern "C"

@@ -10,7 +10,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libnixie.so")
 
-EINVAL, EOVERLAP, ENOMEM, EHIP, ETIMEOUT, EMISMATCH, EBUSY = -1, -2, -3, -4, -5, -6, -7
+EINVAL, EOVERLAP, ENOMEM, EHIP, ETIMEOUT, EMISMATCH, EBUSY, EUNMAPPED = -1, -2, -3, -4, -5, -6, -7, -8
 ORDER_TABLE, ORDER_LARGE_FIRST, ORDER_ADDRESS, ORDER_REVERSE = 0, 1, 2, 3
 SPLIT_BY_BYTES, SERIALIZE, DIAG_RING_ONLY, DIAG_STALL_DRAIN, HOST_PLAIN_MEMCPY, IN_PLACE = 1, 2, 4, 8, 16, 32
 
@@ -21,6 +21,8 @@ DECLARED_SYMBOLS = (
     "nixie_strerror", "nixie_last_hip_error",
     "nixie_sched_create", "nixie_sched_destroy", "nixie_sched_add_app", "nixie_sched_api_enter",
     "nixie_sched_api_return", "nixie_sched_request", "nixie_sched_tick", "nixie_sched_app_info",
+    "nixie_pool_create", "nixie_pool_info", "nixie_pool_destroy", "nixie_space_create", "nixie_space_map",
+    "nixie_space_unmap", "nixie_space_mapped", "nixie_space_destroy",
 )
 
 
@@ -140,6 +142,14 @@ def lib() -> C.CDLL:
     L.nixie_sched_request.argtypes = [vp, i32, u64]
     L.nixie_sched_tick.argtypes = [vp, u64, C.POINTER(_SchedDecision)]
     L.nixie_sched_app_info.argtypes = [vp, i32, u64, C.POINTER(_SchedApp)]
+    L.nixie_pool_create.argtypes = [u64, u64, C.POINTER(vp)]
+    L.nixie_pool_info.argtypes = [vp, C.POINTER(u64), C.POINTER(u64)]
+    L.nixie_pool_destroy.argtypes = [vp]
+    L.nixie_space_create.argtypes = [vp, C.POINTER(vp), C.POINTER(vp)]
+    L.nixie_space_map.argtypes = [vp, u64, u64]
+    L.nixie_space_unmap.argtypes = [vp, u64, u64]
+    L.nixie_space_mapped.argtypes = [vp, u64, u64]
+    L.nixie_space_destroy.argtypes = [vp]
     L.nixie_strerror.argtypes = [i32]
     L.nixie_strerror.restype = C.c_char_p
     L.nixie_last_hip_error.argtypes = []
@@ -313,6 +323,63 @@ def link_peak(nbytes: int = 1 << 30, reps: int = 5) -> dict:
     if rc:
         raise NixieError(rc, "nixie_link_peak")
     return _as_dict(out)
+
+
+class Pool:
+    """nixie_pool_*: physical device memory in equal blocks."""
+
+    def __init__(self, nbytes: int, block_bytes: int = 0):
+        self._h = C.c_void_p()
+        rc = lib().nixie_pool_create(nbytes, block_bytes, C.byref(self._h))
+        if rc:
+            self._h = None
+            raise NixieError(rc, "nixie_pool_create")
+        b, k = C.c_uint64(), C.c_uint64()
+        lib().nixie_pool_info(self._h, C.byref(b), C.byref(k))
+        self.bytes, self.block_bytes = int(b.value), int(k.value)
+
+    def close(self):
+        if self._h:
+            rc = lib().nixie_pool_destroy(self._h)
+            if rc:
+                raise NixieError(rc, "nixie_pool_destroy")
+            self._h = None
+
+
+class Space:
+    """nixie_space_*: a reserved device address range that maps a pool's blocks, offset for offset."""
+
+    def __init__(self, pool: Pool):
+        self._h, base = C.c_void_p(), C.c_void_p()
+        self.pool = pool
+        rc = lib().nixie_space_create(pool._h, C.byref(self._h), C.byref(base))
+        if rc:
+            self._h = None
+            raise NixieError(rc, "nixie_space_create")
+        self.base = int(base.value)
+
+    def map(self, offset: int = 0, nbytes: int | None = None) -> None:
+        rc = lib().nixie_space_map(self._h, offset, self.pool.bytes - offset if nbytes is None else nbytes)
+        if rc:
+            raise NixieError(rc, "nixie_space_map")
+
+    def unmap(self, offset: int = 0, nbytes: int | None = None) -> None:
+        rc = lib().nixie_space_unmap(self._h, offset, self.pool.bytes - offset if nbytes is None else nbytes)
+        if rc:
+            raise NixieError(rc, "nixie_space_unmap")
+
+    def mapped(self, offset: int = 0, nbytes: int | None = None) -> bool:
+        rc = lib().nixie_space_mapped(self._h, offset, self.pool.bytes - offset if nbytes is None else nbytes)
+        if rc < 0:
+            raise NixieError(rc, "nixie_space_mapped")
+        return bool(rc)
+
+    def close(self):
+        if self._h:
+            rc = lib().nixie_space_destroy(self._h)
+            if rc:
+                raise NixieError(rc, "nixie_space_destroy")
+            self._h = None
 
 
 class Sched:

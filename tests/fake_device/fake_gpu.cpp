@@ -11,6 +11,9 @@
 // usage: fake_gpu <scenario> [seed]
 //   swap        bidirectional switch, mixed sizes, small ring; result must equal memcpy
 //   in_place    incoming ranges reuse the outgoing "device" memory; evict-before-overwrite
+//   spaces      the same, but the two applications see that memory at different addresses (one
+//               file mapped twice, registered as two spaces of one pool): the planner must find
+//               the dependencies through the pool coordinate
 //   stall       the host withholds credits (NIXIE_DIAG_STALL_DRAIN): must end with NIXIE_ETIMEOUT
 //   gpu_quits   the device reports that it gave up: the host must stop with NIXIE_ETIMEOUT
 //   dead_gpu    the device never starts: the host watchdog must fire
@@ -23,7 +26,11 @@
 #include <thread>
 #include <vector>
 
+#include <sys/mman.h>
+#include <unistd.h>
+
 #include "hostside.hpp"
+#include "spaces.hpp"
 
 using namespace nixie;
 
@@ -181,14 +188,35 @@ int run(const std::string &scenario, uint64_t seed) {
     for (int i = 0; i < 11; i++) sb.push_back(1 + rnd() % (4 * S));
     sa.push_back(0); sa.push_back(S); sa.push_back(5 * S + 1);
     sb.push_back(S - 1); sb.push_back(15);
-    const bool in_place = scenario == "in_place";
+    const bool spaces = scenario == "spaces";
+    const bool in_place = scenario == "in_place" || spaces;
 
     // in place: B's device ranges lie in the same "device" arena as A's
     std::vector<uint8_t> dev_a(std::max(arena_bytes(sa), in_place ? arena_bytes(sb) : 0) + 64, 0xC3);
     std::vector<uint8_t> dev_b(in_place ? 0 : arena_bytes(sb) + 64, 0xC3);
+    uint8_t *base_a = dev_a.data(), *base_b = in_place ? dev_a.data() : dev_b.data();
+    uint64_t span_bytes = 0;
+    if (spaces) {   // one "pool" seen through two address ranges
+        const uint64_t blk = 64 << 10;
+        span_bytes = (dev_a.size() + blk - 1) / blk * blk;
+        const int fd = memfd_create("fake_pool", 0);
+        if (fd < 0 || ftruncate(fd, (off_t)span_bytes) != 0) { std::printf("memfd failed\n"); return 2; }
+        base_a = (uint8_t *)mmap(nullptr, span_bytes, PROT_READ | PROT_WRITE, MAP_SHARED, fd, 0);
+        base_b = (uint8_t *)mmap(nullptr, span_bytes, PROT_READ | PROT_WRITE, MAP_SHARED, fd, 0);
+        close(fd);
+        if (base_a == MAP_FAILED || base_b == MAP_FAILED || base_a == base_b) { std::printf("mmap failed\n"); return 2; }
+        std::memset(base_a, 0xC3, span_bytes);
+        const uint64_t key = next_pool_key();
+        for (uint8_t *b : {base_a, base_b}) {
+            SpaceSpan sp;
+            sp.base = (uint64_t)(uintptr_t)b; sp.bytes = span_bytes; sp.key_base = key; sp.block_bytes = blk;
+            sp.mapped.assign(span_bytes / blk, 1);
+            space_register(sp);
+        }
+    }
     Arena A, B;
-    build(A, sa, seed, true, dev_a.data(), seed % 16);
-    build(B, sb, seed + 1, false, in_place ? dev_a.data() : dev_b.data(), (seed * 5) % 16);
+    build(A, sa, seed, true, base_a, seed % 16);
+    build(B, sb, seed + 1, false, base_b, (seed * 5) % 16);
     // expectation by plain memcpy, in definition order: all of A out, then B in
     std::vector<std::vector<uint8_t>> want_a, want_b;
     for (auto &r : A.rows) want_a.emplace_back((uint8_t *)r.dev_ptr, (uint8_t *)r.dev_ptr + r.bytes);
@@ -198,14 +226,40 @@ int run(const std::string &scenario, uint64_t seed) {
     o.slot_bytes = S;
     o.drain_threads = 3;
     o.fill_threads = 2;
-    o.timeout_ms = (scenario == "swap" || scenario == "in_place") ? 20000 : 300;
+    o.timeout_ms = (scenario == "swap" || in_place) ? 20000 : 300;
     if (in_place) o.flags |= NIXIE_IN_PLACE;
     if (scenario == "stall") o.flags |= NIXIE_DIAG_STALL_DRAIN;
     nixie_table_t ta{A.rows.data(), A.rows.size()}, tb{B.rows.data(), B.rows.size()};
     Layout L;
     const uint64_t ring_bytes = 12 * S;
+    if (spaces) {
+        // the two address ranges share their bytes, and the planner must know it
+        nixie_opts_t plain = o;
+        plain.flags &= ~(uint32_t)NIXIE_IN_PLACE;
+        int e = build_layout(&ta, &tb, ring_bytes, &plain, L);
+        if (e != NIXIE_EOVERLAP) { std::printf("expected NIXIE_EOVERLAP without NIXIE_IN_PLACE, got %d\n", e); return 1; }
+        // a range that runs over the end of a space belongs to no one
+        std::vector<uint8_t> h(256);
+        nixie_alloc_t over{base_b + span_bytes - 100, h.data(), 200};
+        nixie_table_t tover{&over, 1};
+        e = build_layout(nullptr, &tover, ring_bytes, &o, L);
+        if (e != NIXIE_EINVAL) { std::printf("expected NIXIE_EINVAL for a range across the edge of a space, got %d\n", e); return 1; }
+        if (L.uses[0].size() != 0) { std::printf("stale uses\n"); return 1; }
+    }
     int rc = build_layout(&ta, &tb, ring_bytes, &o, L);
     if (rc) { std::printf("build_layout failed %d\n", rc); return 2; }
+    if (spaces) {
+        if (L.uses[0].size() != A.rows.size() - 1 || L.uses[1].size() != B.rows.size() || !space_uses_mapped(L.uses[1])) {
+            std::printf("uses: %zu out, %zu in\n", L.uses[0].size(), L.uses[1].size());
+            return 1;
+        }
+        uint64_t deps = 0;
+        for (const auto &c : L.dir[1].chunks) deps += c.dep_out != 0;
+        if (deps == 0) { std::printf("no dependencies found through the pool coordinate\n"); return 1; }
+        space_set_mapped((uint64_t)(uintptr_t)base_a, 0, 1, false);
+        if (space_uses_mapped(L.uses[0])) { std::printf("unmapped block not noticed\n"); return 1; }
+        space_set_mapped((uint64_t)(uintptr_t)base_a, 0, 1, true);
+    }
     nixie_plan_info_t info;
     fill_info(L, &info);
 
@@ -254,7 +308,7 @@ int run(const std::string &scenario, uint64_t seed) {
         gpu.join();
         const double ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
         const int err = hs.error.load();
-        if (scenario == "swap" || scenario == "in_place") {
+        if (scenario == "swap" || in_place) {
             if (err) { std::printf("switch failed: %d\n", err); fails++; }
             for (size_t i = 0; i < A.rows.size(); i++)
                 if (std::memcmp(A.rows[i].host_ptr, want_a[i].data(), A.rows[i].bytes)) { std::printf("evicted allocation %zu differs\n", i); fails++; }
@@ -269,12 +323,18 @@ int run(const std::string &scenario, uint64_t seed) {
                     L.dir[0].chunks.size(), L.dir[1].chunks.size(), ms, err);
     }
     crew.stop();
+    if (spaces) {
+        space_unregister((uint64_t)(uintptr_t)base_a);
+        space_unregister((uint64_t)(uintptr_t)base_b);
+        munmap(base_a, span_bytes);
+        munmap(base_b, span_bytes);
+    }
     return fails ? 1 : 0;
 }
 
 }  // namespace
 
 int main(int argc, char **argv) {
-    if (argc < 2) { std::printf("usage: fake_gpu <swap|in_place|stall|gpu_quits|dead_gpu> [seed]\n"); return 2; }
+    if (argc < 2) { std::printf("usage: fake_gpu <swap|in_place|spaces|stall|gpu_quits|dead_gpu> [seed]\n"); return 2; }
     return run(argv[1], argc > 2 ? std::strtoull(argv[2], nullptr, 10) : 1);
 }

@@ -1,0 +1,172 @@
+"""GPU parity for switches between two applications that keep their own device addresses over one
+pool of physical memory (paper, "Maintaining consistent virtual memory addresses").
+
+The oracle's model of shared physical memory is one arena that both tables point into; on the GPU
+the two tables point into two different reserved address ranges that map the same pool blocks.
+Results must agree bit for bit, and every use of an unmapped range must be refused on the host."""
+import numpy as np
+import pytest
+
+import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+KiB, MiB = 1 << 10, 1 << 20
+S = 64 * KiB
+BLOCK = 2 * MiB
+
+CASES = [
+    ([5 * S + 1, 300, 2 * S, 9 * S + 77], [4 * S, 11, 3 * S + 9, 7 * S], 0),
+    ([3 * S, 3 * S, 3 * S, 3 * S], [3 * S, 3 * S, 3 * S, 3 * S], 0),
+    ([20 * S + 5, 999, 13 * S, 40 * S + 3], [17 * S, 4, 15 * S + 1, 38 * S], 256),
+    ([4 * S], [100, 200, 6 * S], 3 * S),
+]
+
+
+@pytest.fixture(scope="module")
+def nx():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2601_11743_amd as nx
+    nx.lib()
+    return nx
+
+
+@pytest.fixture(scope="module")
+def raw(nx):
+    from tests.gpu_helpers import RawDevice
+    return RawDevice(nx.lib_path())
+
+
+def rows(base, ldev, host, lhost, sizes):
+    return [(base + od, host.ctypes.data + oh, b) for od, oh, b in zip(ldev.offsets, lhost.offsets, sizes)]
+
+
+def test_two_spaces_share_the_pool(nx, raw):
+    pool = nx.Pool(3 * BLOCK + 5, BLOCK)
+    assert pool.bytes == 4 * BLOCK and pool.block_bytes == BLOCK
+    a, b = nx.Space(pool), nx.Space(pool)
+    assert a.base != b.base and not a.mapped() and not b.mapped()
+    a.map()
+    b.map(BLOCK, 2 * BLOCK)
+    assert a.mapped() and not b.mapped() and b.mapped(BLOCK, 2 * BLOCK) and not b.mapped(0, BLOCK)
+    img = W.content_bytes(5, 0, 2 * BLOCK)
+    raw.upload(a.base + BLOCK, img)
+    assert np.array_equal(raw.download(b.base + BLOCK, 2 * BLOCK), img)      # same bytes, other address
+    # device hashes see the same content through either address
+    h = nx.hash_buffers([a.base + BLOCK, b.base + BLOCK], [2 * BLOCK, 2 * BLOCK], True)
+    assert h[0] == h[1]
+    a.map()                                      # mapping mapped blocks is not an error
+    b.unmap(BLOCK, BLOCK)
+    assert not b.mapped(BLOCK, 2 * BLOCK) and b.mapped(2 * BLOCK, BLOCK)
+    with pytest.raises(nx.NixieError) as e:
+        nx.hash_buffers([b.base + BLOCK], [64], True)            # refused on the host, never launched
+    assert e.value.code == nx.EUNMAPPED
+    for bad in [(1, BLOCK), (0, BLOCK + 1), (4 * BLOCK, BLOCK)]:
+        with pytest.raises(nx.NixieError) as e:
+            a.map(*bad)
+        assert e.value.code == nx.EINVAL
+    with pytest.raises(nx.NixieError) as e:
+        pool.close()
+    assert e.value.code == nx.EBUSY
+    b.close()
+    a.close()
+    pool.close()
+
+
+@pytest.mark.parametrize("case", range(len(CASES)))
+def test_switch_there_and_back_between_spaces(nx, oracle, raw, case):
+    from tests.helpers import AliasedPair
+    from tests.gpu_helpers import first_diff
+    sa, sb, shift = CASES[case]
+    mk = lambda: AliasedPair(sa, sb, 47, shift_b=shift, skew_a=case % 3, skew_b=(case * 5) % 16)
+    ref, g = mk(), mk()
+    h_a = oracle.hash_table(ref.pairs_a(), "dev")
+    h_b = oracle.hash_table(ref.pairs_b(), "host")
+    oracle.switch_direct(ref.pairs_a(), ref.pairs_b())           # A out, then B in, in one arena
+    ref.check()
+    dev_after_b = ref.dev.copy()
+    oracle.switch_direct(ref.pairs_b(), ref.pairs_a())           # and back: B out, then A in
+    dev_after_a = ref.dev.copy()
+
+    pool = nx.Pool(g.dev.size, BLOCK)
+    sp_a, sp_b = nx.Space(pool), nx.Space(pool)
+    sp_a.map()
+    raw.upload(sp_a.base, g.dev)
+    rows_a = rows(sp_a.base, g.la, g.host_a, g.lha, g.sizes_a)
+    rows_b = rows(sp_b.base, g.lb, g.host_b, g.lhb, g.sizes_b)
+    opts = nx.Opts(slot_bytes=S, flags=nx.IN_PLACE)
+    ring = 8 * S
+
+    # B's addresses are reserved but nothing is behind them yet: planning is fine, switching is not
+    plan_ab = nx.Plan(rows_a, rows_b, ring, opts)
+    assert plan_ab.switch(check=False)["rc"] == nx.EUNMAPPED
+    assert np.array_equal(raw.download(sp_a.base, g.dev.size), g.dev)        # nothing was touched
+    sp_b.map()
+    with pytest.raises(nx.NixieError) as e:
+        nx.Plan(rows_a, rows_b, ring, nx.Opts(slot_bytes=S))     # shared blocks without NIXIE_IN_PLACE
+    assert e.value.code == nx.EOVERLAP
+    lay = nx.Layout(rows_a, rows_b, ring, opts)
+    deps = lay.chunks(1)["dep_out"]
+    assert deps.max() > 0, "dependencies must be found although the addresses differ"
+    lay.close()
+
+    h_out, h_in = plan_ab.hash_tables()
+    assert np.array_equal(h_out, h_a) and np.array_equal(h_in, h_b)
+    plan_ab.switch()
+    sp_a.unmap()                                                 # A keeps its addresses, nothing behind them
+    got = raw.download(sp_b.base, g.dev.size)
+    assert np.array_equal(got, dev_after_b), "pool after A->B: " + first_diff(got, dev_after_b)
+    exp_host_a = g.expected_host_a()
+    assert np.array_equal(g.host_a, exp_host_a), "evicted A: " + first_diff(g.host_a, exp_host_a)
+    plan_ab.verify(h_a, h_b)
+    with pytest.raises(nx.NixieError) as e:
+        plan_ab.hash_tables()                                    # would read A's unmapped addresses
+    assert e.value.code == nx.EUNMAPPED
+    assert plan_ab.switch(check=False)["rc"] == nx.EUNMAPPED
+
+    # the way back: A's old pointers become valid again, holding A's old bytes
+    plan_ba = nx.Plan(rows_b, rows_a, ring, opts)
+    sp_a.map()
+    plan_ba.switch()
+    sp_b.unmap()
+    got = raw.download(sp_a.base, g.dev.size)
+    assert np.array_equal(got, dev_after_a), "pool after B->A: " + first_diff(got, dev_after_a)
+    assert np.array_equal(g.host_b, ref.host_b), "evicted B: " + first_diff(g.host_b, ref.host_b)
+    plan_ba.verify(h_b, h_a)
+    for i, (o, b) in enumerate(zip(g.la.offsets, g.sizes_a)):    # A is back where its pointers say
+        assert np.array_equal(got[o:o + b], W.content_bytes(47, i, b))
+
+    plan_ab.close()
+    plan_ba.close()
+    sp_a.close()
+    sp_b.close()
+    pool.close()
+
+
+def test_disjoint_blocks_need_no_in_place_flag(nx, oracle, raw):
+    """Two spaces over one pool whose tables use different blocks share nothing: an ordinary switch."""
+    from tests.helpers import HostSet
+    from tests.gpu_helpers import first_diff
+    sizes_a, sizes_b = [3 * S + 5, 700, 9 * S], [2 * S, 6 * S + 1, 90]
+    rA, rB = HostSet(sizes_a, 3, "dev"), HostSet(sizes_b, 4, "host")
+    gA, gB = HostSet(sizes_a, 3, "dev"), HostSet(sizes_b, 4, "host")
+    oracle.switch_direct(rA.pairs(), rB.pairs())
+    assert max(gA.ldev.total, gB.ldev.total) <= BLOCK
+    pool = nx.Pool(2 * BLOCK, BLOCK)
+    sp_a, sp_b = nx.Space(pool), nx.Space(pool)
+    sp_a.map(0, BLOCK)
+    sp_b.map(BLOCK, BLOCK)
+    raw.upload(sp_a.base, gA.dev)
+    raw.upload(sp_b.base + BLOCK, gB.dev)
+    rows_a = rows(sp_a.base, gA.ldev, gA.host, gA.lhost, gA.sizes)
+    rows_b = rows(sp_b.base + BLOCK, gB.ldev, gB.host, gB.lhost, gB.sizes)
+    plan = nx.Plan(rows_a, rows_b, 8 * S, nx.Opts(slot_bytes=S))
+    plan.switch()
+    got = raw.download(sp_b.base + BLOCK, gB.dev.size)
+    assert np.array_equal(got, rB.dev), "restored set: " + first_diff(got, rB.dev)
+    assert np.array_equal(gA.host, rA.host), "evicted set: " + first_diff(gA.host, rA.host)
+    plan.close()
+    sp_a.close()
+    sp_b.close()
+    pool.close()

@@ -23,7 +23,7 @@ def fake_gpu(tmp_path_factory):
     cmd = ["g++", "-std=c++17", "-O1", "-g", "-fsanitize=thread", "-pthread",
            "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
            os.path.join(ROOT, "tests", "fake_device", "fake_gpu.cpp"),
-           os.path.join(CSRC, "hostside.cpp"), os.path.join(CSRC, "planner.cpp"), os.path.join(CSRC, "hostcopy.cpp"),
+           os.path.join(CSRC, "hostside.cpp"), os.path.join(CSRC, "planner.cpp"), os.path.join(CSRC, "spaces.cpp"), os.path.join(CSRC, "hostcopy.cpp"),
            "-o", out]
     subprocess.check_call(cmd)
     return out
@@ -47,6 +47,14 @@ def test_swap_equals_memcpy_and_is_race_free(fake_gpu, seed):
 @pytest.mark.parametrize("seed", [1, 2, 3])
 def test_in_place_swap(fake_gpu, seed):
     run(fake_gpu, "in_place", seed)
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_in_place_swap_between_two_spaces_of_one_pool(fake_gpu, seed):
+    """The applications see the shared memory at different addresses (one file mapped twice and
+    registered as two spaces): overlap and dependencies must be found through the pool coordinate,
+    a plan without NIXIE_IN_PLACE must be refused, and so must a range across the edge of a space."""
+    run(fake_gpu, "spaces", seed)
 
 
 @pytest.mark.parametrize("scenario", ["stall", "gpu_quits", "dead_gpu"])

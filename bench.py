@@ -111,6 +111,11 @@ def main() -> int:
     ap.add_argument("--in-place", action="store_true",
                     help="in-place switch: B is restored into the HBM that A is evicted from (one device arena); "
                          "every step is a switch in the opposite direction of the one before")
+    ap.add_argument("--spaces", action="store_true",
+                    help="in-place switch between two applications that keep their own device addresses over one "
+                         "pool of physical memory: every step maps the incoming application's address space, "
+                         "switches, and unmaps the outgoing one's (all inside the timed region)")
+    ap.add_argument("--block-mib", type=int, default=0, help="--spaces: pool block size (0 = library default)")
     ap.add_argument("--ring-sweep", action="store_true",
                     help="config 5 protocol: for every ring size of the config, 10 back-to-back ping-pong "
                          "switches A<->B; adds a 'ring_sweep' list to the JSON line")
@@ -142,8 +147,23 @@ def main() -> int:
         slot = 0 if not slot else max(64 << 10, int(slot * args.scale) >> 12 << 12)
 
     t0 = time.perf_counter()
-    A = BigSet(cf["A"], cf["seed_A"], "dev", cf["content"])
-    B = BigSet(cf["B"], cf["seed_B"], "host", cf["content"], share_dev=A if args.in_place else None)
+    pool = space_a = space_b = None
+    if args.spaces:
+        from workloads.device import device_view
+        args.in_place = True
+        sizes = lambda t: [s if isinstance(s, int) else s[1] for s in t]
+        need = max(W.make_layout(sizes(cf["A"]), redzone=256).total, W.make_layout(sizes(cf["B"]), redzone=256).total)
+        pool = nx.Pool(need, args.block_mib << 20)
+        space_a, space_b = nx.Space(pool), nx.Space(pool)
+        space_a.map()
+        space_b.map()
+        A = BigSet(cf["A"], cf["seed_A"], "dev", cf["content"], dev_arena=device_view(space_a.base, pool.bytes))
+        B = BigSet(cf["B"], cf["seed_B"], "host", cf["content"], dev_arena=device_view(space_b.base, pool.bytes))
+        torch.cuda.synchronize()
+        space_b.unmap()                 # B waits in pageable memory: its addresses are reserved, nothing behind them
+    else:
+        A = BigSet(cf["A"], cf["seed_A"], "dev", cf["content"])
+        B = BigSet(cf["B"], cf["seed_B"], "host", cf["content"], share_dev=A if args.in_place else None)
     if args.in_place:
         args.flags |= nx.IN_PLACE
         torch.cuda.empty_cache()
@@ -169,13 +189,24 @@ def main() -> int:
 
     back = nx.Plan(rows_b, rows_a, ring, opts) if args.in_place else None
     n_switches = [0]
+    remap_ms = {"map": [], "unmap": []}
 
     def step():
         fwd_turn = (n_switches[0] % 2 == 0) or back is None
         lay = nx.Layout(rows_a if fwd_turn else rows_b, rows_b if fwd_turn else rows_a, ring, opts)
         lay.close()                                    # the chunk planner is part of every step
         n_switches[0] += 1
-        return (plan if fwd_turn else back).switch()
+        if pool is None:
+            return (plan if fwd_turn else back).switch()
+        t_a = time.perf_counter()
+        (space_b if fwd_turn else space_a).map()       # the incoming application's addresses get memory
+        t_b = time.perf_counter()
+        st = (plan if fwd_turn else back).switch()
+        t_c = time.perf_counter()
+        (space_a if fwd_turn else space_b).unmap()     # the outgoing application keeps only its addresses
+        remap_ms["map"].append((t_b - t_a) * 1e3)
+        remap_ms["unmap"].append((time.perf_counter() - t_c) * 1e3)
+        return st
 
     for _ in range(args.warmup):
         step()
@@ -222,7 +253,11 @@ def main() -> int:
     if back is not None:                # in place: where the sets are depends on the number of switches so far
         b_in_hbm = n_switches[0] % 2 == 1
         rep = plan.verify(h_out, h_in) if b_in_hbm else back.verify(h_in, h_out)
-        arenas_ok = None if diag else bool((B if b_in_hbm else A).arenas_equal())
+        here = B if b_in_hbm else A
+        if pool is None or A.layout.offsets == B.layout.offsets:
+            arenas_ok = None if diag else bool(here.arenas_equal())
+        else:                           # the gaps of one layout hold the other application's bytes
+            arenas_ok = None if diag or len(here.sizes) > 5000 else bool(here.allocations_equal())
         back.close()
     else:
         rep = plan.verify(h_out, h_in)  # per-allocation hashes on the side that now holds the data
@@ -288,9 +323,21 @@ def main() -> int:
     }
     if serialized is not None:
         res["serialized_self_baseline"] = serialized
+    if pool is not None:
+        k = len(remap_ms["map"]) - args.steps           # timed steps only
+        res["config"]["spaces"] = {"pool_bytes": pool.bytes, "block_bytes": pool.block_bytes,
+                                   "blocks": pool.bytes // pool.block_bytes}
+        res["remap_ms"] = {"map_median": round(med(sorted(remap_ms["map"][k:])), 3),
+                           "unmap_median": round(med(sorted(remap_ms["unmap"][k:])), 3),
+                           "note": "inside ms_per_step: map the incoming application's space before the switch, "
+                                   "unmap the outgoing one's after it"}
     if sweep is not None:
         res["ring_sweep"] = sweep
     del A, B
+    if pool is not None:
+        space_a.close()
+        space_b.close()
+        pool.close()
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(cf, int(args.cpu_sample_gib * 2**30))
     print(json.dumps(res), flush=True)

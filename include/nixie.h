@@ -253,7 +253,7 @@ int nixie_hash_buffers(const void *const *ptrs, const uint64_t *bytes, uint64_t 
  * None of these calls runs inside the switch.  Mapping and unmapping take the library's
  * switch lock, so they wait for a running nixie_switch; nixie_switch returns NIXIE_EUNMAPPED
  * without touching the GPU when a listed range lies in unmapped blocks.
- * block_bytes: multiple of the device's allocation granularity, 0 = 64 MiB (a map or unmap
+ * block_bytes: multiple of the device's allocation granularity, 0 = 256 MiB (a map or unmap
  * call costs the same for any block size, so small blocks make the remap slow).  bytes is
  * rounded up to whole blocks.  offset and bytes of map / unmap must be multiples of the
  * block size; mapping a mapped block or unmapping an unmapped one is not an error.

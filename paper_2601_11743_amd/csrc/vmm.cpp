@@ -34,7 +34,10 @@ struct nixie_space {
 
 namespace {
 
-constexpr uint64_t kDefaultBlock = 64ull << 20;
+// An unmap call takes about 0.25 ms on MI355X whatever the block size (a map call 0.03 ms), so
+// the block size sets the cost of a remap: 17 GiB in 64 MiB blocks unmaps in 71 ms, in 256 MiB
+// blocks in 17 ms, in 1 GiB blocks in 4 ms.
+constexpr uint64_t kDefaultBlock = 256ull << 20;
 
 int fail(hipError_t e) {
     set_last_hip_error((int)e);

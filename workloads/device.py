@@ -30,21 +30,42 @@ def pageable_arena(nbytes: int, fill: int | None = 0) -> np.ndarray:
     return arr
 
 
+def device_view(address: int, nbytes: int, device: str = "cuda:0"):
+    """A uint8 torch tensor over device memory that torch did not allocate (the caller keeps it
+    alive and mapped for as long as the tensor is used)."""
+    import torch
+
+    class _Raw:
+        __cuda_array_interface__ = {"shape": (nbytes,), "typestr": "|u1", "data": (address, False), "version": 2}
+
+    return torch.as_tensor(_Raw(), device=device)
+
+
 class BigSet:
     """One application's working set at full size: an HBM arena (torch uint8) and a pageable
     arena with the same layout (256 B aligned bases, red zones between allocations)."""
 
     def __init__(self, sizes, seed: int, resident: str, content: str, device: str = "cuda:0",
                  redzone: int = 256, red: int = 0xC3, poison_dev: int = 0xA5, poison_host: int = 0x5A,
-                 share_dev: "BigSet | None" = None):
+                 share_dev: "BigSet | None" = None, dev_arena=None):
         """share_dev: for an in-place switch -- this (host-resident) set gets no HBM of its own; its
-        device ranges lie in the other set's arena, which must have the same layout."""
+        device ranges lie in the other set's arena, which must have the same layout.
+        dev_arena: a uint8 device tensor supplied by the caller (for instance a view of a mapped
+        address space) that becomes this set's HBM arena.  A GPU-resident set is generated into it;
+        a host-resident set only takes its addresses and never touches it, since the memory behind
+        it may be another application's."""
         import torch
         self.sizes = [s if isinstance(s, int) else s[1] for s in sizes]
         self.names = [("" if isinstance(s, int) else s[0]) for s in sizes]
         self.seed, self.resident, self.red = seed, resident, red
         self.layout: Layout = make_layout(self.sizes, redzone=redzone)
-        self.dev = torch.full((self.layout.total,), red, dtype=torch.uint8, device=device)
+        if dev_arena is not None:
+            assert dev_arena.dtype == torch.uint8 and dev_arena.numel() >= self.layout.total and share_dev is None
+        if dev_arena is not None and resident == "dev":
+            self.dev = dev_arena[:self.layout.total]
+            self.dev.fill_(red)
+        else:
+            self.dev = torch.full((self.layout.total,), red, dtype=torch.uint8, device=device)
         self.host = pageable_arena(self.layout.total, fill=red)
         self.host_t = torch.from_numpy(self.host)
         g = torch.Generator(device=device)
@@ -64,6 +85,8 @@ class BigSet:
                 assert resident == "host" and share_dev.layout.offsets == self.layout.offsets \
                     and share_dev.sizes == self.sizes, "in-place sets must share one layout"
                 self.dev = share_dev.dev          # the generator's scratch arena is dropped here
+            elif dev_arena is not None:
+                self.dev = dev_arena[:self.layout.total]     # likewise; addresses only
             else:
                 for o, b in zip(self.layout.offsets, self.sizes):
                     self.dev[o:o + b] = poison_dev
@@ -96,6 +119,18 @@ class BigSet:
     def host_view(self, i: int) -> np.ndarray:
         o, b = self.layout.offsets[i], self.sizes[i]
         return self.host[o:o + b]
+
+    def allocations_equal(self) -> bool:
+        """Every allocation's HBM bytes against its pageable bytes (no red zones: for arenas whose
+        gaps belong to someone else)."""
+        import torch
+        for o, b in zip(self.layout.offsets, self.sizes):
+            step = 1 << 30
+            for a in range(o, o + b, step):
+                e = min(a + step, o + b)
+                if not torch.equal(self.dev[a:e], self.host_t[a:e].to(self.dev.device)):
+                    return False
+        return True
 
     def arenas_equal(self) -> bool:
         """Whole-arena compare, HBM against pageable (contents and red zones), in 1 GiB steps."""

@@ -75,12 +75,14 @@ enum nixie_flags {
     NIXIE_DIAG_STALL_DRAIN = 1u << 3, /* failure-path test: drain threads never return credits, so the switch must
                                          end with NIXIE_ETIMEOUT after timeout_ms */
     NIXIE_HOST_PLAIN_MEMCPY = 1u << 4,/* host threads use libc memcpy instead of streaming stores */
-    NIXIE_IN_PLACE = 1u << 5          /* in-place switch: device ranges of the incoming table may overlap device ranges
+    NIXIE_IN_PLACE = 1u << 5,         /* in-place switch: device ranges of the incoming table may overlap device ranges
                                          of the outgoing table (the incoming application reuses the GPU memory the
                                          outgoing one gives up; paper, "Maintaining consistent virtual memory
                                          addresses").  A chunk is scattered only after every outgoing chunk that
                                          covers GPU bytes it overwrites has left HBM.  Ranges inside one table must
                                          still be disjoint, and so must all host ranges. */
+    NIXIE_NO_DIRECT = 1u << 6         /* measurement: allocations whose host side lies in the registered pinned tier
+                                         go through the ring and the host threads like all others */
 };
 
 /* Every field 0 = library default. */
@@ -117,6 +119,8 @@ typedef struct {
     uint64_t pinned_ctrl_bytes; /* flag block, reported separately                  */
     uint32_t gather_wgs, scatter_wgs, team_out, team_in;
     uint32_t drain_threads, fill_threads;
+    uint64_t direct_chunks_out, direct_chunks_in; /* chunks that move between HBM and the pinned tier  */
+    uint64_t direct_bytes_out, direct_bytes_in;   /* directly: the last of chunks_* / part of bytes_*  */
 } nixie_plan_info_t;
 
 /* One contiguous piece of one allocation inside one chunk. */
@@ -127,7 +131,9 @@ typedef struct {
     uint32_t len;
 } nixie_segment_t;
 
-/* One ring-slot's worth of work: segments [seg_begin, seg_begin + seg_count). */
+/* One ring-slot's worth of work: segments [seg_begin, seg_begin + seg_count).  The chunks of a
+ * direction that go through the ring come first; direct chunks (pinned tier) follow, one segment
+ * each, and use no slot. */
 typedef struct {
     uint64_t seg_begin;
     uint32_t seg_count;
@@ -271,6 +277,21 @@ int nixie_space_unmap(nixie_space_t *space, uint64_t offset, uint64_t bytes);
 /* 1 = every block of [offset, offset + bytes) is mapped, 0 = not, negative = error */
 int nixie_space_mapped(const nixie_space_t *space, uint64_t offset, uint64_t bytes);
 int nixie_space_destroy(nixie_space_t *space);
+
+/* ---- pinned tier (paper, "Hierarchical Memory": a chunk lives in exactly one of GPU memory,
+ *      CPU pinned memory, CPU pageable memory or disk, and migrates between tiers as a whole) ---
+ * nixie_tier_register announces a range of pinned host memory that the GPU can address (from
+ * hipHostMalloc; the caller keeps it allocated while registered).  From then on, an allocation
+ * of a table whose [host_ptr, host_ptr + bytes) lies inside a registered range, with
+ * host_ptr == dev_ptr modulo 16, is moved by the kernel straight between HBM and host_ptr: it
+ * takes no ring slot, no host thread touches it, and it costs host DRAM one access per byte
+ * instead of three.  Allocations elsewhere (pageable memory) go through the ring as before,
+ * in the same switch; a plan whose tables are entirely in the pinned tier needs no ring
+ * (ring_bytes may be 0) and starts no host threads.  Semantics of nixie_switch are unchanged.
+ * Plans pick the registry up when they are made.  Errors: NIXIE_EINVAL (NULL, 0 bytes, not
+ * pinned host memory, overlaps a registered range, unknown base), NIXIE_EHIP. */
+int nixie_tier_register(void *host_base, uint64_t bytes);
+int nixie_tier_unregister(void *host_base);
 
 /* ---- host-link probe (paper, "Microbenchmarks": throughput is judged against the link's
  *      measured maximum) ---------------------------------------------------------------------

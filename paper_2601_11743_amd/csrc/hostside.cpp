@@ -92,7 +92,7 @@ void HostSide::run_drain(uint32_t idx) {
     const uint32_t T = threads[0];
     const DirLayout &D = L->dir[0];
     const uint32_t flags = L->opts.flags;
-    const uint64_t n = D.chunks.size(), S = L->slot_bytes;
+    const uint64_t n = D.staged, S = L->slot_bytes;   // direct chunks never come through the ring
     const bool plain = flags & NIXIE_HOST_PLAIN_MEMCPY;
     std::vector<uint64_t> last(D.slots, 0);
     IdleWatch watch{p, 0};
@@ -133,7 +133,7 @@ void HostSide::run_fill(uint32_t idx) {
     const uint32_t T = threads[1];
     const DirLayout &D = L->dir[1];
     const uint32_t flags = L->opts.flags;
-    const uint64_t n = D.chunks.size(), S = L->slot_bytes;
+    const uint64_t n = D.staged, S = L->slot_bytes;   // direct chunks never come through the ring
     const bool plain = flags & NIXIE_HOST_PLAIN_MEMCPY;
     std::vector<uint64_t> pending(D.slots, 0);
     uint64_t outstanding = 0;

@@ -12,9 +12,14 @@ namespace nixie {
 // ---- planner output (host) ---------------------------------------------------------------
 struct DirLayout {
     std::vector<nixie_segment_t> segs;   // sorted by slot_off inside each chunk
-    std::vector<nixie_chunk_t> chunks;   // in execution order
+    std::vector<nixie_chunk_t> chunks;   // in execution order: [0, staged) through the ring, then direct ones
     uint64_t bytes = 0;
     uint32_t slots = 0;
+    uint64_t staged = 0;                 // number of chunks that use ring slots
+    uint64_t direct_bytes = 0;
+    // per direct chunk: GPU address of the pinned-tier image of slot offset 0 (16-byte aligned), so
+    // that "base + slot_off" addresses a direct segment exactly as it addresses one in a ring slot
+    std::vector<uint64_t> direct_base;
 };
 
 struct Layout {
@@ -63,6 +68,8 @@ struct DevDir {
     uint32_t *arrive;            // device memory, one counter per chunk
     uint64_t *stall_ticks;       // device memory, summed wait time
     uint32_t n_chunks, n_slots, team, wgs;
+    uint32_t n_staged;           // chunks [0, n_staged) take ring slots; the rest are direct
+    const uint64_t *direct_base; // device memory, per direct chunk
 };
 
 struct SwapArgs {

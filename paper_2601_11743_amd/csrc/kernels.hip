@@ -43,6 +43,7 @@ namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+constexpr uint32_t kDirect = 0xFFFFFFFFu;             // "slot + 1" of a chunk that uses no slot
 constexpr uint32_t kUnroll = 8;                       // 16 B x 64 lanes x 8 = one 8 KiB tile per wave pass
 static_assert(kTileBytes == 16 * 64 * kUnroll, "tile = one unrolled wave pass");
 
@@ -162,8 +163,10 @@ __device__ void run_direction(const SwapArgs &a) {
                 // The pump wave writes chunk_slot[k] once chunk k has a slot: outgoing, a slot the
                 // host has released; incoming, the slot the host has filled with chunk k.  Workers
                 // only ever poll device memory: a poll over the link queues behind the bulk reads.
+                // A direct chunk (pinned tier) needs no slot: its image already has a place.
                 const uint32_t *where = D.chunk_slot + u / D.team;
-                cs = __hip_atomic_load(where, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                cs = u / D.team >= D.n_staged ? kDirect
+                                              : __hip_atomic_load(where, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 if (cs == 0) {
                     const uint64_t t0 = wall_clock64();
                     uint32_t it = 0;
@@ -210,8 +213,10 @@ __device__ void run_direction(const SwapArgs &a) {
         if (u >= total_units || s_slot == 0) break;
         const uint32_t k = u / D.team, part = u % D.team;
         const uint32_t slot = s_slot - 1;
+        const bool direct = s_slot == kDirect;
         const DevChunk ch = D.chunks[k];
-        uint8_t *slot_base = D.ring + (size_t)slot * a.slot_bytes;
+        uint8_t *slot_base = direct ? (uint8_t *)(uintptr_t)D.direct_base[k - D.n_staged]
+                                    : D.ring + (size_t)slot * a.slot_bytes;
 
         const uint32_t n_tiles = (ch.used + kTileBytes - 1) / kTileBytes;
         for (uint32_t t = part * waves_per_wg + wave; t < n_tiles; t += D.team * waves_per_wg) {
@@ -232,7 +237,7 @@ __device__ void run_direction(const SwapArgs &a) {
             // (for the outgoing direction the counter also tells the pump that the chunk has left HBM:
             //  every load of this unit completed before the barrier above)
             const uint32_t old = __hip_atomic_fetch_add(D.arrive + k, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const bool last = (old == D.team - 1);
+            const bool last = (old == D.team - 1) && !direct;   // nobody waits for a direct chunk's slot
             if (last)   // outgoing: "slot holds chunk k"; incoming: "chunk k has left the slot"
                 __hip_atomic_store(D.post_flags + (size_t)slot * kFlagStride, (uint64_t)k + 1u, __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_SYSTEM);
@@ -284,14 +289,14 @@ __device__ void run_pump(const SwapArgs &a, int dir) {
                 const uint32_t rank = __popcll(mask & ((1ull << lane) - 1ull));
                 if (changed) {
                     const uint32_t k = next + rank;
-                    if (k < D.n_chunks)
+                    if (k < D.n_staged)
                         __hip_atomic_store(D.chunk_slot + k, s + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     D.seen[s] = v;
                 }
                 next += (uint32_t)__popcll(mask);
             } else if (changed) {
                 const uint64_t k = v - 1;
-                if (k < D.n_chunks)
+                if (k < D.n_staged)
                     __hip_atomic_store(D.chunk_slot + k, s + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 D.seen[s] = v;
             }

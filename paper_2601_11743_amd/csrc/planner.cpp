@@ -96,10 +96,13 @@ std::vector<uint64_t> walk_order(const std::vector<nixie_alloc_t> &t, uint32_t o
 
 // Greedy sequential packing.  A segment's slot offset is congruent to its device address
 // modulo 16, so the 16-byte lanes of the copy kernels are aligned on both sides at once.
-void cut(const std::vector<nixie_alloc_t> &t, const std::vector<uint64_t> &walk, uint64_t S, DirLayout &D) {
+// direct[i] != 0: allocation i lives in the pinned tier on the host side and is cut by cut_direct.
+void cut(const std::vector<nixie_alloc_t> &t, const std::vector<uint64_t> &walk, const std::vector<uint64_t> &direct,
+         uint64_t S, DirLayout &D) {
     D.segs.clear();
     D.chunks.clear();
-    D.bytes = 0;
+    D.direct_base.clear();
+    D.bytes = D.direct_bytes = 0;
     uint64_t total = 0;
     for (const auto &a : t) total += a.bytes;
     D.segs.reserve(t.size() + total / S + 8);     // every allocation once, plus one cut per slot boundary
@@ -107,6 +110,7 @@ void cut(const std::vector<nixie_alloc_t> &t, const std::vector<uint64_t> &walk,
     uint64_t fill = 0;
     bool open = false;
     for (uint64_t i : walk) {
+        if (direct[i]) continue;
         const nixie_alloc_t &a = t[i];
         uint64_t off = 0;
         while (off < a.bytes) {
@@ -127,6 +131,25 @@ void cut(const std::vector<nixie_alloc_t> &t, const std::vector<uint64_t> &walk,
             D.bytes += take;
         }
     }
+    D.staged = D.chunks.size();
+    // Pinned tier: nothing to pack, the bytes go where they already have a place.  One chunk per
+    // slot-sized piece, one segment each; the piece's image starts at the same offset modulo 16
+    // as on the device, like a segment in a ring slot.
+    for (uint64_t i : walk) {
+        if (!direct[i]) continue;
+        const nixie_alloc_t &a = t[i];
+        uint64_t off = 0;
+        while (off < a.bytes) {
+            const uint64_t dev = (uint64_t)(uintptr_t)a.dev_ptr + off, pos = dev & 15;
+            const uint64_t take = std::min(S - pos, a.bytes - off);
+            D.chunks.push_back(nixie_chunk_t{(uint64_t)D.segs.size(), 1, (uint32_t)(pos + take), 0});
+            D.segs.push_back(nixie_segment_t{dev, (uint64_t)(uintptr_t)a.host_ptr + off, (uint32_t)pos, (uint32_t)take});
+            D.direct_base.push_back(direct[i] + off - pos);
+            off += take;
+            D.bytes += take;
+            D.direct_bytes += take;
+        }
+    }
 }
 
 }  // namespace
@@ -143,13 +166,17 @@ int build_layout(const nixie_table_t *out_table, const nixie_table_t *in_table, 
 
     // no aliasing: device ranges pairwise disjoint across both tables, host ranges likewise
     std::vector<Range> dev, host;
-    uint64_t tot[2] = {0, 0};
+    std::vector<uint64_t> direct[2];      // per allocation: its GPU-visible pinned-tier address, or 0
+    uint64_t tot[2] = {0, 0}, staged_tot[2] = {0, 0};
+    const bool use_tier = !(L.opts.flags & NIXIE_NO_DIRECT);
     size_t mid = 0;
     dev.reserve(L.table[0].size() + L.table[1].size());
     host.reserve(L.table[0].size() + L.table[1].size());
     for (int x = 0; x < 2; x++) {
         if (x == 1) mid = dev.size();
-        for (const auto &a : L.table[x]) {
+        direct[x].assign(L.table[x].size(), 0);
+        for (size_t i = 0; i < L.table[x].size(); i++) {
+            const nixie_alloc_t &a = L.table[x][i];
             if (a.bytes == 0) continue;
             uint64_t d = (uint64_t)(uintptr_t)a.dev_ptr, h = (uint64_t)(uintptr_t)a.host_ptr;
             uint64_t key = d;
@@ -159,6 +186,9 @@ int build_layout(const nixie_table_t *out_table, const nixie_table_t *in_table, 
             dev.push_back({key, key + a.bytes});
             host.push_back({h, h + a.bytes});
             tot[x] += a.bytes;
+            uint64_t seen_by_gpu = 0;
+            if (use_tier && tier_translate(h, a.bytes, &seen_by_gpu) && ((seen_by_gpu ^ d) & 15) == 0) direct[x][i] = seen_by_gpu;
+            else staged_tot[x] += a.bytes;
         }
     }
     const bool in_place = (L.opts.flags & NIXIE_IN_PLACE) != 0;
@@ -170,9 +200,12 @@ int build_layout(const nixie_table_t *out_table, const nixie_table_t *in_table, 
     }
     if (any_overlap(host, mid)) return NIXIE_EOVERLAP;
 
-    const int active = (tot[0] > 0) + (tot[1] > 0);
+    // only what goes through the ring counts for the ring's geometry
+    const int active = (staged_tot[0] > 0) + (staged_tot[1] > 0);
     uint64_t S = L.opts.slot_bytes;
-    if (S == 0) {
+    if (S == 0 && active == 0) {
+        S = kDefaultSlot;        // no ring: the slot size only sets the size of a direct chunk
+    } else if (S == 0) {
         // About 128 slots per active direction, between 64 KiB and 2 MiB.  Slots are a free pool,
         // so what counts is how finely the ring is recycled: on a 64 MiB ring 2 MiB slots lose
         // 15 % against 256 KiB slots, on a 16 MiB ring 256 KiB slots lose 20 % against 64 KiB ones,
@@ -183,27 +216,27 @@ int build_layout(const nixie_table_t *out_table, const nixie_table_t *in_table, 
         return NIXIE_EINVAL;
     }
     const uint64_t n_slots = ring_bytes / S;
-    if (n_slots < 2ull * (uint64_t)std::max(active, 1) || n_slots > (1ull << 20)) return NIXIE_EINVAL;
+    if (n_slots < 2ull * (uint64_t)active || n_slots > (1ull << 20)) return NIXIE_EINVAL;   // no ring needed when nothing is staged
 
     uint64_t n_out;
-    if (tot[0] == 0) n_out = 0;
-    else if (tot[1] == 0) n_out = n_slots;
+    if (staged_tot[0] == 0) n_out = 0;
+    else if (staged_tot[1] == 0) n_out = n_slots;
     else if (L.opts.out_slots) n_out = L.opts.out_slots;
     else if (L.opts.flags & NIXIE_SPLIT_BY_BYTES) {
-        long double f = (long double)tot[0] / (long double)(tot[0] + tot[1]);
+        long double f = (long double)staged_tot[0] / (long double)(staged_tot[0] + staged_tot[1]);
         n_out = (uint64_t)(f * (long double)n_slots + 0.5L);
         n_out = std::min(std::max<uint64_t>(n_out, 2), n_slots - 2);
     } else n_out = n_slots / 2;
-    if (tot[0] && tot[1] && (n_out < 2 || n_slots - n_out < 2)) return NIXIE_EINVAL;
+    if (staged_tot[0] && staged_tot[1] && (n_out < 2 || n_slots - n_out < 2)) return NIXIE_EINVAL;
 
     L.ring_bytes = ring_bytes;
     L.slot_bytes = S;
     L.dir[0].slots = (uint32_t)n_out;
-    L.dir[1].slots = (uint32_t)(tot[1] ? n_slots - n_out : 0);
+    L.dir[1].slots = (uint32_t)(staged_tot[1] ? n_slots - n_out : 0);
     const std::vector<uint64_t> walk0 = walk_order(L.table[0], L.opts.order);
     std::vector<uint64_t> walk1 = walk_order(L.table[1], L.opts.order);
     if (in_place && tot[0] && tot[1]) {
-        cut(L.table[0], walk0, S, L.dir[0]);
+        cut(L.table[0], walk0, direct[0], S, L.dir[0]);
         std::vector<OutSpan> osegs;
         osegs.reserve(L.dir[0].segs.size());
         for (uint64_t k = 0; k < L.dir[0].chunks.size(); k++) {
@@ -222,7 +255,7 @@ int build_layout(const nixie_table_t *out_table, const nixie_table_t *in_table, 
             adep[i] = dep_of_range(osegs, d, d + L.table[1][i].bytes);
         }
         std::stable_sort(walk1.begin(), walk1.end(), [&](uint64_t a, uint64_t b) { return adep[a] < adep[b]; });
-        cut(L.table[1], walk1, S, L.dir[1]);
+        cut(L.table[1], walk1, direct[1], S, L.dir[1]);
         for (nixie_chunk_t &c : L.dir[1].chunks)
             for (uint64_t q = c.seg_begin; q < c.seg_begin + c.seg_count; q++) {
                 const nixie_segment_t &sg = L.dir[1].segs[q];
@@ -230,12 +263,12 @@ int build_layout(const nixie_table_t *out_table, const nixie_table_t *in_table, 
                 c.dep_out = std::max(c.dep_out, dep_of_range(osegs, key, key + sg.len));
             }
     } else if (L.table[0].size() + L.table[1].size() > 20000) {   // large tables: one direction per thread
-        std::thread other([&] { cut(L.table[1], walk1, S, L.dir[1]); });
-        cut(L.table[0], walk0, S, L.dir[0]);
+        std::thread other([&] { cut(L.table[1], walk1, direct[1], S, L.dir[1]); });
+        cut(L.table[0], walk0, direct[0], S, L.dir[0]);
         other.join();
     } else {
-        cut(L.table[0], walk0, S, L.dir[0]);
-        cut(L.table[1], walk1, S, L.dir[1]);
+        cut(L.table[0], walk0, direct[0], S, L.dir[0]);
+        cut(L.table[1], walk1, direct[1], S, L.dir[1]);
     }
     if (L.dir[0].chunks.size() > 0xFFFFFFF0ull / 256 || L.dir[1].chunks.size() > 0xFFFFFFF0ull / 256 ||
         L.dir[0].segs.size() > 0xFFFFFFF0ull || L.dir[1].segs.size() > 0xFFFFFFF0ull)
@@ -260,6 +293,10 @@ void fill_info(const Layout &L, nixie_plan_info_t *info) {
     info->segments_in = L.dir[1].segs.size();
     info->bytes_out = L.dir[0].bytes;
     info->bytes_in = L.dir[1].bytes;
+    info->direct_chunks_out = L.dir[0].chunks.size() - L.dir[0].staged;
+    info->direct_chunks_in = L.dir[1].chunks.size() - L.dir[1].staged;
+    info->direct_bytes_out = L.dir[0].direct_bytes;
+    info->direct_bytes_in = L.dir[1].direct_bytes;
     info->pinned_ring_bytes = (uint64_t)(L.dir[0].slots + L.dir[1].slots) * L.slot_bytes;
     info->pinned_ctrl_bytes = (wait_flag_words(L.dir[0].slots) + wait_flag_words(L.dir[1].slots) +
                                ((uint64_t)(L.dir[0].slots + L.dir[1].slots) + 2) * kFlagStride) * 8;
@@ -274,9 +311,9 @@ void fill_info(const Layout &L, nixie_plan_info_t *info) {
     // what the host threads drain or fill meanwhile.
     uint32_t team = L.opts.team;
     if (team == 0) {
-        const uint32_t max_slots = std::max(1u, std::max(L.dir[0].slots, L.dir[1].slots));
+        const uint32_t max_slots = std::max(L.dir[0].slots, L.dir[1].slots);
         uint64_t unit = 128u << 10;
-        while (unit > (16u << 10) && unit * 4 * std::max(wgs[0], wgs[1]) > (uint64_t)max_slots * L.slot_bytes) unit >>= 1;
+        while (max_slots && unit > (16u << 10) && unit * 4 * std::max(wgs[0], wgs[1]) > (uint64_t)max_slots * L.slot_bytes) unit >>= 1;
         team = (uint32_t)std::max<uint64_t>(1, L.slot_bytes / unit);
     }
     team = std::min(team, 256u);
@@ -287,11 +324,12 @@ void fill_info(const Layout &L, nixie_plan_info_t *info) {
     uint32_t thr[2] = {L.opts.drain_threads ? L.opts.drain_threads : dflt, L.opts.fill_threads ? L.opts.fill_threads : dflt};
     for (int x = 0; x < 2; x++) {
         if (L.dir[x].chunks.empty()) { wgs[x] = 0; thr[x] = 0; continue; }
-        // more workgroups than slots * team could only spin on credits
-        uint64_t cap = (uint64_t)L.dir[x].slots * team;
+        // more workgroups than slots * team could only spin on credits (direct chunks need none)
+        uint64_t cap = L.dir[x].staged == L.dir[x].chunks.size() ? (uint64_t)L.dir[x].slots * team : ~0ull;
         wgs[x] = (uint32_t)std::max<uint64_t>(1, std::min<uint64_t>(wgs[x], cap));
         wgs[x] = std::min(wgs[x], 1024u);
-        thr[x] = std::min(std::min(thr[x], 64u), std::max(1u, L.dir[x].slots));
+        // no host thread where nothing goes through the ring
+        thr[x] = L.dir[x].staged ? std::min(std::min(thr[x], 64u), std::max(1u, L.dir[x].slots)) : 0;
     }
     info->gather_wgs = wgs[0];
     info->scatter_wgs = wgs[1];

@@ -63,6 +63,7 @@ struct nixie_plan {
     // device memory (descriptors and counters only, never payload)
     DevSeg *segs_d[2] = {nullptr, nullptr};
     DevChunk *chunks_d[2] = {nullptr, nullptr};
+    uint64_t *direct_d[2] = {nullptr, nullptr};
     uint32_t *counters_d = nullptr;
     uint64_t n_counters = 0, seen_off[2] = {0, 0}, cslot_off[2] = {0, 0}, arrive_off[2] = {0, 0};
     HashDesc *hdesc_d[2] = {nullptr, nullptr};
@@ -87,6 +88,7 @@ void destroy_plan(nixie_plan_t *p) {
     for (int x = 0; x < 2; x++) {
         if (p->segs_d[x]) (void)hipFree(p->segs_d[x]);
         if (p->chunks_d[x]) (void)hipFree(p->chunks_d[x]);
+        if (p->direct_d[x]) (void)hipFree(p->direct_d[x]);
         if (p->hdesc_d[x]) (void)hipFree(p->hdesc_d[x]);
     }
     if (p->counters_d) (void)hipFree(p->counters_d);
@@ -148,6 +150,8 @@ int create_plan(nixie_plan_t *p) {
         int rc = upload(segs.data(), segs.size() * sizeof(DevSeg), (void **)&p->segs_d[x]);
         if (rc) return rc;
         rc = upload(chunks.data(), chunks.size() * sizeof(DevChunk), (void **)&p->chunks_d[x]);
+        if (rc) return rc;
+        rc = upload(D.direct_base.data(), D.direct_base.size() * sizeof(uint64_t), (void **)&p->direct_d[x]);
         if (rc) return rc;
 
         // hash descriptors of the table (table order)
@@ -217,7 +221,9 @@ int run_pass(nixie_plan_t *p, uint32_t mask, hipStream_t stream, nixie_stats_t *
         d.arrive = p->counters_d + p->arrive_off[x];
         d.stall_ticks = (uint64_t *)(p->counters_d + 4 + 2 * x);
         d.n_chunks = on ? (uint32_t)D.chunks.size() : 0;
-        d.n_slots = D.slots ? D.slots : 1;
+        d.n_staged = on ? (uint32_t)D.staged : 0;
+        d.direct_base = p->direct_d[x];
+        d.n_slots = D.slots;
         d.team = x ? p->info.team_in : p->info.team_out;
         if (d.team == 0) d.team = 1;
         d.wgs = on ? (x ? p->info.scatter_wgs : p->info.gather_wgs) : 0;
@@ -254,6 +260,9 @@ int run_pass(nixie_plan_t *p, uint32_t mask, hipStream_t stream, nixie_stats_t *
     p->crew.wait();   // drain / fill threads done (finished, aborted or timed out)
     hipError_t se = hipStreamSynchronize(stream);
     if (se != hipSuccess) { t_last_hip_error = (int)se; return NIXIE_EHIP; }
+    // directly moved chunks are complete when the kernel is: no host thread saw them go by
+    for (int x = 0; x < 2; x++)
+        if ((mask & (1u << x)) && L.dir[x].staged < L.dir[x].chunks.size()) p->hs.end_ns[x].store(now_ns());
 
     if (st) {
         float ms = 0.f;

@@ -19,6 +19,37 @@ SpaceSpan *find_locked(uint64_t addr) {
 }
 }  // namespace
 
+namespace {
+std::vector<TierSpan> g_tiers;            // sorted by host_base, disjoint; under g_mu
+}
+
+bool tier_register(const TierSpan &t) {
+    std::lock_guard<std::mutex> g(g_mu);
+    auto it = std::upper_bound(g_tiers.begin(), g_tiers.end(), t.host_base, [](uint64_t v, const TierSpan &x) { return v < x.host_base; });
+    if (it != g_tiers.end() && it->host_base < t.host_base + t.bytes) return false;
+    if (it != g_tiers.begin() && (it - 1)->host_base + (it - 1)->bytes > t.host_base) return false;
+    g_tiers.insert(it, t);
+    return true;
+}
+
+bool tier_unregister(uint64_t host_base) {
+    std::lock_guard<std::mutex> g(g_mu);
+    for (auto it = g_tiers.begin(); it != g_tiers.end(); ++it)
+        if (it->host_base == host_base) { g_tiers.erase(it); return true; }
+    return false;
+}
+
+bool tier_translate(uint64_t host_addr, uint64_t bytes, uint64_t *dev_addr) {
+    std::lock_guard<std::mutex> g(g_mu);
+    if (g_tiers.empty() || bytes == 0) return false;
+    auto it = std::upper_bound(g_tiers.begin(), g_tiers.end(), host_addr, [](uint64_t v, const TierSpan &x) { return v < x.host_base; });
+    if (it == g_tiers.begin()) return false;
+    --it;
+    if (host_addr + bytes > it->host_base + it->bytes) return false;
+    *dev_addr = it->dev_base + (host_addr - it->host_base);
+    return true;
+}
+
 std::shared_mutex &switch_lock() {
     static std::shared_mutex mu;
     return mu;

@@ -39,6 +39,17 @@ bool space_translate(uint64_t addr, uint64_t bytes, uint64_t *key, SpaceUse *use
 bool space_uses_mapped(const std::vector<SpaceUse> &uses);
 
 
+// ---- pinned tier ------------------------------------------------------------------------------
+// Paper, "Hierarchical Memory": a chunk lives in exactly one of GPU memory, CPU pinned memory,
+// CPU pageable memory (or disk).  Host ranges registered here are pinned memory that the GPU can
+// address; an allocation whose host side lies in one moves between HBM and that range directly,
+// with no ring slot and no host copy.
+struct TierSpan { uint64_t host_base, bytes, dev_base; };   // dev_base: the GPU's address of host_base
+bool tier_register(const TierSpan &t);                       // false: overlaps a registered range
+bool tier_unregister(uint64_t host_base);
+// GPU address of [host_addr, host_addr + bytes) when the range lies wholly inside one registered span
+bool tier_translate(uint64_t host_addr, uint64_t bytes, uint64_t *dev_addr);
+
 // Held shared by a running switch (and by the hash kernels), exclusively by map / unmap.
 std::shared_mutex &switch_lock();
 

@@ -1,5 +1,6 @@
-// Pools and spaces: physical device memory in equal blocks, and reserved address ranges that
-// map those blocks (paper, "Maintaining consistent virtual memory addresses"; "Granularity of
+// Memory the library is told about rather than given per call: the pinned tier (paper,
+// "Hierarchical Memory"), and pools and spaces -- physical device memory in equal blocks, and
+// reserved address ranges that map those blocks (paper, "Maintaining consistent virtual memory addresses"; "Granularity of
 // Memory Management").  All driver calls here run outside a switch: they take the switch lock
 // exclusively, nixie_switch holds it shared.
 #include <hip/hip_runtime.h>
@@ -78,6 +79,39 @@ int unmap_blocks(nixie_space *s, uint64_t first, uint64_t count) {
 
 extern "C" {
 
+// ---- pinned tier: announce GPU-addressable pinned host memory to the planner -----------------
+int nixie_tier_register(void *host_base, uint64_t bytes) {
+    if (!host_base || bytes == 0) return NIXIE_EINVAL;
+    hipPointerAttribute_t attr{};
+    hipError_t e = hipPointerGetAttributes(&attr, host_base);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();                 // unknown to the runtime: ordinary pageable memory
+        return NIXIE_EINVAL;
+    }
+    if (attr.type != hipMemoryTypeHost) return NIXIE_EINVAL;
+    void *seen_by_gpu = nullptr;
+    e = hipHostGetDevicePointer(&seen_by_gpu, host_base, 0);
+    if (e != hipSuccess) return fail(e);
+    if (!seen_by_gpu) return NIXIE_EINVAL;
+    // the whole range must belong to the same pinned allocation
+    hipPointerAttribute_t last{};
+    e = hipPointerGetAttributes(&last, (char *)host_base + bytes - 1);
+    if (e != hipSuccess) { (void)hipGetLastError(); return NIXIE_EINVAL; }
+    if (last.type != hipMemoryTypeHost) return NIXIE_EINVAL;
+    void *last_seen = nullptr;
+    e = hipHostGetDevicePointer(&last_seen, (char *)host_base + bytes - 1, 0);
+    if (e != hipSuccess) return fail(e);
+    if ((char *)last_seen - (char *)seen_by_gpu != (ptrdiff_t)(bytes - 1)) return NIXIE_EINVAL;
+    TierSpan t{(uint64_t)(uintptr_t)host_base, bytes, (uint64_t)(uintptr_t)seen_by_gpu};
+    return tier_register(t) ? NIXIE_OK : NIXIE_EINVAL;
+}
+
+int nixie_tier_unregister(void *host_base) {
+    if (!host_base) return NIXIE_EINVAL;
+    return tier_unregister((uint64_t)(uintptr_t)host_base) ? NIXIE_OK : NIXIE_EINVAL;
+}
+
+// ---- pools and spaces ---------------------------------------------------------------------------
 int nixie_pool_create(uint64_t bytes, uint64_t block_bytes, nixie_pool_t **pool) {
     if (!pool || bytes == 0) return NIXIE_EINVAL;
     *pool = nullptr;

@@ -12,7 +12,7 @@ _LIB_PATH = os.path.join(_HERE, "libnixie.so")
 
 EINVAL, EOVERLAP, ENOMEM, EHIP, ETIMEOUT, EMISMATCH, EBUSY, EUNMAPPED = -1, -2, -3, -4, -5, -6, -7, -8
 ORDER_TABLE, ORDER_LARGE_FIRST, ORDER_ADDRESS, ORDER_REVERSE = 0, 1, 2, 3
-SPLIT_BY_BYTES, SERIALIZE, DIAG_RING_ONLY, DIAG_STALL_DRAIN, HOST_PLAIN_MEMCPY, IN_PLACE = 1, 2, 4, 8, 16, 32
+SPLIT_BY_BYTES, SERIALIZE, DIAG_RING_ONLY, DIAG_STALL_DRAIN, HOST_PLAIN_MEMCPY, IN_PLACE, NO_DIRECT = 1, 2, 4, 8, 16, 32, 64
 
 DECLARED_SYMBOLS = (
     "nixie_layout_create", "nixie_layout_info", "nixie_layout_chunks", "nixie_layout_segments",
@@ -23,6 +23,7 @@ DECLARED_SYMBOLS = (
     "nixie_sched_api_return", "nixie_sched_request", "nixie_sched_tick", "nixie_sched_app_info",
     "nixie_pool_create", "nixie_pool_info", "nixie_pool_destroy", "nixie_space_create", "nixie_space_map",
     "nixie_space_unmap", "nixie_space_mapped", "nixie_space_destroy",
+    "nixie_tier_register", "nixie_tier_unregister",
 )
 
 
@@ -50,7 +51,9 @@ class _Info(C.Structure):
                 ("pinned_ring_bytes", C.c_uint64), ("pinned_ctrl_bytes", C.c_uint64),
                 ("gather_wgs", C.c_uint32), ("scatter_wgs", C.c_uint32),
                 ("team_out", C.c_uint32), ("team_in", C.c_uint32),
-                ("drain_threads", C.c_uint32), ("fill_threads", C.c_uint32)]
+                ("drain_threads", C.c_uint32), ("fill_threads", C.c_uint32),
+                ("direct_chunks_out", C.c_uint64), ("direct_chunks_in", C.c_uint64),
+                ("direct_bytes_out", C.c_uint64), ("direct_bytes_in", C.c_uint64)]
 
 
 class _Segment(C.Structure):
@@ -142,6 +145,8 @@ def lib() -> C.CDLL:
     L.nixie_sched_request.argtypes = [vp, i32, u64]
     L.nixie_sched_tick.argtypes = [vp, u64, C.POINTER(_SchedDecision)]
     L.nixie_sched_app_info.argtypes = [vp, i32, u64, C.POINTER(_SchedApp)]
+    L.nixie_tier_register.argtypes = [vp, u64]
+    L.nixie_tier_unregister.argtypes = [vp]
     L.nixie_pool_create.argtypes = [u64, u64, C.POINTER(vp)]
     L.nixie_pool_info.argtypes = [vp, C.POINTER(u64), C.POINTER(u64)]
     L.nixie_pool_destroy.argtypes = [vp]
@@ -323,6 +328,18 @@ def link_peak(nbytes: int = 1 << 30, reps: int = 5) -> dict:
     if rc:
         raise NixieError(rc, "nixie_link_peak")
     return _as_dict(out)
+
+
+def tier_register(host_addr: int, nbytes: int) -> None:
+    rc = lib().nixie_tier_register(C.c_void_p(host_addr), nbytes)
+    if rc:
+        raise NixieError(rc, "nixie_tier_register")
+
+
+def tier_unregister(host_addr: int) -> None:
+    rc = lib().nixie_tier_unregister(C.c_void_p(host_addr))
+    if rc:
+        raise NixieError(rc, "nixie_tier_unregister")
 
 
 class Pool:

@@ -14,6 +14,9 @@
 //   spaces      the same, but the two applications see that memory at different addresses (one
 //               file mapped twice, registered as two spaces of one pool): the planner must find
 //               the dependencies through the pool coordinate
+//   tier        A's host side and half of B's lie in a registered pinned tier: those allocations move
+//               directly, without slots or host threads, next to staged ones in the same switch
+//   tier_in_place  the same with B reusing A's "device" memory
 //   stall       the host withholds credits (NIXIE_DIAG_STALL_DRAIN): must end with NIXIE_ETIMEOUT
 //   gpu_quits   the device reports that it gave up: the host must stop with NIXIE_ETIMEOUT
 //   dead_gpu    the device never starts: the host watchdog must fire
@@ -63,7 +66,8 @@ struct FakeGpu {
     void copy_unit(int dir, uint32_t k, uint32_t part, uint32_t slot) {
         const DirLayout &D = L->dir[dir];
         const nixie_chunk_t &c = D.chunks[k];
-        uint8_t *base = ring + ((dir ? L->dir[0].slots : 0) + (uint64_t)slot) * L->slot_bytes;
+        uint8_t *base = k >= D.staged ? (uint8_t *)(uintptr_t)D.direct_base[k - D.staged]      // pinned tier: no slot
+                                      : ring + ((dir ? L->dir[0].slots : 0) + (uint64_t)slot) * L->slot_bytes;
         const uint32_t n_tiles = (c.used_bytes + kTileBytes - 1) / kTileBytes;
         for (uint32_t t = part; t < n_tiles; t += team[dir]) {
             const uint32_t t0 = t * kTileBytes, t1 = std::min(t0 + kTileBytes, c.used_bytes);
@@ -85,8 +89,9 @@ struct FakeGpu {
             const uint32_t u = ticket[dir].fetch_add(1, std::memory_order_relaxed);
             if (u >= total || dev_abort.load(std::memory_order_acquire)) break;
             const uint32_t k = u / team[dir], part = u % team[dir];
-            uint32_t cs;
-            while ((cs = chunk_slot[dir][k].load(std::memory_order_acquire)) == 0) {
+            const bool direct = k >= D.staged;
+            uint32_t cs = direct ? 0xFFFFFFFFu : 0;
+            while (!direct && (cs = chunk_slot[dir][k].load(std::memory_order_acquire)) == 0) {
                 if (dev_abort.load(std::memory_order_acquire)) break;
                 std::this_thread::yield();
             }
@@ -101,7 +106,7 @@ struct FakeGpu {
             }
             copy_unit(dir, k, part, cs - 1);
             const uint32_t old = arrive[dir][k].fetch_add(1, std::memory_order_acq_rel);
-            if (old == team[dir] - 1)
+            if (old == team[dir] - 1 && !direct)
                 __atomic_store_n(post[dir] + (size_t)(cs - 1) * kFlagStride, (uint64_t)k + 1, __ATOMIC_RELEASE);
         }
         exited[dir].fetch_add(1, std::memory_order_release);
@@ -118,7 +123,7 @@ struct FakeGpu {
                 if (v == seen[s]) continue;
                 seen[s] = v;
                 const uint64_t k = dir == 0 ? next++ : v - 1;
-                if (k < D.chunks.size()) chunk_slot[dir][k].store(s + 1, std::memory_order_release);
+                if (k < D.staged) chunk_slot[dir][k].store(s + 1, std::memory_order_release);
             }
             if (dir == 0 && in_place) {
                 while (prefix < D.chunks.size() && arrive[0][prefix].load(std::memory_order_acquire) >= team[0]) prefix++;
@@ -189,7 +194,8 @@ int run(const std::string &scenario, uint64_t seed) {
     sa.push_back(0); sa.push_back(S); sa.push_back(5 * S + 1);
     sb.push_back(S - 1); sb.push_back(15);
     const bool spaces = scenario == "spaces";
-    const bool in_place = scenario == "in_place" || spaces;
+    const bool tier = scenario == "tier" || scenario == "tier_in_place";
+    const bool in_place = scenario == "in_place" || spaces || scenario == "tier_in_place";
 
     // in place: B's device ranges lie in the same "device" arena as A's
     std::vector<uint8_t> dev_a(std::max(arena_bytes(sa), in_place ? arena_bytes(sb) : 0) + 64, 0xC3);
@@ -222,11 +228,17 @@ int run(const std::string &scenario, uint64_t seed) {
     for (auto &r : A.rows) want_a.emplace_back((uint8_t *)r.dev_ptr, (uint8_t *)r.dev_ptr + r.bytes);
     for (auto &r : B.rows) want_b.emplace_back((uint8_t *)r.host_ptr, (uint8_t *)r.host_ptr + r.bytes);
 
+    if (tier) {   // on the CPU the "GPU's address" of pinned memory is the address itself
+        const uint64_t ha = (uint64_t)(uintptr_t)A.host.data(), hb = (uint64_t)(uintptr_t)B.host.data();
+        if (!tier_register(TierSpan{ha, A.host.size(), ha}) || !tier_register(TierSpan{hb, B.host.size() / 2, hb}) ||
+            tier_register(TierSpan{hb + 100, 50, hb + 100})) { std::printf("tier registration\n"); return 1; }
+    }
     nixie_opts_t o{};
     o.slot_bytes = S;
     o.drain_threads = 3;
     o.fill_threads = 2;
-    o.timeout_ms = (scenario == "swap" || in_place) ? 20000 : 300;
+    const bool must_succeed = scenario == "swap" || in_place || tier;
+    o.timeout_ms = must_succeed ? 20000 : 300;
     if (in_place) o.flags |= NIXIE_IN_PLACE;
     if (scenario == "stall") o.flags |= NIXIE_DIAG_STALL_DRAIN;
     nixie_table_t ta{A.rows.data(), A.rows.size()}, tb{B.rows.data(), B.rows.size()};
@@ -262,6 +274,31 @@ int run(const std::string &scenario, uint64_t seed) {
     }
     nixie_plan_info_t info;
     fill_info(L, &info);
+    if (tier) {
+        uint64_t direct_b = 0, staged_b = 0;
+        for (const auto &r : B.rows) {
+            const bool inside = (uint8_t *)r.host_ptr + r.bytes <= B.host.data() + B.host.size() / 2;
+            const bool congruent = (((uintptr_t)r.host_ptr ^ (uintptr_t)r.dev_ptr) & 15) == 0;
+            (inside && congruent ? direct_b : staged_b) += r.bytes;
+        }
+        const bool a_congruent = (((uintptr_t)A.rows[0].host_ptr ^ (uintptr_t)A.rows[0].dev_ptr) & 15) == 0;
+        if (info.direct_bytes_in != direct_b || info.bytes_in != direct_b + staged_b || direct_b == 0 || staged_b == 0 ||
+            (a_congruent && (info.direct_bytes_out != info.bytes_out || L.dir[0].staged != 0 || info.drain_threads != 0 ||
+                             L.dir[0].slots != 0))) {
+            std::printf("tier split: direct in %llu (want %llu), direct out %llu of %llu, drain threads %u, out slots %u\n",
+                        (unsigned long long)info.direct_bytes_in, (unsigned long long)direct_b,
+                        (unsigned long long)info.direct_bytes_out, (unsigned long long)info.bytes_out, info.drain_threads,
+                        L.dir[0].slots);
+            return 1;
+        }
+        nixie_opts_t off = o;   // the same tables with the tier ignored: everything is staged
+        off.flags |= NIXIE_NO_DIRECT;
+        Layout L2;
+        if (build_layout(&ta, &tb, ring_bytes, &off, L2) || L2.dir[0].staged != L2.dir[0].chunks.size() || L2.dir[0].direct_bytes) {
+            std::printf("NIXIE_NO_DIRECT ignored\n");
+            return 1;
+        }
+    }
 
     std::vector<uint8_t> ring(info.pinned_ring_bytes + 64);
     std::vector<uint64_t> ctrl(info.pinned_ctrl_bytes / 8 + 8, 0);
@@ -308,13 +345,13 @@ int run(const std::string &scenario, uint64_t seed) {
         gpu.join();
         const double ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
         const int err = hs.error.load();
-        if (scenario == "swap" || in_place) {
+        if (must_succeed) {
             if (err) { std::printf("switch failed: %d\n", err); fails++; }
             for (size_t i = 0; i < A.rows.size(); i++)
                 if (std::memcmp(A.rows[i].host_ptr, want_a[i].data(), A.rows[i].bytes)) { std::printf("evicted allocation %zu differs\n", i); fails++; }
             for (size_t i = 0; i < B.rows.size(); i++)
                 if (std::memcmp(B.rows[i].dev_ptr, want_b[i].data(), B.rows[i].bytes)) { std::printf("restored allocation %zu differs\n", i); fails++; }
-            if (hs.done_chunks[0].load() != L.dir[0].chunks.size()) { std::printf("drained %llu of %zu chunks\n", (unsigned long long)hs.done_chunks[0].load(), L.dir[0].chunks.size()); fails++; }
+            if (hs.done_chunks[0].load() != L.dir[0].staged) { std::printf("drained %llu of %llu chunks\n", (unsigned long long)hs.done_chunks[0].load(), (unsigned long long)L.dir[0].staged); fails++; }
         } else {
             if (err != NIXIE_ETIMEOUT) { std::printf("expected NIXIE_ETIMEOUT, got %d\n", err); fails++; }
             if (ms > 5000) { std::printf("took %.0f ms to give up\n", ms); fails++; }
@@ -323,6 +360,10 @@ int run(const std::string &scenario, uint64_t seed) {
                     L.dir[0].chunks.size(), L.dir[1].chunks.size(), ms, err);
     }
     crew.stop();
+    if (tier) {
+        tier_unregister((uint64_t)(uintptr_t)A.host.data());
+        tier_unregister((uint64_t)(uintptr_t)B.host.data());
+    }
     if (spaces) {
         space_unregister((uint64_t)(uintptr_t)base_a);
         space_unregister((uint64_t)(uintptr_t)base_b);
@@ -335,6 +376,6 @@ int run(const std::string &scenario, uint64_t seed) {
 }  // namespace
 
 int main(int argc, char **argv) {
-    if (argc < 2) { std::printf("usage: fake_gpu <swap|in_place|spaces|stall|gpu_quits|dead_gpu> [seed]\n"); return 2; }
+    if (argc < 2) { std::printf("usage: fake_gpu <swap|in_place|spaces|tier|tier_in_place|stall|gpu_quits|dead_gpu> [seed]\n"); return 2; }
     return run(argv[1], argc > 2 ? std::strtoull(argv[2], nullptr, 10) : 1);
 }

@@ -1,0 +1,176 @@
+"""GPU parity for the pinned tier (paper, "Hierarchical Memory"): allocations whose host side lies
+in registered pinned memory move directly between HBM and that memory, the others through the
+ring, in one switch.  The result is the same plain definition the oracle computes."""
+import numpy as np
+import pytest
+
+from tests.helpers import HostSet, AliasedPair
+
+pytestmark = pytest.mark.gpu
+
+KiB, MiB = 1 << 10, 1 << 20
+S = 64 * KiB
+
+SIZES_A = [5 * S + 1, 300, 2 * S, 9 * S + 77, 15, 16, 17, 3 * S - 1, 0, 20 * S + 5]
+SIZES_B = [4 * S, 11, 3 * S + 9, 7 * S, 1, 12 * S + 3, 999]
+
+
+@pytest.fixture(scope="module")
+def nx():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2601_11743_amd as nx
+    nx.lib()
+    return nx
+
+
+class Pinned:
+    """A pinned (GPU-addressable) host buffer from torch, as a numpy array."""
+
+    def __init__(self, nbytes: int):
+        import torch
+        self.t = torch.empty(max(1, nbytes), dtype=torch.uint8, pin_memory=True)
+        self.a = self.t.numpy()
+        assert self.a.ctypes.data % 4096 == 0
+
+
+def move_host_arena(hs, pin: Pinned):
+    """Relocate a HostSet's pageable arena into pinned memory (same bytes, same alignment)."""
+    pin.a[:hs.host.size] = hs.host
+    hs.host = pin.a[:hs.host.size]
+
+
+def test_registration_errors(nx):
+    import torch
+    pageable = np.zeros(1 << 20, dtype=np.uint8)
+    with pytest.raises(nx.NixieError) as e:
+        nx.tier_register(pageable.ctypes.data, pageable.size)
+    assert e.value.code == nx.EINVAL
+    dev = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(nx.NixieError) as e:
+        nx.tier_register(dev.data_ptr(), 1 << 20)
+    assert e.value.code == nx.EINVAL
+    pin = Pinned(1 << 20)
+    base = pin.a.ctypes.data
+    with pytest.raises(nx.NixieError):
+        nx.tier_register(base, 0)
+    nx.tier_register(base, 1 << 19)
+    for lo, n in [(base, 1 << 19), (base + 4096, 4096), (base + (1 << 19) - 1, 4096)]:
+        with pytest.raises(nx.NixieError) as e:
+            nx.tier_register(lo, n)                       # overlaps what is registered
+        assert e.value.code == nx.EINVAL
+    nx.tier_register(base + (1 << 19), 1 << 19)           # adjacent is fine
+    with pytest.raises(nx.NixieError):
+        nx.tier_unregister(base + 4096)                   # not a registered base
+    nx.tier_unregister(base)
+    nx.tier_unregister(base + (1 << 19))
+    with pytest.raises(nx.NixieError):
+        nx.tier_unregister(base)
+
+
+CASES = {
+    # name: (A pinned fraction, B pinned fraction, skew (dev, host), ring bytes, flags, expectation)
+    "all_direct_no_ring": (1.0, 1.0, (0, 0), 0, 0, "direct"),
+    "all_direct_skewed": (1.0, 1.0, (5, 5), 0, 0, "direct"),
+    "out_direct_in_staged": (1.0, 0.0, (3, 3), 8 * S, 0, "mixed"),
+    "in_direct_out_staged": (0.0, 1.0, (0, 0), 8 * S, 0, "mixed"),
+    "half_and_half": (0.5, 0.5, (7, 7), 8 * S, 0, "mixed"),
+    "not_congruent_falls_back": (1.0, 1.0, (1, 2), 8 * S, 0, "staged"),
+    "tier_switched_off": (1.0, 1.0, (0, 0), 8 * S, "NO_DIRECT", "staged"),
+    "serialized": (0.5, 1.0, (0, 0), 8 * S, "SERIALIZE", "mixed"),
+}
+
+
+@pytest.mark.parametrize("case", list(CASES))
+def test_switch_with_pinned_tier_matches_oracle(nx, oracle, case):
+    import torch
+    from tests.gpu_helpers import GpuSet, first_diff
+    fa, fb, skew, ring, flag, expect = CASES[case]
+    kw = dict(skew_dev=skew[0], skew_host=skew[1])
+    rA, rB = HostSet(SIZES_A, 21, "dev", **kw), HostSet(SIZES_B, 22, "host", **kw)
+    h_a, h_b = oracle.hash_table(rA.pairs(), "dev"), oracle.hash_table(rB.pairs(), "host")
+    oracle.switch_direct(rA.pairs(), rB.pairs())
+
+    gA, gB = GpuSet(SIZES_A, 21, "dev", **kw), GpuSet(SIZES_B, 22, "host", **kw)
+    pins, registered = [], []
+    for g, frac in ((gA, fa), (gB, fb)):
+        pin = Pinned(g.hs.host.size)
+        pins.append(pin)
+        move_host_arena(g.hs, pin)
+        n = int(g.hs.host.size * frac) // 4096 * 4096 if frac < 1.0 else g.hs.host.size
+        if n:
+            nx.tier_register(pin.a.ctypes.data, n)
+            registered.append(pin.a.ctypes.data)
+    try:
+        flags = getattr(nx, flag) if flag else 0
+        plan = nx.Plan(gA.rows(), gB.rows(), ring, nx.Opts(slot_bytes=S, flags=flags))
+        info = plan.info()
+        total = sum(SIZES_A) + sum(SIZES_B)
+        direct = info["direct_bytes_out"] + info["direct_bytes_in"]
+        if expect == "direct":
+            assert direct == total and info["pinned_ring_bytes"] == 0
+            assert info["drain_threads"] == 0 and info["fill_threads"] == 0
+        elif expect == "staged":
+            assert direct == 0
+        else:
+            assert 0 < direct < total
+        h_out, h_in = plan.hash_tables()
+        assert np.array_equal(h_out, h_a) and np.array_equal(h_in, h_b)
+        for _ in range(2):                                   # a plan is reusable
+            st = plan.switch()
+            assert st["bytes_out"] == sum(SIZES_A) and st["bytes_in"] == sum(SIZES_B)
+            if _ == 0:
+                dev_B = gB.download()
+                assert np.array_equal(gA.hs.host, rA.host), "evicted set: " + first_diff(gA.hs.host, rA.host)
+                assert np.array_equal(dev_B, rB.dev), "restored set: " + first_diff(dev_B, rB.dev)
+                assert np.array_equal(gA.download(), gA.hs.dev), "device arena of the evicted set was written"
+                # second round: the same move again must give the same bytes
+                gA.hs.host[:] = 0x11
+        dev_B = gB.download()
+        assert np.array_equal(dev_B, rB.dev)
+        for i, (o, b) in enumerate(zip(gA.hs.lhost.offsets, gA.hs.sizes)):
+            assert np.array_equal(gA.hs.host[o:o + b], rA.host[o:o + b]), f"allocation {i} after the second switch"
+        plan.verify(h_a, h_b)
+        plan.close()
+    finally:
+        for r in registered:
+            nx.tier_unregister(r)
+
+
+@pytest.mark.parametrize("pinned", ["a", "b", "both"])
+def test_in_place_switch_with_pinned_tier(nx, oracle, pinned):
+    import torch
+    from tests.gpu_helpers import first_diff
+    sa, sb, shift = [20 * S + 5, 999, 13 * S, 6 * S], [17 * S, 4, 15 * S + 1, 2 * S], 256
+    ref = AliasedPair(sa, sb, 31, shift_b=shift)
+    oracle.switch_direct(ref.pairs_a(), ref.pairs_b())
+    ref.check()
+    g = AliasedPair(sa, sb, 31, shift_b=shift)
+    pins, registered = [], []
+    for which, name in (("a", "host_a"), ("b", "host_b")):
+        if pinned in (which, "both"):
+            arr = getattr(g, name)
+            pin = Pinned(arr.size)
+            pin.a[:arr.size] = arr
+            setattr(g, name, pin.a[:arr.size])
+            pins.append(pin)
+            nx.tier_register(pin.a.ctypes.data, arr.size)
+            registered.append(pin.a.ctypes.data)
+    try:
+        dev_t = torch.from_numpy(g.dev).to("cuda:0")
+        base = dev_t.data_ptr()
+        rows_a = [(base + od, g.host_a.ctypes.data + oh, b) for od, oh, b in zip(g.la.offsets, g.lha.offsets, g.sizes_a)]
+        rows_b = [(base + od, g.host_b.ctypes.data + oh, b) for od, oh, b in zip(g.lb.offsets, g.lhb.offsets, g.sizes_b)]
+        plan = nx.Plan(rows_a, rows_b, 8 * S, nx.Opts(slot_bytes=S, flags=nx.IN_PLACE))
+        info = plan.info()
+        assert info["direct_bytes_out"] == (sum(sa) if pinned in ("a", "both") else 0)
+        assert info["direct_bytes_in"] == (sum(sb) if pinned in ("b", "both") else 0)
+        plan.switch()
+        torch.cuda.synchronize()
+        dev_after = dev_t.cpu().numpy()
+        assert np.array_equal(g.host_a, ref.host_a), "evicted set: " + first_diff(g.host_a, ref.host_a)
+        assert np.array_equal(dev_after, ref.dev), "device arena: " + first_diff(dev_after, ref.dev)
+        plan.close()
+    finally:
+        for r in registered:
+            nx.tier_unregister(r)

@@ -57,6 +57,14 @@ def test_in_place_swap_between_two_spaces_of_one_pool(fake_gpu, seed):
     run(fake_gpu, "spaces", seed)
 
 
+@pytest.mark.parametrize("scenario", ["tier", "tier_in_place"])
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_pinned_tier_allocations_move_directly(fake_gpu, scenario, seed):
+    """Host ranges registered as pinned tier: those allocations take no slot and no host thread,
+    the others are staged in the same switch; NIXIE_NO_DIRECT turns the tier off."""
+    run(fake_gpu, scenario, seed)
+
+
 @pytest.mark.parametrize("scenario", ["stall", "gpu_quits", "dead_gpu"])
 def test_failure_paths_time_out_cleanly(fake_gpu, scenario):
     out = run(fake_gpu, scenario, 1)

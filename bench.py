@@ -116,6 +116,9 @@ def main() -> int:
                          "pool of physical memory: every step maps the incoming application's address space, "
                          "switches, and unmaps the outgoing one's (all inside the timed region)")
     ap.add_argument("--block-mib", type=int, default=0, help="--spaces: pool block size (0 = library default)")
+    ap.add_argument("--pinned-tier", choices=["none", "out", "in", "both"], default="none",
+                    help="keep the host side of the outgoing / incoming / both working sets in registered pinned "
+                         "memory: those allocations move directly, without ring slots or host threads")
     ap.add_argument("--ring-sweep", action="store_true",
                     help="config 5 protocol: for every ring size of the config, 10 back-to-back ping-pong "
                          "switches A<->B; adds a 'ring_sweep' list to the JSON line")
@@ -162,8 +165,13 @@ def main() -> int:
         torch.cuda.synchronize()
         space_b.unmap()                 # B waits in pageable memory: its addresses are reserved, nothing behind them
     else:
-        A = BigSet(cf["A"], cf["seed_A"], "dev", cf["content"])
-        B = BigSet(cf["B"], cf["seed_B"], "host", cf["content"], share_dev=A if args.in_place else None)
+        pin_a, pin_b = args.pinned_tier in ("out", "both"), args.pinned_tier in ("in", "both")
+        A = BigSet(cf["A"], cf["seed_A"], "dev", cf["content"], pinned_host=pin_a)
+        B = BigSet(cf["B"], cf["seed_B"], "host", cf["content"], share_dev=A if args.in_place else None,
+                   pinned_host=pin_b)
+        for s_, pinned in ((A, pin_a), (B, pin_b)):
+            if pinned:
+                nx.tier_register(s_.host.ctypes.data, s_.host.size)
     if args.in_place:
         args.flags |= nx.IN_PLACE
         torch.cuda.empty_cache()
@@ -212,11 +220,13 @@ def main() -> int:
         step()
     torch.cuda.synchronize()
     stats = []
+    cpu_begin = time.process_time()
     t_begin = time.perf_counter()
     for _ in range(args.steps):
         stats.append(step())
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_begin
+    host_cpu_s = (time.process_time() - cpu_begin) / args.steps   # all threads of this process
 
     serialized = None
     if not args.no_serialized and not args.in_place and not (args.flags & nx.SERIALIZE) and info["bytes_out"] and info["bytes_in"]:
@@ -309,10 +319,12 @@ def main() -> int:
                    "in_slots": info["in_slots"], "gather_wgs": info["gather_wgs"], "scatter_wgs": info["scatter_wgs"],
                    "team": info["team_out"], "drain_threads": info["drain_threads"],
                    "fill_threads": info["fill_threads"], "flags": args.flags, "scale": args.scale,
-                   "in_place": bool(args.in_place)},
+                   "in_place": bool(args.in_place), "pinned_tier": args.pinned_tier,
+                   "direct_bytes_out": info["direct_bytes_out"], "direct_bytes_in": info["direct_bytes_in"]},
         "switch_latency_ms": {"min": round(lat[0], 3), "median": round(med(lat), 3), "max": round(lat[-1], 3)},
         "b_ready_ms": round(med(sorted(s["ns_in_done"] / 1e6 for s in stats)), 3),
         "plan_ms": round(plan_ms, 2),
+        "host_cpu_s_per_step": round(host_cpu_s, 4),
         "pinned_bytes": {"ring": info["pinned_ring_bytes"], "control": info["pinned_ctrl_bytes"]},
         "verified": {"hash_mismatches": rep["mismatched_out"] + rep["mismatched_in"], "full_buffer_equal": arenas_ok},
         "stalls": {"drain_wait_ms": round(med(sorted(s["drain_wait_ns"] for s in stats)) / 1e6, 2),

@@ -292,6 +292,13 @@ int nixie_space_destroy(nixie_space_t *space);
  * pinned host memory, overlaps a registered range, unknown base), NIXIE_EHIP. */
 int nixie_tier_register(void *host_base, uint64_t bytes);
 int nixie_tier_unregister(void *host_base);
+/* The leg between the pinned and the pageable tier outside a switch (paper, "Speeding Up Context
+ * Switches": the incoming application's data is brought into pinned memory by several threads,
+ * to use the DRAM bandwidth; "Scheduling": the head of the queue is the prefetch candidate):
+ * dst[i][0..bytes[i]) = src[i][0..bytes[i]) for i < n, HOST pointers on both sides, any
+ * alignment, ranges must not overlap; streaming stores, work split in 1 MiB units over
+ * `threads` threads (0 = half the cores, at most 8).  Blocks until done.  No GPU involved. */
+int nixie_host_copy(void *const *dst, const void *const *src, const uint64_t *bytes, uint64_t n, uint32_t threads);
 
 /* ---- host-link probe (paper, "Microbenchmarks": throughput is judged against the link's
  *      measured maximum) ---------------------------------------------------------------------

@@ -111,4 +111,33 @@ int hash_host_buffers(const void *const *ptrs, const uint64_t *bytes, uint64_t n
     return NIXIE_OK;
 }
 
+// dst[i][0..bytes[i]) = src[i][0..bytes[i]) for every i, in 1 MiB units handed to `threads` threads.
+int copy_host_buffers(void *const *dst, const void *const *src, const uint64_t *bytes, uint64_t n, unsigned threads) {
+    constexpr uint64_t kUnit = 1u << 20;
+    std::vector<uint64_t> first(n + 1, 0);
+    for (uint64_t i = 0; i < n; i++) {
+        if (bytes[i] && (!dst[i] || !src[i])) return NIXIE_EINVAL;
+        first[i + 1] = first[i] + (bytes[i] + kUnit - 1) / kUnit;
+    }
+    const uint64_t units = first[n];
+    if (units == 0) return NIXIE_OK;
+    std::atomic<uint64_t> next{0};
+    auto work = [&]() {
+        for (;;) {
+            const uint64_t u = next.fetch_add(1, std::memory_order_relaxed);
+            if (u >= units) break;
+            const uint64_t i = (uint64_t)(std::upper_bound(first.begin(), first.end(), u) - first.begin()) - 1;
+            const uint64_t b = (u - first[i]) * kUnit, e = std::min(bytes[i], b + kUnit);
+            copy_stream((uint8_t *)dst[i] + b, (const uint8_t *)src[i] + b, e - b);
+        }
+        _mm_sfence();
+    };
+    const unsigned T = (unsigned)std::min<uint64_t>(std::max(1u, threads), units);
+    std::vector<std::thread> pool;
+    for (unsigned t = 1; t < T; t++) pool.emplace_back(work);
+    work();
+    for (auto &t : pool) t.join();
+    return NIXIE_OK;
+}
+
 }  // namespace nixie

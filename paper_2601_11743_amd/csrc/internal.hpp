@@ -38,6 +38,7 @@ void fill_info(const Layout &L, nixie_plan_info_t *info);
 void copy_stream(void *dst, const void *src, size_t n);   // non-temporal stores, any alignment
 uint64_t mix64(uint64_t z);
 uint64_t hash_host_range(const uint8_t *base, uint64_t n, uint64_t word_begin, uint64_t word_end);
+int copy_host_buffers(void *const *dst, const void *const *src, const uint64_t *bytes, uint64_t n, unsigned threads);
 int hash_host_buffers(const void *const *ptrs, const uint64_t *bytes, uint64_t n, uint64_t *hashes,
                       unsigned threads);
 

@@ -151,6 +151,12 @@ int nixie_hash_buffers(const void *const *ptrs, const uint64_t *bytes, uint64_t 
     return rc;
 }
 
+int nixie_host_copy(void *const *dst, const void *const *src, const uint64_t *bytes, uint64_t n, uint32_t threads) {
+    if (n == 0) return NIXIE_OK;
+    if (!dst || !src || !bytes) return NIXIE_EINVAL;
+    return copy_host_buffers(dst, src, bytes, n, threads ? threads : host_threads() / 2);
+}
+
 int nixie_link_peak(uint64_t bytes, int reps, nixie_link_peak_t *out) {
     if (!out || bytes < (1u << 20) || bytes % 16 || reps < 1) return NIXIE_EINVAL;
     std::memset(out, 0, sizeof(*out));

@@ -23,7 +23,7 @@ DECLARED_SYMBOLS = (
     "nixie_sched_api_return", "nixie_sched_request", "nixie_sched_tick", "nixie_sched_app_info",
     "nixie_pool_create", "nixie_pool_info", "nixie_pool_destroy", "nixie_space_create", "nixie_space_map",
     "nixie_space_unmap", "nixie_space_mapped", "nixie_space_destroy",
-    "nixie_tier_register", "nixie_tier_unregister",
+    "nixie_tier_register", "nixie_tier_unregister", "nixie_host_copy",
 )
 
 
@@ -147,6 +147,7 @@ def lib() -> C.CDLL:
     L.nixie_sched_app_info.argtypes = [vp, i32, u64, C.POINTER(_SchedApp)]
     L.nixie_tier_register.argtypes = [vp, u64]
     L.nixie_tier_unregister.argtypes = [vp]
+    L.nixie_host_copy.argtypes = [vp, vp, vp, u64, C.c_uint32]
     L.nixie_pool_create.argtypes = [u64, u64, C.POINTER(vp)]
     L.nixie_pool_info.argtypes = [vp, C.POINTER(u64), C.POINTER(u64)]
     L.nixie_pool_destroy.argtypes = [vp]
@@ -340,6 +341,16 @@ def tier_unregister(host_addr: int) -> None:
     rc = lib().nixie_tier_unregister(C.c_void_p(host_addr))
     if rc:
         raise NixieError(rc, "nixie_tier_unregister")
+
+
+def host_copy(dst: Sequence[int], src: Sequence[int], sizes: Sequence[int], threads: int = 0) -> None:
+    n = len(dst)
+    d = np.asarray(list(dst), dtype=np.uint64)
+    s = np.asarray(list(src), dtype=np.uint64)
+    b = np.asarray(list(sizes), dtype=np.uint64)
+    rc = lib().nixie_host_copy(d.ctypes.data, s.ctypes.data, b.ctypes.data, n, threads) if n else 0
+    if rc:
+        raise NixieError(rc, "nixie_host_copy")
 
 
 class Pool:

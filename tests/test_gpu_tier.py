@@ -174,3 +174,37 @@ def test_in_place_switch_with_pinned_tier(nx, oracle, pinned):
     finally:
         for r in registered:
             nx.tier_unregister(r)
+
+
+def test_prefetch_into_the_pinned_tier_then_switch(nx, oracle):
+    """The incoming application waits in pageable memory, is brought into the pinned tier ahead of
+    the switch (nixie_host_copy, the scheduler's prefetch candidate), and then moves directly;
+    the evicted one lands in the pinned tier and is demoted to pageable memory afterwards."""
+    from tests.gpu_helpers import GpuSet, first_diff
+    rA, rB = HostSet(SIZES_A, 21, "dev"), HostSet(SIZES_B, 22, "host")
+    oracle.switch_direct(rA.pairs(), rB.pairs())
+    gA, gB = GpuSet(SIZES_A, 21, "dev"), GpuSet(SIZES_B, 22, "host")
+    pin_a, pin_b = Pinned(gA.hs.host.size), Pinned(gB.hs.host.size)
+    pin_a.a[:] = 0xEE
+    pin_b.a[:] = 0xEE
+    nx.tier_register(pin_a.a.ctypes.data, pin_a.a.size)
+    nx.tier_register(pin_b.a.ctypes.data, pin_b.a.size)
+    try:
+        offs_a, offs_b = gA.hs.lhost.offsets, gB.hs.lhost.offsets
+        pageable_b, pageable_a = gB.hs.host.ctypes.data, gA.hs.host.ctypes.data
+        nx.host_copy([pin_b.a.ctypes.data + o for o in offs_b], [pageable_b + o for o in offs_b], SIZES_B, 3)
+        dev_a, dev_b = gA.dev_t.data_ptr(), gB.dev_t.data_ptr()
+        rows_a = [(dev_a + od, pin_a.a.ctypes.data + oh, b) for od, oh, b in zip(gA.hs.ldev.offsets, offs_a, SIZES_A)]
+        rows_b = [(dev_b + od, pin_b.a.ctypes.data + oh, b) for od, oh, b in zip(gB.hs.ldev.offsets, offs_b, SIZES_B)]
+        plan = nx.Plan(rows_a, rows_b, 0)
+        info = plan.info()
+        assert info["direct_bytes_out"] == sum(SIZES_A) and info["direct_bytes_in"] == sum(SIZES_B)
+        plan.switch()
+        plan.close()
+        nx.host_copy([pageable_a + o for o in offs_a], [pin_a.a.ctypes.data + o for o in offs_a], SIZES_A)
+        dev_B = gB.download()
+        assert np.array_equal(dev_B, rB.dev), "restored set: " + first_diff(dev_B, rB.dev)
+        assert np.array_equal(gA.hs.host, rA.host), "evicted set: " + first_diff(gA.hs.host, rA.host)
+    finally:
+        nx.tier_unregister(pin_a.a.ctypes.data)
+        nx.tier_unregister(pin_b.a.ctypes.data)

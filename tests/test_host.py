@@ -262,3 +262,26 @@ def test_plan_without_gpu_fails_loudly(nx):
         nx.hash_buffers([0x7F00_0000_0000], [64], on_device=True)
     with pytest.raises(nx.NixieError):
         nx.link_peak(1 << 20, 1)
+
+
+@pytest.mark.parametrize("threads", [0, 1, 5])
+def test_host_copy_equals_plain_copy(nx, threads):
+    """nixie_host_copy (the pinned <-> pageable leg outside a switch) against numpy slicing:
+    ragged sizes across the 1 MiB work unit, every source / destination misalignment, canaries."""
+    rng = np.random.default_rng(5)
+    sizes = [0, 1, 15, 16, 17, 4095, (1 << 20) - 1, 1 << 20, (1 << 20) + 1, 3 * (1 << 20) + 77, 123457]
+    src, dst, want = [], [], []
+    for i, b in enumerate(sizes):
+        s = rng.integers(0, 256, b + 64, dtype=np.uint8)
+        d = np.full(b + 96, 0xC3, dtype=np.uint8)
+        so, do = i % 16, (i * 7) % 16 + 16
+        src.append(s[so:so + b])
+        dst.append(d[do:do + b])
+        want.append((d, do, s[so:so + b].copy()))
+    nx.host_copy([d.ctypes.data for d in dst], [s.ctypes.data for s in src], sizes, threads)
+    for (d, do, w), b in zip(want, sizes):
+        assert np.array_equal(d[do:do + b], w)
+        assert (d[:do] == 0xC3).all() and (d[do + b:] == 0xC3).all()
+    with pytest.raises(nx.NixieError) as e:
+        nx.host_copy([0], [src[3].ctypes.data], [16])
+    assert e.value.code == nx.EINVAL

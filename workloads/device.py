@@ -47,13 +47,15 @@ class BigSet:
 
     def __init__(self, sizes, seed: int, resident: str, content: str, device: str = "cuda:0",
                  redzone: int = 256, red: int = 0xC3, poison_dev: int = 0xA5, poison_host: int = 0x5A,
-                 share_dev: "BigSet | None" = None, dev_arena=None):
+                 share_dev: "BigSet | None" = None, dev_arena=None, pinned_host: bool = False):
         """share_dev: for an in-place switch -- this (host-resident) set gets no HBM of its own; its
         device ranges lie in the other set's arena, which must have the same layout.
         dev_arena: a uint8 device tensor supplied by the caller (for instance a view of a mapped
         address space) that becomes this set's HBM arena.  A GPU-resident set is generated into it;
         a host-resident set only takes its addresses and never touches it, since the memory behind
-        it may be another application's."""
+        it may be another application's.
+        pinned_host: the host arena is pinned, GPU-addressable memory (the pinned tier) instead of
+        pageable memory."""
         import torch
         self.sizes = [s if isinstance(s, int) else s[1] for s in sizes]
         self.names = [("" if isinstance(s, int) else s[0]) for s in sizes]
@@ -66,8 +68,13 @@ class BigSet:
             self.dev.fill_(red)
         else:
             self.dev = torch.full((self.layout.total,), red, dtype=torch.uint8, device=device)
-        self.host = pageable_arena(self.layout.total, fill=red)
-        self.host_t = torch.from_numpy(self.host)
+        if pinned_host:
+            self.host_t = torch.empty(max(self.layout.total, 4096), dtype=torch.uint8, pin_memory=True)
+            self.host = self.host_t.numpy()
+            self.host[:] = red
+        else:
+            self.host = pageable_arena(self.layout.total, fill=red)
+            self.host_t = torch.from_numpy(self.host)
         g = torch.Generator(device=device)
         g.manual_seed(seed)
         for o, b in zip(self.layout.offsets, self.sizes):

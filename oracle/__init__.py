@@ -7,3 +7,4 @@ from .nixie_oracle import (  # noqa: F401
     Oracle, OracleError, build, FAULTS, lib_path,
 )
 from .sched_oracle import SchedOracle  # noqa: F401,E402
+from . import place_oracle  # noqa: F401,E402

@@ -300,6 +300,43 @@ int nixie_tier_unregister(void *host_base);
  * `threads` threads (0 = half the cores, at most 8).  Blocks until done.  No GPU involved. */
 int nixie_host_copy(void *const *dst, const void *const *src, const uint64_t *bytes, uint64_t n, uint32_t threads);
 
+/* ---- placement (paper, "Speeding Up Context Switches": a global plan decides which chunks must
+ *      be migrated, their source and their destination; evicted data stays in the highest tier
+ *      that can hold it; transfers that cross several tiers come first) ----------------------
+ * Host only, no GPU needed.  chunks[i] says where chunk i is now.  On return new_tier[i] says
+ * where it should be once incoming_app owns the GPU:
+ *   - every chunk of incoming_app is in GPU memory;
+ *   - chunks of the applications in victim_apps (in that order, e.g. lowest priority first;
+ *     inside an application in table order) leave GPU memory, but only until incoming_app fits;
+ *   - an evicted chunk stays in the pinned tier if it fits the room left there once
+ *     incoming_app's chunks have gone up, else it goes to pageable memory;
+ *   - everything else stays.
+ * order (nullable, room for n entries) receives the indices of the chunks that move, in
+ * migration order: moves between GPU and pageable memory first; *n_moved their number.
+ * The outgoing table of the switch is the set of chunks with tier GPU -> not GPU, the incoming
+ * table the set with not GPU -> GPU; a chunk's host_ptr is chosen by its host tier.
+ * Errors: NIXIE_EINVAL (NULL, unknown tier, a capacity already exceeded, incoming_app listed
+ * as a victim), NIXIE_ENOMEM (incoming_app does not fit even with every victim evicted);
+ * outputs are unspecified on error. */
+enum nixie_tier { NIXIE_TIER_GPU = 0, NIXIE_TIER_PINNED = 1, NIXIE_TIER_PAGEABLE = 2 };
+typedef struct {
+    uint64_t bytes;
+    uint32_t app;
+    uint32_t tier; /* enum nixie_tier */
+} nixie_chunk_state_t;
+typedef struct {
+    uint64_t gpu_bytes;    /* GPU memory available to applications        */
+    uint64_t pinned_bytes; /* size of the pinned tier (the ring not included) */
+} nixie_capacity_t;
+typedef struct {
+    uint64_t restored_bytes, restored_from_pageable_bytes;
+    uint64_t evicted_bytes, kept_pinned_bytes, to_pageable_bytes;
+    uint64_t gpu_used_after, pinned_used_after;
+} nixie_placement_t;
+int nixie_place(const nixie_capacity_t *cap, const nixie_chunk_state_t *chunks, uint64_t n,
+                uint32_t incoming_app, const uint32_t *victim_apps, uint32_t n_victims,
+                uint32_t *new_tier, uint64_t *order, uint64_t *n_moved, nixie_placement_t *summary);
+
 /* ---- host-link probe (paper, "Microbenchmarks": throughput is judged against the link's
  *      measured maximum) ---------------------------------------------------------------------
  * Allocates 2 device + 2 pinned buffers of `bytes` each for the duration of the call, times

@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libnixie.so")
 SOURCES = ["kernels.hip", "runtime.cpp", "hostside.cpp", "planner.cpp", "hostcopy.cpp", "verify.cpp",
-           "scheduler.cpp", "spaces.cpp", "vmm.cpp"]
+           "scheduler.cpp", "spaces.cpp", "vmm.cpp", "placement.cpp"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wextra",
          # packed FP32 instructions are kept out of all device code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -23,7 +23,7 @@ DECLARED_SYMBOLS = (
     "nixie_sched_api_return", "nixie_sched_request", "nixie_sched_tick", "nixie_sched_app_info",
     "nixie_pool_create", "nixie_pool_info", "nixie_pool_destroy", "nixie_space_create", "nixie_space_map",
     "nixie_space_unmap", "nixie_space_mapped", "nixie_space_destroy",
-    "nixie_tier_register", "nixie_tier_unregister", "nixie_host_copy",
+    "nixie_tier_register", "nixie_tier_unregister", "nixie_host_copy", "nixie_place",
 )
 
 
@@ -83,6 +83,20 @@ class _LinkPeak(C.Structure):
     _fields_ = [(n, C.c_double) for n in (
         "sdma_d2h", "sdma_h2d", "sdma_d2h_both", "sdma_h2d_both",
         "kernel_d2h", "kernel_h2d", "kernel_d2h_both", "kernel_h2d_both")]
+
+
+class _ChunkState(C.Structure):
+    _fields_ = [("bytes", C.c_uint64), ("app", C.c_uint32), ("tier", C.c_uint32)]
+
+
+class _Capacity(C.Structure):
+    _fields_ = [("gpu_bytes", C.c_uint64), ("pinned_bytes", C.c_uint64)]
+
+
+class _Placement(C.Structure):
+    _fields_ = [("restored_bytes", C.c_uint64), ("restored_from_pageable_bytes", C.c_uint64),
+                ("evicted_bytes", C.c_uint64), ("kept_pinned_bytes", C.c_uint64), ("to_pageable_bytes", C.c_uint64),
+                ("gpu_used_after", C.c_uint64), ("pinned_used_after", C.c_uint64)]
 
 
 class _SchedParams(C.Structure):
@@ -147,6 +161,8 @@ def lib() -> C.CDLL:
     L.nixie_sched_app_info.argtypes = [vp, i32, u64, C.POINTER(_SchedApp)]
     L.nixie_tier_register.argtypes = [vp, u64]
     L.nixie_tier_unregister.argtypes = [vp]
+    L.nixie_place.argtypes = [C.POINTER(_Capacity), C.POINTER(_ChunkState), u64, C.c_uint32, vp, C.c_uint32,
+                              vp, vp, C.POINTER(u64), C.POINTER(_Placement)]
     L.nixie_host_copy.argtypes = [vp, vp, vp, u64, C.c_uint32]
     L.nixie_pool_create.argtypes = [u64, u64, C.POINTER(vp)]
     L.nixie_pool_info.argtypes = [vp, C.POINTER(u64), C.POINTER(u64)]
@@ -351,6 +367,28 @@ def host_copy(dst: Sequence[int], src: Sequence[int], sizes: Sequence[int], thre
     rc = lib().nixie_host_copy(d.ctypes.data, s.ctypes.data, b.ctypes.data, n, threads) if n else 0
     if rc:
         raise NixieError(rc, "nixie_host_copy")
+
+
+TIER_GPU, TIER_PINNED, TIER_PAGEABLE = 0, 1, 2
+
+
+def place(gpu_bytes: int, pinned_bytes: int, chunks, incoming_app: int, victim_apps):
+    """nixie_place.  chunks: sequence of (bytes, app, tier).  Returns (new_tier list, summary dict,
+    order list)."""
+    n = len(chunks)
+    arr = (_ChunkState * max(1, n))()
+    for i, (b, a, t) in enumerate(chunks):
+        arr[i] = _ChunkState(b, a, t)
+    vic = np.asarray(list(victim_apps), dtype=np.uint32)
+    tiers = np.zeros(max(1, n), dtype=np.uint32)
+    order = np.zeros(max(1, n), dtype=np.uint64)
+    moved, summ = C.c_uint64(0), _Placement()
+    cap = _Capacity(gpu_bytes, pinned_bytes)
+    rc = lib().nixie_place(C.byref(cap), arr, n, incoming_app, vic.ctypes.data if vic.size else None, vic.size,
+                           tiers.ctypes.data, order.ctypes.data, C.byref(moved), C.byref(summ))
+    if rc:
+        raise NixieError(rc, "nixie_place")
+    return [int(t) for t in tiers[:n]], _as_dict(summ), [int(i) for i in order[:moved.value]]
 
 
 class Pool:

@@ -208,3 +208,81 @@ def test_prefetch_into_the_pinned_tier_then_switch(nx, oracle):
     finally:
         nx.tier_unregister(pin_a.a.ctypes.data)
         nx.tier_unregister(pin_b.a.ctypes.data)
+
+
+def test_placement_drives_a_partial_eviction(nx, oracle):
+    """Three applications on a GPU too small for all: nixie_place picks the victims (C before A,
+    only as far as needed) and their host tiers, the tables of the switch are read off its answer,
+    and the switch is checked against the oracle run on CPU mirrors of the same buffers."""
+    import torch
+    from tests.gpu_helpers import GpuSet, first_diff
+    sizes = {0: [6 * S, 3 * S + 5, 4 * S], 2: [5 * S, 2 * S, 7 * S + 1, 900], 1: [8 * S, 4 * S + 3, 6 * S, 10]}
+    seeds = {0: 51, 1: 52, 2: 53}
+    B_TIERS = [nx.TIER_PINNED, nx.TIER_PAGEABLE, nx.TIER_PAGEABLE, nx.TIER_PINNED]
+    resident = {a: sum(sizes[a]) for a in (0, 2)}
+    gpu_cap = resident[0] + resident[2] + 3 * S           # B needs ~18 S: about 15 S must go
+    pin_cap = 12 * S + 4096
+
+    chunks, index = [], []
+    for a in (0, 2, 1):
+        for i, b in enumerate(sizes[a]):
+            chunks.append((b, a, nx.TIER_GPU if a != 1 else B_TIERS[i]))
+            index.append((a, i))
+    tier, summ, order = nx.place(gpu_cap, pin_cap, chunks, 1, [2, 0])
+    evicted = [index[j] for j in range(len(chunks)) if chunks[j][2] == nx.TIER_GPU and tier[j] != nx.TIER_GPU]
+    assert all(a == 2 for a, _ in evicted[:len(sizes[2])]) and 0 < len(evicted) < len(sizes[0]) + len(sizes[2])
+    assert summ["kept_pinned_bytes"] > 0 and summ["to_pageable_bytes"] > 0 and summ["gpu_used_after"] <= gpu_cap
+
+    def build(make_set, pinned_arena):
+        """Tables of the switch for one copy of the world (GPU or CPU mirror)."""
+        sets = {a: make_set(sizes[a], seeds[a], "host" if a == 1 else "dev") for a in (0, 1, 2)}
+        cursor = 0
+        rows_out, rows_in, pairs_out, pairs_in = [], [], [], []
+        for j, (a, i) in enumerate(index):
+            hs = sets[a].hs if hasattr(sets[a], "hs") else sets[a]
+            b = chunks[j][0]
+            od, oh = hs.ldev.offsets[i], hs.lhost.offsets[i]
+            dev_base = sets[a].dev_t.data_ptr() if hasattr(sets[a], "dev_t") else None
+            was, now = chunks[j][2], tier[j]
+            if was == now:
+                continue
+            host_in_pinned = (now if was == nx.TIER_GPU else was) == nx.TIER_PINNED
+            if host_in_pinned:                       # a place in the pinned tier, congruent with the device address
+                cursor = (cursor + 255) // 256 * 256 + (od % 16)
+                host_view = pinned_arena[cursor:cursor + b]
+                cursor += b
+                if was == nx.TIER_PINNED:
+                    host_view[:] = hs.host[oh:oh + b]          # B's chunk waits in the pinned tier
+            else:
+                host_view = hs.host[oh:oh + b]
+            pair = (hs.dev[od:od + b], host_view)
+            row = ((dev_base + od) if dev_base is not None else 0, host_view.ctypes.data, b)
+            (rows_out if was == nx.TIER_GPU else rows_in).append(row)
+            (pairs_out if was == nx.TIER_GPU else pairs_in).append(pair)
+        assert cursor <= pin_cap
+        return sets, rows_out, rows_in, pairs_out, pairs_in
+
+    ref_pinned = np.full(pin_cap, 0xEE, dtype=np.uint8)
+    ref_sets, _, _, ref_out, ref_in = build(lambda s, seed, res: HostSet(s, seed, res), ref_pinned)
+    oracle.switch_direct(ref_out, ref_in)
+
+    pin = Pinned(pin_cap)
+    pin.a[:] = 0xEE
+    nx.tier_register(pin.a.ctypes.data, pin_cap)
+    try:
+        sets, rows_out, rows_in, _, _ = build(lambda s, seed, res: GpuSet(s, seed, res), pin.a)
+        plan = nx.Plan(rows_out, rows_in, 8 * S, nx.Opts(slot_bytes=S))
+        info = plan.info()
+        assert info["bytes_out"] == summ["evicted_bytes"] and info["bytes_in"] == summ["restored_bytes"]
+        assert info["direct_bytes_out"] == summ["kept_pinned_bytes"]
+        assert info["direct_bytes_in"] == summ["restored_bytes"] - summ["restored_from_pageable_bytes"]
+        plan.switch()
+        plan.close()
+        assert np.array_equal(pin.a, ref_pinned), "pinned tier: " + first_diff(pin.a, ref_pinned)
+        for a in (0, 1, 2):
+            got_dev = sets[a].download()
+            assert np.array_equal(got_dev, ref_sets[a].dev), f"app {a} device arena: " + first_diff(got_dev, ref_sets[a].dev)
+            assert np.array_equal(sets[a].hs.host, ref_sets[a].host), f"app {a} pageable arena"
+        sets[1].hs.check_moved()                     # B is entirely on the GPU, bytes as generated
+    finally:
+        nx.tier_unregister(pin.a.ctypes.data)

@@ -25,7 +25,7 @@ def library_place(gpu, pinned, chunks, incoming, victims):
         raise po.PlacementError(str(e))
 
 
-IMPLS = {"oracle": oracle_place}
+IMPLS = {"oracle": oracle_place, "library": library_place}
 
 
 @pytest.fixture(params=list(IMPLS))

@@ -308,8 +308,9 @@ int nixie_host_copy(void *const *dst, const void *const *src, const uint64_t *by
  *   - every chunk of incoming_app is in GPU memory;
  *   - chunks of the applications in victim_apps (in that order, e.g. lowest priority first;
  *     inside an application in table order) leave GPU memory, but only until incoming_app fits;
- *   - an evicted chunk stays in the pinned tier if it fits the room left there once
- *     incoming_app's chunks have gone up, else it goes to pageable memory;
+ *   - an evicted chunk stays in the pinned tier if it fits the room that is free there now
+ *     (both directions of a switch run at once, so incoming_app's pinned chunks still hold
+ *     their space while evicted data arrives), else it goes to pageable memory;
  *   - everything else stays.
  * order (nullable, room for n entries) receives the indices of the chunks that move, in
  * migration order: moves between GPU and pageable memory first; *n_moved their number.

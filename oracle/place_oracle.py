@@ -5,8 +5,9 @@ What it follows -- paper, "Speeding Up Context Switches", the global plan:
   1. collect the chunks of the incoming application that are not in GPU memory: they all go there;
   2. compute which chunks now in GPU memory must be evicted to make room -- no more than needed;
   3. go through the host tiers, upper one first, and decide how much of the evicted data can stay
-     in a tier without being moved further down: what fits in the pinned tier (after the incoming
-     application's chunks have left it) stays there, the rest goes to pageable memory;
+     in a tier without being moved further down: what fits in the room the pinned tier has now
+     stays there, the rest goes to pageable memory (both directions of a switch run at once, so
+     the incoming application's pinned chunks still hold their space while evicted data arrives);
   4. transfers that cross several tiers come first in the migration order.
 "Hierarchical Memory": every chunk has exactly one copy, so a tier's usage is the sum of the
 chunks placed in it and a capacity is never exceeded.
@@ -44,6 +45,7 @@ def place(gpu_capacity: int, pinned_capacity: int, chunks, incoming_app: int, vi
 
     # step 1: everything of the incoming application goes to the GPU
     need = 0
+    room = pinned_capacity - used[PINNED]      # step 3 works with the room there is before anything moves
     for i, (b, app, t) in enumerate(chunks):
         if app == incoming_app and t != GPU:
             need += b
@@ -62,7 +64,6 @@ def place(gpu_capacity: int, pinned_capacity: int, chunks, incoming_app: int, vi
     if free < need:
         raise PlacementError("the incoming application does not fit even with every victim evicted")
     # step 3: tier by tier, keep what fits
-    room = pinned_capacity - used[PINNED]
     for i in evicted:
         b = chunks[i][0]
         if b <= room:

@@ -32,6 +32,9 @@ extern "C" int nixie_place(const nixie_capacity_t *cap, const nixie_chunk_state_
     for (uint32_t v = 0; v < n_victims; v++)
         if (victim_apps[v] == incoming_app) return NIXIE_EINVAL;
 
+    // Both directions of a switch run at once, so evicted data can only take pinned room that is
+    // free before anything moves: the incoming application's pinned chunks still hold theirs.
+    uint64_t pinned_room = cap->pinned_bytes - in_tier[NIXIE_TIER_PINNED];
     // the incoming application moves up, whatever tier it is in
     for (uint64_t i = 0; i < n; i++) {
         const nixie_chunk_state_t &c = chunks[i];
@@ -48,7 +51,6 @@ extern "C" int nixie_place(const nixie_capacity_t *cap, const nixie_chunk_state_
 
     // victims: one scan of the table per victim application keeps table order inside it
     uint64_t free_gpu = cap->gpu_bytes - in_tier[NIXIE_TIER_GPU];
-    uint64_t pinned_room = cap->pinned_bytes - in_tier[NIXIE_TIER_PINNED];
     for (uint32_t v = 0; v < n_victims && free_gpu < need; v++) {
         for (uint64_t i = 0; i < n && free_gpu < need; i++) {
             const nixie_chunk_state_t &c = chunks[i];
@@ -67,7 +69,7 @@ extern "C" int nixie_place(const nixie_capacity_t *cap, const nixie_chunk_state_
     }
     if (free_gpu < need) return NIXIE_ENOMEM;      // does not fit even with every victim gone
     s.gpu_used_after = cap->gpu_bytes - (free_gpu - need);
-    s.pinned_used_after = cap->pinned_bytes - pinned_room;
+    s.pinned_used_after = in_tier[NIXIE_TIER_PINNED] + s.kept_pinned_bytes;
 
     // migration order: two-tier moves, then one-tier moves, table order inside each
     uint64_t moved = 0;

@@ -46,18 +46,28 @@ def test_worked_example_partial_eviction(place):
 
 
 def test_worked_example_pinned_overflow_and_first_fit(place):
-    """24 GiB GPU, 10 GiB pinned of which B's 4 GiB chunk leaves.  A holds 8 + 8 + 2 + 6 GiB; B needs
-    4 (pinned) + 16 (pageable) = 20; free 0 -> evict 8, 8, 2, 6 until >= 20 free: 8 + 8 + 2 = 18 < 20, so all
-    four (24).  Pinned room = 10 - (4 - 4) = 10: 8 fits (room 2), 8 does not -> pageable, 2 fits (room 0),
-    6 -> pageable."""
+    """24 GiB GPU, 10 GiB pinned of which B's 4 GiB chunk still holds its place while the switch runs.
+    A holds 8 + 8 + 2 + 6 GiB; B needs 4 (pinned) + 16 (pageable) = 20; free 0 -> evict 8, 8, 2, 6 until
+    >= 20 free: 8 + 8 + 2 = 18 < 20, so all four (24).  Pinned room = 10 - 4 = 6: 8 does not fit -> pageable,
+    8 -> pageable, 2 fits (room 4), 6 -> pageable."""
     chunks = [(8 * GiB, 0, GPU), (8 * GiB, 0, GPU), (2 * GiB, 0, GPU), (6 * GiB, 0, GPU),
               (4 * GiB, 1, PIN), (16 * GiB, 1, PAGE)]
     tier, s, order = place(24 * GiB, 10 * GiB, chunks, 1, [0])
-    assert tier == [PIN, PAGE, PIN, PAGE, GPU, GPU]
-    assert s["kept_pinned_bytes"] == 10 * GiB and s["to_pageable_bytes"] == 14 * GiB
+    assert tier == [PAGE, PAGE, PIN, PAGE, GPU, GPU]
+    assert s["kept_pinned_bytes"] == 2 * GiB and s["to_pageable_bytes"] == 22 * GiB
     assert s["restored_from_pageable_bytes"] == 16 * GiB
-    assert s["gpu_used_after"] == 20 * GiB and s["pinned_used_after"] == 10 * GiB
-    assert order == [1, 3, 5, 0, 2, 4]   # the two-tier moves in table order, then the one-tier moves
+    assert s["gpu_used_after"] == 20 * GiB and s["pinned_used_after"] == 2 * GiB
+    assert order == [0, 1, 3, 5, 2, 4]   # the two-tier moves in table order, then the one-tier moves
+
+
+def test_pinned_room_counts_the_incoming_chunks_that_are_still_there(place):
+    """Both directions of a switch run at once: the space of B's pinned chunk is not free for A's
+    evicted chunk, although it will be once the switch is over."""
+    chunks = [(4, 0, GPU), (4, 1, PIN)]
+    tier, s, _ = place(4, 4, chunks, 1, [0])
+    assert tier == [PAGE, GPU] and s["pinned_used_after"] == 0
+    tier, s, _ = place(4, 8, chunks, 1, [0])
+    assert tier == [PIN, GPU] and s["pinned_used_after"] == 4
 
 
 def test_nothing_to_do_and_victim_order(place):
@@ -116,7 +126,7 @@ def test_invariants_and_minimal_eviction_exhaustively(place):
                     if ev:                                          # minimal: one chunk fewer would not fit
                         assert g + chunks[ev[-1]][0] > gpu_cap
                     # a chunk goes to pageable memory only if it did not fit the pinned room left at its turn
-                    room = pin_cap - sum(b for b, a, t in chunks if t == PIN and a != 1)
+                    room = pin_cap - sum(b for b, a, t in chunks if t == PIN)
                     for i in ev:
                         if tier[i] == PIN:
                             room -= chunks[i][0]

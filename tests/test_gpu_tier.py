@@ -283,6 +283,9 @@ def test_placement_drives_a_partial_eviction(nx, oracle):
             got_dev = sets[a].download()
             assert np.array_equal(got_dev, ref_sets[a].dev), f"app {a} device arena: " + first_diff(got_dev, ref_sets[a].dev)
             assert np.array_equal(sets[a].hs.host, ref_sets[a].host), f"app {a} pageable arena"
-        sets[1].hs.check_moved()                     # B is entirely on the GPU, bytes as generated
+        import workloads as W
+        dev_b = sets[1].download()                   # B is entirely on the GPU, bytes as generated
+        for i, (o, b) in enumerate(zip(sets[1].hs.ldev.offsets, sizes[1])):
+            assert np.array_equal(dev_b[o:o + b], W.content_bytes(seeds[1], i, b)), f"B's allocation {i}"
     finally:
         nx.tier_unregister(pin.a.ctypes.data)

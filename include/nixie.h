@@ -223,6 +223,26 @@ void nixie_plan_destroy(nixie_plan_t *plan);
  * Sources are unspecified afterwards.  stats may be NULL. */
 int nixie_switch(nixie_plan_t *plan, void *hip_stream, nixie_stats_t *stats);
 
+/* The same switch in three steps, for a caller that wants to let the incoming application run
+ * as soon as ITS memory is ready (paper, "Overview" step 5: an application is re-enabled when
+ * its memory is ready; what the user waits for is the incoming application) while the outgoing
+ * one is still being evicted:
+ *   nixie_switch_begin    checks, wakes the host threads, launches the kernel, returns at once;
+ *   nixie_switch_wait_in  blocks until every byte of the incoming table is in HBM and visible to
+ *                         kernels launched afterwards on any stream (each scatter workgroup
+ *                         writes its L2 back before it counts as finished); returns the
+ *                         switch's error if it failed meanwhile.  Optional, may be called once;
+ *   nixie_switch_end      blocks until everything is complete, fills stats, returns the result
+ *                         of the switch exactly as nixie_switch does.
+ * Between begin and end the plan is busy (NIXIE_EBUSY for another switch), map / unmap calls
+ * wait, and the three calls must come from one thread.  nixie_switch_wait_in / _end without a
+ * begun switch: NIXIE_EINVAL.  Not available with NIXIE_SERIALIZE (NIXIE_EINVAL).  With
+ * NIXIE_IN_PLACE the incoming bytes are complete at wait_in like otherwise; the outgoing
+ * application's device ranges are the incoming one's by then. */
+int nixie_switch_begin(nixie_plan_t *plan, void *hip_stream);
+int nixie_switch_wait_in(nixie_plan_t *plan);
+int nixie_switch_end(nixie_plan_t *plan, nixie_stats_t *stats);
+
 /* ---- verification: per-allocation 64-bit hash ---------------------------------------------
  * H(b[0..n)) = mix64(n) + sum_k mix64(w_k + G*(k+1)) mod 2^64, w_k the k-th little-endian
  * 8-byte word (last one zero padded), G = 0x9E3779B97F4A7C15, mix64 the splitmix64 output

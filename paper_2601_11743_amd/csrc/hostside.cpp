@@ -54,13 +54,14 @@ struct IdleWatch {
     int dir;
     uint64_t idle_since = 0;
     uint32_t spins = 0;
+    bool force_yield = false;   // for a waiter that is not one of the crew's threads
     // call after a scan that made no progress; false = stop
     bool idle() {
         // Spin: a slot usually turns around in microseconds.  Only where the threads outnumber
         // the cores does a long-idle thread give its core away between looks, so that a waiting
         // thread cannot keep the one it waits for off the processor; with a core each, yielding
         // costs a small ring one to two percent and buys nothing.
-        if (p->yield_when_idle && spins >= 4096) sched_yield();
+        if ((p->yield_when_idle || force_yield) && spins >= 4096) sched_yield();
         else _mm_pause();
         if (idle_since == 0) idle_since = now_ns();
         if ((++spins & 63u) != 0) return true;
@@ -172,6 +173,19 @@ void HostSide::run_fill(uint32_t idx) {
     }
     watch.progressed();
     note_end(p, 1);   // this thread's last chunk has reached HBM; the latest such time is "B ready"
+}
+
+int HostSide::wait_direction(int x) {
+    IdleWatch watch{this, x};
+    watch.force_yield = true;
+    int rc = NIXIE_OK;
+    while (__atomic_load_n(done_word + x, __ATOMIC_ACQUIRE) == 0) {
+        if (!watch.idle()) break;
+    }
+    if (__atomic_load_n(done_word + x, __ATOMIC_ACQUIRE) == 0 || error.load() ||
+        __atomic_load_n(status_word, __ATOMIC_ACQUIRE) != kGpuOk)
+        rc = error.load() ? error.load() : NIXIE_ETIMEOUT;
+    return rc;
 }
 
 void HostCrew::worker(int dir, uint32_t idx) {

@@ -19,6 +19,7 @@ struct HostSide {
     const uint64_t *post[2] = {nullptr, nullptr};     // GPU-written, kFlagStride apart: out ready[s], in freed[s]
     uint32_t *abort_word = nullptr;                   // host-written, the kernel's pump relays it
     const uint32_t *status_word = nullptr;            // GPU-written: kGpuOk or why the kernel gave up
+    const uint32_t *done_word = nullptr;              // GPU-written: [x] = 1 once direction x has left the GPU
     uint64_t timeout_ns = 0;
     uint32_t threads[2] = {0, 0};                     // drain, fill
     bool yield_when_idle = false;                     // set when the threads outnumber the usable cores
@@ -34,6 +35,9 @@ struct HostSide {
     void raise_abort(int err);
     void run_drain(uint32_t idx);                     // ring -> pageable, thread idx of threads[0]
     void run_fill(uint32_t idx);                      // pageable -> ring, thread idx of threads[1]
+    // Blocks until the kernel reports that every workgroup of direction x has left (for x = 1:
+    // every incoming byte is in HBM), or the switch fails.  NIXIE_OK or the switch's error.
+    int wait_direction(int x);
 };
 
 // The parked threads.  wake() starts them on the directions in mask; wait() returns when all of

@@ -83,6 +83,7 @@ struct SwapArgs {
     uint32_t *gathered_prefix;   // device memory: number of leading outgoing chunks that have left HBM
     uint32_t track_prefix;       // 1: in-place switch with both directions running in this launch
     uint32_t xcd_mask;           // 0 = every XCD takes part
+    uint32_t *dir_done;          // pinned, GPU-written: [x] = 1 once every workgroup of direction x has left
 };
 
 struct HashDesc { uint64_t ptr; uint64_t bytes; uint64_t first_tile; };

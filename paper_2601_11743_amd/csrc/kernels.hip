@@ -243,8 +243,17 @@ __device__ void run_direction(const SwapArgs &a) {
                                    __HIP_MEMORY_SCOPE_SYSTEM);
         }
     }
+    // Leaving.  The pump reports "direction complete" to the host once every workgroup of the
+    // direction has left, and the host may then let the incoming application run while this
+    // kernel is still evicting.  What this workgroup scattered into HBM must therefore be out of
+    // this XCD's L2 before it counts as gone: all waves wait for their stores, and one
+    // device-scope release (an L2 write-back, once per workgroup, not per work unit) precedes the
+    // increment.  The gather side wrote only write-through stores and needs none.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
     if (tid == 0) {
         if (stall) __hip_atomic_fetch_add(D.stall_ticks, stall, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (DIR == 1) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
         __hip_atomic_fetch_add(D.exited, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // on every exit path
     }
 }
@@ -311,6 +320,7 @@ __device__ void run_pump(const SwapArgs &a, int dir) {
             // every gather workgroup has left, so every arrive counter is final: publish the rest
             // (bounded: at most n_chunks / 64 + 1 rounds)
             if (track) while (prefix < D.n_chunks && advance_prefix()) {}
+            if (lane == 0) __hip_atomic_store(a.dir_done + dir, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
             break;
         }
         __builtin_amdgcn_s_sleep(8);

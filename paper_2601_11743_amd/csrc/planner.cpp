@@ -299,7 +299,7 @@ void fill_info(const Layout &L, nixie_plan_info_t *info) {
     info->direct_bytes_in = L.dir[1].direct_bytes;
     info->pinned_ring_bytes = (uint64_t)(L.dir[0].slots + L.dir[1].slots) * L.slot_bytes;
     info->pinned_ctrl_bytes = (wait_flag_words(L.dir[0].slots) + wait_flag_words(L.dir[1].slots) +
-                               ((uint64_t)(L.dir[0].slots + L.dir[1].slots) + 2) * kFlagStride) * 8;
+                               ((uint64_t)(L.dir[0].slots + L.dir[1].slots) + 3) * kFlagStride) * 8;
     // Measured on MI355X with both directions active: write-through stores into the ring need
     // about twice the workgroups that the reads out of it need; beyond 128 + 64 the surplus
     // only waits for slots.

@@ -74,6 +74,17 @@ struct nixie_plan {
     HostSide hs;           // flags, ring and counters as the host threads see them
     HostCrew crew;         // the parked drain / fill threads
     std::mutex switch_mu;  // one switch at a time
+
+    // a switch begun with nixie_switch_begin and not yet ended
+    struct Flight {
+        bool on = false;
+        hipStream_t stream = nullptr;
+        uint64_t t_entry = 0;
+        uint32_t mask = 0;
+        nixie_stats_t st{};
+        std::unique_lock<std::mutex> plan_lock;
+        std::shared_lock<std::shared_mutex> maps;
+    } flight;
 };
 
 namespace {
@@ -121,7 +132,7 @@ int create_plan(nixie_plan_t *p) {
         NIXIE_HIP(hipHostGetDevicePointer((void **)&p->ring_d, p->ring_h, 0));
     }
     // control block: [host-written flags out | in (8 B each, padded to lines)] [GPU-written flags out | in
-    // (one 64 B line each)] [abort word] [status word]
+    // (one 64 B line each)] [abort word] [status word] [direction-done words]
     p->ctrl_bytes = p->info.pinned_ctrl_bytes;
     {
         hipError_t e = hipHostMalloc((void **)&p->ctrl_h, p->ctrl_bytes, hipHostMallocMapped | hipHostMallocCoherent);
@@ -136,6 +147,7 @@ int create_plan(nixie_plan_t *p) {
     p->hs.post[1] = c;                                   c += (size_t)L.dir[1].slots * kFlagStride;
     p->hs.abort_word = (uint32_t *)c;                         c += kFlagStride;
     p->hs.status_word = (uint32_t *)c;                        c += kFlagStride;
+    p->hs.done_word = (uint32_t *)c;                          c += kFlagStride;
     if ((size_t)(c - p->ctrl_h) * 8 != p->ctrl_bytes) return NIXIE_EINVAL;
 
     // descriptors
@@ -197,8 +209,9 @@ int create_plan(nixie_plan_t *p) {
     return NIXIE_OK;
 }
 
-// One pass: the directions in mask run together.
-int run_pass(nixie_plan_t *p, uint32_t mask, hipStream_t stream, nixie_stats_t *st, uint64_t t_entry) {
+// One pass: the directions in mask run together.  pass_begin launches and returns; pass_end waits
+// for the host threads and the kernel and collects the figures.
+int pass_begin(nixie_plan_t *p, uint32_t mask, hipStream_t stream, nixie_stats_t *st, uint64_t t_entry) {
     const Layout &L = p->L;
     std::memset(p->ctrl_h, 0, p->ctrl_bytes);
     p->hs.begin_pass();   // counters to zero, every outgoing slot marked released
@@ -231,12 +244,16 @@ int run_pass(nixie_plan_t *p, uint32_t mask, hipStream_t stream, nixie_stats_t *
     a.slot_bytes = L.slot_bytes;
     a.host_abort = (const uint32_t *)(p->ctrl_d + (size_t)((uint64_t *)p->hs.abort_word - p->ctrl_h));
     a.gpu_status = (uint32_t *)(p->ctrl_d + (size_t)((uint64_t *)p->hs.status_word - p->ctrl_h));
+    a.dir_done = (uint32_t *)(p->ctrl_d + (size_t)((uint64_t *)p->hs.done_word - p->ctrl_h));
     a.dev_abort = p->counters_d + 2;
     a.timeout_ticks = p->hs.timeout_ns / 10;   // wall clock runs at 100 MHz
     a.gathered_prefix = p->counters_d + 10;
     a.xcd_mask = L.opts.xcd_mask & 0xFFu;
     // when the directions run one after the other, everything has left HBM before the restore starts
     a.track_prefix = ((L.opts.flags & NIXIE_IN_PLACE) && a.d[0].wgs && a.d[1].wgs) ? 1u : 0u;
+    // a direction that does not run in this pass has nothing to wait for
+    for (int x = 0; x < 2; x++)
+        if (a.d[x].wgs == 0) ((uint32_t *)p->hs.done_word)[x] = 1;
 
     // The host threads start first: while the launches below are in flight they are already waking
     // up and loading the first incoming slots.
@@ -257,12 +274,18 @@ int run_pass(nixie_plan_t *p, uint32_t mask, hipStream_t stream, nixie_stats_t *
         return NIXIE_EHIP;
     }
     if (st && st->ns_launch == 0) st->ns_launch = now_ns() - t_entry;
+    return NIXIE_OK;
+}
+
+int pass_end(nixie_plan_t *p, uint32_t mask, hipStream_t stream, nixie_stats_t *st) {
+    const Layout &L = p->L;
     p->crew.wait();   // drain / fill threads done (finished, aborted or timed out)
     hipError_t se = hipStreamSynchronize(stream);
     if (se != hipSuccess) { t_last_hip_error = (int)se; return NIXIE_EHIP; }
     // directly moved chunks are complete when the kernel is: no host thread saw them go by
     for (int x = 0; x < 2; x++)
-        if ((mask & (1u << x)) && L.dir[x].staged < L.dir[x].chunks.size()) p->hs.end_ns[x].store(now_ns());
+        if ((mask & (1u << x)) && L.dir[x].staged < L.dir[x].chunks.size() && p->hs.end_ns[x].load() == 0)
+            p->hs.end_ns[x].store(now_ns());
 
     if (st) {
         float ms = 0.f;
@@ -280,6 +303,27 @@ int run_pass(nixie_plan_t *p, uint32_t mask, hipStream_t stream, nixie_stats_t *
     int err = p->hs.error.load();
     if (!err && __atomic_load_n(p->hs.status_word, __ATOMIC_ACQUIRE) != kGpuOk) err = NIXIE_ETIMEOUT;
     return err;
+}
+
+int run_pass(nixie_plan_t *p, uint32_t mask, hipStream_t stream, nixie_stats_t *st, uint64_t t_entry) {
+    int rc = pass_begin(p, mask, stream, st, t_entry);
+    return rc ? rc : pass_end(p, mask, stream, st);
+}
+
+void finish_stats(nixie_plan_t *p, nixie_stats_t &st, uint64_t t_entry) {
+    st.ns_total = now_ns() - t_entry;
+    st.ns_out_done = p->hs.end_ns[0].load() > t_entry ? p->hs.end_ns[0].load() - t_entry : 0;
+    st.ns_in_done = p->hs.end_ns[1].load() > t_entry ? p->hs.end_ns[1].load() - t_entry : 0;
+}
+
+void reset_for_switch(nixie_plan_t *p, nixie_stats_t &st) {
+    st = nixie_stats_t{};
+    st.bytes_out = p->L.dir[0].bytes;
+    st.bytes_in = p->L.dir[1].bytes;
+    p->hs.timeout_ns = (uint64_t)(p->L.opts.timeout_ms ? p->L.opts.timeout_ms : 30000u) * 1000000ull;
+    p->hs.error.store(0);
+    p->hs.end_ns[0].store(0);
+    p->hs.end_ns[1].store(0);
 }
 
 }  // namespace
@@ -354,7 +398,13 @@ int nixie_plan_info(const nixie_plan_t *plan, nixie_plan_info_t *info) {
     return NIXIE_OK;
 }
 
-void nixie_plan_destroy(nixie_plan_t *plan) { destroy_plan(plan); }
+void nixie_plan_destroy(nixie_plan_t *plan) {
+    if (plan && plan->flight.on) {           // a switch was begun and never ended: stop it first
+        plan->hs.raise_abort(NIXIE_EBUSY);
+        (void)nixie_switch_end(plan, nullptr);
+    }
+    destroy_plan(plan);
+}
 
 int nixie_switch(nixie_plan_t *p, void *hip_stream, nixie_stats_t *stats) {
     if (!p) return NIXIE_EINVAL;
@@ -367,13 +417,8 @@ int nixie_switch(nixie_plan_t *p, void *hip_stream, nixie_stats_t *stats) {
     int dev = -1;
     NIXIE_HIP(hipGetDevice(&dev));
     if (dev != p->device) return NIXIE_EINVAL;
-    nixie_stats_t st{};
-    st.bytes_out = p->L.dir[0].bytes;
-    st.bytes_in = p->L.dir[1].bytes;
-    p->hs.timeout_ns = (uint64_t)(p->L.opts.timeout_ms ? p->L.opts.timeout_ms : 30000u) * 1000000ull;
-    p->hs.error.store(0);
-    p->hs.end_ns[0].store(0);
-    p->hs.end_ns[1].store(0);
+    nixie_stats_t st;
+    reset_for_switch(p, st);
 
     int rc = NIXIE_OK;
     const bool both = !p->L.dir[0].chunks.empty() && !p->L.dir[1].chunks.empty();
@@ -383,11 +428,51 @@ int nixie_switch(nixie_plan_t *p, void *hip_stream, nixie_stats_t *stats) {
     } else {
         rc = run_pass(p, 3u, (hipStream_t)hip_stream, &st, t_entry);
     }
-    const uint64_t t_end = now_ns();
-    st.ns_total = t_end - t_entry;
-    st.ns_out_done = p->hs.end_ns[0].load() > t_entry ? p->hs.end_ns[0].load() - t_entry : 0;
-    st.ns_in_done = p->hs.end_ns[1].load() > t_entry ? p->hs.end_ns[1].load() - t_entry : 0;
+    finish_stats(p, st, t_entry);
     if (stats) *stats = st;
+    return rc;
+}
+
+int nixie_switch_begin(nixie_plan_t *p, void *hip_stream) {
+    if (!p) return NIXIE_EINVAL;
+    if (p->L.opts.flags & NIXIE_SERIALIZE) return NIXIE_EINVAL;   // two passes cannot be left running
+    std::unique_lock<std::mutex> lk(p->switch_mu, std::try_to_lock);
+    if (!lk.owns_lock()) return NIXIE_EBUSY;
+    std::shared_lock<std::shared_mutex> maps(switch_lock());
+    if (!space_uses_mapped(p->L.uses[0]) || !space_uses_mapped(p->L.uses[1])) return NIXIE_EUNMAPPED;
+    const uint64_t t_entry = now_ns();
+    int dev = -1;
+    NIXIE_HIP(hipGetDevice(&dev));
+    if (dev != p->device) return NIXIE_EINVAL;
+    nixie_plan::Flight &f = p->flight;
+    reset_for_switch(p, f.st);
+    int rc = pass_begin(p, 3u, (hipStream_t)hip_stream, &f.st, t_entry);
+    if (rc) return rc;                                           // nothing is left running
+    f.on = true;
+    f.stream = (hipStream_t)hip_stream;
+    f.t_entry = t_entry;
+    f.mask = 3u;
+    f.plan_lock = std::move(lk);                                 // held until nixie_switch_end
+    f.maps = std::move(maps);
+    return NIXIE_OK;
+}
+
+int nixie_switch_wait_in(nixie_plan_t *p) {
+    if (!p || !p->flight.on) return NIXIE_EINVAL;
+    const int rc = p->hs.wait_direction(1);
+    if (!rc && p->hs.end_ns[1].load() == 0) p->hs.end_ns[1].store(now_ns());
+    return rc;
+}
+
+int nixie_switch_end(nixie_plan_t *p, nixie_stats_t *stats) {
+    if (!p || !p->flight.on) return NIXIE_EINVAL;
+    nixie_plan::Flight &f = p->flight;
+    const int rc = pass_end(p, f.mask, f.stream, &f.st);
+    finish_stats(p, f.st, f.t_entry);
+    if (stats) *stats = f.st;
+    f.on = false;
+    f.maps.unlock();
+    f.plan_lock.unlock();
     return rc;
 }
 

@@ -24,6 +24,7 @@ DECLARED_SYMBOLS = (
     "nixie_pool_create", "nixie_pool_info", "nixie_pool_destroy", "nixie_space_create", "nixie_space_map",
     "nixie_space_unmap", "nixie_space_mapped", "nixie_space_destroy",
     "nixie_tier_register", "nixie_tier_unregister", "nixie_host_copy", "nixie_place",
+    "nixie_switch_begin", "nixie_switch_wait_in", "nixie_switch_end",
 )
 
 
@@ -146,6 +147,9 @@ def lib() -> C.CDLL:
     L.nixie_plan_destroy.argtypes = [vp]
     L.nixie_plan_destroy.restype = None
     L.nixie_switch.argtypes = [vp, vp, C.POINTER(_Stats)]
+    L.nixie_switch_begin.argtypes = [vp, vp]
+    L.nixie_switch_wait_in.argtypes = [vp]
+    L.nixie_switch_end.argtypes = [vp, C.POINTER(_Stats)]
     L.nixie_hash_tables.argtypes = [vp, vp, vp, vp]
     L.nixie_verify.argtypes = [vp, vp, vp, vp, C.POINTER(_Report)]
     L.nixie_hash_buffers.argtypes = [vp, vp, u64, i32, vp, vp]
@@ -296,6 +300,25 @@ class Plan:
         d["rc"] = rc
         if rc and check:
             raise NixieError(rc, "nixie_switch")
+        return d
+
+    def switch_begin(self, stream: int = 0) -> None:
+        rc = lib().nixie_switch_begin(self._h, C.c_void_p(stream))
+        if rc:
+            raise NixieError(rc, "nixie_switch_begin")
+
+    def switch_wait_in(self) -> None:
+        rc = lib().nixie_switch_wait_in(self._h)
+        if rc:
+            raise NixieError(rc, "nixie_switch_wait_in")
+
+    def switch_end(self, check: bool = True) -> dict:
+        st = _Stats()
+        rc = lib().nixie_switch_end(self._h, C.byref(st))
+        if rc and check:
+            raise NixieError(rc, "nixie_switch_end")
+        d = _as_dict(st)
+        d["rc"] = rc
         return d
 
     def hash_tables(self, stream: int = 0):

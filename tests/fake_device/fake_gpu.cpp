@@ -55,6 +55,7 @@ struct FakeGpu {
     uint64_t *post[2];               // "GPU"-written (kFlagStride apart)
     const uint32_t *host_abort;
     uint32_t *status;
+    uint32_t *done = nullptr;        // [dir] = 1 once every worker of the direction has left
     uint32_t team[2], wgs[2];
     bool in_place = false;
     bool never_start = false, quit_early = false;
@@ -133,7 +134,10 @@ struct FakeGpu {
                 dev_abort.store(1, std::memory_order_release);
                 __atomic_store_n(status, (uint32_t)kGpuSawAbort, __ATOMIC_RELEASE);
             }
-            if (exited[dir].load(std::memory_order_acquire) >= wgs[dir]) break;
+            if (exited[dir].load(std::memory_order_acquire) >= wgs[dir]) {
+                __atomic_store_n(done + dir, 1u, __ATOMIC_RELEASE);
+                break;
+            }
             std::this_thread::yield();
         }
     }
@@ -310,8 +314,10 @@ int run(const std::string &scenario, uint64_t seed) {
     uint64_t *post1 = c; c += (size_t)L.dir[1].slots * kFlagStride;
     hs.post[0] = post0; hs.post[1] = post1;
     hs.abort_word = (uint32_t *)c; c += kFlagStride;
-    uint32_t *status = (uint32_t *)c;
+    uint32_t *status = (uint32_t *)c; c += kFlagStride;
     hs.status_word = status;
+    uint32_t *done = (uint32_t *)c;
+    hs.done_word = done;
     hs.L = &L;
     hs.ring = ring.data();
     hs.threads[0] = info.drain_threads;
@@ -327,7 +333,7 @@ int run(const std::string &scenario, uint64_t seed) {
     gpu.L = &L; gpu.ring = ring.data();
     gpu.host_flags[0] = hs.wait[0]; gpu.host_flags[1] = hs.wait[1];
     gpu.post[0] = post0; gpu.post[1] = post1;
-    gpu.host_abort = hs.abort_word; gpu.status = status;
+    gpu.host_abort = hs.abort_word; gpu.status = status; gpu.done = done;
     gpu.team[0] = info.team_out ? info.team_out : 1; gpu.team[1] = info.team_in ? info.team_in : 1;
     gpu.wgs[0] = 5; gpu.wgs[1] = 3;
     gpu.in_place = in_place;
@@ -340,9 +346,24 @@ int run(const std::string &scenario, uint64_t seed) {
         hs.begin_pass();
         gpu.dev_abort.store(0); gpu.gathered_prefix.store(0);
         const auto t0 = std::chrono::steady_clock::now();
+        for (int x = 0; x < 2; x++)
+            if (L.dir[x].chunks.empty()) done[x] = 1;
         gpu.launch();
-        crew.run_pass(3u);
+        crew.wake(3u);
+        // the caller's early exit: every incoming byte is in "HBM" when this returns 0
+        const int in_rc = hs.wait_direction(1);
+        int early_fails = 0;
+        if (must_succeed || scenario == "stall") {   // withheld outgoing credits do not hold the incoming side up
+            if (in_rc) { std::printf("wait_direction(1) failed: %d\n", in_rc); early_fails++; }
+            for (size_t i = 0; i < B.rows.size() && !in_rc; i++)
+                if (std::memcmp(B.rows[i].dev_ptr, want_b[i].data(), B.rows[i].bytes)) { std::printf("incoming allocation %zu not complete at wait_direction\n", i); early_fails++; }
+        } else if (in_rc != NIXIE_ETIMEOUT) {
+            std::printf("wait_direction(1) on a dead device returned %d\n", in_rc);
+            early_fails++;
+        }
+        crew.wait();
         gpu.join();
+        fails += early_fails;
         const double ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
         const int err = hs.error.load();
         if (must_succeed) {

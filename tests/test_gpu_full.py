@@ -299,3 +299,86 @@ def test_scheduler_drives_the_swaps(nx, oracle):
     sched.close()
     del sets
     torch.cuda.empty_cache()
+
+
+def test_config2_between_two_spaces_full(nx, oracle):
+    """Config 2 at full size, A and B each in an address space of their own over ONE 17 GiB pool of
+    physical memory: map B, switch in place, unmap A; and the way back."""
+    import torch
+    from workloads.device import BigSet, device_view
+    cf = W.config(2)
+    sizes = [s[1] for s in cf["A"]]
+    pool = nx.Pool(W.make_layout(sizes, redzone=256).total, 0)
+    sp_a, sp_b = nx.Space(pool), nx.Space(pool)
+    sp_a.map()
+    sp_b.map()
+    A = BigSet(cf["A"], cf["seed_A"], "dev", cf["content"], dev_arena=device_view(sp_a.base, pool.bytes))
+    B = BigSet(cf["B"], cf["seed_B"], "host", cf["content"], dev_arena=device_view(sp_b.base, pool.bytes))
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    sp_b.unmap()
+    ia, ib = sample_indices(A.sizes, 1), sample_indices(B.sizes, 2)
+    exp_a, hash_a = oracle_expectation(oracle, A, ia, "dev")
+    exp_b, hash_b = oracle_expectation(oracle, B, ib, "host")
+    opts = nx.Opts(slot_bytes=cf["slot_bytes"], flags=nx.IN_PLACE)
+    fwd = nx.Plan(A.rows_np(), B.rows_np(), 256 * MiB, opts)
+    back = nx.Plan(B.rows_np(), A.rows_np(), 256 * MiB, opts)
+    h_a, h_b = fwd.hash_tables()
+    assert [int(h_a[i]) for i in ia] == hash_a and [int(h_b[i]) for i in ib] == hash_b
+    assert fwd.switch(check=False)["rc"] == nx.EUNMAPPED          # B's addresses have no memory yet
+    sp_b.map()
+    st = fwd.switch()
+    sp_a.unmap()
+    for i, e in zip(ia, exp_a):
+        assert np.array_equal(A.host_view(i), e), f"evicted allocation {i} differs from the oracle"
+    for i, e in zip(ib, exp_b):
+        assert np.array_equal(B.dev_view(i).cpu().numpy(), e), f"restored allocation {i} differs from the oracle"
+    assert B.arenas_equal(), "pool seen through B's space differs from B's pageable arena"
+    fwd.verify(h_a, h_b)
+    print(f"\nconfig 2 between two spaces: {st['ns_total'] / 1e6:.1f} ms")
+    sp_a.map()
+    back.switch()
+    sp_b.unmap()
+    back.verify(h_b, h_a)
+    for i, e in zip(ia, exp_a):
+        assert np.array_equal(A.dev_view(i).cpu().numpy(), e)
+    assert A.arenas_equal()
+    fwd.close(); back.close()
+    del A, B
+    sp_a.close(); sp_b.close(); pool.close()
+
+
+def test_config2_pinned_tier_full(nx, oracle):
+    """Config 2 at full size with the host side of both working sets in the registered pinned tier:
+    no ring, no host threads, every chunk direct."""
+    import torch
+    from workloads.device import BigSet
+    cf = W.config(2)
+    A = BigSet(cf["A"], cf["seed_A"], "dev", cf["content"], pinned_host=True)
+    B = BigSet(cf["B"], cf["seed_B"], "host", cf["content"], pinned_host=True)
+    nx.tier_register(A.host.ctypes.data, A.host.size)
+    nx.tier_register(B.host.ctypes.data, B.host.size)
+    try:
+        ia, ib = sample_indices(A.sizes, 1), sample_indices(B.sizes, 2)
+        exp_a, hash_a = oracle_expectation(oracle, A, ia, "dev")
+        exp_b, hash_b = oracle_expectation(oracle, B, ib, "host")
+        plan = nx.Plan(A.rows_np(), B.rows_np(), 0)
+        info = plan.info()
+        assert info["pinned_ring_bytes"] == 0 and info["drain_threads"] == 0 and info["fill_threads"] == 0
+        assert info["direct_bytes_out"] == A.total_bytes and info["direct_bytes_in"] == B.total_bytes
+        h_a, h_b = plan.hash_tables()
+        assert [int(h_a[i]) for i in ia] == hash_a and [int(h_b[i]) for i in ib] == hash_b
+        st = plan.switch()
+        for i, e in zip(ia, exp_a):
+            assert np.array_equal(A.host_view(i), e), f"evicted allocation {i} differs from the oracle"
+        for i, e in zip(ib, exp_b):
+            assert np.array_equal(B.dev_view(i).cpu().numpy(), e), f"restored allocation {i} differs from the oracle"
+        assert A.arenas_equal() and B.arenas_equal()
+        plan.verify(h_a, h_b)
+        print(f"\nconfig 2, pinned tier both sides: {st['ns_total'] / 1e6:.1f} ms")
+        plan.close()
+    finally:
+        nx.tier_unregister(A.host.ctypes.data)
+        nx.tier_unregister(B.host.ctypes.data)
+    del A, B
+    torch.cuda.empty_cache()

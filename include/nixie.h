@@ -81,6 +81,9 @@ enum nixie_flags {
                                          addresses").  A chunk is scattered only after every outgoing chunk that
                                          covers GPU bytes it overwrites has left HBM.  Ranges inside one table must
                                          still be disjoint, and so must all host ranges. */
+    NIXIE_HOST_SPIN = 1u << 7,        /* host threads with nothing to do spin.  By default they sleep for 1/16 of the time
+                                         their direction's share of the ring lasts at link rate (at most 50 us, never
+                                         when that is under 4 us): same latency, less than half the CPU time */
     NIXIE_NO_DIRECT = 1u << 6         /* measurement: allocations whose host side lies in the registered pinned tier
                                          go through the ring and the host threads like all others */
 };

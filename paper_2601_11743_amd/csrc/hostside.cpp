@@ -9,6 +9,7 @@
 
 #include <immintrin.h>
 #include <sched.h>
+#include <sys/prctl.h>
 #include <time.h>
 
 #include <cstring>
@@ -61,7 +62,12 @@ struct IdleWatch {
         // the cores does a long-idle thread give its core away between looks, so that a waiting
         // thread cannot keep the one it waits for off the processor; with a core each, yielding
         // costs a small ring one to two percent and buys nothing.
-        if ((p->yield_when_idle || force_yield) && spins >= 4096) sched_yield();
+        if (p->idle_sleep_ns && spins >= 64 && !force_yield) {
+            // Nothing for a few microseconds: the ring holds far more than a nap's worth of
+            // transfer, so give the core to whoever needs it (the applications do).
+            timespec nap{0, (long)p->idle_sleep_ns};
+            nanosleep(&nap, nullptr);
+        } else if ((p->yield_when_idle || force_yield) && spins >= 4096) sched_yield();
         else _mm_pause();
         if (idle_since == 0) idle_since = now_ns();
         if ((++spins & 63u) != 0) return true;
@@ -189,6 +195,7 @@ int HostSide::wait_direction(int x) {
 }
 
 void HostCrew::worker(int dir, uint32_t idx) {
+    prctl(PR_SET_TIMERSLACK, 1000UL, 0UL, 0UL, 0UL);   // naps of tens of microseconds, not the default 50 us slack on top
     uint64_t seen = 0;
     for (;;) {
         uint32_t mask;

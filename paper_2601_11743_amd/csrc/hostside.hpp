@@ -23,6 +23,7 @@ struct HostSide {
     uint64_t timeout_ns = 0;
     uint32_t threads[2] = {0, 0};                     // drain, fill
     bool yield_when_idle = false;                     // set when the threads outnumber the usable cores
+    uint64_t idle_sleep_ns = 0;                       // > 0: a thread with nothing to do sleeps this long between looks
 
     std::atomic<uint64_t> next_chunk[2];              // incoming: next chunk to claim
     std::atomic<uint64_t> done_chunks[2];             // outgoing: chunks that reached pageable memory

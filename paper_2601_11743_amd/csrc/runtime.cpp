@@ -205,6 +205,17 @@ int create_plan(nixie_plan_t *p) {
     p->hs.threads[1] = p->info.fill_threads;
     // +1: the thread that calls nixie_switch also needs a core while it launches the kernel
     p->hs.yield_when_idle = p->info.drain_threads + p->info.fill_threads + 1 > std::max(1u, std::thread::hardware_concurrency());
+    if (!(L.opts.flags & NIXIE_HOST_SPIN)) {
+        // One sixteenth of the time the smaller direction's share of the ring lasts at link rate
+        // (50 GB/s = 50 B/ns), at most 50 us; below 4 us a system call is not worth it.
+        uint64_t share = 0;
+        for (int x = 0; x < 2; x++) {
+            const uint64_t b = (uint64_t)L.dir[x].slots * L.slot_bytes;
+            if (b && (share == 0 || b < share)) share = b;
+        }
+        const uint64_t nap = std::min<uint64_t>(50000, share / 50 / 16);
+        p->hs.idle_sleep_ns = nap < 4000 ? 0 : nap;
+    }
     p->crew.start(&p->hs);
     return NIXIE_OK;
 }

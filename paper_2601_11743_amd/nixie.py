@@ -12,7 +12,7 @@ _LIB_PATH = os.path.join(_HERE, "libnixie.so")
 
 EINVAL, EOVERLAP, ENOMEM, EHIP, ETIMEOUT, EMISMATCH, EBUSY, EUNMAPPED = -1, -2, -3, -4, -5, -6, -7, -8
 ORDER_TABLE, ORDER_LARGE_FIRST, ORDER_ADDRESS, ORDER_REVERSE = 0, 1, 2, 3
-SPLIT_BY_BYTES, SERIALIZE, DIAG_RING_ONLY, DIAG_STALL_DRAIN, HOST_PLAIN_MEMCPY, IN_PLACE, NO_DIRECT = 1, 2, 4, 8, 16, 32, 64
+SPLIT_BY_BYTES, SERIALIZE, DIAG_RING_ONLY, DIAG_STALL_DRAIN, HOST_PLAIN_MEMCPY, IN_PLACE, NO_DIRECT, HOST_SPIN = 1, 2, 4, 8, 16, 32, 64, 128
 
 DECLARED_SYMBOLS = (
     "nixie_layout_create", "nixie_layout_info", "nixie_layout_chunks", "nixie_layout_segments",

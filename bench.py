@@ -244,19 +244,19 @@ def main() -> int:
     if args.ring_sweep:
         sweep = []
         for r in cf["ring_bytes"]:
-            fwd, back = nx.Plan(rows_a, rows_b, r, opts), nx.Plan(rows_b, rows_a, r, opts)
-            fwd.switch(); back.switch()                  # warm-up round trip
+            fwd, rev = nx.Plan(rows_a, rows_b, r, opts), nx.Plan(rows_b, rows_a, r, opts)
+            fwd.switch(); rev.switch()                   # warm-up round trip
             sts = []
             for t in range(10):
-                sts.append((fwd if t % 2 == 0 else back).switch())
-            back.verify(h_in, h_out)                     # 10 switches end with A back in HBM, B in pageable memory
+                sts.append((fwd if t % 2 == 0 else rev).switch())
+            rev.verify(h_in, h_out)                      # 10 switches end with A back in HBM, B in pageable memory
             pi = fwd.info()
             msl = sorted(x["ns_total"] / 1e6 for x in sts)
             sweep.append({"ring_mib": r >> 20, "slot_kib": pi["slot_bytes"] >> 10,
                           "pinned_bytes": pi["pinned_ring_bytes"] + pi["pinned_ctrl_bytes"],
                           "latency_ms": {"min": round(msl[0], 2), "median": round(msl[5], 2), "max": round(msl[-1], 2)},
                           "bidir_GBps": round((pi["bytes_out"] + pi["bytes_in"]) / msl[5] / 1e6, 2)})
-            fwd.close(); back.close()
+            fwd.close(); rev.close()
             log("[bench] ring sweep:", sweep[-1])
 
     diag = bool(args.flags & nx.DIAG_RING_ONLY)

@@ -1,8 +1,8 @@
 // Memory the library is told about rather than given per call: the pinned tier (paper,
 // "Hierarchical Memory"), and pools and spaces -- physical device memory in equal blocks, and
-// reserved address ranges that map those blocks (paper, "Maintaining consistent virtual memory addresses"; "Granularity of
-// Memory Management").  All driver calls here run outside a switch: they take the switch lock
-// exclusively, nixie_switch holds it shared.
+// reserved address ranges that map those blocks (paper, "Maintaining consistent virtual memory
+// addresses"; "Granularity of Memory Management").  All driver calls here run outside a switch:
+// they take the switch lock exclusively, nixie_switch holds it shared.
 #include <hip/hip_runtime.h>
 
 #include <mutex>

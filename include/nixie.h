@@ -271,12 +271,18 @@ int nixie_hash_buffers(const void *const *ptrs, const uint64_t *bytes, uint64_t 
  *      Management": physical memory is handled in fixed-size blocks) -------------------------
  * A pool is physical device memory of the current device, cut into equal blocks.  A space is
  * a reserved range of device addresses as long as the pool, owned by one application, which
- * keeps its pointers for life.  nixie_space_map puts pool block i behind offset
- * i * block_bytes of the space; several spaces may map the same block at once, and then they
- * share its bytes.  The planner knows this: device ranges of two spaces over one pool count
- * as overlapping exactly where they share blocks and offsets, so a switch between two
- * applications that take turns on one pool is an in-place switch (NIXIE_IN_PLACE), ordered
- * by the same per-chunk dependencies as for equal addresses.  The calls around a switch:
+ * keeps its pointers for life.  Every block of a space is ASSIGNED a block of the pool: the
+ * physical block that backs it whenever it is mapped (block i for block i unless
+ * nixie_space_assign says otherwise; a mapped block cannot be reassigned: NIXIE_EBUSY).
+ * nixie_space_map puts the assigned pool blocks behind a range of the space; several spaces
+ * (or several blocks of one) may map the same pool block at once, and then they share its
+ * bytes.  The planner knows this: device ranges count as overlapping exactly where they
+ * share pool blocks and offsets inside them, whatever their addresses, so a switch between
+ * two applications that take turns on the same physical blocks is an in-place switch
+ * (NIXIE_IN_PLACE), ordered by the same per-chunk dependencies as for equal addresses, and
+ * applications assigned different blocks are resident side by side.  A plan remembers the
+ * assignment it was made under; nixie_switch returns NIXIE_EUNMAPPED if a block it needs is
+ * unmapped or has been reassigned since.  The calls around a switch:
  *     nixie_space_map(B)  ->  nixie_switch(plan(A's table, B's table, NIXIE_IN_PLACE))
  *     ->  nixie_space_unmap(A)           (A's pointers stay reserved, and fault if used)
  * None of these calls runs inside the switch.  Mapping and unmapping take the library's
@@ -295,6 +301,8 @@ int nixie_pool_create(uint64_t bytes, uint64_t block_bytes, nixie_pool_t **pool)
 int nixie_pool_info(const nixie_pool_t *pool, uint64_t *bytes, uint64_t *block_bytes);
 int nixie_pool_destroy(nixie_pool_t *pool);
 int nixie_space_create(nixie_pool_t *pool, nixie_space_t **space, void **base /* device address */);
+/* pool_blocks[i] (an index into the pool) backs block offset / block_bytes + i from now on */
+int nixie_space_assign(nixie_space_t *space, uint64_t offset, const uint64_t *pool_blocks, uint64_t n_blocks);
 int nixie_space_map(nixie_space_t *space, uint64_t offset, uint64_t bytes);
 int nixie_space_unmap(nixie_space_t *space, uint64_t offset, uint64_t bytes);
 /* 1 = every block of [offset, offset + bytes) is mapped, 0 = not, negative = error */

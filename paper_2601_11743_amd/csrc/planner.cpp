@@ -20,12 +20,13 @@ namespace nixie {
 namespace {
 
 // Device ranges are compared where they really live: a range inside a registered space is
-// translated into the coordinate of the physical pool behind it, so two spaces that map the
-// same pool are seen to share memory although their addresses differ.
-uint64_t dev_key(uint64_t addr, uint64_t len) {
-    uint64_t key = addr;
-    space_translate(addr, len, &key, nullptr);   // ranges were validated when the table was copied
-    return key;
+// translated into the coordinate of the physical pool behind it (one piece per run of pool
+// blocks), so two spaces that map the same pool are seen to share memory although their
+// addresses differ.  Ranges were validated when the table was copied.
+const std::vector<KeyPiece> &dev_pieces(uint64_t addr, uint64_t len, std::vector<KeyPiece> &scratch) {
+    scratch.clear();
+    space_translate(addr, len, &scratch, nullptr);
+    return scratch;
 }
 
 constexpr uint64_t kDefaultSlot = 2ull << 20;
@@ -70,6 +71,12 @@ uint64_t dep_of_range(const std::vector<OutSpan> &osegs, uint64_t a, uint64_t b)
     auto it = std::upper_bound(osegs.begin(), osegs.end(), a, [](uint64_t v, const OutSpan &s) { return v < s.hi; });
     uint64_t dep = 0;
     for (; it != osegs.end() && it->lo < b; ++it) dep = std::max(dep, it->chunk + 1);
+    return dep;
+}
+
+uint64_t dep_of_pieces(const std::vector<OutSpan> &osegs, const std::vector<KeyPiece> &pieces) {
+    uint64_t dep = 0;
+    for (const KeyPiece &p : pieces) dep = std::max(dep, dep_of_range(osegs, p.key, p.key + p.len));
     return dep;
 }
 
@@ -169,21 +176,20 @@ int build_layout(const nixie_table_t *out_table, const nixie_table_t *in_table, 
     std::vector<uint64_t> direct[2];      // per allocation: its GPU-visible pinned-tier address, or 0
     uint64_t tot[2] = {0, 0}, staged_tot[2] = {0, 0};
     const bool use_tier = !(L.opts.flags & NIXIE_NO_DIRECT);
-    size_t mid = 0;
+    size_t mid = 0, mid_host = 0;
+    std::vector<KeyPiece> pieces;
     dev.reserve(L.table[0].size() + L.table[1].size());
     host.reserve(L.table[0].size() + L.table[1].size());
     for (int x = 0; x < 2; x++) {
-        if (x == 1) mid = dev.size();
+        if (x == 1) { mid = dev.size(); mid_host = host.size(); }
         direct[x].assign(L.table[x].size(), 0);
         for (size_t i = 0; i < L.table[x].size(); i++) {
             const nixie_alloc_t &a = L.table[x][i];
             if (a.bytes == 0) continue;
             uint64_t d = (uint64_t)(uintptr_t)a.dev_ptr, h = (uint64_t)(uintptr_t)a.host_ptr;
-            uint64_t key = d;
-            SpaceUse use;
-            if (!space_translate(d, a.bytes, &key, &use)) return NIXIE_EINVAL;   // straddles the edge of a space
-            if (use.count) L.uses[x].push_back(use);
-            dev.push_back({key, key + a.bytes});
+            pieces.clear();
+            if (!space_translate(d, a.bytes, &pieces, &L.uses[x])) return NIXIE_EINVAL;   // straddles the edge of a space
+            for (const KeyPiece &p : pieces) dev.push_back({p.key, p.key + p.len});
             host.push_back({h, h + a.bytes});
             tot[x] += a.bytes;
             uint64_t seen_by_gpu = 0;
@@ -198,7 +204,11 @@ int build_layout(const nixie_table_t *out_table, const nixie_table_t *in_table, 
     } else if (any_overlap(dev, mid)) {
         return NIXIE_EOVERLAP;
     }
-    if (any_overlap(host, mid)) return NIXIE_EOVERLAP;
+    if (any_overlap(host, mid_host)) return NIXIE_EOVERLAP;
+    for (int x = 0; x < 2; x++) {   // one entry per block of a space that the table touches
+        std::sort(L.uses[x].begin(), L.uses[x].end());
+        L.uses[x].erase(std::unique(L.uses[x].begin(), L.uses[x].end()), L.uses[x].end());
+    }
 
     // only what goes through the ring counts for the ring's geometry
     const int active = (staged_tot[0] > 0) + (staged_tot[1] > 0);
@@ -241,26 +251,23 @@ int build_layout(const nixie_table_t *out_table, const nixie_table_t *in_table, 
         osegs.reserve(L.dir[0].segs.size());
         for (uint64_t k = 0; k < L.dir[0].chunks.size(); k++) {
             const nixie_chunk_t &c = L.dir[0].chunks[k];
-            for (uint64_t q = c.seg_begin; q < c.seg_begin + c.seg_count; q++) {
-                const uint64_t key = dev_key(L.dir[0].segs[q].dev_addr, L.dir[0].segs[q].len);
-                osegs.push_back({key, key + L.dir[0].segs[q].len, k});
-            }
+            for (uint64_t q = c.seg_begin; q < c.seg_begin + c.seg_count; q++)
+                for (const KeyPiece &p : dev_pieces(L.dir[0].segs[q].dev_addr, L.dir[0].segs[q].len, pieces))
+                    osegs.push_back({p.key, p.key + p.len, k});
         }
         std::sort(osegs.begin(), osegs.end(), [](const OutSpan &a, const OutSpan &b) { return a.lo < b.lo; });
         // Walk the incoming table in the order in which its GPU memory becomes free, so that the
         // scatter side follows right behind the gather side instead of waiting for its end.
         std::vector<uint64_t> adep(L.table[1].size());
         for (size_t i = 0; i < adep.size(); i++) {
-            const uint64_t d = dev_key((uint64_t)(uintptr_t)L.table[1][i].dev_ptr, L.table[1][i].bytes);
-            adep[i] = dep_of_range(osegs, d, d + L.table[1][i].bytes);
+            adep[i] = dep_of_pieces(osegs, dev_pieces((uint64_t)(uintptr_t)L.table[1][i].dev_ptr, L.table[1][i].bytes, pieces));
         }
         std::stable_sort(walk1.begin(), walk1.end(), [&](uint64_t a, uint64_t b) { return adep[a] < adep[b]; });
         cut(L.table[1], walk1, direct[1], S, L.dir[1]);
         for (nixie_chunk_t &c : L.dir[1].chunks)
             for (uint64_t q = c.seg_begin; q < c.seg_begin + c.seg_count; q++) {
                 const nixie_segment_t &sg = L.dir[1].segs[q];
-                const uint64_t key = dev_key(sg.dev_addr, sg.len);
-                c.dep_out = std::max(c.dep_out, dep_of_range(osegs, key, key + sg.len));
+                c.dep_out = std::max(c.dep_out, dep_of_pieces(osegs, dev_pieces(sg.dev_addr, sg.len, pieces)));
             }
     } else if (L.table[0].size() + L.table[1].size() > 20000) {   // large tables: one direction per thread
         std::thread other([&] { cut(L.table[1], walk1, direct[1], S, L.dir[1]); });

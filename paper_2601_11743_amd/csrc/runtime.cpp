@@ -423,7 +423,7 @@ int nixie_switch(nixie_plan_t *p, void *hip_stream, nixie_stats_t *stats) {
     if (!lk.owns_lock()) return NIXIE_EBUSY;
     // no block of a registered space is mapped or unmapped while the kernel runs
     std::shared_lock<std::shared_mutex> maps(switch_lock());
-    if (!space_uses_mapped(p->L.uses[0]) || !space_uses_mapped(p->L.uses[1])) return NIXIE_EUNMAPPED;
+    if (!space_uses_valid(p->L.uses[0]) || !space_uses_valid(p->L.uses[1])) return NIXIE_EUNMAPPED;
     const uint64_t t_entry = now_ns();
     int dev = -1;
     NIXIE_HIP(hipGetDevice(&dev));
@@ -450,7 +450,7 @@ int nixie_switch_begin(nixie_plan_t *p, void *hip_stream) {
     std::unique_lock<std::mutex> lk(p->switch_mu, std::try_to_lock);
     if (!lk.owns_lock()) return NIXIE_EBUSY;
     std::shared_lock<std::shared_mutex> maps(switch_lock());
-    if (!space_uses_mapped(p->L.uses[0]) || !space_uses_mapped(p->L.uses[1])) return NIXIE_EUNMAPPED;
+    if (!space_uses_valid(p->L.uses[0]) || !space_uses_valid(p->L.uses[1])) return NIXIE_EUNMAPPED;
     const uint64_t t_entry = now_ns();
     int dev = -1;
     NIXIE_HIP(hipGetDevice(&dev));

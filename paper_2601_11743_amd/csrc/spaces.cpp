@@ -78,34 +78,52 @@ void space_set_mapped(uint64_t base, uint64_t first, uint64_t count, bool on) {
     for (uint64_t b = first; b < first + count && b < s->mapped.size(); b++) s->mapped[b] = on ? 1 : 0;
 }
 
-bool space_translate(uint64_t addr, uint64_t bytes, uint64_t *key, SpaceUse *use) {
+bool space_assign(uint64_t base, uint64_t first, const uint64_t *pool_blocks, uint64_t count) {
     std::lock_guard<std::mutex> g(g_mu);
-    if (use) *use = SpaceUse{0, 0, 0};
-    *key = addr;
+    SpaceSpan *s = find_locked(base);
+    if (!s || s->base != base || first > s->assigned.size() || count > s->assigned.size() - first) return false;
+    for (uint64_t i = 0; i < count; i++)
+        if (pool_blocks[i] >= s->assigned.size() || (s->mapped[first + i] && s->assigned[first + i] != pool_blocks[i])) return false;
+    for (uint64_t i = 0; i < count; i++) s->assigned[first + i] = pool_blocks[i];
+    return true;
+}
+
+bool space_translate(uint64_t addr, uint64_t bytes, std::vector<KeyPiece> *pieces, std::vector<SpaceUse> *uses) {
+    std::lock_guard<std::mutex> g(g_mu);
     if (bytes == 0) return true;
     SpaceSpan *s = find_locked(addr);
     if (!s) {
         // outside every space: must not reach into one that starts behind addr
         auto it = std::upper_bound(g_spaces.begin(), g_spaces.end(), addr, [](uint64_t v, const SpaceSpan &x) { return v < x.base; });
-        return it == g_spaces.end() || addr + bytes <= it->base;
+        if (it != g_spaces.end() && addr + bytes > it->base) return false;
+        if (pieces) pieces->push_back(KeyPiece{addr, bytes});
+        return true;
     }
     if (addr + bytes > s->base + s->bytes) return false;
-    *key = s->key_base + (addr - s->base);
-    if (use) {
-        use->base = s->base;
-        use->first = (addr - s->base) / s->block_bytes;
-        use->count = (addr + bytes - 1 - s->base) / s->block_bytes - use->first + 1;
+    const uint64_t B = s->block_bytes;
+    uint64_t off = addr - s->base, left = bytes;
+    bool first_piece = true;
+    while (left) {
+        const uint64_t blk = off / B, in = off % B, take = std::min(left, B - in);
+        const uint64_t key = s->key_base + s->assigned[blk] * B + in;
+        if (pieces) {
+            if (!first_piece && pieces->back().key + pieces->back().len == key) pieces->back().len += take;
+            else pieces->push_back(KeyPiece{key, take});
+        }
+        if (uses) uses->push_back(SpaceUse{s->base, blk, s->assigned[blk]});
+        first_piece = false;
+        off += take;
+        left -= take;
     }
     return true;
 }
 
-bool space_uses_mapped(const std::vector<SpaceUse> &uses) {
+bool space_uses_valid(const std::vector<SpaceUse> &uses) {
     std::lock_guard<std::mutex> g(g_mu);
     for (const SpaceUse &u : uses) {
         SpaceSpan *s = find_locked(u.base);
-        if (!s || s->base != u.base) return false;
-        for (uint64_t b = u.first; b < u.first + u.count; b++)
-            if (b >= s->mapped.size() || !s->mapped[b]) return false;
+        if (!s || s->base != u.base || u.index >= s->mapped.size()) return false;
+        if (!s->mapped[u.index] || s->assigned[u.index] != u.pool_block) return false;
     }
     return true;
 }

@@ -2,9 +2,11 @@
 // HIP-free, so the planner can be built and tested without a GPU.
 //
 // Paper, "Maintaining consistent virtual memory addresses": an application keeps its device
-// addresses while the physical memory behind them changes hands.  Two spaces of one pool map
-// block i of the pool at the same offset, so "do these two device ranges share memory?" is
-// answered by translating both into the pool's own coordinate (a key) and comparing there.
+// addresses while the physical memory behind them changes hands.  Every block of a space is
+// ASSIGNED one block of the pool (which physical block backs it whenever it is mapped; block i
+// by default) and is MAPPED or not.  "Do these two device ranges share memory?" is answered by
+// translating both into the pool's own coordinate (a key: pool, pool block, offset in the
+// block) and comparing there; a range that spans several blocks becomes several pieces.
 #pragma once
 #include <cstdint>
 #include <shared_mutex>
@@ -18,25 +20,36 @@ constexpr uint64_t kKeyStride = 1ull << 44;
 
 struct SpaceSpan {
     uint64_t base = 0, bytes = 0;     // the reserved device address range
-    uint64_t key_base = 0;            // pool coordinate of its first byte
+    uint64_t key_base = 0;            // pool coordinate of the pool's first byte
     uint64_t block_bytes = 0;
-    std::vector<uint8_t> mapped;      // per block: 1 while physical memory is mapped there
+    std::vector<uint64_t> assigned;   // per block: the pool block that backs it
+    std::vector<uint8_t> mapped;      // per block: 1 while that pool block is mapped there
 };
 
-// One use of a space by a plan: blocks [first, first + count) must be mapped during a switch.
-struct SpaceUse { uint64_t base, first, count; };
+// One block of a space as a plan saw it: a switch needs it mapped, and backed by the same pool
+// block as when the dependencies were computed.
+struct SpaceUse {
+    uint64_t base, index, pool_block;
+    bool operator<(const SpaceUse &o) const { return base != o.base ? base < o.base : index < o.index; }
+    bool operator==(const SpaceUse &o) const { return base == o.base && index == o.index && pool_block == o.pool_block; }
+};
+
+// A run of bytes in pool coordinates (or plain addresses, outside every space).
+struct KeyPiece { uint64_t key, len; };
 
 uint64_t next_pool_key();                                      // a fresh key_base
 void space_register(const SpaceSpan &s);
 void space_unregister(uint64_t base);
 void space_set_mapped(uint64_t base, uint64_t first, uint64_t count, bool on);
+// false if the space is unknown, a block is out of range, or a block to be reassigned is mapped
+bool space_assign(uint64_t base, uint64_t first, const uint64_t *pool_blocks, uint64_t count);
 
-// Pool coordinate of [addr, addr + bytes): `key` = addr itself when the range touches no space.
-// Returns false when the range straddles the edge of a space.  `use`, when given, receives the
-// blocks the range occupies (count 0 outside spaces).
-bool space_translate(uint64_t addr, uint64_t bytes, uint64_t *key, SpaceUse *use);
-// True when every block of every use is mapped right now.
-bool space_uses_mapped(const std::vector<SpaceUse> &uses);
+// Pool coordinates of [addr, addr + bytes), appended to pieces (pieces with adjacent keys are
+// merged; one piece {addr, bytes} when the range touches no space).  Returns false when the
+// range straddles the edge of a space.  uses, when given, receives the blocks the range occupies.
+bool space_translate(uint64_t addr, uint64_t bytes, std::vector<KeyPiece> *pieces, std::vector<SpaceUse> *uses);
+// True when every block is mapped right now and backed by the pool block recorded in its use.
+bool space_uses_valid(const std::vector<SpaceUse> &uses);
 
 
 // ---- pinned tier ------------------------------------------------------------------------------

@@ -78,7 +78,7 @@ int nixie_hash_tables(const nixie_plan_t *plan, void *hip_stream, uint64_t *out_
     const Layout &L = plan_layout(plan);
     if ((!L.table[0].empty() && !out_hash) || (!L.table[1].empty() && !in_hash)) return NIXIE_EINVAL;
     std::shared_lock<std::shared_mutex> maps(switch_lock());
-    if (!space_uses_mapped(L.uses[0])) return NIXIE_EUNMAPPED;
+    if (!space_uses_valid(L.uses[0])) return NIXIE_EUNMAPPED;
     int rc = hash_device(plan_hash_descs(plan, 0), L.table[0].size(), plan_hash_tiles(plan, 0),
                          plan_hash_buffer(plan), (hipStream_t)hip_stream, out_hash);
     if (rc) return rc;
@@ -104,7 +104,7 @@ int nixie_verify(const nixie_plan_t *plan, void *hip_stream, const uint64_t *exp
     }
     if (expect_in_hash && !L.table[1].empty()) {    // the restored set now lives in HBM
         std::shared_lock<std::shared_mutex> maps(switch_lock());
-        if (!space_uses_mapped(L.uses[1])) return NIXIE_EUNMAPPED;
+        if (!space_uses_valid(L.uses[1])) return NIXIE_EUNMAPPED;
         std::vector<uint64_t> h(L.table[1].size());
         rc = hash_device(plan_hash_descs(plan, 1), h.size(), plan_hash_tiles(plan, 1), plan_hash_buffer(plan),
                          (hipStream_t)hip_stream, h.data());
@@ -128,15 +128,12 @@ int nixie_hash_buffers(const void *const *ptrs, const uint64_t *bytes, uint64_t 
     uint64_t tiles = 0;
     for (uint64_t i = 0; i < n; i++) {
         if (bytes[i] && !ptrs[i]) return NIXIE_EINVAL;
-        uint64_t key;
-        SpaceUse use;
-        if (!space_translate((uint64_t)(uintptr_t)ptrs[i], bytes[i], &key, &use)) return NIXIE_EINVAL;
-        if (use.count) uses.push_back(use);
+        if (!space_translate((uint64_t)(uintptr_t)ptrs[i], bytes[i], nullptr, &uses)) return NIXIE_EINVAL;
         hd[i] = HashDesc{(uint64_t)(uintptr_t)ptrs[i], bytes[i], tiles};
         tiles += ((bytes[i] + 7) / 8 + kHashTileWords - 1) / kHashTileWords;
     }
     std::shared_lock<std::shared_mutex> maps(switch_lock());
-    if (!space_uses_mapped(uses)) return NIXIE_EUNMAPPED;
+    if (!space_uses_valid(uses)) return NIXIE_EUNMAPPED;
     HashDesc *hd_d = nullptr;
     uint64_t *h_d = nullptr;
     NIXIE_HIP(hipMalloc((void **)&hd_d, n * sizeof(HashDesc)));

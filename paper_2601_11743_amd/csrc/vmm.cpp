@@ -30,6 +30,7 @@ struct nixie_pool {
 struct nixie_space {
     nixie_pool *pool = nullptr;
     void *base = nullptr;
+    std::vector<uint64_t> assigned;   // pool block behind each block of the space (block i by default)
     std::vector<uint8_t> mapped;
 };
 
@@ -186,12 +187,15 @@ int nixie_space_create(nixie_pool_t *pool, nixie_space_t **space, void **base) {
     }
     s->pool = pool;
     s->mapped.assign(pool->blocks.size(), 0);
+    s->assigned.resize(pool->blocks.size());
+    for (size_t i = 0; i < s->assigned.size(); i++) s->assigned[i] = i;
     SpaceSpan span;
     span.base = (uint64_t)(uintptr_t)s->base;
     span.bytes = pool->bytes;
     span.key_base = pool->key_base;
     span.block_bytes = pool->block_bytes;
     span.mapped.assign(pool->blocks.size(), 0);
+    span.assigned = s->assigned;
     space_register(span);
     {
         std::lock_guard<std::mutex> g(pool->mu);
@@ -223,7 +227,7 @@ int nixie_space_map(nixie_space_t *s, uint64_t offset, uint64_t bytes) {
         if (s->mapped[b]) { b++; continue; }
         uint64_t run = b;
         while (run < first + count && !s->mapped[run]) {
-            e = hipMemMap((char *)s->base + run * B, B, 0, s->pool->blocks[run], 0);
+            e = hipMemMap((char *)s->base + run * B, B, 0, s->pool->blocks[s->assigned[run]], 0);
             if (e != hipSuccess) break;
             run++;
         }
@@ -238,6 +242,23 @@ int nixie_space_map(nixie_space_t *s, uint64_t offset, uint64_t bytes) {
         if (e != hipSuccess) return fail(e);
         b = run;
     }
+    return NIXIE_OK;
+}
+
+int nixie_space_assign(nixie_space_t *s, uint64_t offset, const uint64_t *pool_blocks, uint64_t n_blocks) {
+    if (!s || (n_blocks && !pool_blocks)) return NIXIE_EINVAL;
+    uint64_t first = 0, count = 0;
+    const uint64_t B = s->pool->block_bytes;
+    if (n_blocks > s->assigned.size()) return NIXIE_EINVAL;
+    int rc = block_range(s, offset, n_blocks * B, &first, &count);
+    if (rc) return rc;
+    std::unique_lock<std::shared_mutex> lk(switch_lock());
+    for (uint64_t i = 0; i < count; i++) {
+        if (pool_blocks[i] >= s->assigned.size()) return NIXIE_EINVAL;
+        if (s->mapped[first + i] && s->assigned[first + i] != pool_blocks[i]) return NIXIE_EBUSY;   // unmap it first
+    }
+    if (!space_assign((uint64_t)(uintptr_t)s->base, first, pool_blocks, count)) return NIXIE_EINVAL;
+    for (uint64_t i = 0; i < count; i++) s->assigned[first + i] = pool_blocks[i];
     return NIXIE_OK;
 }
 

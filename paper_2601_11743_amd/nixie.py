@@ -21,7 +21,7 @@ DECLARED_SYMBOLS = (
     "nixie_strerror", "nixie_last_hip_error",
     "nixie_sched_create", "nixie_sched_destroy", "nixie_sched_add_app", "nixie_sched_api_enter",
     "nixie_sched_api_return", "nixie_sched_request", "nixie_sched_tick", "nixie_sched_app_info",
-    "nixie_pool_create", "nixie_pool_info", "nixie_pool_destroy", "nixie_space_create", "nixie_space_map",
+    "nixie_pool_create", "nixie_pool_info", "nixie_pool_destroy", "nixie_space_create", "nixie_space_assign", "nixie_space_map",
     "nixie_space_unmap", "nixie_space_mapped", "nixie_space_destroy",
     "nixie_tier_register", "nixie_tier_unregister", "nixie_host_copy", "nixie_place",
     "nixie_switch_begin", "nixie_switch_wait_in", "nixie_switch_end",
@@ -172,6 +172,7 @@ def lib() -> C.CDLL:
     L.nixie_pool_info.argtypes = [vp, C.POINTER(u64), C.POINTER(u64)]
     L.nixie_pool_destroy.argtypes = [vp]
     L.nixie_space_create.argtypes = [vp, C.POINTER(vp), C.POINTER(vp)]
+    L.nixie_space_assign.argtypes = [vp, u64, vp, u64]
     L.nixie_space_map.argtypes = [vp, u64, u64]
     L.nixie_space_unmap.argtypes = [vp, u64, u64]
     L.nixie_space_mapped.argtypes = [vp, u64, u64]
@@ -446,6 +447,13 @@ class Space:
             self._h = None
             raise NixieError(rc, "nixie_space_create")
         self.base = int(base.value)
+
+    def assign(self, offset: int, pool_blocks: Sequence[int]) -> None:
+        """Pool block pool_blocks[i] backs block offset / block_bytes + i of this space from now on."""
+        pb = np.asarray(list(pool_blocks), dtype=np.uint64)
+        rc = lib().nixie_space_assign(self._h, offset, pb.ctypes.data, pb.size)
+        if rc:
+            raise NixieError(rc, "nixie_space_assign")
 
     def map(self, offset: int = 0, nbytes: int | None = None) -> None:
         rc = lib().nixie_space_map(self._h, offset, self.pool.bytes - offset if nbytes is None else nbytes)

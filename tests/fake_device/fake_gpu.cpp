@@ -213,15 +213,33 @@ int run(const std::string &scenario, uint64_t seed) {
         if (fd < 0 || ftruncate(fd, (off_t)span_bytes) != 0) { std::printf("memfd failed\n"); return 2; }
         base_a = (uint8_t *)mmap(nullptr, span_bytes, PROT_READ | PROT_WRITE, MAP_SHARED, fd, 0);
         base_b = (uint8_t *)mmap(nullptr, span_bytes, PROT_READ | PROT_WRITE, MAP_SHARED, fd, 0);
-        close(fd);
         if (base_a == MAP_FAILED || base_b == MAP_FAILED || base_a == base_b) { std::printf("mmap failed\n"); return 2; }
         std::memset(base_a, 0xC3, span_bytes);
+        // B sees the pool's blocks in another order (odd seeds): block i of B's range is pool block perm[i]
+        const uint64_t nblk = span_bytes / blk;
+        std::vector<uint64_t> perm(nblk);
+        for (uint64_t i = 0; i < nblk; i++) perm[i] = seed % 2 ? (i * 5 + 3) % nblk : i;
+        if (seed % 2 && nblk % 5 == 0) for (uint64_t i = 0; i < nblk; i++) perm[i] = nblk - 1 - i;   // keep it a permutation
+        for (uint64_t i = 0; i < nblk; i++)
+            if (mmap(base_b + i * blk, blk, PROT_READ | PROT_WRITE, MAP_SHARED | MAP_FIXED, fd, (off_t)(perm[i] * blk)) == MAP_FAILED) {
+                std::printf("mmap of block %llu failed\n", (unsigned long long)i);
+                return 2;
+            }
+        close(fd);
         const uint64_t key = next_pool_key();
         for (uint8_t *b : {base_a, base_b}) {
             SpaceSpan sp;
             sp.base = (uint64_t)(uintptr_t)b; sp.bytes = span_bytes; sp.key_base = key; sp.block_bytes = blk;
-            sp.mapped.assign(span_bytes / blk, 1);
+            sp.mapped.assign(nblk, 1);
+            sp.assigned.resize(nblk);
+            for (uint64_t i = 0; i < nblk; i++) sp.assigned[i] = b == base_b ? perm[i] : i;
             space_register(sp);
+        }
+        // a mapped block keeps its pool block; naming the one it has is fine
+        const uint64_t other = (perm[0] + 1) % nblk;
+        if (space_assign((uint64_t)(uintptr_t)base_b, 0, &other, 1) || !space_assign((uint64_t)(uintptr_t)base_b, 0, &perm[0], 1)) {
+            std::printf("space_assign on a mapped block\n");
+            return 1;
         }
     }
     Arena A, B;
@@ -261,11 +279,23 @@ int run(const std::string &scenario, uint64_t seed) {
         e = build_layout(nullptr, &tover, ring_bytes, &o, L);
         if (e != NIXIE_EINVAL) { std::printf("expected NIXIE_EINVAL for a range across the edge of a space, got %d\n", e); return 1; }
         if (L.uses[0].size() != 0) { std::printf("stale uses\n"); return 1; }
+        // the planner sees the pool through the assignment: a piece of B's range that shares a pool
+        // block and offset with A's first allocation overlaps it, one in another block does not
+        std::vector<KeyPiece> pa, pb;
+        space_translate((uint64_t)(uintptr_t)A.rows[0].dev_ptr, 16, &pa, nullptr);
+        const uint64_t blk_sz = 64 << 10, off_a = (uint64_t)((uint8_t *)A.rows[0].dev_ptr - base_a);
+        uint64_t where = 0;
+        for (uint64_t i = 0; i < span_bytes / blk_sz; i++) {
+            std::vector<KeyPiece> t;
+            space_translate((uint64_t)(uintptr_t)(base_b + i * blk_sz + off_a % blk_sz), 16, &t, nullptr);
+            if (t.size() == 1 && t[0].key == pa[0].key) where++;
+        }
+        if (pa.size() != 1 || where != 1) { std::printf("translation: %zu pieces, %llu aliases\n", pa.size(), (unsigned long long)where); return 1; }
     }
     int rc = build_layout(&ta, &tb, ring_bytes, &o, L);
     if (rc) { std::printf("build_layout failed %d\n", rc); return 2; }
     if (spaces) {
-        if (L.uses[0].size() != A.rows.size() - 1 || L.uses[1].size() != B.rows.size() || !space_uses_mapped(L.uses[1])) {
+        if (L.uses[0].empty() || L.uses[1].empty() || !space_uses_valid(L.uses[0]) || !space_uses_valid(L.uses[1])) {
             std::printf("uses: %zu out, %zu in\n", L.uses[0].size(), L.uses[1].size());
             return 1;
         }
@@ -273,8 +303,16 @@ int run(const std::string &scenario, uint64_t seed) {
         for (const auto &c : L.dir[1].chunks) deps += c.dep_out != 0;
         if (deps == 0) { std::printf("no dependencies found through the pool coordinate\n"); return 1; }
         space_set_mapped((uint64_t)(uintptr_t)base_a, 0, 1, false);
-        if (space_uses_mapped(L.uses[0])) { std::printf("unmapped block not noticed\n"); return 1; }
+        if (space_uses_valid(L.uses[0])) { std::printf("unmapped block not noticed\n"); return 1; }
+        // ... and a block that comes back with other memory behind it is not the block the plan saw
+        const uint64_t one = 1, zero = 0;
+        if (!space_assign((uint64_t)(uintptr_t)base_a, 0, &one, 1)) { std::printf("reassignment of an unmapped block refused\n"); return 1; }
         space_set_mapped((uint64_t)(uintptr_t)base_a, 0, 1, true);
+        if (space_uses_valid(L.uses[0])) { std::printf("reassigned block not noticed\n"); return 1; }
+        space_set_mapped((uint64_t)(uintptr_t)base_a, 0, 1, false);
+        space_assign((uint64_t)(uintptr_t)base_a, 0, &zero, 1);
+        space_set_mapped((uint64_t)(uintptr_t)base_a, 0, 1, true);
+        if (!space_uses_valid(L.uses[0])) { std::printf("restored block not accepted\n"); return 1; }
     }
     nixie_plan_info_t info;
     fill_info(L, &info);

@@ -170,3 +170,78 @@ def test_disjoint_blocks_need_no_in_place_flag(nx, oracle, raw):
     sp_a.close()
     sp_b.close()
     pool.close()
+
+
+def physical_pairs(phys, offsets, sizes, host, host_offsets, perm):
+    """(device piece, host piece) pairs of allocations seen through a space whose block i is pool block
+    perm[i]: an allocation that crosses a block boundary is several pieces of the physical arena."""
+    pairs = []
+    for o, b, oh in zip(offsets, sizes, host_offsets):
+        done = 0
+        while done < b:
+            va = o + done
+            take = min(b - done, BLOCK - va % BLOCK)
+            p = perm[va // BLOCK] * BLOCK + va % BLOCK
+            pairs.append((phys[p:p + take], host[oh + done:oh + done + take]))
+            done += take
+    return pairs
+
+
+@pytest.mark.parametrize("perm", [[5, 2, 7, 0, 1, 3, 4, 6], [1, 0, 3, 2, 5, 4, 7, 6], [0, 1, 2, 3, 4, 5, 6, 7]])
+def test_switch_with_any_pool_block_behind_any_address(nx, oracle, raw, perm):
+    """A sees the pool in order, B sees its blocks permuted: B's allocations are scattered over the
+    physical memory and cross block boundaries.  Oracle: one physical arena, B's allocations as the
+    pieces they are there; the definition (all of A out, then B in) gives the expected arena."""
+    from tests.helpers import HostSet
+    from tests.gpu_helpers import first_diff
+    sizes_a = [20 * S + 5, 999, 13 * S, 40 * S + 3, 30 * S]          # 6.4 MiB: pool blocks 0..3 through A
+    sizes_b = [17 * S, 4, 45 * S + 1, 38 * S, 700]                   # crosses block boundaries of B's space
+    n_blocks = len(perm)
+    A_ref, B_ref = HostSet(sizes_a, 71, "dev"), HostSet(sizes_b, 72, "host")
+    A_gpu, B_gpu = HostSet(sizes_a, 71, "dev"), HostSet(sizes_b, 72, "host")
+    assert max(A_ref.ldev.total, B_ref.ldev.total) <= 4 * BLOCK
+    ident = list(range(n_blocks))
+    phys = np.full(n_blocks * BLOCK, 0xC3, dtype=np.uint8)
+    phys[:A_ref.dev.size] = A_ref.dev                                # A is resident, seen in order
+    out_pairs = physical_pairs(phys, A_ref.ldev.offsets, sizes_a, A_ref.host, A_ref.lhost.offsets, ident)
+    in_pairs = physical_pairs(phys, B_ref.ldev.offsets, sizes_b, B_ref.host, B_ref.lhost.offsets, perm)
+    oracle.switch_direct(out_pairs, in_pairs)
+
+    pool = nx.Pool(n_blocks * BLOCK, BLOCK)
+    sp_a, sp_b, sp_all = nx.Space(pool), nx.Space(pool), nx.Space(pool)
+    sp_b.assign(0, perm)
+    sp_a.map(0, 4 * BLOCK)
+    sp_all.map()                                                     # an observer that sees the pool in order
+    raw.upload(sp_all.base, np.full(n_blocks * BLOCK, 0xC3, dtype=np.uint8))
+    raw.upload(sp_a.base, A_gpu.dev)
+    rows_a = rows(sp_a.base, A_gpu.ldev, A_gpu.host, A_gpu.lhost, sizes_a)
+    rows_b = rows(sp_b.base, B_gpu.ldev, B_gpu.host, B_gpu.lhost, sizes_b)
+    opts = nx.Opts(slot_bytes=S, flags=nx.IN_PLACE)
+    plan = nx.Plan(rows_a, rows_b, 8 * S, opts)
+    assert plan.switch(check=False)["rc"] == nx.EUNMAPPED
+    sp_b.map(0, 4 * BLOCK)
+    with pytest.raises(nx.NixieError) as e:
+        sp_b.assign(0, [perm[1]])                                    # a mapped block keeps what is behind it
+    assert e.value.code == nx.EBUSY
+    shares = len(set(perm[:4]) & {0, 1, 2, 3})
+    if shares:
+        with pytest.raises(nx.NixieError) as e:
+            nx.Plan(rows_a, rows_b, 8 * S, nx.Opts(slot_bytes=S))
+        assert e.value.code == nx.EOVERLAP
+    plan.switch()
+    got = raw.download(sp_all.base, n_blocks * BLOCK)
+    assert np.array_equal(got, phys), "physical memory: " + first_diff(got, phys)
+    assert np.array_equal(A_gpu.host, A_ref.host), "evicted A: " + first_diff(A_gpu.host, A_ref.host)
+    seen_by_b = raw.download(sp_b.base, B_gpu.ldev.total)            # and B finds its bytes at its own addresses
+    for i, (o, b) in enumerate(zip(B_gpu.ldev.offsets, sizes_b)):
+        assert np.array_equal(seen_by_b[o:o + b], W.content_bytes(72, i, b)), f"B's allocation {i}"
+    # the plan saw one assignment; with another pool block behind a block it needs, it refuses to run
+    sp_b.unmap(0, BLOCK)
+    spare = next(k for k in range(n_blocks) if k not in perm[:4])
+    sp_b.assign(0, [spare])
+    sp_b.map(0, BLOCK)
+    assert plan.switch(check=False)["rc"] == nx.EUNMAPPED
+    plan.close()
+    for sp in (sp_a, sp_b, sp_all):
+        sp.close()
+    pool.close()

@@ -285,3 +285,32 @@ def test_host_copy_equals_plain_copy(nx, threads):
     with pytest.raises(nx.NixieError) as e:
         nx.host_copy([0], [src[3].ctypes.data], [16])
     assert e.value.code == nx.EINVAL
+
+
+def test_header_is_plain_c_and_binding_structs_match(tmp_path):
+    """include/nixie.h compiles as C99 and as C++, and every struct of the ctypes binding has the
+    size the C compiler gives it (a drifted field would shift every one behind it)."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    from paper_2601_11743_amd import nixie as binding
+    import ctypes
+    pairs = {"nixie_alloc_t": binding._Alloc, "nixie_table_t": binding._Table, "nixie_opts_t": binding._Opts,
+             "nixie_plan_info_t": binding._Info, "nixie_segment_t": binding._Segment, "nixie_chunk_t": binding._Chunk,
+             "nixie_stats_t": binding._Stats, "nixie_verify_report_t": binding._Report,
+             "nixie_link_peak_t": binding._LinkPeak, "nixie_sched_params_t": binding._SchedParams,
+             "nixie_sched_decision_t": binding._SchedDecision, "nixie_sched_app_t": binding._SchedApp,
+             "nixie_chunk_state_t": binding._ChunkState, "nixie_capacity_t": binding._Capacity,
+             "nixie_placement_t": binding._Placement}
+    src = tmp_path / "sizes.c"
+    body = "".join(f'    printf("{name} %zu\\n", sizeof({name}));\n' for name in pairs)
+    src.write_text('#include <stdio.h>\n#include "nixie.h"\nint main(void) {\n' + body + "    return 0;\n}\n")
+    exe = tmp_path / "sizes"
+    inc = "-I" + os.path.join(ROOT, "include")
+    subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", inc, str(src), "-o", str(exe)])
+    subprocess.check_call(["g++", "-std=c++17", "-fsyntax-only", "-x", "c++", inc, str(src)])
+    out = subprocess.run([str(exe)], capture_output=True, text=True, check=True).stdout
+    sizes = dict(line.split() for line in out.splitlines())
+    for name, ct in pairs.items():
+        assert int(sizes[name]) == ctypes.sizeof(ct), f"{name}: C says {sizes[name]}, the binding {ctypes.sizeof(ct)}"

@@ -119,6 +119,10 @@ def main() -> int:
     ap.add_argument("--pinned-tier", choices=["none", "out", "in", "both"], default="none",
                     help="keep the host side of the outgoing / incoming / both working sets in registered pinned "
                          "memory: those allocations move directly, without ring slots or host threads")
+    ap.add_argument("--oversub-sweep", action="store_true",
+                    help="switch latency against the amount of memory oversubscription: a notional GPU capacity "
+                         "of (A + B - oversubscribed size); nixie_place evicts only what the incoming application "
+                         "needs; ping-pong A<->B; adds an 'oversubscription_sweep' list to the JSON line")
     ap.add_argument("--ring-sweep", action="store_true",
                     help="config 5 protocol: for every ring size of the config, 10 back-to-back ping-pong "
                          "switches A<->B; adds a 'ring_sweep' list to the JSON line")
@@ -240,6 +244,51 @@ def main() -> int:
         sp.close()
         serialized = {"ms": round(sms[0], 3), "slowdown_vs_bidirectional": round(sms[0] / (elapsed / args.steps * 1e3), 3)}
 
+    oversub = None
+    if args.oversub_sweep and pool is None and not args.in_place:
+        # The timed steps left A in pageable memory and B in HBM.  From here on a chunk is an allocation
+        # and lives where the placement says; both sets have HBM of their own on this machine, the
+        # capacity is the planner's input.
+        oversub = []
+        shared_ring = nx.Ring(ring)                       # every switch is planned anew; the pinned ring stays
+        sets, rws = (A, B), (rows_a, rows_b)
+        chunks0 = [(int(b), a, nx.TIER_GPU if a == 1 else nx.TIER_PAGEABLE) for a in (0, 1) for b in sets[a].sizes]
+        owner_of = [(a, i) for a in (0, 1) for i in range(len(sets[a].sizes))]
+        total = [sets[0].total_bytes, sets[1].total_bytes]
+        for frac in (0.125, 0.25, 0.5, 0.75, 1.0):
+            capacity = int(total[0] + total[1] - frac * min(total))
+            tiers = [t for _, _, t in chunks0]
+            lat, moved = [], []
+            for turn in range(6):                           # A in, B in, A in, ...
+                run = turn % 2
+                cur = [(b, a, t) for (b, a, _), t in zip(chunks0, tiers)]
+                new, summ, _ = nx.place(capacity, 0, cur, run, [1 - run])
+                out_rows = np.array([rws[a][i] for (a, i), t0, t1 in zip(owner_of, tiers, new) if t0 == nx.TIER_GPU and t1 != nx.TIER_GPU], dtype=np.uint64).reshape(-1, 3)
+                in_rows = np.array([rws[a][i] for (a, i), t0, t1 in zip(owner_of, tiers, new) if t0 != nx.TIER_GPU and t1 == nx.TIER_GPU], dtype=np.uint64).reshape(-1, 3)
+                pl = nx.Plan(out_rows, in_rows, shared_ring, opts)
+                st = pl.switch()
+                pl.close()
+                tiers = new
+                if turn >= 2:                               # the first two turns only establish the steady state
+                    lat.append(st["ns_total"] / 1e6)
+                    moved.append((summ["evicted_bytes"], summ["restored_bytes"]))
+            lat.sort()
+            oversub.append({"oversubscribed_GiB": round(frac * min(total) / 2**30, 2),
+                            "evicted_GiB": round(float(np.mean([m[0] for m in moved])) / 2**30, 2),
+                            "restored_GiB": round(float(np.mean([m[1] for m in moved])) / 2**30, 2),
+                            "latency_ms": {"min": round(lat[0], 2), "median": round(lat[len(lat) // 2], 2), "max": round(lat[-1], 2)}})
+            log("[bench] oversubscription sweep:", oversub[-1])
+            # back to the state the sweep started from (B in HBM, A in pageable memory), every chunk moved by a switch
+            cur = [(b, a, t) for (b, a, _), t in zip(chunks0, tiers)]
+            want = [t for _, _, t in chunks0]
+            out_rows = np.array([rws[a][i] for (a, i), t0, t1 in zip(owner_of, tiers, want) if t0 == nx.TIER_GPU and t1 != nx.TIER_GPU], dtype=np.uint64).reshape(-1, 3)
+            in_rows = np.array([rws[a][i] for (a, i), t0, t1 in zip(owner_of, tiers, want) if t0 != nx.TIER_GPU and t1 == nx.TIER_GPU], dtype=np.uint64).reshape(-1, 3)
+            if len(out_rows) or len(in_rows):
+                pl = nx.Plan(out_rows, in_rows, shared_ring, opts)
+                pl.switch()
+                pl.close()
+        shared_ring.close()
+
     sweep = None
     if args.ring_sweep:
         sweep = []
@@ -345,6 +394,8 @@ def main() -> int:
                                    "unmap the outgoing one's after it"}
     if sweep is not None:
         res["ring_sweep"] = sweep
+    if oversub is not None:
+        res["oversubscription_sweep"] = oversub
     del A, B
     if pool is not None:
         space_a.close()

@@ -212,6 +212,19 @@ int nixie_plan(const nixie_table_t *out_table, const nixie_table_t *in_table,
 int nixie_plan_info(const nixie_plan_t *plan, nixie_plan_info_t *info);
 void nixie_plan_destroy(nixie_plan_t *plan);
 
+/* One ring for many plans.  Allocation tables change while applications run, so a caller
+ * typically plans anew for every switch; a ring object keeps the pinned payload memory (and
+ * the GPU's mappings of it, which a fresh allocation has to fault in during its first switch)
+ * across plans, and keeps the pinned budget exact when several plans exist at once.
+ * nixie_plan_on_ring is nixie_plan with ring_bytes = the ring's size; the plan borrows the
+ * memory.  Plans of one ring switch one at a time (NIXIE_EBUSY otherwise).  A ring is
+ * destroyed after its plans (NIXIE_EBUSY before).  bytes: multiple of 4096. */
+typedef struct nixie_ring nixie_ring_t;
+int nixie_ring_create(uint64_t bytes, nixie_ring_t **ring);
+int nixie_ring_destroy(nixie_ring_t *ring);
+int nixie_plan_on_ring(const nixie_table_t *out_table, const nixie_table_t *in_table, nixie_ring_t *ring,
+                       const nixie_opts_t *opts /* NULL = defaults */, nixie_plan_t **plan);
+
 /* ---- the switch (paper, "Overview" step 4; "Speeding Up Context Switches") ----------------
  * Stream-ordered after everything already queued on hip_stream (a hipStream_t, NULL = the
  * default stream); this stands in for the paper's quiesce ("Valid memory access during

@@ -50,6 +50,15 @@ struct nixie_layout {
     Layout L;
 };
 
+// Pinned payload memory that several plans use in turn.
+struct nixie_ring {
+    uint8_t *h = nullptr, *d = nullptr;
+    uint64_t bytes = 0;
+    int device = -1;
+    std::mutex busy;                 // one switch at a time on this memory
+    std::atomic<uint32_t> users{0};  // plans made on it and not yet destroyed
+};
+
 struct nixie_plan {
     Layout L;
     nixie_plan_info_t info{};
@@ -57,6 +66,7 @@ struct nixie_plan {
 
     // pinned, mapped, coherent
     uint8_t *ring_h = nullptr, *ring_d = nullptr;
+    nixie_ring *shared = nullptr;    // non-null: ring_h / ring_d belong to it
     uint64_t *ctrl_h = nullptr, *ctrl_d = nullptr;
     size_t ctrl_bytes = 0;
 
@@ -82,7 +92,7 @@ struct nixie_plan {
         uint64_t t_entry = 0;
         uint32_t mask = 0;
         nixie_stats_t st{};
-        std::unique_lock<std::mutex> plan_lock;
+        std::unique_lock<std::mutex> plan_lock, ring_lock;
         std::shared_lock<std::shared_mutex> maps;
     } flight;
 };
@@ -104,7 +114,8 @@ void destroy_plan(nixie_plan_t *p) {
     }
     if (p->counters_d) (void)hipFree(p->counters_d);
     if (p->hashes_d) (void)hipFree(p->hashes_d);
-    if (p->ring_h) (void)hipHostFree(p->ring_h);
+    if (p->shared) p->shared->users.fetch_sub(1);
+    else if (p->ring_h) (void)hipHostFree(p->ring_h);
     if (p->ctrl_h) (void)hipHostFree(p->ctrl_h);
     if (prev >= 0 && prev != p->device) (void)hipSetDevice(prev);
     delete p;
@@ -125,7 +136,11 @@ int create_plan(nixie_plan_t *p) {
 
     // payload ring: exactly (out_slots + in_slots) * slot_bytes, never more than the budget
     if (p->info.pinned_ring_bytes > L.ring_bytes) return NIXIE_EINVAL;
-    if (p->info.pinned_ring_bytes) {
+    if (p->shared) {
+        if (p->shared->device != p->device || p->info.pinned_ring_bytes > p->shared->bytes) return NIXIE_EINVAL;
+        p->ring_h = p->shared->h;
+        p->ring_d = p->shared->d;
+    } else if (p->info.pinned_ring_bytes) {
         hipError_t e = hipHostMalloc((void **)&p->ring_h, p->info.pinned_ring_bytes,
                                      hipHostMallocMapped | hipHostMallocCoherent);
         if (e != hipSuccess) { t_last_hip_error = (int)e; return NIXIE_ENOMEM; }
@@ -403,6 +418,53 @@ int nixie_plan(const nixie_table_t *out_table, const nixie_table_t *in_table, ui
     return NIXIE_OK;
 }
 
+int nixie_ring_create(uint64_t bytes, nixie_ring_t **ring) {
+    if (!ring || bytes == 0 || bytes % 4096) return NIXIE_EINVAL;
+    *ring = nullptr;
+    nixie_ring *r = new (std::nothrow) nixie_ring;
+    if (!r) return NIXIE_ENOMEM;
+    hipError_t e = hipGetDevice(&r->device);
+    if (e == hipSuccess) e = hipHostMalloc((void **)&r->h, bytes, hipHostMallocMapped | hipHostMallocCoherent);
+    if (e != hipSuccess) { t_last_hip_error = (int)e; delete r; return e == hipErrorOutOfMemory ? NIXIE_ENOMEM : NIXIE_EHIP; }
+    e = hipHostGetDevicePointer((void **)&r->d, r->h, 0);
+    if (e != hipSuccess) { t_last_hip_error = (int)e; (void)hipHostFree(r->h); delete r; return NIXIE_EHIP; }
+    r->bytes = bytes;
+    *ring = r;
+    return NIXIE_OK;
+}
+
+int nixie_ring_destroy(nixie_ring_t *ring) {
+    if (!ring) return NIXIE_OK;
+    if (ring->users.load()) return NIXIE_EBUSY;
+    (void)hipHostFree(ring->h);
+    delete ring;
+    return NIXIE_OK;
+}
+
+int nixie_plan_on_ring(const nixie_table_t *out_table, const nixie_table_t *in_table, nixie_ring_t *ring,
+                       const nixie_opts_t *opts, nixie_plan_t **plan) {
+    if (!plan || !ring) return NIXIE_EINVAL;
+    nixie_plan_t *p = new (std::nothrow) nixie_plan_t();
+    if (!p) return NIXIE_ENOMEM;
+    int rc;
+    try {
+        rc = build_layout(out_table, in_table, ring->bytes, opts, p->L);
+        if (!rc) {
+            fill_info(p->L, &p->info);
+            p->shared = ring;
+            ring->users.fetch_add(1);
+            rc = create_plan(p);
+        }
+    } catch (const std::bad_alloc &) {
+        rc = NIXIE_ENOMEM;
+    } catch (const std::system_error &) {
+        rc = NIXIE_ENOMEM;
+    }
+    if (rc) { destroy_plan(p); return rc; }
+    *plan = p;
+    return NIXIE_OK;
+}
+
 int nixie_plan_info(const nixie_plan_t *plan, nixie_plan_info_t *info) {
     if (!plan || !info) return NIXIE_EINVAL;
     *info = plan->info;
@@ -421,6 +483,11 @@ int nixie_switch(nixie_plan_t *p, void *hip_stream, nixie_stats_t *stats) {
     if (!p) return NIXIE_EINVAL;
     std::unique_lock<std::mutex> lk(p->switch_mu, std::try_to_lock);
     if (!lk.owns_lock()) return NIXIE_EBUSY;
+    std::unique_lock<std::mutex> ring_lk;
+    if (p->shared) {
+        ring_lk = std::unique_lock<std::mutex>(p->shared->busy, std::try_to_lock);
+        if (!ring_lk.owns_lock()) return NIXIE_EBUSY;   // another plan is switching through the same ring
+    }
     // no block of a registered space is mapped or unmapped while the kernel runs
     std::shared_lock<std::shared_mutex> maps(switch_lock());
     if (!space_uses_valid(p->L.uses[0]) || !space_uses_valid(p->L.uses[1])) return NIXIE_EUNMAPPED;
@@ -449,6 +516,11 @@ int nixie_switch_begin(nixie_plan_t *p, void *hip_stream) {
     if (p->L.opts.flags & NIXIE_SERIALIZE) return NIXIE_EINVAL;   // two passes cannot be left running
     std::unique_lock<std::mutex> lk(p->switch_mu, std::try_to_lock);
     if (!lk.owns_lock()) return NIXIE_EBUSY;
+    std::unique_lock<std::mutex> ring_lk;
+    if (p->shared) {
+        ring_lk = std::unique_lock<std::mutex>(p->shared->busy, std::try_to_lock);
+        if (!ring_lk.owns_lock()) return NIXIE_EBUSY;
+    }
     std::shared_lock<std::shared_mutex> maps(switch_lock());
     if (!space_uses_valid(p->L.uses[0]) || !space_uses_valid(p->L.uses[1])) return NIXIE_EUNMAPPED;
     const uint64_t t_entry = now_ns();
@@ -464,6 +536,7 @@ int nixie_switch_begin(nixie_plan_t *p, void *hip_stream) {
     f.t_entry = t_entry;
     f.mask = 3u;
     f.plan_lock = std::move(lk);                                 // held until nixie_switch_end
+    f.ring_lock = std::move(ring_lk);
     f.maps = std::move(maps);
     return NIXIE_OK;
 }
@@ -483,6 +556,7 @@ int nixie_switch_end(nixie_plan_t *p, nixie_stats_t *stats) {
     if (stats) *stats = f.st;
     f.on = false;
     f.maps.unlock();
+    if (f.ring_lock.owns_lock()) f.ring_lock.unlock();
     f.plan_lock.unlock();
     return rc;
 }

@@ -25,6 +25,7 @@ DECLARED_SYMBOLS = (
     "nixie_space_unmap", "nixie_space_mapped", "nixie_space_destroy",
     "nixie_tier_register", "nixie_tier_unregister", "nixie_host_copy", "nixie_place",
     "nixie_switch_begin", "nixie_switch_wait_in", "nixie_switch_end",
+    "nixie_ring_create", "nixie_ring_destroy", "nixie_plan_on_ring",
 )
 
 
@@ -143,6 +144,9 @@ def lib() -> C.CDLL:
     L.nixie_layout_destroy.argtypes = [vp]
     L.nixie_layout_destroy.restype = None
     L.nixie_plan.argtypes = [C.POINTER(_Table), C.POINTER(_Table), u64, C.POINTER(_Opts), C.POINTER(vp)]
+    L.nixie_ring_create.argtypes = [u64, C.POINTER(vp)]
+    L.nixie_ring_destroy.argtypes = [vp]
+    L.nixie_plan_on_ring.argtypes = [C.POINTER(_Table), C.POINTER(_Table), vp, C.POINTER(_Opts), C.POINTER(vp)]
     L.nixie_plan_info.argtypes = [vp, C.POINTER(_Info)]
     L.nixie_plan_destroy.argtypes = [vp]
     L.nixie_plan_destroy.restype = None
@@ -273,15 +277,39 @@ class Layout:
     __del__ = close
 
 
+class Ring:
+    """nixie_ring_*: pinned payload memory shared by many plans, one switch at a time."""
+
+    def __init__(self, nbytes: int):
+        self._h = C.c_void_p()
+        self.bytes = nbytes
+        rc = lib().nixie_ring_create(nbytes, C.byref(self._h))
+        if rc:
+            self._h = None
+            raise NixieError(rc, "nixie_ring_create")
+
+    def close(self):
+        if self._h:
+            rc = lib().nixie_ring_destroy(self._h)
+            if rc:
+                raise NixieError(rc, "nixie_ring_destroy")
+            self._h = None
+
+
 class Plan:
     """nixie_plan / nixie_switch / nixie_hash_tables / nixie_verify / nixie_plan_destroy."""
 
-    def __init__(self, out_allocs, in_allocs, ring_bytes: int, opts: Opts | None = None):
+    def __init__(self, out_allocs, in_allocs, ring_bytes, opts: Opts | None = None):
+        """ring_bytes: a size (the plan allocates its own ring) or a Ring (nixie_plan_on_ring)."""
         self._h = C.c_void_p()
         to, self._ko = _table(out_allocs)
         ti, self._ki = _table(in_allocs)
         self.n_out, self.n_in = int(to.count), int(ti.count)
-        rc = lib().nixie_plan(C.byref(to), C.byref(ti), ring_bytes, _opts_ptr(opts), C.byref(self._h))
+        if isinstance(ring_bytes, Ring):
+            self._ring = ring_bytes              # keeps the ring alive as long as the plan
+            rc = lib().nixie_plan_on_ring(C.byref(to), C.byref(ti), ring_bytes._h, _opts_ptr(opts), C.byref(self._h))
+        else:
+            rc = lib().nixie_plan(C.byref(to), C.byref(ti), ring_bytes, _opts_ptr(opts), C.byref(self._h))
         if rc:
             self._h = None
             raise NixieError(rc, "nixie_plan")

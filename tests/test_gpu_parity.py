@@ -232,3 +232,39 @@ def test_in_place_switch(nx, oracle, case, mode):
     assert np.array_equal(dev_after, ref.dev), "device arena: " + first_diff(dev_after, ref.dev)
     plan.verify(h_out_ref, h_in_ref)
     plan.close()
+
+
+# ---- one ring for many plans --------------------------------------------------------------------
+
+def test_plans_share_one_ring(nx, oracle):
+    """Three plans made on one ring object, switched one after the other: each matches the oracle;
+    the pinned payload memory is the ring's; a ring in use cannot be destroyed, nor serve two
+    switches at once."""
+    from tests.gpu_helpers import GpuSet, first_diff
+    ring = nx.Ring(8 * S)
+    plans, sets, refs = [], [], []
+    for k, (sa, sb) in enumerate([([5 * S + 1, 300, 2 * S], [4 * S, 11]), ([S, S, S - 1], [7 * S + 3]),
+                                  ([9 * S + 77], [3 * S + 9, 7 * S, 15])]):
+        rA, rB = HostSet(sa, 80 + k, "dev"), HostSet(sb, 90 + k, "host")
+        oracle.switch_direct(rA.pairs(), rB.pairs())
+        gA, gB = GpuSet(sa, 80 + k, "dev"), GpuSet(sb, 90 + k, "host")
+        p = nx.Plan(gA.rows(), gB.rows(), ring, nx.Opts(slot_bytes=S))
+        assert p.info()["ring_bytes"] == 8 * S and p.info()["pinned_ring_bytes"] <= 8 * S
+        plans.append(p); sets.append((gA, gB)); refs.append((rA, rB))
+    with pytest.raises(nx.NixieError) as e:
+        ring.close()                                             # three plans still use it
+    assert e.value.code == nx.EBUSY
+    plans[0].switch_begin()
+    assert plans[1].switch(check=False)["rc"] == nx.EBUSY        # the ring is busy with another plan's switch
+    plans[0].switch_end()
+    for p in plans[1:] + plans[:1]:                              # plan 0 a second time, in another order
+        p.switch()
+    for (gA, gB), (rA, rB) in zip(sets, refs):
+        dev_B = gB.download()
+        assert np.array_equal(gA.hs.host, rA.host), "evicted set: " + first_diff(gA.hs.host, rA.host)
+        assert np.array_equal(dev_B, rB.dev), "restored set: " + first_diff(dev_B, rB.dev)
+    with pytest.raises(nx.NixieError):
+        nx.Plan(sets[0][0].rows(), sets[0][1].rows(), ring, nx.Opts(slot_bytes=4 * S))   # 2 slots: too small a ring
+    for p in plans:
+        p.close()
+    ring.close()

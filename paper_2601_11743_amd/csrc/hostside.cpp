@@ -56,16 +56,18 @@ struct IdleWatch {
     uint64_t idle_since = 0;
     uint32_t spins = 0;
     bool force_yield = false;   // for a waiter that is not one of the crew's threads
+    uint64_t nap_ns = ~0ull;    // ~0: the plan's setting
     // call after a scan that made no progress; false = stop
     bool idle() {
         // Spin: a slot usually turns around in microseconds.  Only where the threads outnumber
         // the cores does a long-idle thread give its core away between looks, so that a waiting
         // thread cannot keep the one it waits for off the processor; with a core each, yielding
         // costs a small ring one to two percent and buys nothing.
-        if (p->idle_sleep_ns && spins >= 64 && !force_yield) {
+        const uint64_t nap_for = nap_ns != ~0ull ? nap_ns : (force_yield ? 0 : p->idle_sleep_ns);
+        if (nap_for && spins >= 64) {
             // Nothing for a few microseconds: the ring holds far more than a nap's worth of
             // transfer, so give the core to whoever needs it (the applications do).
-            timespec nap{0, (long)p->idle_sleep_ns};
+            timespec nap{0, (long)nap_for};
             nanosleep(&nap, nullptr);
         } else if ((p->yield_when_idle || force_yield) && spins >= 4096) sched_yield();
         else _mm_pause();
@@ -181,9 +183,10 @@ void HostSide::run_fill(uint32_t idx) {
     note_end(p, 1);   // this thread's last chunk has reached HBM; the latest such time is "B ready"
 }
 
-int HostSide::wait_direction(int x) {
+int HostSide::wait_direction(int x, uint64_t nap_ns) {
     IdleWatch watch{this, x};
     watch.force_yield = true;
+    watch.nap_ns = nap_ns;
     int rc = NIXIE_OK;
     while (__atomic_load_n(done_word + x, __ATOMIC_ACQUIRE) == 0) {
         if (!watch.idle()) break;

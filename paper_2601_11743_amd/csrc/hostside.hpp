@@ -38,7 +38,8 @@ struct HostSide {
     void run_fill(uint32_t idx);                      // pageable -> ring, thread idx of threads[1]
     // Blocks until the kernel reports that every workgroup of direction x has left (for x = 1:
     // every incoming byte is in HBM), or the switch fails.  NIXIE_OK or the switch's error.
-    int wait_direction(int x);
+    // nap_ns > 0: sleep that long between looks instead of spinning.
+    int wait_direction(int x, uint64_t nap_ns = 0);
 };
 
 // The parked threads.  wake() starts them on the directions in mask; wait() returns when all of

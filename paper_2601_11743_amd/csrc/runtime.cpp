@@ -306,6 +306,12 @@ int pass_begin(nixie_plan_t *p, uint32_t mask, hipStream_t stream, nixie_stats_t
 int pass_end(nixie_plan_t *p, uint32_t mask, hipStream_t stream, nixie_stats_t *st) {
     const Layout &L = p->L;
     p->crew.wait();   // drain / fill threads done (finished, aborted or timed out)
+    // A long switch whose chunks move without host threads would leave the caller spinning in the
+    // stream synchronize for its whole length: sleep in short naps until the kernel's pump waves
+    // report both directions complete (or the switch fails), then synchronize.
+    if (L.dir[0].bytes + L.dir[1].bytes >= (256ull << 20) && !(L.opts.flags & NIXIE_HOST_SPIN))
+        for (int x = 0; x < 2; x++)
+            if ((mask & (1u << x)) && p->hs.wait_direction(x, 50000) != NIXIE_OK) break;
     hipError_t se = hipStreamSynchronize(stream);
     if (se != hipSuccess) { t_last_hip_error = (int)se; return NIXIE_EHIP; }
     // directly moved chunks are complete when the kernel is: no host thread saw them go by

@@ -268,3 +268,44 @@ def test_plans_share_one_ring(nx, oracle):
     for p in plans:
         p.close()
     ring.close()
+
+
+# ---- special cases that reduce to a library routine ---------------------------------------------
+
+def test_single_allocation_equals_a_plain_device_copy(nx):
+    """One allocation each way, ring larger than both: the switch is one D2H and one H2D copy, and
+    must give what torch's own copies (the runtime's hipMemcpy path) give."""
+    import torch
+    n_a, n_b = 3 * MiB + 17, 2 * MiB + 5
+    g = torch.Generator(device="cuda:0")
+    g.manual_seed(5)
+    dev_a = torch.randint(0, 256, (n_a,), dtype=torch.uint8, device="cuda:0", generator=g)
+    host_b = np.random.default_rng(6).integers(0, 256, n_b, dtype=np.uint8)
+    host_a = np.zeros(n_a, dtype=np.uint8)
+    dev_b = torch.zeros(n_b, dtype=torch.uint8, device="cuda:0")
+    want_a = dev_a.cpu().numpy()                                    # library D2H
+    want_b = torch.from_numpy(host_b).to("cuda:0")                  # library H2D
+    torch.cuda.synchronize()
+    plan = nx.Plan([(dev_a.data_ptr(), host_a.ctypes.data, n_a)], [(dev_b.data_ptr(), host_b.ctypes.data, n_b)], 16 * MiB)
+    plan.switch()
+    plan.close()
+    assert np.array_equal(host_a, want_a)
+    assert torch.equal(dev_b, want_b)
+
+
+def test_pure_eviction_equals_concatenation_copied_to_the_host(nx):
+    """Empty incoming table: the gather of many allocations into one host buffer is torch.cat(...).cpu()."""
+    import torch
+    g = torch.Generator(device="cuda:0")
+    g.manual_seed(9)
+    sizes = [5 * S + 1, 300, 2 * S, 9 * S + 77, 15, 16, 17, 1, 3 * S - 1]
+    parts = [torch.randint(0, 256, (b,), dtype=torch.uint8, device="cuda:0", generator=g) for b in sizes]
+    want = torch.cat(parts).cpu().numpy()
+    host = np.full(sum(sizes), 0x5A, dtype=np.uint8)
+    offs = np.concatenate([[0], np.cumsum(sizes)[:-1]]).astype(int)
+    rows_out = [(p.data_ptr(), host.ctypes.data + int(o), b) for p, o, b in zip(parts, offs, sizes)]
+    plan = nx.Plan(rows_out, [], 4 * S, nx.Opts(slot_bytes=S))
+    assert plan.info()["in_slots"] == 0
+    plan.switch()
+    plan.close()
+    assert np.array_equal(host, want)

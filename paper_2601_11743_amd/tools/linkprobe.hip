@@ -8,7 +8,7 @@
 // into / loaded from host memory and what is done between work pieces to order payload against
 // a flag.  Output: GB/s per direction (time until both directions are done).
 //
-// usage: nixie_linkprobe [ordering] [loads] [stores] [pieces] [xcd] [sdma]      (no argument = all)
+// usage: nixie_linkprobe [ordering] [loads] [stores] [pieces] [xcd] [sdma] [slots]      (no argument = all)
 #include <hip/hip_runtime.h>
 
 #include <chrono>
@@ -16,7 +16,10 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <atomic>
 #include <string>
+#include <thread>
+#include <vector>
 
 #define CK(x)                                                                                  \
     do {                                                                                       \
@@ -230,6 +233,39 @@ int main(int argc, char **argv) {
                 if (it && dt < best) best = dt;
             }
             std::printf("sdma      hipMemcpyAsync %-18s %6.2f GB/s per direction\n", names[mode], (double)b.bytes / best / 1e9);
+        }
+    }
+    if (want("slots")) {
+        // The alternative to a copy kernel on the link: the copy engines moving one ring slot per call
+        // (the kernels would then only gather / scatter inside HBM).  Host threads issue
+        // hipMemcpyAsync calls of one slot each, both directions at once, one copy in flight per thread.
+        for (size_t slot : {(size_t)1 << 20, (size_t)4 << 20, (size_t)16 << 20}) {
+            for (int threads : {1, 2}) {
+                std::atomic<size_t> next[2];
+                next[0].store(0); next[1].store(0);
+                const size_t n = b.bytes / slot, window = (size_t)128 << 20;
+                auto worker = [&](int dir) {
+                    CK(hipSetDevice(0));
+                    hipStream_t st;
+                    CK(hipStreamCreateWithFlags(&st, hipStreamNonBlocking));
+                    for (;;) {
+                        const size_t i = next[dir].fetch_add(1);
+                        if (i >= n) break;
+                        if (dir) CK(hipMemcpyAsync(b.d_dst + i * slot, b.h_in + (i * slot) % window, slot, hipMemcpyHostToDevice, st));
+                        else CK(hipMemcpyAsync(b.h_out + (i * slot) % window, b.d_src + i * slot, slot, hipMemcpyDeviceToHost, st));
+                        CK(hipStreamSynchronize(st));
+                    }
+                    CK(hipStreamDestroy(st));
+                };
+                CK(hipDeviceSynchronize());
+                const double t0 = now_s();
+                std::vector<std::thread> pool;
+                for (int t = 0; t < threads; t++) { pool.emplace_back(worker, 0); pool.emplace_back(worker, 1); }
+                for (auto &th : pool) th.join();
+                const double dt = now_s() - t0;
+                std::printf("slots     hipMemcpyAsync of %2zu MiB per call, %d thread(s) per direction, both at once   %6.2f GB/s per direction\n",
+                            slot >> 20, threads, (double)b.bytes / dt / 1e9);
+            }
         }
     }
     if (want("ordering")) {

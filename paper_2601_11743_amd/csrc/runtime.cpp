@@ -121,6 +121,24 @@ void destroy_plan(nixie_plan_t *p) {
     delete p;
 }
 
+// Fresh pinned memory is mapped into the process lazily: the host threads' first pass over a new
+// ring would take a page fault per 4 KiB inside the switch (about 15 ms for 256 MiB).  Touch every
+// page here, where nobody is waiting.
+int warm_ring(uint8_t *ring_h, uint64_t bytes) {
+    const unsigned T = (unsigned)std::min<uint64_t>(std::max(1u, std::min(8u, std::thread::hardware_concurrency() / 2)),
+                                                     bytes / (8u << 20) + 1);
+    auto touch = [&](unsigned t) {
+        volatile uint8_t *p = ring_h;
+        const uint64_t per = (bytes / T + 4095) / 4096 * 4096;
+        for (uint64_t off = t * per; off < std::min(bytes, (t + 1) * per); off += 4096) p[off] = 0;
+    };
+    std::vector<std::thread> pool;
+    for (unsigned t = 1; t < T; t++) pool.emplace_back(touch, t);
+    touch(0);
+    for (auto &th : pool) th.join();
+    return NIXIE_OK;
+}
+
 int upload(const void *src, size_t bytes, void **dst) {
     *dst = nullptr;
     if (bytes == 0) return NIXIE_OK;
@@ -145,6 +163,8 @@ int create_plan(nixie_plan_t *p) {
                                      hipHostMallocMapped | hipHostMallocCoherent);
         if (e != hipSuccess) { t_last_hip_error = (int)e; return NIXIE_ENOMEM; }
         NIXIE_HIP(hipHostGetDevicePointer((void **)&p->ring_d, p->ring_h, 0));
+        int rc = warm_ring(p->ring_h, p->info.pinned_ring_bytes);
+        if (rc) return rc;
     }
     // control block: [host-written flags out | in (8 B each, padded to lines)] [GPU-written flags out | in
     // (one 64 B line each)] [abort word] [status word] [direction-done words]
@@ -435,6 +455,8 @@ int nixie_ring_create(uint64_t bytes, nixie_ring_t **ring) {
     e = hipHostGetDevicePointer((void **)&r->d, r->h, 0);
     if (e != hipSuccess) { t_last_hip_error = (int)e; (void)hipHostFree(r->h); delete r; return NIXIE_EHIP; }
     r->bytes = bytes;
+    const int rc = warm_ring(r->h, bytes);
+    if (rc) { (void)hipHostFree(r->h); delete r; return rc; }
     *ring = r;
     return NIXIE_OK;
 }

@@ -356,7 +356,7 @@ def main() -> int:
                     link_peak={k: round(v, 3) for k, v in peak.items()})
 
     res = {
-        "metric": "bidirectional swap GB/s (switch latency in ms_per_step), 16 GiB-class out/in, 256 MiB ring",
+        "metric": "bidirectional swap GB/s and switch latency (ms), 16 GiB out/in, 256 MiB ring",
         "value": round(value, 3), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u8", "data": "synthetic",

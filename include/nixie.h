@@ -251,7 +251,7 @@ int nixie_switch(nixie_plan_t *plan, void *hip_stream, nixie_stats_t *stats);
  *   nixie_switch_end      blocks until everything is complete, fills stats, returns the result
  *                         of the switch exactly as nixie_switch does.
  * Between begin and end the plan is busy (NIXIE_EBUSY for another switch), map / unmap calls
- * wait, and the three calls must come from one thread.  nixie_switch_wait_in / _end without a
+ * return NIXIE_EBUSY, and the three calls must come from one thread.  nixie_switch_wait_in / _end without a
  * begun switch: NIXIE_EINVAL.  Not available with NIXIE_SERIALIZE (NIXIE_EINVAL).  With
  * NIXIE_IN_PLACE the incoming bytes are complete at wait_in like otherwise; the outgoing
  * application's device ranges are the incoming one's by then. */
@@ -298,9 +298,10 @@ int nixie_hash_buffers(const void *const *ptrs, const uint64_t *bytes, uint64_t 
  * unmapped or has been reassigned since.  The calls around a switch:
  *     nixie_space_map(B)  ->  nixie_switch(plan(A's table, B's table, NIXIE_IN_PLACE))
  *     ->  nixie_space_unmap(A)           (A's pointers stay reserved, and fault if used)
- * None of these calls runs inside the switch.  Mapping and unmapping take the library's
- * switch lock, so they wait for a running nixie_switch; nixie_switch returns NIXIE_EUNMAPPED
- * without touching the GPU when a listed range lies in unmapped blocks.
+ * None of these calls runs inside the switch: while any switch is running (between
+ * nixie_switch_begin and nixie_switch_end too) assign, map, unmap and destroy return
+ * NIXIE_EBUSY and change nothing.  nixie_switch returns NIXIE_EUNMAPPED without touching the
+ * GPU when a listed range lies in unmapped blocks.
  * block_bytes: multiple of the device's allocation granularity, 0 = 256 MiB (a map or unmap
  * call costs the same for any block size, so small blocks make the remap slow).  bytes is
  * rounded up to whole blocks.  offset and bytes of map / unmap must be multiples of the

@@ -2,7 +2,7 @@
 // "Hierarchical Memory"), and pools and spaces -- physical device memory in equal blocks, and
 // reserved address ranges that map those blocks (paper, "Maintaining consistent virtual memory
 // addresses"; "Granularity of Memory Management").  All driver calls here run outside a switch:
-// they take the switch lock exclusively, nixie_switch holds it shared.
+// they need the switch lock exclusively and return NIXIE_EBUSY while a switch holds it shared.
 #include <hip/hip_runtime.h>
 
 #include <mutex>
@@ -215,7 +215,8 @@ int nixie_space_map(nixie_space_t *s, uint64_t offset, uint64_t bytes) {
     hipError_t e = hipGetDevice(&device);
     if (e != hipSuccess) return fail(e);
     if (device != s->pool->device) return NIXIE_EINVAL;
-    std::unique_lock<std::shared_mutex> lk(switch_lock());
+    std::unique_lock<std::shared_mutex> lk(switch_lock(), std::try_to_lock);
+    if (!lk.owns_lock()) return NIXIE_EBUSY;   // a switch is running: never wait for it here (it may be the caller's own)
     const uint64_t B = s->pool->block_bytes;
     hipMemAccessDesc acc{};
     acc.location.type = hipMemLocationTypeDevice;
@@ -252,7 +253,8 @@ int nixie_space_assign(nixie_space_t *s, uint64_t offset, const uint64_t *pool_b
     if (n_blocks > s->assigned.size()) return NIXIE_EINVAL;
     int rc = block_range(s, offset, n_blocks * B, &first, &count);
     if (rc) return rc;
-    std::unique_lock<std::shared_mutex> lk(switch_lock());
+    std::unique_lock<std::shared_mutex> lk(switch_lock(), std::try_to_lock);
+    if (!lk.owns_lock()) return NIXIE_EBUSY;   // a switch is running: never wait for it here (it may be the caller's own)
     for (uint64_t i = 0; i < count; i++) {
         if (pool_blocks[i] >= s->assigned.size()) return NIXIE_EINVAL;
         if (s->mapped[first + i] && s->assigned[first + i] != pool_blocks[i]) return NIXIE_EBUSY;   // unmap it first
@@ -267,7 +269,8 @@ int nixie_space_unmap(nixie_space_t *s, uint64_t offset, uint64_t bytes) {
     uint64_t first = 0, count = 0;
     int rc = block_range(s, offset, bytes, &first, &count);
     if (rc) return rc;
-    std::unique_lock<std::shared_mutex> lk(switch_lock());
+    std::unique_lock<std::shared_mutex> lk(switch_lock(), std::try_to_lock);
+    if (!lk.owns_lock()) return NIXIE_EBUSY;   // a switch is running: never wait for it here (it may be the caller's own)
     // work queued on any stream may still use these addresses
     hipError_t e = hipDeviceSynchronize();
     if (e != hipSuccess) return fail(e);
@@ -279,8 +282,7 @@ int nixie_space_mapped(const nixie_space_t *s, uint64_t offset, uint64_t bytes) 
     uint64_t first = 0, count = 0;
     int rc = block_range(s, offset, bytes, &first, &count);
     if (rc) return rc;
-    std::shared_lock<std::shared_mutex> lk(switch_lock());
-    for (uint64_t b = first; b < first + count; b++)
+    for (uint64_t b = first; b < first + count; b++)   // (changed only by the owner's own map / unmap calls)
         if (!s->mapped[b]) return 0;
     return 1;
 }
@@ -289,7 +291,8 @@ int nixie_space_destroy(nixie_space_t *s) {
     if (!s) return NIXIE_OK;
     int rc;
     {
-        std::unique_lock<std::shared_mutex> lk(switch_lock());
+        std::unique_lock<std::shared_mutex> lk(switch_lock(), std::try_to_lock);
+    if (!lk.owns_lock()) return NIXIE_EBUSY;   // a switch is running: never wait for it here (it may be the caller's own)
         hipError_t e = hipDeviceSynchronize();
         if (e != hipSuccess) return fail(e);
         rc = unmap_blocks(s, 0, s->mapped.size());

@@ -113,7 +113,12 @@ def test_switch_there_and_back_between_spaces(nx, oracle, raw, case):
 
     h_out, h_in = plan_ab.hash_tables()
     assert np.array_equal(h_out, h_a) and np.array_equal(h_in, h_b)
-    plan_ab.switch()
+    plan_ab.switch_begin()
+    for call in (sp_a.unmap, sp_b.map, lambda: sp_b.assign(0, [0])):
+        with pytest.raises(nx.NixieError) as e:
+            call()                                               # nothing is remapped while a switch is running
+        assert e.value.code == nx.EBUSY
+    plan_ab.switch_end()
     sp_a.unmap()                                                 # A keeps its addresses, nothing behind them
     got = raw.download(sp_b.base, g.dev.size)
     assert np.array_equal(got, dev_after_b), "pool after A->B: " + first_diff(got, dev_after_b)

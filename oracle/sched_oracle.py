@@ -19,7 +19,10 @@ Readings where the paper is silent (also listed in the design notes): R = 1/(N+1
 application whose level changes starts with t_a = 0 there; new applications start in Q_1; a
 running application that is idle yields to any waiting application; execution time accrues, tick
 to tick, while the application owns the GPU and is not idle; "time since last execution" counts
-from the last tick at which it was executing (or from its creation).
+from the last tick at which it was executing (or from its creation); in the lowest queue Q_K the
+demotion branch has no queue to move to but still ends with t_a <- 0 as the algorithm prints it
+(the priority, and so p_a, is unchanged), which keeps the idle branch reachable for an
+application that once outran T_K.
 """
 from __future__ import annotations
 
@@ -94,7 +97,8 @@ class SchedOracle:
             p = app.p
             if app.t_a > self.T(p):                               # standard MLFQ demotion
                 if p < self.K:
-                    app.p, app.t_a, app.last_prio_change = p + 1, 0, now
+                    app.p, app.last_prio_change = p + 1, now
+                app.t_a = 0                                       # also in Q_K, where there is no lower queue
             elif self.is_idle(a, now):
                 i_a = now - app.last_exec                          # time since last execution
                 p_a = now - app.last_prio_change                   # time since last priority change

@@ -186,3 +186,32 @@ def test_pending_time_is_discounted_with_R_below_one_over_N(SchedImpl):
     # N = 1 at level 3 (hog is demoted on its own clock but never shares level 3 before this):
     # 2 i_a - q_a > 2 * 16 s with i_a = s and q_a = s - 1  ->  s + 1 > 32  ->  s = 32, and p_a = s > 32 s -> s = 33
     assert promoted_at == 33
+
+
+def test_bottom_queue_allotment_restarts_so_soft_promotion_stays_reachable(SchedImpl):
+    """Algorithm 1's demotion branch ends with t_a <- 0 also where there is no lower queue to move to.
+    K = 2 (T_1 = 8 s, T_2 = 16 s), one application computing without pause: level 2 at 9 s; at 26 s
+    t_a = 17 s > T_2, it stays in Q_2 and its allotment restarts; 4 more seconds of work (t_a = 4 s at
+    30 s), then silence.  p_a counts from 9 s (no priority change at 26 s), so p_a > T_2 already
+    holds, and the promotion waits for i_a > T_1 + t_a = 12 s: the tick at 43 s."""
+    o = SchedImpl(levels=2)
+    a = o.add_app(0)
+    o.request(a, 0)
+    o.tick(0)
+    level_at = {}
+    for s in range(1, 31):
+        active(o, a, (s - 1) * SEC, s * SEC)
+        o.tick(s * SEC)
+        level_at[s] = o.info(a, s * SEC)["priority"]
+        if s == 25:
+            assert o.info(a, s * SEC)["t_a"] == 16 * SEC       # not yet above T_2
+        if s == 26:
+            assert o.info(a, s * SEC)["t_a"] == 0              # restarted in place
+    assert level_at[8] == 1 and level_at[9] == 2 and level_at[30] == 2
+    assert o.info(a, 30 * SEC)["t_a"] == 4 * SEC
+    promoted_at = None
+    for s in range(31, 80):
+        o.tick(s * SEC)
+        if promoted_at is None and o.info(a, s * SEC)["priority"] == 1:
+            promoted_at = s
+    assert promoted_at == 43

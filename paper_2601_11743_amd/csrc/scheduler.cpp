@@ -137,7 +137,11 @@ int nixie_sched_tick(nixie_sched_t *s, uint64_t now, nixie_sched_decision_t *out
     for (AppState &a : s->apps) {
         const uint32_t p = a.level;
         if (a.exec_ns > s->T(p)) {
+            // The demotion branch ends with t_a <- 0 also in the lowest queue, where there is nowhere
+            // to move to: the allotment restarts, level and time of the last change stay, and a later
+            // long idle period can still lift the application again.
             if (p < s->levels) s->move(a, p + 1, now);
+            else a.exec_ns = 0;
         } else if (p > 1 && s->is_idle(a, now) && now - a.last_change > s->T(p)) {
             const __int128 n1 = (__int128)s->population[p] + 1;                 // 1 / R
             const __int128 idle_for = (__int128)(now - a.last_exec);

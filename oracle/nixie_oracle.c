@@ -18,7 +18,10 @@
  * through a pinned staging ring of bounded size, one step at a time in a
  * seeded random order, and checks the invariants the problem fixes while it
  * goes (every byte moved exactly once, nothing written outside an allocation,
- * staged bytes never above the ring size, ring empty at the end).
+ * a slot free before it is used and staged bytes never above the ring size --
+ * both recounted from the slot table after every step, so that a planted
+ * mistake in the slot choice or in a direction's share trips them -- and the
+ * ring empty at the end).
  *
  * o_switch_staged with in_place = 1 is the in-place switch: the incoming
  * allocations may reuse GPU memory of the outgoing ones, and a GPU byte is
@@ -179,13 +182,16 @@ enum {
 enum {
     O_FAULT_NONE = 0, O_FAULT_DROP_CHUNK = 1, O_FAULT_SHORT_PIECE = 2,
     O_FAULT_SLOT_SHIFT = 3, O_FAULT_DOUBLE_COPY = 4, O_FAULT_OVERRUN = 5,
-    O_FAULT_WRONG_DIRECTION = 6, O_FAULT_IGNORE_ALIAS = 7
+    O_FAULT_WRONG_DIRECTION = 6, O_FAULT_IGNORE_ALIAS = 7,
+    O_FAULT_REUSE_BUSY_SLOT = 8,   /* a chunk is staged into a slot that still holds another one      */
+    O_FAULT_OVERCOMMIT = 9         /* a direction believes it owns one slot more than the ring gives it */
 };
 
 typedef struct {
     const o_alloc *t; uint64_t n; o_cut cut;
     uint64_t *order; uint64_t next;          /* seeded chunk order          */
     int64_t *slot_chunk; uint64_t n_slots;   /* -1 = free, else staged chunk */
+    uint64_t granted_slots;                  /* slots of the ring this direction really owns */
     uint8_t *ring;                           /* this direction's sub-ring   */
     uint8_t **stage_cnt, **dest_cnt;         /* per-byte copy counts or NULL */
     uint8_t **gone;                          /* out only, in-place mode: byte has left the GPU */
@@ -199,16 +205,17 @@ static int dir_init(o_dir *d, const o_alloc *t, uint64_t n, uint64_t S, int pack
 {
     memset(d, 0, sizeof(*d));
     d->t = t; d->n = n; d->n_slots = n_slots; d->ring = ring; d->to_host = to_host;
+    d->granted_slots = n_slots;
     if (cut_table(t, n, S, pack, &d->cut))
         return O_ENOMEM;
     d->order = (uint64_t *)malloc((d->cut.n_chunks + 1) * sizeof(uint64_t));
-    d->slot_chunk = (int64_t *)malloc((n_slots + 1) * sizeof(int64_t));
+    d->slot_chunk = (int64_t *)malloc((n_slots + 2) * sizeof(int64_t));
     if (!d->order || !d->slot_chunk)
         return O_ENOMEM;
     for (uint64_t k = 0; k < d->cut.n_chunks; k++)
         d->order[k] = k;
     shuffle(d->order, d->cut.n_chunks, rng);
-    for (uint64_t s = 0; s < n_slots; s++)
+    for (uint64_t s = 0; s < n_slots + 2; s++)
         d->slot_chunk[s] = -1;
     if (check_bytes) {
         d->stage_cnt = (uint8_t **)calloc(n + 1, sizeof(uint8_t *));
@@ -256,6 +263,35 @@ static uint64_t pick_slot(const o_dir *d, int want_free, uint64_t *rng)
             r--;
         }
     return cand;
+}
+
+/* The two invariants of the staging tier, recounted from the slot table after every step and
+ * independently of how the step chose its slot:
+ *   - a slot is free before it is used: every chunk that has been staged and not yet delivered
+ *     must still sit in a slot (a chunk staged over a live one makes the live one vanish), and
+ *     no chunk sits in two slots;
+ *   - pinned bytes never above ring_bytes: every occupied slot is one the ring really gave to its
+ *     direction, and the payload held by all occupied slots fits the ring.
+ * running = the step loop's own byte count, which must agree with the recount. */
+static int audit_ring(const o_dir *d, uint64_t slot_bytes, uint64_t ring_bytes, uint64_t running)
+{
+    uint64_t held = 0, extent = 0;
+    for (int x = 0; x < 2; x++) {
+        uint64_t occupied = 0;
+        for (uint64_t s = 0; s < d[x].n_slots; s++) {
+            if (d[x].slot_chunk[s] < 0) continue;
+            occupied++;
+            if (s >= d[x].granted_slots) return O_EBUDGET;          /* memory beyond this direction's share */
+            held += d[x].cut.chunks[d[x].slot_chunk[s]].bytes;
+            for (uint64_t r = s + 1; r < d[x].n_slots; r++)
+                if (d[x].slot_chunk[r] == d[x].slot_chunk[s]) return O_ESLOT_BUSY;
+        }
+        if (d[x].next - d[x].done != occupied) return O_ESLOT_BUSY;  /* a staged chunk was overwritten */
+        extent += d[x].granted_slots * slot_bytes;
+    }
+    if (held != running) return O_ECOUNT;
+    if (held > ring_bytes || extent > ring_bytes) return O_EBUDGET;
+    return O_OK;
 }
 
 /* In-place switch (the incoming application reuses GPU memory the outgoing one gives up; paper,
@@ -306,7 +342,9 @@ int o_switch_staged(const o_alloc *out, uint64_t n_out,
     if (tot_out && n_out_slots == 0) return O_EINVAL;
     if (tot_in && n_out_slots == n_slots) return O_EINVAL;
 
-    uint8_t *ring = (uint8_t *)malloc(ring_bytes);   /* the pinned budget */
+    /* the pinned budget; one slot of slack behind it so that a planted overcommit is caught by the
+     * audit, not by the allocator */
+    uint8_t *ring = (uint8_t *)malloc(ring_bytes + slot_bytes);
     if (!ring) return O_ENOMEM;
     uint64_t rng = seed;
     o_dir d[2];
@@ -324,6 +362,8 @@ int o_switch_staged(const o_alloc *out, uint64_t n_out,
     }
     uint64_t staged = 0;
     int fault_armed = fault;
+    if (rc == O_OK && fault == O_FAULT_OVERCOMMIT)   /* the last direction in the ring counts one slot too many */
+        d[tot_in ? 1 : 0].n_slots++;
 
     while (rc == O_OK) {
         /* feasible steps: 0 stage-out (GPU->ring), 1 drain (ring->host),
@@ -349,8 +389,15 @@ int o_switch_staged(const o_alloc *out, uint64_t n_out,
         rep->steps++;
         if (stage_in) {
             uint64_t s = pick_slot(D, 1, &rng);
+            if (fault_armed == O_FAULT_REUSE_BUSY_SLOT && (uint64_t)count_free(D) < D->n_slots) {
+                s = pick_slot(D, 0, &rng);
+                fault_armed = 0;
+            }
+            if (fault_armed == O_FAULT_OVERCOMMIT && D->n_slots > D->granted_slots) {
+                s = D->granted_slots;
+                fault_armed = 0;
+            }
             uint64_t k = D->order[D->next++];
-            if (D->slot_chunk[s] >= 0) { rc = O_ESLOT_BUSY; break; }
             const o_chunk *ch = &D->cut.chunks[k];
             for (uint64_t q = ch->first; q < ch->first + ch->count; q++) {
                 const o_piece *p = &D->cut.pieces[q];
@@ -368,7 +415,6 @@ int o_switch_staged(const o_alloc *out, uint64_t n_out,
             D->slot_chunk[s] = (int64_t)k;
             staged += ch->bytes;
             if (staged > rep->hwm_staged_bytes) rep->hwm_staged_bytes = staged;
-            if (staged > ring_bytes) { rc = O_EBUDGET; break; }
         } else {
             uint64_t s = n_ok && step == 3 ? (uint64_t)ok_slot[rng_next(&rng) % n_ok] : pick_slot(D, 0, &rng);
             uint64_t k = (uint64_t)D->slot_chunk[s];
@@ -398,6 +444,7 @@ int o_switch_staged(const o_alloc *out, uint64_t n_out,
             D->done++;
             if (D->to_host) rep->bytes_out += ch->bytes; else rep->bytes_in += ch->bytes;
         }
+        if (rc == O_OK) rc = audit_ring(d, slot_bytes, ring_bytes, staged);
     }
 
     if (rc == O_OK) {

@@ -43,7 +43,8 @@ class OracleError(RuntimeError):
 _CODES = {0: "OK", -1: "EINVAL", -2: "ENOMEM", -3: "ESLOT_BUSY", -4: "EBUDGET",
           -5: "ECOUNT", -6: "ERANGE", -7: "ELEFTOVER"}
 FAULTS = {"none": 0, "drop_chunk": 1, "short_piece": 2, "slot_shift": 3,
-          "double_copy": 4, "overrun": 5, "wrong_direction": 6, "ignore_alias": 7}
+          "double_copy": 4, "overrun": 5, "wrong_direction": 6, "ignore_alias": 7,
+          "reuse_busy_slot": 8, "overcommit": 9}
 
 
 class _Alloc(C.Structure):

@@ -227,6 +227,22 @@ def test_planted_mistakes_are_caught(oracle, fault):
     assert caught, fault
 
 
+@pytest.mark.parametrize("seed", range(6))
+@pytest.mark.parametrize("fault,code", [("reuse_busy_slot", -3), ("overcommit", -4)])
+def test_slot_and_budget_invariants_are_falsifiable(oracle, fault, code, seed):
+    """The two staging-tier invariants are recounted from the slot table after every step: a chunk
+    staged into a slot that still holds another one is reported as ESLOT_BUSY (the overwritten chunk
+    is missing from the table), a direction that uses a slot the ring never gave it as EBUDGET."""
+    A, B = _sets([5 * S + 100, 555, S], [6 * S, 64])
+    with pytest.raises(OracleError) as e:
+        oracle.switch_staged(A.pairs(), B.pairs(), 4 * S, S, seed=seed, fault=fault)
+    assert e.value.code == code
+    # the same inputs without the planted mistake pass, and really use the whole budget at some point
+    A, B = _sets([5 * S + 100, 555, S], [6 * S, 64])
+    rep = oracle.switch_staged(A.pairs(), B.pairs(), 4 * S, S, seed=seed)
+    assert 0 < rep["hwm_staged_bytes"] <= 4 * S
+
+
 # ---- in-place switch: B reuses the GPU memory A gives up ---------------------
 
 ALIAS_CASES = [

@@ -231,7 +231,12 @@ int build_layout(const nixie_table_t *out_table, const nixie_table_t *in_table, 
     uint64_t n_out;
     if (staged_tot[0] == 0) n_out = 0;
     else if (staged_tot[1] == 0) n_out = n_slots;
-    else if (L.opts.out_slots) n_out = L.opts.out_slots;
+    else if (L.opts.out_slots) {
+        // both directions are staged: each needs two slots, and the caller's share for the outgoing
+        // one must leave them (checked before any subtraction: these are unsigned counts)
+        if ((uint64_t)L.opts.out_slots < 2 || (uint64_t)L.opts.out_slots + 2 > n_slots) return NIXIE_EINVAL;
+        n_out = L.opts.out_slots;
+    }
     else if (L.opts.flags & NIXIE_SPLIT_BY_BYTES) {
         long double f = (long double)staged_tot[0] / (long double)(staged_tot[0] + staged_tot[1]);
         n_out = (uint64_t)(f * (long double)n_slots + 0.5L);
@@ -304,9 +309,10 @@ void fill_info(const Layout &L, nixie_plan_info_t *info) {
     info->direct_chunks_in = L.dir[1].chunks.size() - L.dir[1].staged;
     info->direct_bytes_out = L.dir[0].direct_bytes;
     info->direct_bytes_in = L.dir[1].direct_bytes;
-    info->pinned_ring_bytes = (uint64_t)(L.dir[0].slots + L.dir[1].slots) * L.slot_bytes;
+    const uint64_t all_slots = (uint64_t)L.dir[0].slots + (uint64_t)L.dir[1].slots;   // 64-bit: no wrap
+    info->pinned_ring_bytes = all_slots * L.slot_bytes;
     info->pinned_ctrl_bytes = (wait_flag_words(L.dir[0].slots) + wait_flag_words(L.dir[1].slots) +
-                               ((uint64_t)(L.dir[0].slots + L.dir[1].slots) + 3) * kFlagStride) * 8;
+                               (all_slots + 3) * kFlagStride) * 8;
     // Measured on MI355X with both directions active: write-through stores into the ring need
     // about twice the workgroups that the reads out of it need; beyond 128 + 64 the surplus
     // only waits for slots.

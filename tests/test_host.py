@@ -130,6 +130,27 @@ def test_planner_packing_is_dense(nx):
     lay.close()
 
 
+def test_out_slots_must_leave_two_slots_for_the_other_direction(nx):
+    """The caller's share for the outgoing direction is an unsigned count: one that exceeds the ring
+    must be refused before it is subtracted, or the incoming share wraps round and the pinned
+    budget with it (ring 4 MiB in 64 KiB slots = 64 slots)."""
+    ra, rb = fake_rows([1 * MiB]), fake_rows([1 * MiB], dev_base=0x7F80_0000_0000, host_base=0x1800_0000_0000)
+    for bad in (1, 63, 64, 65, 100, 2**32 - 1):
+        with pytest.raises(nx.NixieError) as e:
+            nx.Layout(ra, rb, 4 * MiB, nx.Opts(slot_bytes=64 * KiB, out_slots=bad))
+        assert e.value.code == nx.EINVAL, bad
+    for good in (2, 32, 62):
+        lay = nx.Layout(ra, rb, 4 * MiB, nx.Opts(slot_bytes=64 * KiB, out_slots=good))
+        i = lay.info()
+        assert i["out_slots"] == good and i["in_slots"] == 64 - good
+        assert i["pinned_ring_bytes"] == 4 * MiB and i["pinned_ctrl_bytes"] < 64 * KiB
+        lay.close()
+    # one direction only: the option does not apply, the whole ring serves the staged direction
+    lay = nx.Layout(ra, [], 4 * MiB, nx.Opts(slot_bytes=64 * KiB, out_slots=100))
+    assert lay.info()["out_slots"] == 64 and lay.info()["in_slots"] == 0
+    lay.close()
+
+
 def test_planner_ring_split_and_defaults(nx):
     ra, rb = fake_rows([20 * MiB]), fake_rows([6 * MiB], dev_base=0x7F80_0000_0000, host_base=0x1800_0000_0000)
     lay = nx.Layout(ra, rb, 512 * MiB)

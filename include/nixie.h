@@ -333,8 +333,12 @@ int nixie_space_destroy(nixie_space_t *space);
  * instead of three.  Allocations elsewhere (pageable memory) go through the ring as before,
  * in the same switch; a plan whose tables are entirely in the pinned tier needs no ring
  * (ring_bytes may be 0) and starts no host threads.  Semantics of nixie_switch are unchanged.
- * Plans pick the registry up when they are made.  Errors: NIXIE_EINVAL (NULL, 0 bytes, not
- * pinned host memory, overlaps a registered range, unknown base), NIXIE_EHIP. */
+ * Plans pick the registry up when they are made, and a plan that moves chunks directly holds the
+ * GPU's addresses of the registered memory: until every such plan is destroyed
+ * nixie_tier_unregister returns NIXIE_EBUSY and changes nothing, and the caller must not free the
+ * memory (unregister first, free after it returned 0).  Plans whose chunks all go through the
+ * ring hold nothing.  Errors: NIXIE_EINVAL (NULL, 0 bytes, not pinned host memory, overlaps a
+ * registered range, unknown base), NIXIE_EBUSY, NIXIE_EHIP. */
 int nixie_tier_register(void *host_base, uint64_t bytes);
 int nixie_tier_unregister(void *host_base);
 /* The leg between the pinned and the pageable tier outside a switch (paper, "Speeding Up Context

@@ -28,6 +28,7 @@ struct Layout {
     DirLayout dir[2];                     // 0 = outgoing (GPU -> host), 1 = incoming
     std::vector<nixie_alloc_t> table[2];  // copies of the caller's tables, table order
     std::vector<SpaceUse> uses[2];        // blocks of registered spaces that each table touches
+    std::vector<uint64_t> tier_ids;       // registrations of the pinned tier that direct chunks point into
 };
 
 int build_layout(const nixie_table_t *out_table, const nixie_table_t *in_table, uint64_t ring_bytes,

@@ -192,9 +192,11 @@ int build_layout(const nixie_table_t *out_table, const nixie_table_t *in_table, 
             for (const KeyPiece &p : pieces) dev.push_back({p.key, p.key + p.len});
             host.push_back({h, h + a.bytes});
             tot[x] += a.bytes;
-            uint64_t seen_by_gpu = 0;
-            if (use_tier && tier_translate(h, a.bytes, &seen_by_gpu) && ((seen_by_gpu ^ d) & 15) == 0) direct[x][i] = seen_by_gpu;
-            else staged_tot[x] += a.bytes;
+            uint64_t seen_by_gpu = 0, span_id = 0;
+            if (use_tier && tier_translate(h, a.bytes, &seen_by_gpu, &span_id) && ((seen_by_gpu ^ d) & 15) == 0) {
+                direct[x][i] = seen_by_gpu;
+                if (L.tier_ids.empty() || L.tier_ids.back() != span_id) L.tier_ids.push_back(span_id);
+            } else staged_tot[x] += a.bytes;
         }
     }
     const bool in_place = (L.opts.flags & NIXIE_IN_PLACE) != 0;
@@ -205,6 +207,8 @@ int build_layout(const nixie_table_t *out_table, const nixie_table_t *in_table, 
         return NIXIE_EOVERLAP;
     }
     if (any_overlap(host, mid_host)) return NIXIE_EOVERLAP;
+    std::sort(L.tier_ids.begin(), L.tier_ids.end());
+    L.tier_ids.erase(std::unique(L.tier_ids.begin(), L.tier_ids.end()), L.tier_ids.end());
     for (int x = 0; x < 2; x++) {   // one entry per block of a space that the table touches
         std::sort(L.uses[x].begin(), L.uses[x].end());
         L.uses[x].erase(std::unique(L.uses[x].begin(), L.uses[x].end()), L.uses[x].end());

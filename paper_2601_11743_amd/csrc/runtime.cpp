@@ -81,6 +81,8 @@ struct nixie_plan {
     uint64_t *hashes_d = nullptr;
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
 
+    bool tier_held = false;  // L.tier_ids are counted as in use by this plan
+
     HostSide hs;           // flags, ring and counters as the host threads see them
     HostCrew crew;         // the parked drain / fill threads
     std::mutex switch_mu;  // one switch at a time
@@ -114,6 +116,7 @@ void destroy_plan(nixie_plan_t *p) {
     }
     if (p->counters_d) (void)hipFree(p->counters_d);
     if (p->hashes_d) (void)hipFree(p->hashes_d);
+    if (p->tier_held) tier_release(p->L.tier_ids);
     if (p->shared) p->shared->users.fetch_sub(1);
     else if (p->ring_h) (void)hipHostFree(p->ring_h);
     if (p->ctrl_h) (void)hipHostFree(p->ctrl_h);
@@ -151,6 +154,10 @@ int upload(const void *src, size_t bytes, void **dst) {
 int create_plan(nixie_plan_t *p) {
     const Layout &L = p->L;
     NIXIE_HIP(hipGetDevice(&p->device));
+    // The direct chunks carry raw GPU addresses of pinned-tier memory: from here until the plan is
+    // destroyed its registrations cannot be dropped (nixie_tier_unregister returns NIXIE_EBUSY).
+    if (!tier_acquire(L.tier_ids)) return NIXIE_EINVAL;   // unregistered while the layout was being made
+    p->tier_held = true;
 
     // payload ring: exactly (out_slots + in_slots) * slot_bytes, never more than the budget
     if (p->info.pinned_ring_bytes > L.ring_bytes) return NIXIE_EINVAL;

@@ -20,34 +20,58 @@ SpaceSpan *find_locked(uint64_t addr) {
 }  // namespace
 
 namespace {
-std::vector<TierSpan> g_tiers;            // sorted by host_base, disjoint; under g_mu
+struct TierEntry { TierSpan span; uint64_t id; uint64_t users; };
+std::vector<TierEntry> g_tiers;           // sorted by host_base, disjoint; under g_mu
+uint64_t g_tier_ids = 0;
 }
 
 bool tier_register(const TierSpan &t) {
     std::lock_guard<std::mutex> g(g_mu);
-    auto it = std::upper_bound(g_tiers.begin(), g_tiers.end(), t.host_base, [](uint64_t v, const TierSpan &x) { return v < x.host_base; });
-    if (it != g_tiers.end() && it->host_base < t.host_base + t.bytes) return false;
-    if (it != g_tiers.begin() && (it - 1)->host_base + (it - 1)->bytes > t.host_base) return false;
-    g_tiers.insert(it, t);
+    auto it = std::upper_bound(g_tiers.begin(), g_tiers.end(), t.host_base, [](uint64_t v, const TierEntry &x) { return v < x.span.host_base; });
+    if (it != g_tiers.end() && it->span.host_base < t.host_base + t.bytes) return false;
+    if (it != g_tiers.begin() && (it - 1)->span.host_base + (it - 1)->span.bytes > t.host_base) return false;
+    g_tiers.insert(it, TierEntry{t, ++g_tier_ids, 0});
     return true;
 }
 
-bool tier_unregister(uint64_t host_base) {
+TierDrop tier_unregister(uint64_t host_base) {
     std::lock_guard<std::mutex> g(g_mu);
     for (auto it = g_tiers.begin(); it != g_tiers.end(); ++it)
-        if (it->host_base == host_base) { g_tiers.erase(it); return true; }
-    return false;
+        if (it->span.host_base == host_base) {
+            if (it->users) return kTierInUse;
+            g_tiers.erase(it);
+            return kTierDropped;
+        }
+    return kTierUnknown;
 }
 
-bool tier_translate(uint64_t host_addr, uint64_t bytes, uint64_t *dev_addr) {
+bool tier_translate(uint64_t host_addr, uint64_t bytes, uint64_t *dev_addr, uint64_t *span_id) {
     std::lock_guard<std::mutex> g(g_mu);
     if (g_tiers.empty() || bytes == 0) return false;
-    auto it = std::upper_bound(g_tiers.begin(), g_tiers.end(), host_addr, [](uint64_t v, const TierSpan &x) { return v < x.host_base; });
+    auto it = std::upper_bound(g_tiers.begin(), g_tiers.end(), host_addr, [](uint64_t v, const TierEntry &x) { return v < x.span.host_base; });
     if (it == g_tiers.begin()) return false;
     --it;
-    if (host_addr + bytes > it->host_base + it->bytes) return false;
-    *dev_addr = it->dev_base + (host_addr - it->host_base);
+    if (host_addr + bytes > it->span.host_base + it->span.bytes) return false;
+    *dev_addr = it->span.dev_base + (host_addr - it->span.host_base);
+    if (span_id) *span_id = it->id;
     return true;
+}
+
+bool tier_acquire(const std::vector<uint64_t> &span_ids) {
+    std::lock_guard<std::mutex> g(g_mu);
+    for (uint64_t id : span_ids)
+        if (std::none_of(g_tiers.begin(), g_tiers.end(), [&](const TierEntry &e) { return e.id == id; })) return false;
+    for (uint64_t id : span_ids)
+        for (TierEntry &e : g_tiers)
+            if (e.id == id) e.users++;
+    return true;
+}
+
+void tier_release(const std::vector<uint64_t> &span_ids) {
+    std::lock_guard<std::mutex> g(g_mu);
+    for (uint64_t id : span_ids)
+        for (TierEntry &e : g_tiers)
+            if (e.id == id && e.users) e.users--;
 }
 
 std::shared_mutex &switch_lock() {

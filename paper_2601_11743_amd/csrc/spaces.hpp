@@ -59,9 +59,17 @@ bool space_uses_valid(const std::vector<SpaceUse> &uses);
 // with no ring slot and no host copy.
 struct TierSpan { uint64_t host_base, bytes, dev_base; };   // dev_base: the GPU's address of host_base
 bool tier_register(const TierSpan &t);                       // false: overlaps a registered range
-bool tier_unregister(uint64_t host_base);
-// GPU address of [host_addr, host_addr + bytes) when the range lies wholly inside one registered span
-bool tier_translate(uint64_t host_addr, uint64_t bytes, uint64_t *dev_addr);
+// A plan with direct chunks holds raw GPU addresses of the span, so a span stays registered (and
+// the caller keeps its memory allocated) while such a plan lives.  Every registration has an id
+// of its own; a plan acquires the ids its layout recorded and releases them when it is destroyed.
+enum TierDrop { kTierDropped = 0, kTierUnknown = 1, kTierInUse = 2 };
+TierDrop tier_unregister(uint64_t host_base);
+// GPU address of [host_addr, host_addr + bytes) when the range lies wholly inside one registered
+// span; span_id, when given, receives the id of that registration
+bool tier_translate(uint64_t host_addr, uint64_t bytes, uint64_t *dev_addr, uint64_t *span_id = nullptr);
+// all or nothing: false (and nothing counted) when one of the registrations is gone
+bool tier_acquire(const std::vector<uint64_t> &span_ids);
+void tier_release(const std::vector<uint64_t> &span_ids);
 
 // Held shared by a running switch (and by the hash kernels), exclusively by map / unmap.
 std::shared_mutex &switch_lock();

@@ -109,7 +109,11 @@ int nixie_tier_register(void *host_base, uint64_t bytes) {
 
 int nixie_tier_unregister(void *host_base) {
     if (!host_base) return NIXIE_EINVAL;
-    return tier_unregister((uint64_t)(uintptr_t)host_base) ? NIXIE_OK : NIXIE_EINVAL;
+    switch (tier_unregister((uint64_t)(uintptr_t)host_base)) {
+    case kTierDropped: return NIXIE_OK;
+    case kTierInUse: return NIXIE_EBUSY;   // a live plan moves chunks straight to or from this memory
+    default: return NIXIE_EINVAL;
+    }
 }
 
 // ---- pools and spaces ---------------------------------------------------------------------------

@@ -333,6 +333,19 @@ int run(const std::string &scenario, uint64_t seed) {
                         L.dir[0].slots);
             return 1;
         }
+        // a plan made from this layout would hold both registrations: no unregistering under it
+        const uint64_t ha = (uint64_t)(uintptr_t)A.host.data(), hb = (uint64_t)(uintptr_t)B.host.data();
+        if (L.tier_ids.size() != (a_congruent ? 2u : 1u) || !tier_acquire(L.tier_ids) || tier_unregister(hb) != kTierInUse ||
+            (a_congruent && tier_unregister(ha) != kTierInUse) || tier_unregister(hb + 8) != kTierUnknown) {
+            std::printf("tier lifetime: a registration in use was dropped\n");
+            return 1;
+        }
+        tier_release(L.tier_ids);
+        if (tier_unregister(hb) != kTierDropped || tier_acquire(L.tier_ids) ||                 // gone: all or nothing
+            !tier_register(TierSpan{hb, B.host.size() / 2, hb}) || tier_acquire(L.tier_ids)) {  // a new registration is a new id
+            std::printf("tier lifetime: stale registration acquired\n");
+            return 1;
+        }
         nixie_opts_t off = o;   // the same tables with the tier ignored: everything is staged
         off.flags |= NIXIE_NO_DIRECT;
         Layout L2;

@@ -68,6 +68,37 @@ def test_registration_errors(nx):
         nx.tier_unregister(base)
 
 
+def test_registration_in_use_cannot_be_dropped(nx):
+    """A plan with direct chunks holds GPU addresses of the registered memory: while it lives the
+    registration stays (NIXIE_EBUSY), so a later switch can never touch freed pinned memory.  A plan
+    whose chunks are all staged holds nothing."""
+    from tests.gpu_helpers import GpuSet
+    g = GpuSet([3 * S + 5, 100], 5, "dev")
+    pin = Pinned(g.hs.host.size)
+    move_host_arena(g.hs, pin)
+    base = pin.a.ctypes.data
+    nx.tier_register(base, g.hs.host.size)
+    staged = nx.Plan(g.rows(), [], 8 * S, nx.Opts(slot_bytes=S, flags=nx.NO_DIRECT))
+    nx.tier_unregister(base)                              # nothing points into it
+    nx.tier_register(base, g.hs.host.size)
+    plan = nx.Plan(g.rows(), [], 0, nx.Opts(slot_bytes=S))
+    assert plan.info()["direct_bytes_out"] == sum(g.hs.sizes)
+    second = nx.Plan(g.rows(), [], 0, nx.Opts(slot_bytes=S))
+    for _ in range(2):
+        with pytest.raises(nx.NixieError) as e:
+            nx.tier_unregister(base)
+        assert e.value.code == nx.EBUSY
+    plan.switch()                                         # still valid, still correct
+    g.hs.check_moved()
+    plan.close()
+    with pytest.raises(nx.NixieError) as e:
+        nx.tier_unregister(base)                          # the second plan still holds it
+    assert e.value.code == nx.EBUSY
+    second.close()
+    staged.close()
+    nx.tier_unregister(base)
+
+
 CASES = {
     # name: (A pinned fraction, B pinned fraction, skew (dev, host), ring bytes, flags, expectation)
     "all_direct_no_ring": (1.0, 1.0, (0, 0), 0, 0, "direct"),

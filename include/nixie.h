@@ -100,7 +100,11 @@ typedef struct {
     uint32_t team;           /* workgroups that share one chunk; default one per 16-128 KiB of slot, at most 256 */
     uint32_t drain_threads;  /* host threads moving ring -> pageable; default min(4, cores / 4), at least 1   */
     uint32_t fill_threads;   /* host threads moving pageable -> ring; same default                           */
-    uint32_t timeout_ms;     /* bound on any single credit wait, host or GPU side; default 30000            */
+    uint32_t timeout_ms;     /* bound on any single credit wait, host or GPU side; default 30000.  It is a
+                                bound on time without progress, not on the length of a switch: a caller waiting
+                                for a whole direction gives up only after this long with no chunk claimed,
+                                delivered or handed out.  Until the kernel is seen running (it may be queued
+                                behind earlier work on the stream) host threads allow four times as long     */
     uint32_t flags;          /* enum nixie_flags                                                            */
     uint32_t xcd_mask;       /* tuning: bit i set = workgroups that land on XCD i take part, the others leave at
                                 once (workgroups are dealt round-robin over the 8 XCDs, so raise gather_wgs /

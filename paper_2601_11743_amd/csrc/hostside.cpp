@@ -57,6 +57,8 @@ struct IdleWatch {
     uint32_t spins = 0;
     bool force_yield = false;   // for a waiter that is not one of the crew's threads
     uint64_t nap_ns = ~0ull;    // ~0: the plan's setting
+    bool account = true;        // idle time counts towards the direction's wait_ns
+    bool started = false;       // the kernel has been seen running
     // call after a scan that made no progress; false = stop
     bool idle() {
         // Spin: a slot usually turns around in microseconds.  Only where the threads outnumber
@@ -74,14 +76,22 @@ struct IdleWatch {
         if (idle_since == 0) idle_since = now_ns();
         if ((++spins & 63u) != 0) return true;
         if (p->abort_local.load(std::memory_order_acquire)) return false;
-        if (__atomic_load_n(p->status_word, __ATOMIC_ACQUIRE) != kGpuOk || now_ns() - idle_since > p->timeout_ns) {
+        // The bound is on a credit wait.  While the kernel has not been seen running (it may be queued
+        // behind the caller's earlier work on the stream) the thread waits longer, and the clock of
+        // the credit wait starts when the kernel does.
+        if (!started && __atomic_load_n(p->done_word + kStartedWord, __ATOMIC_ACQUIRE)) {
+            started = true;
+            idle_since = now_ns();
+        }
+        const uint64_t bound = started ? p->timeout_ns : kStartGrace * p->timeout_ns;
+        if (__atomic_load_n(p->status_word, __ATOMIC_ACQUIRE) != kGpuOk || now_ns() - idle_since > bound) {
             p->raise_abort(NIXIE_ETIMEOUT);
             return false;
         }
         return true;
     }
     void progressed() {
-        if (idle_since) p->wait_ns[dir].fetch_add(now_ns() - idle_since, std::memory_order_relaxed);
+        if (idle_since && account) p->wait_ns[dir].fetch_add(now_ns() - idle_since, std::memory_order_relaxed);
         idle_since = 0;
         spins = 0;
     }
@@ -187,9 +197,18 @@ int HostSide::wait_direction(int x, uint64_t nap_ns) {
     IdleWatch watch{this, x};
     watch.force_yield = true;
     watch.nap_ns = nap_ns;
+    watch.account = false;
     int rc = NIXIE_OK;
+    // The bound is on the time without any sign of progress, not on the length of the direction:
+    // chunks claimed or delivered by the host threads, or work units handed out on the GPU.
+    uint64_t seen = 0;
     while (__atomic_load_n(done_word + x, __ATOMIC_ACQUIRE) == 0) {
-        if (!watch.idle()) break;
+        const uint64_t sign = done_chunks[x].load(std::memory_order_relaxed) + next_chunk[x].load(std::memory_order_relaxed) +
+                              __atomic_load_n(done_word + kProgressWord + x, __ATOMIC_RELAXED);
+        if (sign != seen) {
+            seen = sign;
+            watch.progressed();
+        } else if (!watch.idle()) break;
     }
     if (__atomic_load_n(done_word + x, __ATOMIC_ACQUIRE) == 0 || error.load() ||
         __atomic_load_n(status_word, __ATOMIC_ACQUIRE) != kGpuOk)

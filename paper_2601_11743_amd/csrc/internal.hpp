@@ -54,6 +54,15 @@ inline uint64_t wait_flag_words(uint32_t slots) { return ((uint64_t)slots + 7) /
 constexpr uint32_t kWgThreads = 256;
 constexpr uint32_t kTileBytes = 8192;
 
+// Words of the GPU-written "done" line (u32 each): [0], [1] = 1 once every workgroup of direction
+// 0 / 1 has left; [kStartedWord] = 1 once the kernel runs (until then a waiting host thread is
+// looking at queue delay, not at a stalled credit); [kProgressWord + x] = work units of direction
+// x handed out so far, refreshed by the pump now and then (a sign of life for a waiter that sees
+// no slot traffic, e.g. when every chunk moves directly).
+constexpr uint32_t kStartedWord = 2, kProgressWord = 4;
+// a host thread that has not yet seen the kernel start waits this many times the credit bound
+constexpr uint64_t kStartGrace = 4;
+
 // gpu_status values (host-visible word written by the kernel when it stops early)
 enum : uint32_t { kGpuOk = 0, kGpuSawAbort = 1, kGpuTimeout = 2 };
 
@@ -84,7 +93,7 @@ struct SwapArgs {
     uint32_t *gathered_prefix;   // device memory: number of leading outgoing chunks that have left HBM
     uint32_t track_prefix;       // 1: in-place switch with both directions running in this launch
     uint32_t xcd_mask;           // 0 = every XCD takes part
-    uint32_t *dir_done;          // pinned, GPU-written: [x] = 1 once every workgroup of direction x has left
+    uint32_t *dir_done;          // pinned, GPU-written "done" line: see kStartedWord / kProgressWord
 };
 
 struct HashDesc { uint64_t ptr; uint64_t bytes; uint64_t first_tile; };

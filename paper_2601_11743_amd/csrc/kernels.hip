@@ -273,6 +273,7 @@ __device__ void run_pump(const SwapArgs &a, int dir) {
     uint32_t next = 0;     // outgoing: next chunk without a slot (wave-uniform)
     uint32_t prefix = 0;   // outgoing, in-place switch: leading chunks that have left HBM (wave-uniform)
     const bool track = dir == 0 && a.track_prefix;
+    uint32_t rounds = 0, told = 0;   // sign of life for the host: units handed out, every 32nd round if it moved
     auto advance_prefix = [&]() {   // up to 64 chunks per call; true if it moved
         const uint32_t k = prefix + lane;
         const bool done = k < D.n_chunks &&
@@ -316,6 +317,12 @@ __device__ void run_pump(const SwapArgs &a, int dir) {
             __hip_atomic_store(a.gpu_status, (uint32_t)kGpuSawAbort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
         }
         if (track) advance_prefix();
+        if ((++rounds & 31u) == 0) {
+            const uint32_t t = __hip_atomic_load(D.ticket, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (t != told && lane == 0)
+                __hip_atomic_store(a.dir_done + kProgressWord + dir, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            told = t;
+        }
         if (__hip_atomic_load(D.exited, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= D.wgs) {
             // every gather workgroup has left, so every arrive counter is final: publish the rest
             // (bounded: at most n_chunks / 64 + 1 rounds)
@@ -332,6 +339,8 @@ __device__ void run_pump(const SwapArgs &a, int dir) {
 __global__ void __launch_bounds__(kWgThreads) nixie_swap_kernel(SwapArgs a) {
     if (blockIdx.x == 0) {
         const uint32_t wave = threadIdx.x >> 6;
+        if (threadIdx.x == 0)   // from here on a host thread's wait is a credit wait, not queue delay
+            __hip_atomic_store(a.dir_done + kStartedWord, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
         if (wave < 2) run_pump(a, (int)wave);
         return;
     }

@@ -134,6 +134,7 @@ struct FakeGpu {
                 dev_abort.store(1, std::memory_order_release);
                 __atomic_store_n(status, (uint32_t)kGpuSawAbort, __ATOMIC_RELEASE);
             }
+            __atomic_store_n(done + kProgressWord + dir, ticket[dir].load(std::memory_order_relaxed), __ATOMIC_RELAXED);
             if (exited[dir].load(std::memory_order_acquire) >= wgs[dir]) {
                 __atomic_store_n(done + dir, 1u, __ATOMIC_RELEASE);
                 break;
@@ -153,6 +154,7 @@ struct FakeGpu {
             if (n == 0) wgs[x] = 0;
         }
         if (never_start) return;
+        __atomic_store_n(done + kStartedWord, 1u, __ATOMIC_RELEASE);
         if (quit_early) {   // the kernel hit its own wait bound
             __atomic_store_n(status, (uint32_t)kGpuTimeout, __ATOMIC_RELEASE);
             return;

@@ -34,23 +34,5 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
-PROBE = os.path.join(HERE, "nixie_linkprobe")
-
-
-def build_linkprobe(verbose: bool = False) -> str:
-    """The stand-alone link probe (measurements behind the kernel design); not needed by the library."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, "-O3", "-std=c++17", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
-           "-packed-fp32-ops", "-o", PROBE, os.path.join(HERE, "tools", "linkprobe.hip")]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    res = subprocess.run(cmd, capture_output=True, text=True)
-    if res.returncode != 0:
-        sys.stderr.write(res.stderr + "\n")
-        raise RuntimeError("hipcc failed building nixie_linkprobe")
-    return PROBE
-
-
 if __name__ == "__main__":
     print(build(verbose=True))
-    print(build_linkprobe(verbose=True))

@@ -282,6 +282,23 @@ int nixie_verify(const nixie_plan_t *plan, void *hip_stream, const uint64_t *exp
 int nixie_hash_buffers(const void *const *ptrs, const uint64_t *bytes, uint64_t n, int on_device,
                        void *hip_stream, uint64_t *hashes);
 
+/* nixie_hash_buffers for DEVICE buffers, for callers that cannot allocate: code between the
+ * begin and end of a HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * It calls no hipMalloc / hipFree or other allocating routine and copies nothing between host and
+ * device: the descriptor table reaches the GPU as kernel arguments, and it and the per-buffer
+ * sums live in 128 KiB of static device memory that every GPU the library is used on holds until
+ * the process ends.
+ * ptrs, bytes: HOST arrays of n (ptrs[i] a DEVICE address).  hashes_dev: DEVICE array of n,
+ * caller-owned; hashes_dev[i] = H(buffer i) once the work enqueued on hip_stream has run.
+ * The call only enqueues kernels on hip_stream and returns; the buffers, and the mapping of any
+ * space they lie in, must stay as they are until that work is complete.
+ * n > 4096: NIXIE_EINVAL (use nixie_hash_buffers).  Other errors as nixie_hash_buffers.
+ * All calls on one GPU share the static memory: calls on the same stream run one after the
+ * other and are fine; calls whose kernels could overlap on one GPU (different streams, no
+ * dependency between them) race and give wrong hashes. */
+int nixie_hash_buffers_noalloc(const void *const *ptrs, const uint64_t *bytes, uint64_t n, void *hip_stream,
+                               uint64_t *hashes_dev);
+
 /* ---- stable device addresses over shared physical memory (paper, "Maintaining consistent
  *      virtual memory addresses": addresses are reserved once and mapped to different
  *      physical allocations before and after a migration; "Granularity of Memory

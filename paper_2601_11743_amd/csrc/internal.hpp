@@ -98,6 +98,7 @@ struct SwapArgs {
 
 struct HashDesc { uint64_t ptr; uint64_t bytes; uint64_t first_tile; };
 constexpr uint32_t kHashTileWords = 4096;   // 32 KiB per tile
+constexpr uint32_t kNoAllocMaxBuffers = 4096;   // nixie_hash_buffers_noalloc: 128 KiB of static device memory
 
 }  // namespace nixie
 
@@ -108,4 +109,7 @@ int nixie_launch_zero32(uint32_t *p, uint64_t n, void *stream);
 int nixie_launch_hash(const nixie::HashDesc *descs, uint64_t n, uint64_t total_tiles, uint64_t *hashes,
                       void *stream);
 int nixie_launch_copy16(const void *src, void *dst, uint64_t bytes, uint32_t wgs, void *stream);
+int nixie_noalloc_scratch(void **out);   // this device's address of the static scratch array
+int nixie_launch_hash_noalloc(const nixie::HashDesc *descs, uint32_t n, uint64_t total_tiles, uint64_t *out_d,
+                              void *stream);
 }

@@ -35,6 +35,8 @@
 // wall-clock limit) and the pump leaves once all workers have, so the grid always drains.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "internal.hpp"
 
 using namespace nixie;
@@ -433,7 +435,87 @@ __global__ void __launch_bounds__(256) nixie_copy16_kernel(const u32x4 *__restri
     }
 }
 
+// ---- hashing without allocation -------------------------------------------------------------
+// The descriptor table and the per-buffer sums of nixie_hash_buffers live in device memory that
+// the call allocates and frees.  The variant below keeps them in this array instead, so that it
+// can be called where nothing may be allocated.  One copy of the array exists on every GPU the
+// library runs on, from the moment the code object is loaded until the process ends.
+struct HashScratch {
+    HashDesc descs[kNoAllocMaxBuffers];
+    uint64_t sums[kNoAllocMaxBuffers];
+};
+static __device__ __align__(256) unsigned char scratch[sizeof(HashScratch)];
+
+// Descriptors travel as kernel arguments (by value), 128 at a time: no staging copy, nothing for
+// the runtime to allocate.  Each launch writes its batch and clears the matching sums.
+constexpr uint32_t kDescBatch = 128;
+struct DescBatch { HashDesc d[kDescBatch]; };
+static_assert(sizeof(DescBatch) + 32 <= 4096, "a batch must fit the kernel argument buffer");
+
+__global__ void __launch_bounds__(kDescBatch) nixie_put_descs_kernel(DescBatch b, uint32_t count, HashScratch *hs,
+                                                                      uint32_t first) {
+    const uint32_t i = threadIdx.x;
+    if (i < count) {
+        hs->descs[first + i] = b.d[i];
+        hs->sums[first + i] = 0;
+    }
+}
+
+__global__ void __launch_bounds__(256) nixie_copy64_kernel(const uint64_t *src, uint64_t *dst, uint32_t n) {
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = src[i];
+}
+
 }  // namespace
+
+// The array's name is only a handle on the host; its address differs from GPU to GPU and is asked
+// for once per device, with that device current.
+int nixie_noalloc_scratch(void **out) {
+    constexpr int kMaxDevices = 64;
+    static void *addr[kMaxDevices];
+    static std::mutex mu;
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return (int)e;
+    if (dev < 0 || dev >= kMaxDevices) return (int)hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> g(mu);
+    if (!addr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return (int)e;
+        if (!ptr) return (int)hipErrorInvalidSymbol;
+        addr[dev] = ptr;
+    }
+    *out = addr[dev];
+    return (int)hipSuccess;
+}
+
+// descs: HOST array of n <= kNoAllocMaxBuffers entries with first_tile filled in; out_d: DEVICE
+// array of n.  Enqueues on stream and returns; nothing is allocated, copied or waited for.
+int nixie_launch_hash_noalloc(const HashDesc *descs, uint32_t n, uint64_t total_tiles, uint64_t *out_d, void *stream) {
+    void *base = nullptr;
+    int e = nixie_noalloc_scratch(&base);
+    if (e) return e;
+    HashScratch *hs = (HashScratch *)base;
+    hipStream_t st = (hipStream_t)stream;
+    for (uint32_t first = 0; first < n; first += kDescBatch) {
+        DescBatch b;
+        const uint32_t count = n - first < kDescBatch ? n - first : kDescBatch;
+        for (uint32_t i = 0; i < count; i++) b.d[i] = descs[first + i];
+        for (uint32_t i = count; i < kDescBatch; i++) b.d[i] = HashDesc{0, 0, 0};
+        nixie_put_descs_kernel<<<1, kDescBatch, 0, st>>>(b, count, hs, first);
+        e = (int)hipGetLastError();
+        if (e) return e;
+    }
+    if (total_tiles) {
+        const uint32_t grid = (uint32_t)(total_tiles < 4096 ? total_tiles : 4096);
+        nixie_hash_kernel<<<grid, 256, 0, st>>>(hs->descs, n, total_tiles, hs->sums);
+        e = (int)hipGetLastError();
+        if (e) return e;
+    }
+    nixie_copy64_kernel<<<(n + 255) / 256, 256, 0, st>>>(hs->sums, out_d, n);
+    return (int)hipGetLastError();
+}
 
 int nixie_launch_swap(const SwapArgs &a, void *stream) {
     if (a.d[0].wgs + a.d[1].wgs == 0) return (int)hipSuccess;

@@ -142,6 +142,20 @@ bool space_translate(uint64_t addr, uint64_t bytes, std::vector<KeyPiece> *piece
     return true;
 }
 
+int space_range_state(uint64_t addr, uint64_t bytes) {
+    std::lock_guard<std::mutex> g(g_mu);
+    if (bytes == 0) return 0;
+    SpaceSpan *s = find_locked(addr);
+    if (!s) {
+        auto it = std::upper_bound(g_spaces.begin(), g_spaces.end(), addr, [](uint64_t v, const SpaceSpan &x) { return v < x.base; });
+        return it != g_spaces.end() && addr + bytes > it->base ? 2 : 0;
+    }
+    if (addr + bytes > s->base + s->bytes) return 2;
+    for (uint64_t blk = (addr - s->base) / s->block_bytes; blk <= (addr + bytes - 1 - s->base) / s->block_bytes; blk++)
+        if (!s->mapped[blk]) return 1;
+    return 0;
+}
+
 bool space_uses_valid(const std::vector<SpaceUse> &uses) {
     std::lock_guard<std::mutex> g(g_mu);
     for (const SpaceUse &u : uses) {

@@ -48,6 +48,9 @@ bool space_assign(uint64_t base, uint64_t first, const uint64_t *pool_blocks, ui
 // merged; one piece {addr, bytes} when the range touches no space).  Returns false when the
 // range straddles the edge of a space.  uses, when given, receives the blocks the range occupies.
 bool space_translate(uint64_t addr, uint64_t bytes, std::vector<KeyPiece> *pieces, std::vector<SpaceUse> *uses);
+// The same question without building anything (no heap use): 0 = the range touches no space or lies
+// in mapped blocks of one, 1 = it touches an unmapped block, 2 = it straddles the edge of a space.
+int space_range_state(uint64_t addr, uint64_t bytes);
 // True when every block is mapped right now and backed by the pool block recorded in its use.
 bool space_uses_valid(const std::vector<SpaceUse> &uses);
 

@@ -148,6 +148,26 @@ int nixie_hash_buffers(const void *const *ptrs, const uint64_t *bytes, uint64_t 
     return rc;
 }
 
+int nixie_hash_buffers_noalloc(const void *const *ptrs, const uint64_t *bytes, uint64_t n, void *hip_stream,
+                               uint64_t *hashes_dev) {
+    if (n == 0) return NIXIE_OK;
+    if (!ptrs || !bytes || !hashes_dev) return NIXIE_EINVAL;
+    if (n > kNoAllocMaxBuffers) return NIXIE_EINVAL;   // beyond the static scratch memory: use nixie_hash_buffers
+    static thread_local HashDesc hd[kNoAllocMaxBuffers];   // host side of the table: no heap either
+    std::shared_lock<std::shared_mutex> maps(switch_lock());
+    uint64_t tiles = 0;
+    for (uint64_t i = 0; i < n; i++) {
+        if (bytes[i] && !ptrs[i]) return NIXIE_EINVAL;
+        const int where = space_range_state((uint64_t)(uintptr_t)ptrs[i], bytes[i]);
+        if (where) return where == 1 ? NIXIE_EUNMAPPED : NIXIE_EINVAL;
+        hd[i] = HashDesc{(uint64_t)(uintptr_t)ptrs[i], bytes[i], tiles};
+        tiles += ((bytes[i] + 7) / 8 + kHashTileWords - 1) / kHashTileWords;
+    }
+    const int e = nixie_launch_hash_noalloc(hd, (uint32_t)n, tiles, hashes_dev, hip_stream);
+    if (e) { set_last_hip_error(e); return NIXIE_EHIP; }
+    return NIXIE_OK;
+}
+
 int nixie_host_copy(void *const *dst, const void *const *src, const uint64_t *bytes, uint64_t n, uint32_t threads) {
     if (n == 0) return NIXIE_OK;
     if (!dst || !src || !bytes) return NIXIE_EINVAL;

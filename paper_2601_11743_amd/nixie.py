@@ -26,6 +26,7 @@ DECLARED_SYMBOLS = (
     "nixie_tier_register", "nixie_tier_unregister", "nixie_host_copy", "nixie_place",
     "nixie_switch_begin", "nixie_switch_wait_in", "nixie_switch_end",
     "nixie_ring_create", "nixie_ring_destroy", "nixie_plan_on_ring",
+    "nixie_hash_buffers_noalloc",
 )
 
 
@@ -157,6 +158,7 @@ def lib() -> C.CDLL:
     L.nixie_hash_tables.argtypes = [vp, vp, vp, vp]
     L.nixie_verify.argtypes = [vp, vp, vp, vp, C.POINTER(_Report)]
     L.nixie_hash_buffers.argtypes = [vp, vp, u64, i32, vp, vp]
+    L.nixie_hash_buffers_noalloc.argtypes = [vp, vp, u64, vp, vp]
     L.nixie_link_peak.argtypes = [u64, i32, C.POINTER(_LinkPeak)]
     L.nixie_sched_create.argtypes = [C.POINTER(_SchedParams), C.POINTER(vp)]
     L.nixie_sched_destroy.argtypes = [vp]
@@ -389,6 +391,16 @@ def hash_buffers(ptrs: Sequence[int], sizes: Sequence[int], on_device: bool, str
         if rc:
             raise NixieError(rc, "nixie_hash_buffers")
     return h[:n]
+
+
+def hash_buffers_noalloc(ptrs: Sequence[int], sizes: Sequence[int], hashes_dev: int, stream: int = 0) -> None:
+    """Enqueue the hashing of device buffers on stream; hashes_dev: device address of len(ptrs) uint64."""
+    n = len(ptrs)
+    p = np.asarray(list(ptrs), dtype=np.uint64)
+    b = np.asarray(list(sizes), dtype=np.uint64)
+    rc = lib().nixie_hash_buffers_noalloc(p.ctypes.data, b.ctypes.data, n, C.c_void_p(stream), C.c_void_p(hashes_dev))
+    if rc:
+        raise NixieError(rc, "nixie_hash_buffers_noalloc")
 
 
 def link_peak(nbytes: int = 1 << 30, reps: int = 5) -> dict:

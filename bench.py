@@ -6,6 +6,12 @@ runs, then nixie_switch evicts application A (8B bf16 decoder + 2 GiB KV cache, 
 allocations) to pageable memory while bringing application B (same shapes, other seed) into HBM,
 through a 256 MiB pinned ring in 4 MiB slots.  Inputs are resident (A in HBM, B in pageable
 memory) before the timed region.  Prints one JSON line.
+
+Without --config the same line also carries a "configs" list: the metric taken literally (config 6,
+64 x 256 MiB each way), the asymmetric (3), fragmented (4) and tiny (1) configs, and config 5's
+pinned-budget sweep (rings of 16 / 64 / 256 / 1024 MiB, 10 ping-pong switches each), every one
+in the library's default launch configuration, verified by per-allocation hashes and, except for the
+sweep, a whole-arena compare.
 """
 from __future__ import annotations
 
@@ -75,10 +81,20 @@ def cpu_baseline(cf, sample_bytes: int) -> dict:
     }
 
 
-def read_traffic(path: str):
-    """HBM bytes per launch of the swap kernel from the committed rocprofv3 --pmc summary."""
+# committed rocprofv3 --pmc summaries, by (config, ring MiB): the counters were read on exactly that workload
+PMC_SUMMARIES = {(2, 256): "nixie_swap_kernel_llm_pmc.txt",
+                 (4, 64): "nixie_swap_kernel_fragmented_pmc.txt",
+                 (5, 16): "nixie_swap_kernel_budget16_pmc.txt"}
+
+
+def read_traffic(config: int, ring_bytes: int, plain: bool):
+    """HBM bytes per launch of the swap kernel from the committed rocprofv3 --pmc summary of this
+    very workload, or None when no counters were taken on it (or options changed the run)."""
+    name = PMC_SUMMARIES.get((config, ring_bytes >> 20))
+    if not name or not plain:
+        return None
     try:
-        for line in open(path):
+        for line in open(os.path.join(ROOT, "profiles", name)):
             if line.startswith("traffic_bytes_per_launch:"):
                 return float(line.split(":", 1)[1].split()[0])
     except OSError:
@@ -86,13 +102,114 @@ def read_traffic(path: str):
     return None
 
 
+def summarize(stats, info, peak) -> dict:
+    """Latency, rates and stall sums of a list of nixie_stats dicts (one per switch)."""
+    med = lambda v: sorted(v)[len(v) // 2]
+    lat = sorted(s["ns_total"] / 1e6 for s in stats)
+    out_gbs = med([s["bytes_out"] / max(1, s["ns_out_done"]) for s in stats]) if info["bytes_out"] else 0.0
+    in_gbs = med([s["bytes_in"] / max(1, s["ns_in_done"]) for s in stats]) if info["bytes_in"] else 0.0
+    r = {"latency_ms": {"min": round(lat[0], 3), "median": round(med(lat), 3), "max": round(lat[-1], 3)},
+         "bidir_GBps": round((info["bytes_out"] + info["bytes_in"]) / med(lat) / 1e6, 3),
+         "out_GBps": round(out_gbs, 3), "in_GBps": round(in_gbs, 3),
+         "b_ready_ms": round(med([s["ns_in_done"] / 1e6 for s in stats]), 3),
+         "kernel_ms": round(med([s["ns_kernel"] / 1e6 for s in stats]), 3),
+         "stalls": {"drain_wait_ms": round(med([s["drain_wait_ns"] for s in stats]) / 1e6, 2),
+                    "fill_wait_ms": round(med([s["fill_wait_ns"] for s in stats]) / 1e6, 2),
+                    "gather_stall_ms_sum": round(med([s["gather_stall_ticks"] for s in stats]) / 1e5, 2),
+                    "scatter_stall_ms_sum": round(med([s["scatter_stall_ticks"] for s in stats]) / 1e5, 2)}}
+    if peak:
+        r["out_frac_of_unidirectional_peak"] = round(out_gbs / peak["sdma_d2h"], 4)
+        r["in_frac_of_unidirectional_peak"] = round(in_gbs / peak["sdma_h2d"], 4)
+    return r
+
+
+def workload_name(W, cfg_id, A, B, info, ring) -> str:
+    return (f"config {cfg_id} ({W.CONFIG_NAMES[cfg_id]}): {info['bytes_out'] / 2**30:.2f} GiB out in {len(A.sizes)} "
+            f"allocations / {info['bytes_in'] / 2**30:.2f} GiB in in {len(B.sizes)} allocations, "
+            f"ring {ring >> 20} MiB in {info['slot_bytes'] >> 10} KiB slots")
+
+
+def ring_sweep(nx, rows_a, rows_b, rings, opts, h_a, h_b, peak, log, switches: int = 10) -> list:
+    """Config 5 protocol: per ring size a warm-up round trip, then `switches` back-to-back ping-pong
+    switches A<->B over the same buffers, hashes checked at the end (A is back in HBM, B in
+    pageable memory after an even number)."""
+    out = []
+    for r in rings:
+        fwd, rev = nx.Plan(rows_a, rows_b, r, opts), nx.Plan(rows_b, rows_a, r, opts)
+        fwd.switch(); rev.switch()
+        sts = [(fwd if t % 2 == 0 else rev).switch() for t in range(switches)]
+        rep = (rev if switches % 2 == 0 else fwd).verify(*((h_b, h_a) if switches % 2 == 0 else (h_a, h_b)), check=False)
+        pi = fwd.info()
+        row = {"ring_mib": r >> 20, "slot_kib": pi["slot_bytes"] >> 10,
+               "pinned_bytes": pi["pinned_ring_bytes"] + pi["pinned_ctrl_bytes"], "switches": switches,
+               **summarize(sts, pi, peak),
+               "hash_mismatches": rep["mismatched_out"] + rep["mismatched_in"]}
+        fwd.close(); rev.close()
+        out.append(row)
+        log("[bench] ring sweep:", row)
+    return out
+
+
+def extra_config(nx, W, torch, cfg_id: int, peak, log) -> dict:
+    """One of the other benchmark configs, in the library's default launch configuration: built,
+    switched (1 warm-up + timed), verified by per-allocation hashes and a whole-arena compare."""
+    from workloads.device import BigSet
+    cf = W.config(cfg_id)
+    t0 = time.perf_counter()
+    A = BigSet(cf["A"], cf["seed_A"], "dev", cf["content"])
+    B = BigSet(cf["B"], cf["seed_B"], "host", cf["content"])
+    rows_a, rows_b = A.rows_np(), B.rows_np()
+    opts = nx.Opts(slot_bytes=cf["slot_bytes"] or 0)
+    res = {"config": cfg_id, "build_s": round(time.perf_counter() - t0, 1)}
+    if cfg_id == 5:
+        probe = nx.Plan(rows_a, rows_b, cf["ring_bytes"][0], opts)
+        h_a, h_b = probe.hash_tables()
+        res["workload"] = workload_name(W, cfg_id, A, B, probe.info(), cf["ring_bytes"][0]) + " (ring swept)"
+        probe.close()
+        res["ring_sweep"] = ring_sweep(nx, rows_a, rows_b, cf["ring_bytes"], opts, h_a, h_b, peak, log)
+        res["verified"] = {"hash_mismatches": sum(r["hash_mismatches"] for r in res["ring_sweep"]),
+                           "full_buffer_equal": None,
+                           "note": "after each ring size's 10 switches A is back in HBM and B in pageable memory: "
+                                   "per-allocation hashes of both against the hashes taken before the first switch"}
+    else:
+        ring = cf["ring_bytes"][0]
+        plan = nx.Plan(rows_a, rows_b, ring, opts)
+        info = plan.info()
+        h_out, h_in = plan.hash_tables()
+        steps = 20 if cfg_id == 1 else 5
+
+        def step():
+            nx.Layout(rows_a, rows_b, ring, opts).close()      # the chunk planner is part of every step
+            return plan.switch()
+        step()
+        t1 = time.perf_counter()
+        stats = [step() for _ in range(steps)]
+        ms = (time.perf_counter() - t1) / steps * 1e3
+        rep = plan.verify(h_out, h_in, check=False)
+        equal = bool(A.arenas_equal() and B.arenas_equal())
+        plan.close()
+        res.update(workload=workload_name(W, cfg_id, A, B, info, ring), steps=steps, ms_per_step=round(ms, 3),
+                   **summarize(stats, info, peak),
+                   pinned_bytes=info["pinned_ring_bytes"] + info["pinned_ctrl_bytes"],
+                   traffic=read_traffic(cfg_id, ring, True),
+                   algorithmic_bytes_per_launch=info["bytes_out"] + info["bytes_in"],
+                   verified={"hash_mismatches": rep["mismatched_out"] + rep["mismatched_in"], "full_buffer_equal": equal})
+    del A, B
+    torch.cuda.empty_cache()
+    log(f"[bench] config {cfg_id}:", {k: v for k, v in res.items() if k != "ring_sweep"})
+    return res
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--config", type=int, default=2,
-                    help="benchmark config 1..5 (2 = headline); 6 = exactly 16 GiB out / 16 GiB in as 64 x 256 MiB")
+    ap.add_argument("--config", type=int, default=0,
+                    help="run only this benchmark config: 1..5 (2 = headline); 6 = exactly 16 GiB out / 16 GiB in as "
+                         "64 x 256 MiB.  Default: the headline config 2 as the timed steps, then configs 6, 3, 4, 1 "
+                         "and the ring sweep of config 5 as a 'configs' list in the same JSON line")
+    ap.add_argument("--no-extras", action="store_true", help="default run without the 'configs' list")
     ap.add_argument("--no-serialized", action="store_true",
                     help="skip the serialised self-baseline (evict completely, then restore)")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink all sizes (debug only)")
@@ -146,6 +263,12 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     nx.lib()
     torch.cuda.set_device(0)
+    plain_run = (args.config in (0, 2) and not (args.ring_mib or args.slot_kib or args.gather_wgs or args.scatter_wgs or
+                 args.team or args.flags or args.order or args.in_place or args.spaces or args.pinned_tier != "none" or
+                 args.scale != 1.0))
+    with_extras = args.config == 0 and not args.no_extras and plain_run
+    if args.config == 0:
+        args.config = 2
     cf = W.config(args.config, scale=args.scale)
     ring = (args.ring_mib << 20) if args.ring_mib else cf["ring_bytes"][min(2, len(cf["ring_bytes"]) - 1)]
     slot = (args.slot_kib << 10) if args.slot_kib else (cf["slot_bytes"] or 0)
@@ -291,22 +414,7 @@ def main() -> int:
 
     sweep = None
     if args.ring_sweep:
-        sweep = []
-        for r in cf["ring_bytes"]:
-            fwd, rev = nx.Plan(rows_a, rows_b, r, opts), nx.Plan(rows_b, rows_a, r, opts)
-            fwd.switch(); rev.switch()                   # warm-up round trip
-            sts = []
-            for t in range(10):
-                sts.append((fwd if t % 2 == 0 else rev).switch())
-            rev.verify(h_in, h_out)                      # 10 switches end with A back in HBM, B in pageable memory
-            pi = fwd.info()
-            msl = sorted(x["ns_total"] / 1e6 for x in sts)
-            sweep.append({"ring_mib": r >> 20, "slot_kib": pi["slot_bytes"] >> 10,
-                          "pinned_bytes": pi["pinned_ring_bytes"] + pi["pinned_ctrl_bytes"],
-                          "latency_ms": {"min": round(msl[0], 2), "median": round(msl[5], 2), "max": round(msl[-1], 2)},
-                          "bidir_GBps": round((pi["bytes_out"] + pi["bytes_in"]) / msl[5] / 1e6, 2)})
-            fwd.close(); rev.close()
-            log("[bench] ring sweep:", sweep[-1])
+        sweep = ring_sweep(nx, rows_a, rows_b, cf["ring_bytes"], opts, h_out, h_in, peak, log)
 
     diag = bool(args.flags & nx.DIAG_RING_ONLY)
     if back is not None:                # in place: where the sets are depends on the number of switches so far
@@ -336,7 +444,7 @@ def main() -> int:
 
     roof = {"bound": "host_link", "kernel": "nixie_swap_kernel", "unit": "GB/s",
             "achieved": round(nbytes / kern_s / 1e9, 3), "peak": None, "frac": None,
-            "traffic": read_traffic(os.path.join(ROOT, "profiles", "nixie_swap_kernel_llm_pmc.txt")),
+            "traffic": read_traffic(args.config, ring, plain_run or (args.config in (4, 5) and not args.flags)),
             "algorithmic_bytes_per_launch": nbytes, "kernel_ms": round(kern_s * 1e3, 3),
             "traffic_note": "FETCH_SIZE + WRITE_SIZE count every switched byte twice (fetched once, from HBM or over "
                             "the link, and written once, over the link or into HBM): compare with 2 x "
@@ -369,6 +477,9 @@ def main() -> int:
                    "team": info["team_out"], "drain_threads": info["drain_threads"],
                    "fill_threads": info["fill_threads"], "flags": args.flags, "scale": args.scale,
                    "in_place": bool(args.in_place), "pinned_tier": args.pinned_tier,
+                   "repeat": "every timed step runs the chunk planner and then the same switch again (A out, B in; "
+                             "a source's bytes are unspecified after a switch and are not restored in between); "
+                             "the ping-pong protocol is config 5's ring sweep",
                    "direct_bytes_out": info["direct_bytes_out"], "direct_bytes_in": info["direct_bytes_in"]},
         "switch_latency_ms": {"min": round(lat[0], 3), "median": round(med(lat), 3), "max": round(lat[-1], 3)},
         "b_ready_ms": round(med(sorted(s["ns_in_done"] / 1e6 for s in stats)), 3),
@@ -401,6 +512,9 @@ def main() -> int:
         space_a.close()
         space_b.close()
         pool.close()
+    torch.cuda.empty_cache()
+    if with_extras:
+        res["configs"] = [extra_config(nx, W, torch, c, peak, log) for c in (6, 3, 4, 1, 5)]
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(cf, int(args.cpu_sample_gib * 2**30))
     print(json.dumps(res), flush=True)

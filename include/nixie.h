@@ -163,6 +163,11 @@ typedef struct {
     uint64_t scatter_stall_ticks; /* summed over scatter workgroups, ticks waiting for filled slots   */
     uint32_t kernels;         /* swap kernels launched (2 when serialised)                      */
     uint32_t gpu_status;      /* 0, or the reason the kernel stopped early                      */
+    uint32_t pump_rounds_out, pump_rounds_in; /* times the kernel read the host's flags of a direction: kernel
+                                 time / rounds = how stale a credit can be when the GPU sees it  */
+    uint32_t credit_rtt_ticks_out, credit_rtt_ticks_in; /* mean credit round trip of the last kernel, 100 MHz ticks:
+                                 from the GPU's flag for a slot (outgoing: "slot holds a chunk", incoming: "slot
+                                 is free") to the kernel seeing the host's answer for that slot                 */
 } nixie_stats_t;
 
 typedef struct {

@@ -1,0 +1,89 @@
+/*
+ * nixie_shim.h -- the transparent shim (libnixie_shim.so), for unmodified HIP applications.
+ *
+ * Paper, "Supporting Unmodified CUDA Applications": a library loaded with LD_PRELOAD interposes
+ * the runtime's memory allocation and free, its kernel launches and its memory-usage report, so
+ * that an application that knows nothing of the system can lose the GPU and get it back:
+ *   - "Maintaining consistent virtual memory addresses": device addresses are reserved once and
+ *     the physical memory behind them changes across a migration -- here every large allocation
+ *     is a range of one nixie_space over one nixie_pool, so the application's pointers stay
+ *     valid for life;
+ *   - "Valid memory access during migration": before a migration new launches are held back and
+ *     the device is synchronized;
+ *   - "GPU Memory information": the memory report is the sum of the process's own allocations;
+ *   - "Overview", steps 1, 2, 5, 6 of the architecture figure: a launch first checks the
+ *     execution flag; if the application's memory is not resident it is brought back (the
+ *     context-switch swap of nixie.h) before the launch goes ahead.
+ * Single process: there is no daemon and no IPC here.  The scheduler's side is either a thread in
+ * the same process calling nixie_shim_evict / nixie_shim_restore, or the shim's own idleness
+ * rule (paper, "Idleness Detection": idle = no runtime call has returned for longer than a
+ * threshold), after which the application is evicted as if another one had been scheduled.
+ *
+ * Use:  LD_PRELOAD=/path/to/libnixie_shim.so  ./application      (set before the process starts)
+ *
+ * Interposed runtime calls (same prototypes as the HIP runtime's; everything else passes through):
+ *   hipMalloc        size >= NIXIE_SHIM_MIN_BYTES: whole blocks of the shim's address space
+ *                    (first fit), entered in the application's allocation table; smaller ones go
+ *                    to the runtime unchanged (the paper leaves allocations under one block to the
+ *                    plain allocator).  hipErrorOutOfMemory when the space is full.
+ *   hipFree          releases such a range (and its host copy, if the application is evicted).
+ *   hipMemGetInfo    total = the capacity the shim was given, free = total - the application's
+ *                    own managed allocations (in whole blocks).
+ *   hipLaunchKernel, hipModuleLaunchKernel
+ *                    check the execution flag; restore the application first if it is evicted.
+ *                    Launches made by the shim's own library calls pass straight through.
+ *   hipMemcpy, hipMemcpyAsync, hipMemset, hipMemsetAsync
+ *                    address device memory as well: the same flag check before they go ahead.
+ * Interposed only to time the application's activity (idleness), bracketed as calls that may
+ * block: hipDeviceSynchronize, hipStreamSynchronize (and the synchronous hipMemcpy / hipMemset).
+ * Graph capture, stream-ordered allocators and the other launch entry points are not interposed.
+ *
+ * Environment (read once, at the first interposed call):
+ *   NIXIE_SHIM_POOL_MIB     capacity of the managed GPU memory, MiB (default 1024)
+ *   NIXIE_SHIM_BLOCK_MIB    block size, MiB (default 2: the paper's block; must suit the device's
+ *                           allocation granularity)
+ *   NIXIE_SHIM_MIN_BYTES    smallest managed allocation (default: one block)
+ *   NIXIE_SHIM_RING_MIB     pinned staging ring of the swap, MiB (default 64)
+ *   NIXIE_SHIM_IDLE_MS      > 0: a watcher thread evicts the application once it has been idle
+ *                           this long (default 0 = never; the paper's threshold is 100)
+ *   NIXIE_SHIM_SCRIBBLE     1: after an eviction the freed physical memory is overwritten through
+ *                           a second address space, as another application would (test aid)
+ *   NIXIE_SHIM_LOG          1: one line per eviction / restore on stderr
+ */
+#ifndef NIXIE_SHIM_H
+#define NIXIE_SHIM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct {
+    uint64_t capacity_bytes;    /* managed GPU memory                                     */
+    uint64_t block_bytes;
+    uint64_t managed_bytes;     /* live managed allocations, in whole blocks              */
+    uint64_t managed_allocs;
+    uint64_t passthrough_allocs;/* live allocations below the threshold                   */
+    uint32_t resident;          /* the execution flag: 1 = the application's memory is in HBM */
+    uint32_t evictions, restores;
+    uint64_t last_switch_ns;    /* duration of the last eviction or restore               */
+    uint64_t launches_held;     /* launches that found the flag off and waited for a restore */
+} nixie_shim_info_t;
+
+/* HOST out.  Returns 0, or NIXIE_EINVAL when the shim has not been initialised yet (no interposed
+ * call so far) or info is NULL. */
+int nixie_shim_info(nixie_shim_info_t *info);
+
+/* The scheduler's two actions, for a caller inside the process.  nixie_shim_evict holds back new
+ * launches, waits for the device, moves every managed allocation to pageable host memory with
+ * nixie_switch, and unmaps the physical memory; the application keeps its pointers.
+ * nixie_shim_restore maps it again and brings the bytes back; any launch does the same on its own.
+ * Both return 0 (also when there is nothing to do) or a negative nixie_err code. */
+int nixie_shim_evict(void);
+int nixie_shim_restore(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NIXIE_SHIM_H */

@@ -34,5 +34,28 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+SHIM = os.path.join(HERE, "libnixie_shim.so")
+SHIM_APP = os.path.join(ROOT, "tests", "shim_app", "shim_app")
+
+
+def build_shim(verbose: bool = False) -> str:
+    """The LD_PRELOAD shim (host code only; finds libnixie.so beside itself) and the small
+    unmodified HIP program the shim's GPU test runs under it."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmds = [[hipcc, "-O2", "-std=c++17", "-fPIC", "-Wall", "-Wextra", "-I" + os.path.join(ROOT, "include"), "-shared",
+             "-o", SHIM, os.path.join(CSRC, "shim.cpp"), "-L" + HERE, "-lnixie", "-Wl,-rpath,$ORIGIN", "-ldl", "-lpthread"],
+            [hipcc, "-O2", "-std=c++17", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+             "-o", SHIM_APP, os.path.join(ROOT, "tests", "shim_app", "shim_app.hip")]]
+    for cmd in cmds:
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        if res.returncode != 0:
+            sys.stderr.write(res.stderr + "\n")
+            raise RuntimeError("hipcc failed: " + cmd[-1])
+    return SHIM
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
+    print(build_shim(verbose=True))

@@ -52,7 +52,11 @@ constexpr uint32_t kFlagStride = 8;        // GPU-written flags: one 64 B line (
 // a single wave of the kernel reads a direction's credits with a few line-sized link reads.
 inline uint64_t wait_flag_words(uint32_t slots) { return ((uint64_t)slots + 7) / 8 * 8; }
 constexpr uint32_t kWgThreads = 256;
-constexpr uint32_t kTileBytes = 8192;
+// One wave pass: 16 B per lane, 64 lanes, NIXIE_UNROLL loads in flight per lane before the stores.
+#ifndef NIXIE_UNROLL
+#define NIXIE_UNROLL 8
+#endif
+constexpr uint32_t kTileBytes = 16 * 64 * NIXIE_UNROLL;
 
 // Words of the GPU-written "done" line (u32 each): [0], [1] = 1 once every workgroup of direction
 // 0 / 1 has left; [kStartedWord] = 1 once the kernel runs (until then a waiting host thread is
@@ -60,6 +64,10 @@ constexpr uint32_t kTileBytes = 8192;
 // x handed out so far, refreshed by the pump now and then (a sign of life for a waiter that sees
 // no slot traffic, e.g. when every chunk moves directly).
 constexpr uint32_t kStartedWord = 2, kProgressWord = 4;
+constexpr uint32_t kRoundsWord = 6;  // [kRoundsWord + x]: rounds the pump of direction x made over the host's flags
+constexpr uint32_t kRttWord = 12;    // [kRttWord + x]: mean time, in 100 MHz ticks, between the GPU's flag for a slot of direction x
+                                     // and the pump seeing the host's answer for that slot (the credit round trip)
+constexpr uint32_t kStallWord = 8;   // u32 index of two u64: summed stall ticks per direction, written as the kernel ends
 // a host thread that has not yet seen the kernel start waits this many times the credit bound
 constexpr uint64_t kStartGrace = 4;
 
@@ -72,7 +80,8 @@ struct DevDir {
     uint8_t *ring;               // device-visible address of this direction's first slot
     const uint64_t *host_flags;  // host-written, pinned, packed: out: released[s]  in: filled[s]
     uint64_t *post_flags;        // GPU-written,  pinned, one line each: out: ready[s]  in: freed[s]
-    uint64_t *seen;              // device memory, pump only: last value of host_flags[s] acted on
+    uint64_t *seen;              // device memory, pump only: last value of host_flags[s] acted on (slots beyond 256)
+    uint64_t *stamp;             // device memory, per slot: wall clock when the GPU last posted a flag for it
     uint32_t *chunk_slot;        // device memory, per chunk: 0 = no slot yet, else slot + 1
     uint32_t *ticket;            // device memory, one counter
     uint32_t *exited;            // device memory, workgroups of this direction that have left
@@ -94,6 +103,10 @@ struct SwapArgs {
     uint32_t track_prefix;       // 1: in-place switch with both directions running in this launch
     uint32_t xcd_mask;           // 0 = every XCD takes part
     uint32_t *dir_done;          // pinned, GPU-written "done" line: see kStartedWord / kProgressWord
+    uint32_t *counters;          // device memory: the whole counter block, cleared by the last workgroup to leave
+    uint64_t n_counters;
+    uint32_t *all_left;          // device memory: workgroups (pump included) that have left the kernel
+    uint64_t *stall_out;         // pinned, GPU-written at the end: [x] = summed stall ticks of direction x
 };
 
 struct HashDesc { uint64_t ptr; uint64_t bytes; uint64_t first_tile; };

@@ -46,8 +46,9 @@ namespace {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr uint32_t kDirect = 0xFFFFFFFFu;             // "slot + 1" of a chunk that uses no slot
-constexpr uint32_t kUnroll = 8;                       // 16 B x 64 lanes x 8 = one 8 KiB tile per wave pass
+constexpr uint32_t kUnroll = NIXIE_UNROLL;            // 16 B x 64 lanes x kUnroll = one tile per wave pass
 static_assert(kTileBytes == 16 * 64 * kUnroll, "tile = one unrolled wave pass");
+static_assert(kUnroll == 8 || kUnroll == 4 || kUnroll == 2, "load_from_host is written out for these");
 
 __device__ __forceinline__ uint64_t mix64_dev(uint64_t z) {
     z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
@@ -55,12 +56,13 @@ __device__ __forceinline__ uint64_t mix64_dev(uint64_t z) {
     return z ^ (z >> 31);
 }
 
-// Eight 16-byte loads from the pinned ring, then one wait for all of them.  The loads carry
+// kUnroll 16-byte loads from the pinned ring, then one wait for all of them.  The loads carry
 // the system-scope bits (sc0 sc1), so they are served from host memory itself and never from
 // a cache line left over from an earlier use of the slot; no cache invalidation is needed
 // between the host's "slot ready" flag and these loads.  One asm block, because the compiler
 // does not track loads issued from inline asm: the values are only valid after the wait.
-__device__ __forceinline__ void load8_from_host(u32x4 (&v)[8], const u32x4 *const (&a)[8]) {
+__device__ __forceinline__ void load_from_host(u32x4 (&v)[kUnroll], const u32x4 *const (&a)[kUnroll]) {
+#if NIXIE_UNROLL == 8
     asm volatile(
         "global_load_dwordx4 %0, %8, off sc0 sc1\n"
         "global_load_dwordx4 %1, %9, off sc0 sc1\n"
@@ -74,6 +76,25 @@ __device__ __forceinline__ void load8_from_host(u32x4 (&v)[8], const u32x4 *cons
         : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3]), "=&v"(v[4]), "=&v"(v[5]), "=&v"(v[6]), "=&v"(v[7])
         : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(a[4]), "v"(a[5]), "v"(a[6]), "v"(a[7])
         : "memory");
+#elif NIXIE_UNROLL == 4
+    asm volatile(
+        "global_load_dwordx4 %0, %4, off sc0 sc1\n"
+        "global_load_dwordx4 %1, %5, off sc0 sc1\n"
+        "global_load_dwordx4 %2, %6, off sc0 sc1\n"
+        "global_load_dwordx4 %3, %7, off sc0 sc1\n"
+        "s_waitcnt vmcnt(0)"
+        : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3])
+        : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3])
+        : "memory");
+#else
+    asm volatile(
+        "global_load_dwordx4 %0, %2, off sc0 sc1\n"
+        "global_load_dwordx4 %1, %3, off sc0 sc1\n"
+        "s_waitcnt vmcnt(0)"
+        : "=&v"(v[0]), "=&v"(v[1])
+        : "v"(a[0]), "v"(a[1])
+        : "memory");
+#endif
 }
 
 // One 16-byte store into the pinned ring with the system-scope bits set: written through to
@@ -109,7 +130,7 @@ __device__ __forceinline__ void copy_span(uint8_t *dev, uint8_t *ring, uint32_t 
             const u32x4 *a[kUnroll];
 #pragma unroll
             for (uint32_t u = 0; u < kUnroll; u++) a[u] = s4 + (j + 64 * u < nvec ? j + 64 * u : nvec - 1);
-            load8_from_host(v, a);
+            load_from_host(v, a);
         }
 #pragma unroll
         for (uint32_t u = 0; u < kUnroll; u++)
@@ -240,9 +261,11 @@ __device__ void run_direction(const SwapArgs &a) {
             //  every load of this unit completed before the barrier above)
             const uint32_t old = __hip_atomic_fetch_add(D.arrive + k, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             const bool last = (old == D.team - 1) && !direct;   // nobody waits for a direct chunk's slot
-            if (last)   // outgoing: "slot holds chunk k"; incoming: "chunk k has left the slot"
+            if (last) {   // outgoing: "slot holds chunk k"; incoming: "chunk k has left the slot"
                 __hip_atomic_store(D.post_flags + (size_t)slot * kFlagStride, (uint64_t)k + 1u, __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_SYSTEM);
+                __hip_atomic_store(D.stamp + slot, wall_clock64(), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
         }
     }
     // Leaving.  The pump reports "direction complete" to the host once every workgroup of the
@@ -287,33 +310,63 @@ __device__ void run_pump(const SwapArgs &a, int dir) {
         if (lane == 0) __hip_atomic_store(a.gathered_prefix, prefix, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return true;
     };
+    // One round: read every host-written flag once, act on the changes.  The first 256 slots (four
+    // per lane) are read with all loads in flight at once -- a round then costs one trip over the link
+    // instead of one per 64 slots -- and their last-seen values stay in registers; slots beyond that
+    // go 64 at a time through seen[] in device memory.
+    constexpr uint32_t kRegGroups = 4;
+    uint64_t seen_r[kRegGroups] = {0, 0, 0, 0};
+    uint64_t rtt_sum = 0;   // per lane: credit round trips of this lane's slots
+    uint32_t rtt_n = 0;
+    auto act = [&](uint32_t s, uint64_t v, bool changed) {   // wave-uniform call, per-lane arguments
+        if (changed) {
+            const uint64_t posted = __hip_atomic_load(D.stamp + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (posted) { rtt_sum += wall_clock64() - posted; rtt_n++; }
+        }
+        if (dir == 0) {
+            const uint64_t mask = __ballot(changed);
+            const uint32_t rank = __popcll(mask & ((1ull << lane) - 1ull));
+            if (changed) {
+                const uint32_t k = next + rank;
+                if (k < D.n_staged)
+                    __hip_atomic_store(D.chunk_slot + k, s + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            next += (uint32_t)__popcll(mask);
+        } else if (changed) {
+            const uint64_t k = v - 1;
+            if (k < D.n_staged)
+                __hip_atomic_store(D.chunk_slot + k, s + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    };
     for (;;) {
-        for (uint32_t base = 0; base < D.n_slots; base += 64) {
+        uint64_t v_r[kRegGroups];
+#pragma unroll
+        for (uint32_t j = 0; j < kRegGroups; j++) {   // unconditional (a lane without a slot re-reads slot 0): no branch, no wait between them
+            const uint32_t s = lane + 64 * j;
+            v_r[j] = __hip_atomic_load(D.host_flags + (s < D.n_slots ? s : 0), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+        const uint32_t gone = __hip_atomic_load(D.exited, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (uint32_t j = 0; j < kRegGroups; j++) {
+            if (64 * j >= D.n_slots) break;
+            const bool mine = lane + 64 * j < D.n_slots;
+            const bool changed = mine && v_r[j] != seen_r[j];
+            act(lane + 64 * j, v_r[j], changed);
+            if (mine) seen_r[j] = v_r[j];
+        }
+        for (uint32_t base = 64 * kRegGroups; base < D.n_slots; base += 64) {
             const uint32_t s = base + lane;
             uint64_t v = 0, old = 0;
             if (s < D.n_slots) {
                 v = __hip_atomic_load(D.host_flags + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-                old = D.seen[s];
+                old = __hip_atomic_load(D.seen + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
             const bool changed = v != old;
-            if (dir == 0) {
-                const uint64_t mask = __ballot(changed);
-                const uint32_t rank = __popcll(mask & ((1ull << lane) - 1ull));
-                if (changed) {
-                    const uint32_t k = next + rank;
-                    if (k < D.n_staged)
-                        __hip_atomic_store(D.chunk_slot + k, s + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    D.seen[s] = v;
-                }
-                next += (uint32_t)__popcll(mask);
-            } else if (changed) {
-                const uint64_t k = v - 1;
-                if (k < D.n_staged)
-                    __hip_atomic_store(D.chunk_slot + k, s + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                D.seen[s] = v;
-            }
+            act(s, v, changed);
+            if (changed) __hip_atomic_store(D.seen + s, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        if (__hip_atomic_load(a.host_abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) &&
+        // the host's abort word: every eighth round is soon enough (every wait is bounded anyway)
+        if ((rounds & 7u) == 0 && __hip_atomic_load(a.host_abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) &&
             !__hip_atomic_load(a.dev_abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) && lane == 0) {
             __hip_atomic_store(a.dev_abort, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __hip_atomic_store(a.gpu_status, (uint32_t)kGpuSawAbort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
@@ -325,15 +378,47 @@ __device__ void run_pump(const SwapArgs &a, int dir) {
                 __hip_atomic_store(a.dir_done + kProgressWord + dir, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
             told = t;
         }
-        if (__hip_atomic_load(D.exited, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= D.wgs) {
+        if (gone >= D.wgs) {   // (read at the start of this round: everything those workgroups did came before)
             // every gather workgroup has left, so every arrive counter is final: publish the rest
             // (bounded: at most n_chunks / 64 + 1 rounds)
             if (track) while (prefix < D.n_chunks && advance_prefix()) {}
-            if (lane == 0) __hip_atomic_store(a.dir_done + dir, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            for (int off = 32; off > 0; off >>= 1) {
+                rtt_sum += __shfl_down((unsigned long long)rtt_sum, off, 64);
+                rtt_n += __shfl_down(rtt_n, off, 64);
+            }
+            if (lane == 0) {
+                __hip_atomic_store(a.dir_done + kRttWord + dir, rtt_n ? (uint32_t)(rtt_sum / rtt_n) : 0u, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_SYSTEM);
+                __hip_atomic_store(a.dir_done + kRoundsWord + dir, rounds, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                __hip_atomic_store(a.dir_done + dir, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            }
             break;
         }
-        __builtin_amdgcn_s_sleep(8);
+        __builtin_amdgcn_s_sleep(2);
     }
+}
+
+// The last workgroup to leave the kernel hands the stall sums to the host and clears every counter,
+// so the next switch needs no clearing launch of its own.  Every access to the counters, the
+// clearing included, is an agent-scope atomic: the XCDs' L2s are not coherent with each other for
+// plain accesses, and a stale dirty line written back at the end of the kernel must not undo the
+// clearing.  A workgroup only counts as gone once its own counter traffic has been acknowledged.
+__device__ void leave_kernel(const SwapArgs &a) {
+    __shared__ uint32_t s_last;
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0)
+        s_last = __hip_atomic_fetch_add(a.all_left, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == gridDim.x - 1;
+    __syncthreads();
+    if (!s_last) return;
+    if (threadIdx.x < 2) {
+        const uint64_t t = __hip_atomic_load(a.d[threadIdx.x].stall_ticks, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(a.stall_out + threadIdx.x, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    for (uint64_t i = threadIdx.x; i < a.n_counters; i += kWgThreads)
+        __hip_atomic_store(a.counters + i, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Block 0 is the pump (first to be dispatched, so it is resident before any worker can wait on
@@ -344,10 +429,12 @@ __global__ void __launch_bounds__(kWgThreads) nixie_swap_kernel(SwapArgs a) {
         if (threadIdx.x == 0)   // from here on a host thread's wait is a credit wait, not queue delay
             __hip_atomic_store(a.dir_done + kStartedWord, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
         if (wave < 2) run_pump(a, (int)wave);
-        return;
+    } else if (blockIdx.x - 1 < a.d[0].wgs) {
+        run_direction<0>(a);
+    } else {
+        run_direction<1>(a);
     }
-    if (blockIdx.x - 1 < a.d[0].wgs) run_direction<0>(a);
-    else run_direction<1>(a);
+    leave_kernel(a);
 }
 
 __global__ void __launch_bounds__(256) nixie_zero32_kernel(uint32_t *p, uint64_t n) {

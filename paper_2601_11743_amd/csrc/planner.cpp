@@ -324,13 +324,16 @@ void fill_info(const Layout &L, nixie_plan_info_t *info) {
     // Work unit: at most 128 KiB of a slot -- per unit a workgroup pays a ticket, a slot lookup, a
     // store drain and a barrier (4 % of the rate at 64 KiB), while at 256 KiB and more a chunk
     // waits too long for its slowest unit -- and small enough that the units in flight (one per
-    // workgroup) occupy no more than a quarter of the direction's share of the ring: the rest is
+    // workgroup) occupy no more than a quarter of the direction's share of the ring (where the unit floor allows): the rest is
     // what the host threads drain or fill meanwhile.
     uint32_t team = L.opts.team;
     if (team == 0) {
         const uint32_t max_slots = std::max(L.dir[0].slots, L.dir[1].slots);
+        // Never below 32 KiB: a workgroup's four waves take one 8 KiB tile each per pass, so a smaller
+        // unit would leave waves, or whole units, without a tile while still paying for the unit.
+        constexpr uint64_t kMinUnit = (uint64_t)(kWgThreads / 64) * kTileBytes;
         uint64_t unit = 128u << 10;
-        while (max_slots && unit > (16u << 10) && unit * 4 * std::max(wgs[0], wgs[1]) > (uint64_t)max_slots * L.slot_bytes) unit >>= 1;
+        while (max_slots && unit > kMinUnit && unit * 4 * std::max(wgs[0], wgs[1]) > (uint64_t)max_slots * L.slot_bytes) unit >>= 1;
         team = (uint32_t)std::max<uint64_t>(1, L.slot_bytes / unit);
     }
     team = std::min(team, 256u);

@@ -75,7 +75,7 @@ struct nixie_plan {
     DevChunk *chunks_d[2] = {nullptr, nullptr};
     uint64_t *direct_d[2] = {nullptr, nullptr};
     uint32_t *counters_d = nullptr;
-    uint64_t n_counters = 0, seen_off[2] = {0, 0}, cslot_off[2] = {0, 0}, arrive_off[2] = {0, 0};
+    uint64_t n_counters = 0, seen_off[2] = {0, 0}, stamp_off[2] = {0, 0}, cslot_off[2] = {0, 0}, arrive_off[2] = {0, 0};
     HashDesc *hdesc_d[2] = {nullptr, nullptr};
     uint64_t htiles[2] = {0, 0};
     uint64_t *hashes_d = nullptr;
@@ -222,16 +222,20 @@ int create_plan(nixie_plan_t *p) {
         if (rc) return rc;
     }
     // counters (u32 units): [0] ticket out, [1] ticket in, [2] abort, [3] pad, [4,5] stall out, [6,7] stall in,
-    // [8] exited out, [9] exited in, [10] gathered prefix, [11..15] pad, then per direction: seen[] (u64 per slot),
-    // chunk_slot[] and arrive[] (u32 per chunk).  All of it is cleared before every launch.
+    // [8] exited out, [9] exited in, [10] gathered prefix, [11] workgroups that have left, [12..15] pad, then per
+    // direction: seen[] and stamp[] (u64 per slot), chunk_slot[] and arrive[] (u32 per chunk).  All zero between switches:
+    // cleared here once, and by the last workgroup to leave every kernel.
     uint64_t off = 16;
     for (int x = 0; x < 2; x++) { p->seen_off[x] = off; off += 2 * wait_flag_words(L.dir[x].slots); }
+    for (int x = 0; x < 2; x++) { p->stamp_off[x] = off; off += 2 * wait_flag_words(L.dir[x].slots); }
     for (int x = 0; x < 2; x++) { p->cslot_off[x] = off; off += L.dir[x].chunks.size(); }
     for (int x = 0; x < 2; x++) { p->arrive_off[x] = off; off += L.dir[x].chunks.size(); }
     p->n_counters = off;
     {
         hipError_t e = hipMalloc((void **)&p->counters_d, p->n_counters * sizeof(uint32_t));
         if (e != hipSuccess) { t_last_hip_error = (int)e; return NIXIE_ENOMEM; }
+        NIXIE_HIP(hipMemset(p->counters_d, 0, p->n_counters * sizeof(uint32_t)));
+        NIXIE_HIP(hipDeviceSynchronize());
     }
     const size_t n_hash = std::max<size_t>(1, std::max(L.table[0].size(), L.table[1].size()));
     {
@@ -283,6 +287,7 @@ int pass_begin(nixie_plan_t *p, uint32_t mask, hipStream_t stream, nixie_stats_t
         d.ticket = p->counters_d + x;
         d.exited = p->counters_d + 8 + x;
         d.seen = (uint64_t *)(p->counters_d + p->seen_off[x]);
+        d.stamp = (uint64_t *)(p->counters_d + p->stamp_off[x]);
         d.chunk_slot = p->counters_d + p->cslot_off[x];
         d.arrive = p->counters_d + p->arrive_off[x];
         d.stall_ticks = (uint64_t *)(p->counters_d + 4 + 2 * x);
@@ -301,6 +306,10 @@ int pass_begin(nixie_plan_t *p, uint32_t mask, hipStream_t stream, nixie_stats_t
     a.dev_abort = p->counters_d + 2;
     a.timeout_ticks = p->hs.timeout_ns / 10;   // wall clock runs at 100 MHz
     a.gathered_prefix = p->counters_d + 10;
+    a.all_left = p->counters_d + 11;
+    a.counters = p->counters_d;
+    a.n_counters = p->n_counters;
+    a.stall_out = (uint64_t *)(a.dir_done + kStallWord);
     a.xcd_mask = L.opts.xcd_mask & 0xFFu;
     // when the directions run one after the other, everything has left HBM before the restore starts
     a.track_prefix = ((L.opts.flags & NIXIE_IN_PLACE) && a.d[0].wgs && a.d[1].wgs) ? 1u : 0u;
@@ -311,8 +320,7 @@ int pass_begin(nixie_plan_t *p, uint32_t mask, hipStream_t stream, nixie_stats_t
     // The host threads start first: while the launches below are in flight they are already waking
     // up and loading the first incoming slots.
     p->crew.wake(mask);
-    int e = nixie_launch_zero32(p->counters_d, p->n_counters, stream);
-    if (!e) e = (int)hipEventRecord(p->ev0, stream);
+    int e = (int)hipEventRecord(p->ev0, stream);
     if (!e) e = nixie_launch_swap(a, stream);
     if (!e) e = (int)hipEventRecord(p->ev1, stream);
     if (e) {
@@ -349,10 +357,14 @@ int pass_end(nixie_plan_t *p, uint32_t mask, hipStream_t stream, nixie_stats_t *
     if (st) {
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, p->ev0, p->ev1) == hipSuccess) st->ns_kernel += (uint64_t)((double)ms * 1e6);
-        uint64_t stall[2] = {0, 0};
-        NIXIE_HIP(hipMemcpy(stall, p->counters_d + 4, sizeof(stall), hipMemcpyDeviceToHost));
-        st->gather_stall_ticks += stall[0];
-        st->scatter_stall_ticks += stall[1];
+        // written by the last workgroup to leave; the kernel is complete, so they are final
+        const uint64_t *stall = (const uint64_t *)(p->hs.done_word + kStallWord);
+        st->gather_stall_ticks += __atomic_load_n(stall + 0, __ATOMIC_ACQUIRE);
+        st->scatter_stall_ticks += __atomic_load_n(stall + 1, __ATOMIC_ACQUIRE);
+        st->pump_rounds_out += __atomic_load_n(p->hs.done_word + kRoundsWord + 0, __ATOMIC_ACQUIRE);
+        st->pump_rounds_in += __atomic_load_n(p->hs.done_word + kRoundsWord + 1, __ATOMIC_ACQUIRE);
+        st->credit_rtt_ticks_out = __atomic_load_n(p->hs.done_word + kRttWord + 0, __ATOMIC_ACQUIRE);
+        st->credit_rtt_ticks_in = __atomic_load_n(p->hs.done_word + kRttWord + 1, __ATOMIC_ACQUIRE);
         st->drain_wait_ns += p->hs.wait_ns[0].load();
         st->fill_wait_ns += p->hs.wait_ns[1].load();
         st->kernels++;

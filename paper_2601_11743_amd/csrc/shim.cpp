@@ -1,0 +1,491 @@
+// libnixie_shim.so: the transparent shim for unmodified HIP applications (LD_PRELOAD).
+//
+// Paper, "Supporting Unmodified CUDA Applications": the shim interposes allocation and free,
+// kernel launches and the memory report.  Large allocations become ranges of one reserved
+// address space over a pool of physical blocks ("Maintaining consistent virtual memory
+// addresses"), so the application keeps its pointers while its bytes are in host memory; before a
+// migration new launches are held back and the device is synchronized ("Valid memory access during
+// migration"); the memory report is the process's own sum ("GPU Memory information"); a launch
+// checks the execution flag first and brings the application back when it is off ("Overview",
+// steps 1, 2, 5, 6 of the architecture figure).  The migration itself is the library's
+// context-switch swap (nixie_plan / nixie_switch).  One process, no daemon: the scheduler's side is
+// nixie_shim_evict / nixie_shim_restore, or the shim's own idleness rule ("Idleness Detection").
+#include <hip/hip_runtime_api.h>
+
+#include <dlfcn.h>
+#include <sys/mman.h>
+#include <time.h>
+
+#include <algorithm>
+#include <atomic>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <map>
+#include <mutex>
+#include <shared_mutex>
+#include <thread>
+#include <vector>
+
+#include "nixie.h"
+#include "nixie_shim.h"
+
+namespace {
+
+// ---- the runtime's own entry points -----------------------------------------------------------
+template <typename F>
+F next_symbol(const char *name) {
+    void *p = dlsym(RTLD_NEXT, name);
+    if (!p) {
+        std::fprintf(stderr, "nixie-shim: the HIP runtime does not export %s\n", name);
+        std::abort();   // nothing sensible can be returned for a call that cannot be forwarded
+    }
+    return reinterpret_cast<F>(p);
+}
+// (spelled out rather than taken from the declarations: the runtime's header overloads some of these names)
+using fn_hipMalloc = hipError_t (*)(void **, size_t);
+using fn_hipFree = hipError_t (*)(void *);
+using fn_hipMemGetInfo = hipError_t (*)(size_t *, size_t *);
+using fn_hipLaunchKernel = hipError_t (*)(const void *, dim3, dim3, void **, size_t, hipStream_t);
+using fn_hipModuleLaunchKernel = hipError_t (*)(hipFunction_t, unsigned int, unsigned int, unsigned int, unsigned int,
+                                                unsigned int, unsigned int, unsigned int, hipStream_t, void **, void **);
+using fn_hipMemcpy = hipError_t (*)(void *, const void *, size_t, hipMemcpyKind);
+using fn_hipMemcpyAsync = hipError_t (*)(void *, const void *, size_t, hipMemcpyKind, hipStream_t);
+using fn_hipMemset = hipError_t (*)(void *, int, size_t);
+using fn_hipMemsetAsync = hipError_t (*)(void *, int, size_t, hipStream_t);
+using fn_hipDeviceSynchronize = hipError_t (*)(void);
+using fn_hipStreamSynchronize = hipError_t (*)(hipStream_t);
+#define REAL(name) ([]() { static fn_##name f = next_symbol<fn_##name>(#name); return f; }())
+
+// Calls made by the shim itself (and by libnixie underneath it) pass straight through.
+thread_local int t_inside = 0;
+struct Inside {
+    Inside() { t_inside++; }
+    ~Inside() { t_inside--; }
+};
+
+uint64_t now_ns() {
+    timespec ts;
+    clock_gettime(CLOCK_MONOTONIC, &ts);
+    return (uint64_t)ts.tv_sec * 1000000000ull + (uint64_t)ts.tv_nsec;
+}
+
+uint64_t env_u64(const char *name, uint64_t dflt) {
+    const char *v = std::getenv(name);
+    if (!v || !*v) return dflt;
+    char *end = nullptr;
+    const unsigned long long x = std::strtoull(v, &end, 10);
+    return end && *end == 0 ? (uint64_t)x : dflt;
+}
+
+struct Alloc {
+    uint64_t bytes = 0;    // as the application asked
+    uint64_t blocks = 0;   // what it occupies
+    void *host = nullptr;  // pageable copy while evicted (exactly one copy: freed on restore)
+};
+
+struct Shim {
+    bool ok = false;
+    uint64_t capacity = 0, block = 0, min_bytes = 0, ring = 0, idle_ns = 0;
+    bool scribble = false, log = false;
+    nixie_pool_t *pool = nullptr;
+    nixie_space_t *space = nullptr;
+    uint64_t base = 0;
+
+    // Launches hold `gate` shared; eviction and restore hold it exclusively, which is what holds
+    // new launches back during a migration.  `mu` guards the tables.
+    std::shared_mutex gate;
+    std::mutex mu;
+    std::map<uint64_t, Alloc> table;          // by device address
+    std::map<uint64_t, uint64_t> free_runs;   // first block -> number of blocks
+    uint64_t managed_bytes = 0, passthrough = 0;
+    std::atomic<bool> resident{true};
+    std::atomic<uint32_t> evictions{0}, restores{0};
+    std::atomic<uint64_t> last_switch_ns{0}, launches_held{0};
+
+    // idleness: time of the last return from a runtime call; calls that may block are bracketed
+    std::atomic<uint64_t> last_return{0};
+    std::atomic<int> blocking{0};
+    std::thread watcher;
+    std::atomic<bool> quit{false};
+};
+
+Shim *g = nullptr;
+std::once_flag g_once;
+
+void say(const char *fmt, ...) __attribute__((format(printf, 1, 2)));
+void say(const char *fmt, ...) {
+    if (!g || !g->log) return;
+    va_list ap;
+    va_start(ap, fmt);
+    std::fputs("nixie-shim: ", stderr);
+    std::vfprintf(stderr, fmt, ap);
+    std::fputc('\n', stderr);
+    va_end(ap);
+}
+
+int evict_locked(Shim &s);
+int restore_locked(Shim &s);
+
+void watch_idleness(Shim *s) {
+    const timespec nap{0, (long)std::min<uint64_t>(s->idle_ns / 4 + 1, 20000000)};
+    while (!s->quit.load()) {
+        nanosleep(&nap, nullptr);
+        if (!s->resident.load() || s->blocking.load() > 0) continue;
+        const uint64_t last = s->last_return.load();
+        if (last == 0 || now_ns() - last <= s->idle_ns) continue;
+        std::unique_lock<std::shared_mutex> hold(s->gate);
+        if (s->blocking.load() > 0 || now_ns() - s->last_return.load() <= s->idle_ns) continue;   // woke up meanwhile
+        Inside in;
+        (void)evict_locked(*s);
+    }
+}
+
+void init_once() {
+    static Shim shim;
+    Inside in;
+    Shim &s = shim;
+    s.capacity = env_u64("NIXIE_SHIM_POOL_MIB", 1024) << 20;
+    s.block = env_u64("NIXIE_SHIM_BLOCK_MIB", 2) << 20;
+    s.ring = env_u64("NIXIE_SHIM_RING_MIB", 64) << 20;
+    s.idle_ns = env_u64("NIXIE_SHIM_IDLE_MS", 0) * 1000000ull;
+    s.scribble = env_u64("NIXIE_SHIM_SCRIBBLE", 0) != 0;
+    s.log = env_u64("NIXIE_SHIM_LOG", 0) != 0;
+    g = &s;
+    int rc = nixie_pool_create(s.capacity, s.block, &s.pool);
+    if (rc == NIXIE_EINVAL) {   // the device wants coarser blocks: take the library's default
+        say("block of %llu MiB does not suit this device, using the default", (unsigned long long)(s.block >> 20));
+        rc = nixie_pool_create(s.capacity, 0, &s.pool);
+    }
+    void *base = nullptr;
+    if (!rc) rc = nixie_pool_info(s.pool, &s.capacity, &s.block);
+    if (!rc) rc = nixie_space_create(s.pool, &s.space, &base);
+    if (rc) {
+        std::fprintf(stderr, "nixie-shim: cannot set up %llu MiB of managed GPU memory (%s); allocations pass through\n",
+                     (unsigned long long)(s.capacity >> 20), nixie_strerror(rc));
+        return;
+    }
+    s.base = (uint64_t)(uintptr_t)base;
+    s.min_bytes = env_u64("NIXIE_SHIM_MIN_BYTES", s.block);
+    s.free_runs[0] = s.capacity / s.block;
+    s.last_return.store(now_ns());
+    s.ok = true;
+    say("managing %llu MiB in %llu MiB blocks at %p, allocations from %llu bytes", (unsigned long long)(s.capacity >> 20),
+        (unsigned long long)(s.block >> 20), base, (unsigned long long)s.min_bytes);
+    if (s.idle_ns) s.watcher = std::thread(watch_idleness, &s);
+    std::atexit([] {
+        if (!g) return;
+        g->quit.store(true);
+        if (g->watcher.joinable()) g->watcher.join();
+    });
+}
+
+Shim *shim() {
+    std::call_once(g_once, init_once);
+    return g && g->ok ? g : nullptr;
+}
+
+// ---- the application's allocation table as a swap table -------------------------------------------
+std::vector<nixie_alloc_t> rows_with_host_copy(Shim &s) {
+    std::vector<nixie_alloc_t> rows;
+    for (auto &kv : s.table)
+        if (kv.second.host) rows.push_back(nixie_alloc_t{(void *)(uintptr_t)kv.first, kv.second.host, kv.second.bytes});
+    return rows;
+}
+
+int run_switch(Shim &s, const std::vector<nixie_alloc_t> &out, const std::vector<nixie_alloc_t> &in) {
+    nixie_table_t to{out.data(), out.size()}, ti{in.data(), in.size()};
+    uint64_t moved = 0;
+    for (auto &r : out) moved += r.bytes;
+    for (auto &r : in) moved += r.bytes;
+    if (moved == 0) return NIXIE_OK;
+    nixie_plan_t *plan = nullptr;
+    int rc = nixie_plan(&to, &ti, s.ring, nullptr, &plan);
+    if (rc) return rc;
+    nixie_stats_t st{};
+    rc = nixie_switch(plan, nullptr, &st);
+    nixie_plan_destroy(plan);
+    s.last_switch_ns.store(st.ns_total);
+    return rc;
+}
+
+// gate held exclusively, t_inside set
+int evict_locked(Shim &s) {
+    if (!s.resident.load()) return NIXIE_OK;
+    std::lock_guard<std::mutex> lk(s.mu);
+    if (REAL(hipDeviceSynchronize)() != hipSuccess) return NIXIE_EHIP;   // nothing of the application's is running any more
+    uint64_t bytes = 0;
+    for (auto &kv : s.table) {
+        Alloc &a = kv.second;
+        a.host = mmap(nullptr, a.bytes, PROT_READ | PROT_WRITE, MAP_PRIVATE | MAP_ANONYMOUS, -1, 0);
+        if (a.host == MAP_FAILED) {
+            a.host = nullptr;
+            for (auto &u : s.table)
+                if (u.second.host) { munmap(u.second.host, u.second.bytes); u.second.host = nullptr; }
+            return NIXIE_ENOMEM;
+        }
+        bytes += a.bytes;
+    }
+    int rc = run_switch(s, rows_with_host_copy(s), {});
+    if (rc) {            // the application stays resident, its bytes are still in HBM
+        for (auto &u : s.table)
+            if (u.second.host) { munmap(u.second.host, u.second.bytes); u.second.host = nullptr; }
+        return rc;
+    }
+    for (auto &kv : s.table)
+        if ((rc = nixie_space_unmap(s.space, kv.first - s.base, kv.second.blocks * s.block)) != 0) return rc;
+    if (s.scribble) {
+        // what another application would do with the physical memory meanwhile
+        nixie_space_t *other = nullptr;
+        void *ob = nullptr;
+        if (nixie_space_create(s.pool, &other, &ob) == NIXIE_OK) {
+            if (nixie_space_map(other, 0, s.capacity) == NIXIE_OK) {
+                (void)REAL(hipMemset)(ob, 0xEE, s.capacity);
+                (void)REAL(hipDeviceSynchronize)();
+            }
+            (void)nixie_space_destroy(other);
+        }
+    }
+    s.resident.store(false);
+    s.evictions++;
+    say("evicted %zu allocations, %llu bytes, in %.3f ms", s.table.size(), (unsigned long long)bytes, s.last_switch_ns.load() / 1e6);
+    return NIXIE_OK;
+}
+
+int restore_locked(Shim &s) {
+    if (s.resident.load()) return NIXIE_OK;
+    std::lock_guard<std::mutex> lk(s.mu);
+    int rc = NIXIE_OK;
+    for (auto &kv : s.table)
+        if ((rc = nixie_space_map(s.space, kv.first - s.base, kv.second.blocks * s.block)) != 0) return rc;
+    const std::vector<nixie_alloc_t> rows = rows_with_host_copy(s);   // allocations made while evicted have nothing to bring back
+    rc = run_switch(s, {}, rows);
+    if (rc) return rc;
+    uint64_t bytes = 0;
+    for (auto &kv : s.table)
+        if (kv.second.host) {
+            munmap(kv.second.host, kv.second.bytes);
+            kv.second.host = nullptr;
+            bytes += kv.second.bytes;
+        }
+    s.resident.store(true);
+    s.restores++;
+    say("restored %zu allocations, %llu bytes, in %.3f ms", rows.size(), (unsigned long long)bytes, s.last_switch_ns.load() / 1e6);
+    return NIXIE_OK;
+}
+
+// Around every interposed call of the application that uses device memory: the execution flag.
+// Holds the gate shared for the duration of the call, so a migration cannot start underneath it.
+struct Running {
+    Shim *s;
+    std::shared_lock<std::shared_mutex> hold;
+    explicit Running(Shim *sh, bool may_block = false) : s(sh), may_block_(may_block) {
+        if (!s) return;
+        hold = std::shared_lock<std::shared_mutex>(s->gate);
+        while (!s->resident.load()) {          // step 2: not runnable -> ask for the GPU, wait for the memory
+            hold.unlock();
+            s->launches_held++;
+            {
+                std::unique_lock<std::shared_mutex> x(s->gate);
+                Inside in;
+                const int rc = restore_locked(*s);
+                if (rc) {
+                    std::fprintf(stderr, "nixie-shim: cannot bring the application back (%s)\n", nixie_strerror(rc));
+                    std::abort();   // its pointers have nothing behind them: no call can go ahead
+                }
+            }
+            hold.lock();
+        }
+        if (may_block_) s->blocking++;
+    }
+    ~Running() {
+        if (!s) return;
+        if (may_block_) s->blocking--;
+        s->last_return.store(now_ns());
+    }
+
+private:
+    bool may_block_;
+};
+
+}  // namespace
+
+extern "C" {
+
+hipError_t hipMalloc(void **ptr, size_t size) {
+    if (t_inside) return REAL(hipMalloc)(ptr, size);
+    Shim *s = shim();
+    if (!s || !ptr || size < s->min_bytes) {
+        const hipError_t e = REAL(hipMalloc)(ptr, size);
+        if (s && e == hipSuccess && ptr && *ptr) { std::lock_guard<std::mutex> lk(s->mu); s->passthrough++; }
+        if (s) s->last_return.store(now_ns());
+        return e;
+    }
+    std::shared_lock<std::shared_mutex> hold(s->gate);   // not in the middle of a migration
+    Inside in;
+    std::lock_guard<std::mutex> lk(s->mu);
+    const uint64_t need = (size + s->block - 1) / s->block;
+    for (auto it = s->free_runs.begin(); it != s->free_runs.end(); ++it) {
+        if (it->second < need) continue;
+        const uint64_t first = it->first, rest = it->second - need;
+        // an evicted application's new memory gets its physical blocks when the application comes back
+        if (s->resident.load() && nixie_space_map(s->space, first * s->block, need * s->block) != NIXIE_OK) break;
+        s->free_runs.erase(it);
+        if (rest) s->free_runs[first + need] = rest;
+        const uint64_t addr = s->base + first * s->block;
+        s->table[addr] = Alloc{size, need, nullptr};
+        s->managed_bytes += need * s->block;
+        *ptr = (void *)(uintptr_t)addr;
+        s->last_return.store(now_ns());
+        return hipSuccess;
+    }
+    s->last_return.store(now_ns());
+    return hipErrorOutOfMemory;
+}
+
+hipError_t hipFree(void *ptr) {
+    if (t_inside) return REAL(hipFree)(ptr);
+    Shim *s = shim();
+    if (s && ptr) {
+        std::shared_lock<std::shared_mutex> hold(s->gate);
+        Inside in;
+        std::unique_lock<std::mutex> lk(s->mu);
+        auto it = s->table.find((uint64_t)(uintptr_t)ptr);
+        if (it != s->table.end()) {
+            const Alloc a = it->second;
+            if (s->resident.load()) {
+                lk.unlock();
+                (void)REAL(hipDeviceSynchronize)();   // as the runtime's hipFree does: nothing may still use it
+                lk.lock();
+                (void)nixie_space_unmap(s->space, it->first - s->base, a.blocks * s->block);
+            }
+            if (a.host) munmap(a.host, a.bytes);
+            uint64_t first = (it->first - s->base) / s->block, n = a.blocks;
+            s->table.erase(it);
+            s->managed_bytes -= n * s->block;
+            auto nx = s->free_runs.lower_bound(first);           // merge with the free neighbours
+            if (nx != s->free_runs.end() && nx->first == first + n) { n += nx->second; nx = s->free_runs.erase(nx); }
+            if (nx != s->free_runs.begin()) {
+                auto pv = std::prev(nx);
+                if (pv->first + pv->second == first) { first = pv->first; n += pv->second; s->free_runs.erase(pv); }
+            }
+            s->free_runs[first] = n;
+            s->last_return.store(now_ns());
+            return hipSuccess;
+        }
+        if (s->passthrough) s->passthrough--;
+    }
+    const hipError_t e = REAL(hipFree)(ptr);
+    if (s) s->last_return.store(now_ns());
+    return e;
+}
+
+hipError_t hipMemGetInfo(size_t *free_bytes, size_t *total_bytes) {
+    if (t_inside) return REAL(hipMemGetInfo)(free_bytes, total_bytes);
+    Shim *s = shim();
+    if (!s) return REAL(hipMemGetInfo)(free_bytes, total_bytes);
+    if (!free_bytes || !total_bytes) return hipErrorInvalidValue;
+    std::lock_guard<std::mutex> lk(s->mu);
+    *total_bytes = s->capacity;
+    *free_bytes = s->capacity - s->managed_bytes;
+    s->last_return.store(now_ns());
+    return hipSuccess;
+}
+
+hipError_t hipLaunchKernel(const void *function_address, dim3 numBlocks, dim3 dimBlocks, void **args, size_t sharedMemBytes,
+                           hipStream_t stream) {
+    if (t_inside) return REAL(hipLaunchKernel)(function_address, numBlocks, dimBlocks, args, sharedMemBytes, stream);
+    Running r(shim());
+    return REAL(hipLaunchKernel)(function_address, numBlocks, dimBlocks, args, sharedMemBytes, stream);
+}
+
+hipError_t hipModuleLaunchKernel(hipFunction_t f, unsigned int gridDimX, unsigned int gridDimY, unsigned int gridDimZ,
+                                 unsigned int blockDimX, unsigned int blockDimY, unsigned int blockDimZ,
+                                 unsigned int sharedMemBytes, hipStream_t stream, void **kernelParams, void **extra) {
+    if (t_inside)
+        return REAL(hipModuleLaunchKernel)(f, gridDimX, gridDimY, gridDimZ, blockDimX, blockDimY, blockDimZ, sharedMemBytes,
+                                           stream, kernelParams, extra);
+    Running r(shim());
+    return REAL(hipModuleLaunchKernel)(f, gridDimX, gridDimY, gridDimZ, blockDimX, blockDimY, blockDimZ, sharedMemBytes, stream,
+                                       kernelParams, extra);
+}
+
+// Copies and fills address device memory too: same flag.  The synchronous ones may block.
+hipError_t hipMemcpy(void *dst, const void *src, size_t sizeBytes, hipMemcpyKind kind) {
+    if (t_inside) return REAL(hipMemcpy)(dst, src, sizeBytes, kind);
+    Running r(shim(), true);
+    return REAL(hipMemcpy)(dst, src, sizeBytes, kind);
+}
+
+hipError_t hipMemcpyAsync(void *dst, const void *src, size_t sizeBytes, hipMemcpyKind kind, hipStream_t stream) {
+    if (t_inside) return REAL(hipMemcpyAsync)(dst, src, sizeBytes, kind, stream);
+    Running r(shim());
+    return REAL(hipMemcpyAsync)(dst, src, sizeBytes, kind, stream);
+}
+
+hipError_t hipMemset(void *dst, int value, size_t sizeBytes) {
+    if (t_inside) return REAL(hipMemset)(dst, value, sizeBytes);
+    Running r(shim(), true);
+    return REAL(hipMemset)(dst, value, sizeBytes);
+}
+
+hipError_t hipMemsetAsync(void *dst, int value, size_t sizeBytes, hipStream_t stream) {
+    if (t_inside) return REAL(hipMemsetAsync)(dst, value, sizeBytes, stream);
+    Running r(shim());
+    return REAL(hipMemsetAsync)(dst, value, sizeBytes, stream);
+}
+
+// Blocking calls are bracketed so that an application waiting inside the runtime is not taken for idle.
+hipError_t hipDeviceSynchronize(void) {
+    if (t_inside) return REAL(hipDeviceSynchronize)();
+    Shim *s = shim();
+    if (s) s->blocking++;
+    const hipError_t e = REAL(hipDeviceSynchronize)();
+    if (s) { s->blocking--; s->last_return.store(now_ns()); }
+    return e;
+}
+
+hipError_t hipStreamSynchronize(hipStream_t stream) {
+    if (t_inside) return REAL(hipStreamSynchronize)(stream);
+    Shim *s = shim();
+    if (s) s->blocking++;
+    const hipError_t e = REAL(hipStreamSynchronize)(stream);
+    if (s) { s->blocking--; s->last_return.store(now_ns()); }
+    return e;
+}
+
+int nixie_shim_info(nixie_shim_info_t *info) {
+    if (!info || !g || !g->ok) return NIXIE_EINVAL;
+    Shim &s = *g;
+    std::lock_guard<std::mutex> lk(s.mu);
+    info->capacity_bytes = s.capacity;
+    info->block_bytes = s.block;
+    info->managed_bytes = s.managed_bytes;
+    info->managed_allocs = s.table.size();
+    info->passthrough_allocs = s.passthrough;
+    info->resident = s.resident.load() ? 1u : 0u;
+    info->evictions = s.evictions.load();
+    info->restores = s.restores.load();
+    info->last_switch_ns = s.last_switch_ns.load();
+    info->launches_held = s.launches_held.load();
+    return NIXIE_OK;
+}
+
+int nixie_shim_evict(void) {
+    Shim *s = shim();
+    if (!s) return NIXIE_EINVAL;
+    std::unique_lock<std::shared_mutex> hold(s->gate);
+    Inside in;
+    return evict_locked(*s);
+}
+
+int nixie_shim_restore(void) {
+    Shim *s = shim();
+    if (!s) return NIXIE_EINVAL;
+    std::unique_lock<std::shared_mutex> hold(s->gate);
+    Inside in;
+    return restore_locked(*s);
+}
+
+}  // extern "C"

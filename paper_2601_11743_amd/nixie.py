@@ -73,7 +73,8 @@ class _Stats(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in (
         "bytes_out", "bytes_in", "ns_total", "ns_out_done", "ns_in_done", "ns_kernel", "ns_launch",
         "drain_wait_ns", "fill_wait_ns", "gather_stall_ticks", "scatter_stall_ticks")] + [
-        ("kernels", C.c_uint32), ("gpu_status", C.c_uint32)]
+        ("kernels", C.c_uint32), ("gpu_status", C.c_uint32), ("pump_rounds_out", C.c_uint32), ("pump_rounds_in", C.c_uint32),
+        ("credit_rtt_ticks_out", C.c_uint32), ("credit_rtt_ticks_in", C.c_uint32)]
 
 
 class _Report(C.Structure):

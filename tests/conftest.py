@@ -1,4 +1,6 @@
+import json
 import os
+import subprocess
 import sys
 
 import pytest
@@ -7,9 +9,39 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+_spawner = None
+
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # Started now, before any test can have initialised the GPU in this process: see tests/spawner.py.
+    global _spawner
+    if _spawner is None:
+        _spawner = subprocess.Popen([sys.executable, "-u", os.path.join(ROOT, "tests", "spawner.py")],
+                                    stdin=subprocess.PIPE, stdout=subprocess.PIPE, text=True, cwd=ROOT)
+
+
+def pytest_unconfigure(config):
+    global _spawner
+    if _spawner is not None:
+        try:
+            _spawner.stdin.close()
+            _spawner.wait(timeout=10)
+        except Exception:
+            _spawner.kill()
+        _spawner = None
+
+
+@pytest.fixture(scope="session")
+def run_program():
+    """run_program(argv, env=None, timeout=60) -> {"rc", "stdout", "stderr"}: a fresh process started by
+    the helper, which never touched the GPU."""
+    def run(argv, env=None, timeout=60):
+        assert _spawner is not None and _spawner.poll() is None, "the program-starting helper is not running"
+        _spawner.stdin.write(json.dumps({"argv": list(argv), "env": env or {}, "timeout": timeout}) + "\n")
+        _spawner.stdin.flush()
+        return json.loads(_spawner.stdout.readline())
+    return run
 
 
 @pytest.fixture(scope="session")

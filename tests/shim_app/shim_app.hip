@@ -1,0 +1,96 @@
+// A small, ordinary HIP program that knows nothing of nixie: it allocates, fills its buffers with
+// kernels, falls silent for a while (an interactive application waiting for its user), then
+// checks every buffer with kernels through the pointers it got at the start.  The shim's GPU test
+// runs it unchanged, once alone and once under LD_PRELOAD=libnixie_shim.so with idle eviction on:
+// there it loses its GPU memory while it is silent and must find the same bytes at the same
+// addresses when it wakes up.
+//
+// usage: shim_app <pause_ms> <big_mib> [rounds]
+#include <hip/hip_runtime.h>
+
+#include <chrono>
+#include <cstdint>
+#include <cstdio>
+#include <cstdlib>
+#include <thread>
+#include <vector>
+
+#define CHECK(call)                                                                           \
+    do {                                                                                      \
+        hipError_t e_ = (call);                                                               \
+        if (e_ != hipSuccess) {                                                               \
+            std::printf("FAIL %s: %s\n", #call, hipGetErrorString(e_));                       \
+            return 1;                                                                         \
+        }                                                                                     \
+    } while (0)
+
+__device__ __host__ inline uint32_t pattern(uint32_t seed, uint64_t i) {
+    uint64_t z = (i + 1) * 0x9E3779B97F4A7C15ull + seed;
+    z = (z ^ (z >> 29)) * 0xBF58476D1CE4E5B9ull;
+    return (uint32_t)(z >> 32);
+}
+
+__global__ void fill(uint32_t *p, uint64_t n, uint32_t seed) {
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (uint64_t)gridDim.x * blockDim.x)
+        p[i] = pattern(seed, i);
+}
+
+__global__ void bump(uint32_t *p, uint64_t n) {
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (uint64_t)gridDim.x * blockDim.x)
+        p[i] += 1;
+}
+
+__global__ void check(const uint32_t *p, uint64_t n, uint32_t seed, uint32_t bumps, unsigned long long *bad) {
+    unsigned long long mine = 0;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (uint64_t)gridDim.x * blockDim.x)
+        mine += p[i] != pattern(seed, i) + bumps;
+    if (mine) atomicAdd(bad, mine);
+}
+
+int main(int argc, char **argv) {
+    const int pause_ms = argc > 1 ? std::atoi(argv[1]) : 500;
+    const uint64_t big = (argc > 2 ? std::strtoull(argv[2], nullptr, 10) : 48) << 20;
+    const int rounds = argc > 3 ? std::atoi(argv[3]) : 2;
+    size_t free0 = 0, total0 = 0;
+    CHECK(hipMemGetInfo(&free0, &total0));
+    // a few buffers of mixed sizes: three large ones and two small ones
+    const uint64_t sizes[5] = {big, big / 3 + 4096, 5u << 20, 64u << 10, 1000};
+    uint32_t *buf[5];
+    for (int b = 0; b < 5; b++) CHECK(hipMalloc((void **)&buf[b], sizes[b]));
+    size_t free1 = 0, total1 = 0;
+    CHECK(hipMemGetInfo(&free1, &total1));
+    std::printf("meminfo total %zu free_before %zu free_after %zu\n", total1, free0, free1);
+    for (int b = 0; b < 5; b++) std::printf("buffer %d at %p, %llu bytes\n", b, (void *)buf[b], (unsigned long long)sizes[b]);
+    unsigned long long *bad = nullptr;
+    CHECK(hipMalloc((void **)&bad, sizeof(*bad)));
+    CHECK(hipMemset(bad, 0, sizeof(*bad)));
+    for (int b = 0; b < 5; b++) fill<<<256, 256>>>(buf[b], sizes[b] / 4, 100 + b);
+    CHECK(hipGetLastError());
+    CHECK(hipDeviceSynchronize());
+    std::fflush(stdout);
+    unsigned long long total_bad = 0;
+    for (int r = 0; r < rounds; r++) {
+        std::this_thread::sleep_for(std::chrono::milliseconds(pause_ms));   // silence: no runtime call at all
+        for (int b = 0; b < 5; b++) check<<<256, 256>>>(buf[b], sizes[b] / 4, 100 + b, (uint32_t)r, bad);
+        for (int b = 0; b < 5; b++) bump<<<256, 256>>>(buf[b], sizes[b] / 4);                  // the state moves on
+        CHECK(hipGetLastError());
+        unsigned long long h = 0;
+        CHECK(hipMemcpy(&h, bad, sizeof(h), hipMemcpyDeviceToHost));
+        std::printf("round %d: %llu wrong words\n", r, h);
+        std::fflush(stdout);
+        total_bad = h;
+    }
+    // a host-side look at one large buffer through the runtime's copy, as an application would read results back
+    std::vector<uint32_t> head(1024);
+    CHECK(hipMemcpy(head.data(), buf[0], head.size() * 4, hipMemcpyDeviceToHost));
+    for (size_t i = 0; i < head.size(); i++) total_bad += head[i] != pattern(100, i) + (uint32_t)rounds;
+    CHECK(hipFree(buf[1]));
+    size_t free2 = 0, total2 = 0;
+    CHECK(hipMemGetInfo(&free2, &total2));
+    std::printf("meminfo free_after_one_free %zu\n", free2);
+    for (int b = 0; b < 5; b++)
+        if (b != 1) CHECK(hipFree(buf[b]));
+    CHECK(hipFree(bad));
+    std::printf(total_bad ? "RESULT wrong %llu\n" : "RESULT ok %llu\n", total_bad);
+    return total_bad ? 1 : 0;
+}

@@ -1,0 +1,87 @@
+"""The transparent shim on the GPU (paper, "Supporting Unmodified CUDA Applications").
+
+tests/shim_app/shim_app is an ordinary HIP program that knows nothing of nixie.  Started as a
+fresh process with LD_PRELOAD=libnixie_shim.so and idle eviction on, it loses its GPU memory
+every time it falls silent (the shim moves its large allocations to pageable host memory with
+the context-switch swap, unmaps the physical blocks and overwrites them through another address
+space, as a second application would), and every time it wakes up its first launch brings the
+bytes back to the same addresses.  The program's own kernels do the checking."""
+import os
+import re
+
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+APP = os.path.join(ROOT, "tests", "shim_app", "shim_app")
+SHIM = os.path.join(ROOT, "paper_2601_11743_amd", "libnixie_shim.so")
+MiB = 1 << 20
+
+
+def preload_env(**extra):
+    """LD_PRELOAD with the shim appended to whatever is preloaded already."""
+    have = os.environ.get("LD_PRELOAD", "")
+    env = {"LD_PRELOAD": (have + ":" if have else "") + SHIM}
+    env.update({k: str(v) for k, v in extra.items()})
+    return env
+
+
+def parse(out):
+    m = re.search(r"meminfo total (\d+) free_before (\d+) free_after (\d+)", out)
+    info = dict(total=int(m.group(1)), free_before=int(m.group(2)), free_after=int(m.group(3)))
+    info["free_after_one_free"] = int(re.search(r"meminfo free_after_one_free (\d+)", out).group(1))
+    info["buffers"] = [(int(a, 16), int(b)) for a, b in re.findall(r"buffer \d+ at (0x[0-9a-f]+), (\d+) bytes", out)]
+    info["rounds"] = [int(x) for x in re.findall(r"round \d+: (\d+) wrong words", out)]
+    return info
+
+
+def test_application_alone(run_program):
+    assert os.path.exists(APP) and os.path.exists(SHIM), "build first (python -m paper_2601_11743_amd.build)"
+    print("shim_app without the shim", flush=True)
+    r = run_program([APP, "50", "48", "2"], timeout=90)
+    assert r["rc"] == 0 and "RESULT ok" in r["stdout"], r
+    assert parse(r["stdout"])["total"] > 64 << 30          # the real device
+
+
+def test_idle_application_is_evicted_and_comes_back_at_the_same_addresses(run_program):
+    print("shim_app under LD_PRELOAD, idle eviction after 100 ms, 600 ms pauses", flush=True)
+    env = preload_env(NIXIE_SHIM_IDLE_MS=100, NIXIE_SHIM_SCRIBBLE=1, NIXIE_SHIM_LOG=1, NIXIE_SHIM_POOL_MIB=256,
+                      NIXIE_SHIM_RING_MIB=16)
+    r = run_program([APP, "600", "48", "3"], env=env, timeout=120)
+    assert r["rc"] == 0 and "RESULT ok" in r["stdout"], r
+    log = r["stderr"]
+    m = re.search(r"managing (\d+) MiB in (\d+) MiB blocks at (0x[0-9a-f]+), allocations from (\d+) bytes", log)
+    assert m, log
+    cap, block, base = int(m.group(1)) * MiB, int(m.group(2)) * MiB, int(m.group(3), 16)
+    info = parse(r["stdout"])
+    assert info["rounds"] == [0, 0, 0]
+    # three pauses -> three evictions, each undone by the first launch after it
+    evicted = re.findall(r"evicted (\d+) allocations, (\d+) bytes", log)
+    restored = re.findall(r"restored (\d+) allocations, (\d+) bytes", log)
+    assert len(evicted) == 3 and len(restored) == 3, log
+    managed = [(a, b) for a, b in info["buffers"] if b >= block]
+    small = [(a, b) for a, b in info["buffers"] if b < block]
+    assert all(base <= a and a + b <= base + cap and (a - base) % block == 0 for a, b in managed)
+    assert all(not (base <= a < base + cap) for a, b in small)           # small allocations pass through
+    assert all(int(n) == len(managed) and int(b) == sum(x for _, x in managed) for n, b in evicted + restored)
+    # the memory report: the capacity the shim was given, minus this process's own whole blocks
+    blocks = lambda b: -(-b // block) * block
+    assert info["total"] == cap and info["free_before"] == cap
+    assert info["free_after"] == cap - sum(blocks(b) for _, b in managed)
+    assert info["free_after_one_free"] == info["free_after"] + blocks(info["buffers"][1][1])
+
+
+def test_busy_application_is_left_alone(run_program):
+    """No pause longer than the threshold: nothing is evicted, and without idle eviction configured
+    the shim only manages addresses."""
+    env = preload_env(NIXIE_SHIM_IDLE_MS=2000, NIXIE_SHIM_LOG=1, NIXIE_SHIM_POOL_MIB=256)
+    r = run_program([APP, "20", "48", "3"], env=env, timeout=120)
+    assert r["rc"] == 0 and "RESULT ok" in r["stdout"], r
+    assert "evicted" not in r["stderr"] and "managing 256 MiB" in r["stderr"]
+
+
+def test_allocation_beyond_the_capacity_fails_cleanly(run_program):
+    env = preload_env(NIXIE_SHIM_LOG=1, NIXIE_SHIM_POOL_MIB=64)
+    r = run_program([APP, "10", "48", "1"], env=env, timeout=120)      # 48 + 16 + 5 MiB do not fit 64 MiB
+    assert r["rc"] == 1 and "FAIL hipMalloc" in r["stdout"], r

@@ -171,7 +171,7 @@ def test_planner_ring_split_and_defaults(nx):
     lay = nx.Layout(ra, rb, 16 * MiB)                  # small ring: smaller slots and smaller work units
     i = lay.info()
     assert i["slot_bytes"] == 64 * KiB and i["out_slots"] == 128
-    assert i["team_out"] == 4                          # 16 KiB units: 128 units in flight = a quarter of 8 MiB
+    assert i["team_out"] == 2                          # 32 KiB units, the floor: one 8 KiB tile per wave
     lay = nx.Layout(ra, rb, 4 * MiB)
     assert lay.info()["slot_bytes"] == 64 * KiB and lay.info()["out_slots"] == 32
     lay = nx.Layout(ra, rb, 256 * KiB)
@@ -335,3 +335,25 @@ def test_header_is_plain_c_and_binding_structs_match(tmp_path):
     sizes = dict(line.split() for line in out.splitlines())
     for name, ct in pairs.items():
         assert int(sizes[name]) == ctypes.sizeof(ct), f"{name}: C says {sizes[name]}, the binding {ctypes.sizeof(ct)}"
+
+
+def test_shim_library_exports_what_its_header_declares():
+    """libnixie_shim.so (include/nixie_shim.h): the interposed runtime calls under the runtime's own
+    names plus the three nixie_shim_* calls.  Loaded privately here, so nothing is interposed."""
+    import ctypes
+    import re
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    path = os.path.join(root, "paper_2601_11743_amd", "libnixie_shim.so")
+    assert os.path.exists(path), "build first: python -m paper_2601_11743_amd.build"
+    header = open(os.path.join(root, "include", "nixie_shim.h")).read()
+    declared = set(re.findall(r"\b(nixie_shim_\w+)\s*\(", header)) - {"nixie_shim_info_t"}
+    assert declared == {"nixie_shim_info", "nixie_shim_evict", "nixie_shim_restore"}
+    lib = ctypes.CDLL(path, mode=os.RTLD_LOCAL)
+    interposed = ["hipMalloc", "hipFree", "hipMemGetInfo", "hipLaunchKernel", "hipModuleLaunchKernel", "hipMemcpy",
+                  "hipMemcpyAsync", "hipMemset", "hipMemsetAsync", "hipDeviceSynchronize", "hipStreamSynchronize"]
+    for name in interposed:
+        assert name in header, name                      # documented
+    for name in sorted(declared) + interposed:
+        assert getattr(lib, name) is not None, name
+    info = (ctypes.c_uint64 * 16)()
+    assert lib.nixie_shim_info(info) == -1               # NIXIE_EINVAL: no interposed call has been made

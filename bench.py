@@ -240,6 +240,10 @@ def main() -> int:
                     help="switch latency against the amount of memory oversubscription: a notional GPU capacity "
                          "of (A + B - oversubscribed size); nixie_place evicts only what the incoming application "
                          "needs; ping-pong A<->B; adds an 'oversubscription_sweep' list to the JSON line")
+    ap.add_argument("--prefetch", action="store_true",
+                    help="after the timed steps: act on a scheduler's prefetch hint for B -- nixie_host_copy moves B from "
+                         "pageable memory into a registered pinned tier (timed, off the switch's critical path), then the "
+                         "same switch runs with B moving directly; adds a 'prefetch' object to the JSON line")
     ap.add_argument("--ring-sweep", action="store_true",
                     help="config 5 protocol: for every ring size of the config, 10 back-to-back ping-pong "
                          "switches A<->B; adds a 'ring_sweep' list to the JSON line")
@@ -412,6 +416,41 @@ def main() -> int:
                 pl.close()
         shared_ring.close()
 
+    prefetch = None
+    if args.prefetch and pool is None and not args.in_place and args.pinned_tier == "none":
+        # B's bytes are still in its pageable arena (a switch leaves its sources alone unless they are reused).
+        pin_t = torch.empty(max(B.layout.total, 4096), dtype=torch.uint8, pin_memory=True)
+        pin = pin_t.numpy()
+        nx.tier_register(pin.ctypes.data, pin.size)
+        offs = np.asarray(B.layout.offsets, dtype=np.uint64)
+        src = (np.uint64(B.host.ctypes.data) + offs).tolist()
+        dst = (np.uint64(pin.ctypes.data) + offs).tolist()
+        threads = max(1, min(8, (os.cpu_count() or 2) // 2))
+        nx.host_copy(dst[:1], src[:1], B.sizes[:1], threads)          # touch the code path
+        c0, t0 = time.process_time(), time.perf_counter()
+        nx.host_copy(dst, src, B.sizes, threads)
+        pf_s, pf_cpu = time.perf_counter() - t0, time.process_time() - c0
+        rows_bp = rows_b.copy()
+        rows_bp[:, 1] = np.uint64(pin.ctypes.data) + offs
+        pp = nx.Plan(rows_a, rows_bp, ring, opts)
+        pi = pp.info()
+        pp.switch()
+        c0 = time.process_time()
+        sts = [pp.switch() for _ in range(3)]
+        cpu_after = (time.process_time() - c0) / 3
+        rep_p = pp.verify(h_out, h_in, check=False)
+        pp.close()
+        nx.tier_unregister(pin.ctypes.data)
+        prefetch = {"prefetch_ms": round(pf_s * 1e3, 2), "prefetch_GBps": round(B.total_bytes / pf_s / 1e9, 2),
+                    "prefetch_threads": threads, "prefetch_cpu_s": round(pf_cpu, 3),
+                    "direct_bytes_in": pi["direct_bytes_in"], "fill_threads_after": pi["fill_threads"],
+                    "switch_after_prefetch": summarize(sts, pi, peak), "host_cpu_s_per_switch_after": round(cpu_after, 4),
+                    "hash_mismatches": rep_p["mismatched_out"] + rep_p["mismatched_in"],
+                    "note": "the prefetch runs while the outgoing application still owns the GPU; compare "
+                            "switch_after_prefetch and host_cpu_s_per_switch_after with the line's own figures"}
+        log("[bench] prefetch:", prefetch)
+        del pin, pin_t
+
     sweep = None
     if args.ring_sweep:
         sweep = ring_sweep(nx, rows_a, rows_b, cf["ring_bytes"], opts, h_out, h_in, peak, log)
@@ -503,6 +542,8 @@ def main() -> int:
                            "unmap_median": round(med(sorted(remap_ms["unmap"][k:])), 3),
                            "note": "inside ms_per_step: map the incoming application's space before the switch, "
                                    "unmap the outgoing one's after it"}
+    if prefetch is not None:
+        res["prefetch"] = prefetch
     if sweep is not None:
         res["ring_sweep"] = sweep
     if oversub is not None:

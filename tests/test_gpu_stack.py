@@ -71,6 +71,24 @@ class World:
                 return got
         return None
 
+    def prefetch(self, a):
+        """Act on the scheduler's prefetch hint (paper, "MLFQ with Prefetching": the application at the
+        head of the queue is the one most likely to run next, so its data is brought up a tier ahead
+        of time): chunks of application a that wait in pageable memory move into the pinned tier with
+        nixie_host_copy while there is room.  Returns the bytes moved."""
+        nx, ap, moved = self.nx, self.apps[a], 0
+        for j, b in enumerate(ap["sizes"]):
+            if ap["tier"][j] != nx.TIER_PAGEABLE:
+                continue
+            units = self.take_units(b // BLOCK)
+            if units is None:
+                continue
+            nx.host_copy([self.pin.ctypes.data + units[0] * BLOCK], [ap["pageable"].ctypes.data + ap["offs"][j]], [b])
+            ap["pageable"][ap["offs"][j]:ap["offs"][j] + b] = 0xDD          # exactly one copy: the old one is dead
+            ap["tier"][j], ap["units"][j] = nx.TIER_PINNED, units
+            moved += b
+        return moved
+
     def activate(self, run, victims):
         nx = self.nx
         index, chunks = [], []
@@ -112,6 +130,7 @@ class World:
         if out_rows or in_rows:
             plan = nx.Plan(out_rows, in_rows, 8 * MiB, nx.Opts(flags=nx.IN_PLACE))
             info = plan.info()
+            self.last_info = info
             assert info["bytes_out"] == summ["evicted_bytes"] and info["bytes_in"] == summ["restored_bytes"]
             plan.switch_begin()
             plan.switch_wait_in()                                        # the application could run from here on
@@ -189,5 +208,54 @@ def test_scheduler_placement_and_switch_together(nx):
     assert log[0][1] == 0 and log[1][1] == 0            # the first two fit side by side: nothing is evicted
     assert any(e > 0 and k > 0 for _, e, k, _ in log)   # later someone has to go, partly into the pinned tier
     assert any(0 < e < 14 for _, e, _, _ in log)        # and only as far as needed (the batch job has 14 blocks)
+    sched.close()
+    world.close()
+
+
+def test_prefetch_hint_is_acted_on_before_the_switch(nx):
+    """Two applications of level 1, a pool that holds one of them.  While application 0 computes,
+    application 1 asks for the GPU and has to wait for the end of the turn (S_1 = 4 s): every tick
+    names it as the prefetch candidate, and the harness moves its chunks from pageable memory into
+    the pinned tier as far as that has room.  The switch that follows then moves exactly those
+    chunks directly (no ring slot, no host thread) and the rest through the ring, and every chunk of
+    both applications holds its bytes before and after."""
+    from tests.gpu_helpers import RawDevice
+    raw = RawDevice(nx.lib_path())
+    SEC, MS = 1_000_000_000, 1_000_000
+    world = World(nx, raw, [[4, 3, 2], [3, 3, 3]], pool_blocks=10, pinned_units=6)
+    sched = nx.Sched()
+    a0, a1 = sched.add_app(0), sched.add_app(0)
+    sched.request(a0, 0)
+    d = sched.tick(0)
+    assert d["run"] == a0 and d["switched"]
+    world.activate(a0, [a1])
+    world.check_everything()
+    t, prefetched, hints, switched_at = 0, 0, 0, None
+    while t < 6 * SEC and switched_at is None:
+        t += 250 * MS
+        for k in range(1, 26):                                   # application 0 computes without a pause
+            sched.api_return(a0, t - 250 * MS + k * 10 * MS)
+        if t == 1 * SEC:
+            sched.request(a1, t - 5 * MS)
+        d = sched.tick(t)
+        if d["switched"]:
+            assert d["run"] == a1 and d["evict"] == a0
+            switched_at = t
+            break
+        if d["prefetch"] >= 0:
+            assert d["prefetch"] == a1 and d["run"] == a0
+            hints += 1
+            prefetched += world.prefetch(d["prefetch"])          # idempotent once the tier is full
+            world.check_everything()
+    assert switched_at == 4 * SEC                                 # the turn of application 0 began at 0
+    assert hints >= 10 and prefetched == 6 * BLOCK               # two of its three chunks fit the six units
+    assert [x == nx.TIER_PINNED for x in world.apps[a1]["tier"]] == [True, True, False]
+    summ, st = world.activate(a1, [a0])
+    info = world.last_info
+    assert info["direct_bytes_in"] == prefetched and info["bytes_in"] == 9 * BLOCK
+    assert info["direct_bytes_out"] == 0                          # the pinned tier was full when the eviction was planned
+    assert summ["restored_from_pageable_bytes"] == 3 * BLOCK
+    world.check_everything()
+    assert all(x == nx.TIER_GPU for x in world.apps[a1]["tier"]) and sorted(world.free_units) == list(range(6))
     sched.close()
     world.close()

@@ -136,7 +136,14 @@ def test_config4_fragmented_full(nx, oracle):
     print(f"\nconfig 4: {st['ns_total'] / 1e6:.1f} ms, {info['segments_out']} segments out")
 
 
-@pytest.mark.parametrize("ring_mib", [16, 1024])
+def test_config6_the_metric_taken_literally_full(nx, oracle):
+    """Exactly 16 GiB out and 16 GiB in (64 x 256 MiB each) through the 256 MiB ring in 4 MiB slots."""
+    info, st = full_case(nx, oracle, 6, 256 * MiB)
+    assert info["bytes_out"] == 16 * GiB and info["bytes_in"] == 16 * GiB
+    assert info["slot_bytes"] == 4 * MiB and info["pinned_ring_bytes"] == 256 * MiB
+
+
+@pytest.mark.parametrize("ring_mib", [16, 64, 256, 1024])
 def test_config5_pingpong_full(nx, oracle, ring_mib):
     info, st = full_case(nx, oracle, 5, ring_mib * MiB, round_trips=1)
     assert info["pinned_ring_bytes"] <= ring_mib * MiB

@@ -426,6 +426,7 @@ def main() -> int:
         src = (np.uint64(B.host.ctypes.data) + offs).tolist()
         dst = (np.uint64(pin.ctypes.data) + offs).tolist()
         threads = max(1, min(8, (os.cpu_count() or 2) // 2))
+        pin[::4096] = 0                                               # a long-lived tier: its pages are mapped already
         nx.host_copy(dst[:1], src[:1], B.sizes[:1], threads)          # touch the code path
         c0, t0 = time.process_time(), time.perf_counter()
         nx.host_copy(dst, src, B.sizes, threads)
@@ -513,6 +514,7 @@ def main() -> int:
                                f"ring {ring >> 20} MiB in {info['slot_bytes'] >> 10} KiB slots",
                    "ring_bytes": ring, "slot_bytes": info["slot_bytes"], "out_slots": info["out_slots"],
                    "in_slots": info["in_slots"], "gather_wgs": info["gather_wgs"], "scatter_wgs": info["scatter_wgs"],
+                   "flex_wgs": info["flex_wgs"],
                    "team": info["team_out"], "drain_threads": info["drain_threads"],
                    "fill_threads": info["fill_threads"], "flags": args.flags, "scale": args.scale,
                    "in_place": bool(args.in_place), "pinned_tier": args.pinned_tier,

@@ -84,8 +84,9 @@ enum nixie_flags {
     NIXIE_HOST_SPIN = 1u << 7,        /* host threads with nothing to do spin.  By default they sleep for 1/16 of the time
                                          their direction's share of the ring lasts at link rate (at most 50 us, never
                                          when that is under 4 us): same latency, less than half the CPU time */
-    NIXIE_NO_DIRECT = 1u << 6         /* measurement: allocations whose host side lies in the registered pinned tier
+    NIXIE_NO_DIRECT = 1u << 6,        /* measurement: allocations whose host side lies in the registered pinned tier
                                          go through the ring and the host threads like all others */
+    NIXIE_NO_FLEX_WGS = 1u << 8       /* every workgroup has a fixed direction (flex_wgs = 0 means "default") */
 };
 
 /* Every field 0 = library default. */
@@ -109,6 +110,9 @@ typedef struct {
     uint32_t xcd_mask;       /* tuning: bit i set = workgroups that land on XCD i take part, the others leave at
                                 once (workgroups are dealt round-robin over the 8 XCDs, so raise gather_wgs /
                                 scatter_wgs accordingly); 0 = all XCDs                                       */
+    uint32_t flex_wgs;       /* workgroups on top of gather_wgs + scatter_wgs that serve either direction: before
+                                every work unit they take the direction with more chunks left, so that two
+                                working sets of equal size finish together; NIXIE_NO_FLEX_WGS in flags = none */
 } nixie_opts_t;
 
 typedef struct nixie_plan nixie_plan_t;     /* opaque; owns ring, flags, descriptors, host threads */
@@ -128,6 +132,7 @@ typedef struct {
     uint32_t drain_threads, fill_threads;
     uint64_t direct_chunks_out, direct_chunks_in; /* chunks that move between HBM and the pinned tier  */
     uint64_t direct_bytes_out, direct_bytes_in;   /* directly: the last of chunks_* / part of bytes_*  */
+    uint32_t flex_wgs;                            /* workgroups that serve either direction            */
 } nixie_plan_info_t;
 
 /* One contiguous piece of one allocation inside one chunk. */
@@ -464,6 +469,12 @@ int nixie_sched_request(nixie_sched_t *sched, int app, uint64_t now_ns);
  * execution time, applies the priority inference to every application, then decides. */
 int nixie_sched_tick(nixie_sched_t *sched, uint64_t now_ns, nixie_sched_decision_t *decision);
 int nixie_sched_app_info(const nixie_sched_t *sched, int app, uint64_t now_ns, nixie_sched_app_t *info);
+
+/* A caller compiled against another version of this header would hand the library structures of the
+ * wrong size.  Pass sizeof(nixie_opts_t), sizeof(nixie_plan_info_t), sizeof(nixie_stats_t): 0 if
+ * they are the library's own, NIXIE_EINVAL otherwise.  The shim and the Python binding check this
+ * once when they start. */
+int nixie_abi_check(uint64_t sizeof_opts, uint64_t sizeof_plan_info, uint64_t sizeof_stats);
 
 const char *nixie_strerror(int err);
 int nixie_last_hip_error(void); /* hipError_t of the last NIXIE_EHIP on this thread */

@@ -18,6 +18,14 @@ FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wextr
 
 
 def build(verbose: bool = False) -> str:
+    """libnixie.so, then everything that is compiled against its header (the shim and the shim's
+    test program), so that the three can never be out of step."""
+    lib = build_library(verbose)
+    build_shim(verbose)
+    return lib
+
+
+def build_library(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc, *FLAGS, "-shared", "-o", LIB,
            *[os.path.join(CSRC, s) for s in SOURCES], "-lpthread"]
@@ -58,4 +66,3 @@ def build_shim(verbose: bool = False) -> str:
 
 if __name__ == "__main__":
     print(build(verbose=True))
-    print(build_shim(verbose=True))

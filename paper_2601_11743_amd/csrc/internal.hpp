@@ -52,11 +52,17 @@ constexpr uint32_t kFlagStride = 8;        // GPU-written flags: one 64 B line (
 // a single wave of the kernel reads a direction's credits with a few line-sized link reads.
 inline uint64_t wait_flag_words(uint32_t slots) { return ((uint64_t)slots + 7) / 8 * 8; }
 constexpr uint32_t kWgThreads = 256;
-// One wave pass: 16 B per lane, 64 lanes, NIXIE_UNROLL loads in flight per lane before the stores.
-#ifndef NIXIE_UNROLL
-#define NIXIE_UNROLL 8
+// One wave pass ("tile"): 16 B per lane, 64 lanes, N loads in flight per lane before the stores.  N is
+// chosen per direction: the bytes a wave has in flight set how deep the queues towards the link run,
+// and posted writes (outgoing) want shallower queues than reads (incoming).
+#ifndef NIXIE_UNROLL_OUT
+#define NIXIE_UNROLL_OUT 4
 #endif
-constexpr uint32_t kTileBytes = 16 * 64 * NIXIE_UNROLL;
+#ifndef NIXIE_UNROLL_IN
+#define NIXIE_UNROLL_IN 4
+#endif
+constexpr uint32_t kTileBytesDir[2] = {16 * 64 * NIXIE_UNROLL_OUT, 16 * 64 * NIXIE_UNROLL_IN};
+constexpr uint32_t kTileBytes = 16 * 64 * 8;   // nominal tile of the host-side device model used in tests
 
 // Words of the GPU-written "done" line (u32 each): [0], [1] = 1 once every workgroup of direction
 // 0 / 1 has left; [kStartedWord] = 1 once the kernel runs (until then a waiting host thread is
@@ -87,7 +93,8 @@ struct DevDir {
     uint32_t *exited;            // device memory, workgroups of this direction that have left
     uint32_t *arrive;            // device memory, one counter per chunk
     uint64_t *stall_ticks;       // device memory, summed wait time
-    uint32_t n_chunks, n_slots, team, wgs;
+    uint32_t n_chunks, n_slots, team;
+    uint32_t wgs;                // workgroups that may take units of this direction (fixed + either); 0 = the direction does not run
     uint32_t n_staged;           // chunks [0, n_staged) take ring slots; the rest are direct
     const uint64_t *direct_base; // device memory, per direct chunk
 };
@@ -103,6 +110,8 @@ struct SwapArgs {
     uint32_t track_prefix;       // 1: in-place switch with both directions running in this launch
     uint32_t xcd_mask;           // 0 = every XCD takes part
     uint32_t *dir_done;          // pinned, GPU-written "done" line: see kStartedWord / kProgressWord
+    uint32_t fixed_wgs[2];       // workgroups that only gather / only scatter
+    uint32_t flex_wgs;           // workgroups that take units of whichever direction has more left
     uint32_t *counters;          // device memory: the whole counter block, cleared by the last workgroup to leave
     uint64_t n_counters;
     uint32_t *all_left;          // device memory: workgroups (pump included) that have left the kernel

@@ -46,9 +46,10 @@ namespace {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr uint32_t kDirect = 0xFFFFFFFFu;             // "slot + 1" of a chunk that uses no slot
-constexpr uint32_t kUnroll = NIXIE_UNROLL;            // 16 B x 64 lanes x kUnroll = one tile per wave pass
-static_assert(kTileBytes == 16 * 64 * kUnroll, "tile = one unrolled wave pass");
-static_assert(kUnroll == 8 || kUnroll == 4 || kUnroll == 2, "load_from_host is written out for these");
+// loads in flight per lane before the stores, per direction: 16 B x 64 lanes x N = one tile per wave pass
+constexpr uint32_t kUnrollOut = NIXIE_UNROLL_OUT, kUnrollIn = NIXIE_UNROLL_IN;
+static_assert(kUnrollOut == 8 || kUnrollOut == 4 || kUnrollOut == 2 || kUnrollOut == 1, "gather unroll");
+static_assert(kUnrollIn == 8 || kUnrollIn == 4 || kUnrollIn == 2, "load_from_host is written out for these");
 
 __device__ __forceinline__ uint64_t mix64_dev(uint64_t z) {
     z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
@@ -56,13 +57,13 @@ __device__ __forceinline__ uint64_t mix64_dev(uint64_t z) {
     return z ^ (z >> 31);
 }
 
-// kUnroll 16-byte loads from the pinned ring, then one wait for all of them.  The loads carry
+// kUnrollIn 16-byte loads from the pinned ring, then one wait for all of them.  The loads carry
 // the system-scope bits (sc0 sc1), so they are served from host memory itself and never from
 // a cache line left over from an earlier use of the slot; no cache invalidation is needed
 // between the host's "slot ready" flag and these loads.  One asm block, because the compiler
 // does not track loads issued from inline asm: the values are only valid after the wait.
-__device__ __forceinline__ void load_from_host(u32x4 (&v)[kUnroll], const u32x4 *const (&a)[kUnroll]) {
-#if NIXIE_UNROLL == 8
+__device__ __forceinline__ void load_from_host(u32x4 (&v)[kUnrollIn], const u32x4 *const (&a)[kUnrollIn]) {
+#if NIXIE_UNROLL_IN == 8
     asm volatile(
         "global_load_dwordx4 %0, %8, off sc0 sc1\n"
         "global_load_dwordx4 %1, %9, off sc0 sc1\n"
@@ -76,7 +77,7 @@ __device__ __forceinline__ void load_from_host(u32x4 (&v)[kUnroll], const u32x4 
         : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3]), "=&v"(v[4]), "=&v"(v[5]), "=&v"(v[6]), "=&v"(v[7])
         : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(a[4]), "v"(a[5]), "v"(a[6]), "v"(a[7])
         : "memory");
-#elif NIXIE_UNROLL == 4
+#elif NIXIE_UNROLL_IN == 4
     asm volatile(
         "global_load_dwordx4 %0, %4, off sc0 sc1\n"
         "global_load_dwordx4 %1, %5, off sc0 sc1\n"
@@ -119,21 +120,22 @@ __device__ __forceinline__ void copy_span(uint8_t *dev, uint8_t *ring, uint32_t 
     const uint32_t nvec = (n - head) >> 4;
     const u32x4 *s4 = (const u32x4 *)(src + head);
     u32x4 *d4 = (u32x4 *)(dst + head);
-    for (uint32_t j = lane; j - lane < nvec; j += 64 * kUnroll) {   // wave-uniform trip count
-        u32x4 v[kUnroll];
-        if (TO_RING) {
+    constexpr uint32_t kU = TO_RING ? kUnrollOut : kUnrollIn;
+    for (uint32_t j = lane; j - lane < nvec; j += 64 * kU) {   // wave-uniform trip count
+        u32x4 v[kU];
+        if constexpr (TO_RING) {
 #pragma unroll
-            for (uint32_t u = 0; u < kUnroll; u++)
+            for (uint32_t u = 0; u < kU; u++)
                 if (j + 64 * u < nvec) v[u] = s4[j + 64 * u];
         } else {
             // out-of-range lanes re-read the last vector of the span (one extra line) and drop it
-            const u32x4 *a[kUnroll];
+            const u32x4 *a[kU];
 #pragma unroll
-            for (uint32_t u = 0; u < kUnroll; u++) a[u] = s4 + (j + 64 * u < nvec ? j + 64 * u : nvec - 1);
+            for (uint32_t u = 0; u < kU; u++) a[u] = s4 + (j + 64 * u < nvec ? j + 64 * u : nvec - 1);
             load_from_host(v, a);
         }
 #pragma unroll
-        for (uint32_t u = 0; u < kUnroll; u++)
+        for (uint32_t u = 0; u < kU; u++)
             if (j + 64 * u < nvec) {
                 if (TO_RING) store_to_host(d4 + j + 64 * u, v[u]);
                 else d4[j + 64 * u] = v[u];
@@ -166,39 +168,57 @@ __device__ __forceinline__ void copy_tile(const DevSeg *segs, uint32_t nseg, uin
     }
 }
 
+// One work unit of direction DIR: take a ticket, wait for the chunk's slot (and, in place, for the
+// GPU bytes it overwrites to have left), copy, arrive.  Returns false when the direction has no
+// unit left for this workgroup (tickets used up, abort, or a wait ran out).  Workgroup-uniform.
 template <int DIR>
-__device__ void run_direction(const SwapArgs &a) {
+__device__ bool do_unit(const SwapArgs &a, uint64_t &stall) {
     const DevDir &D = a.d[DIR];
     __shared__ uint32_t s_unit;
     __shared__ uint32_t s_slot;   // slot + 1 of the unit's chunk, 0 = stop
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const uint32_t waves_per_wg = kWgThreads / 64;
     const uint32_t total_units = D.n_chunks * D.team;
-    uint64_t stall = 0;
-    // XCC_ID hardware register, bits 3:0 = the XCD this workgroup runs on
-    const bool sit_out = a.xcd_mask && !((a.xcd_mask >> (__builtin_amdgcn_s_getreg((3 << 11) | 20) & 7u)) & 1u);
-
-    for (; !sit_out;) {
-        if (tid == 0) {
-            uint32_t cs = 0;
-            const uint32_t u = __hip_atomic_fetch_add(D.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (u < total_units && !__hip_atomic_load(a.dev_abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
-                // The pump wave writes chunk_slot[k] once chunk k has a slot: outgoing, a slot the
-                // host has released; incoming, the slot the host has filled with chunk k.  Workers
-                // only ever poll device memory: a poll over the link queues behind the bulk reads.
-                // A direct chunk (pinned tier) needs no slot: its image already has a place.
-                const uint32_t *where = D.chunk_slot + u / D.team;
-                cs = u / D.team >= D.n_staged ? kDirect
-                                              : __hip_atomic_load(where, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if (cs == 0) {
+    if (tid == 0) {
+        uint32_t cs = 0;
+        const uint32_t u = __hip_atomic_fetch_add(D.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (u < total_units && !__hip_atomic_load(a.dev_abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
+            // The pump wave writes chunk_slot[k] once chunk k has a slot: outgoing, a slot the
+            // host has released; incoming, the slot the host has filled with chunk k.  Workers
+            // only ever poll device memory: a poll over the link queues behind the bulk reads.
+            // A direct chunk (pinned tier) needs no slot: its image already has a place.
+            const uint32_t *where = D.chunk_slot + u / D.team;
+            cs = u / D.team >= D.n_staged ? kDirect
+                                          : __hip_atomic_load(where, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (cs == 0) {
+                const uint64_t t0 = wall_clock64();
+                uint32_t it = 0;
+                while ((cs = __hip_atomic_load(where, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) == 0) {
+                    if ((++it & 7u) == 0) {
+                        if (__hip_atomic_load(a.dev_abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) break;
+                        if (wall_clock64() - t0 > a.timeout_ticks) {
+                            __hip_atomic_store(a.dev_abort, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            __hip_atomic_store(a.gpu_status, (uint32_t)kGpuTimeout, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                            break;
+                        }
+                    }
+                    __builtin_amdgcn_s_sleep(4);
+                }
+                stall += wall_clock64() - t0;
+            }
+            // In-place switch: the GPU bytes this chunk overwrites must have been gathered.
+            if (DIR == 1 && cs != 0 && a.track_prefix) {
+                const uint32_t dep = D.chunks[u / D.team].dep;
+                if (__hip_atomic_load(a.gathered_prefix, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < dep) {
                     const uint64_t t0 = wall_clock64();
                     uint32_t it = 0;
-                    while ((cs = __hip_atomic_load(where, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) == 0) {
+                    while (__hip_atomic_load(a.gathered_prefix, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < dep) {
                         if ((++it & 7u) == 0) {
-                            if (__hip_atomic_load(a.dev_abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) break;
+                            if (__hip_atomic_load(a.dev_abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) { cs = 0; break; }
                             if (wall_clock64() - t0 > a.timeout_ticks) {
                                 __hip_atomic_store(a.dev_abort, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                                 __hip_atomic_store(a.gpu_status, (uint32_t)kGpuTimeout, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                                cs = 0;
                                 break;
                             }
                         }
@@ -206,80 +226,117 @@ __device__ void run_direction(const SwapArgs &a) {
                     }
                     stall += wall_clock64() - t0;
                 }
-                // In-place switch: the GPU bytes this chunk overwrites must have been gathered.
-                if (DIR == 1 && cs != 0 && a.track_prefix) {
-                    const uint32_t dep = D.chunks[u / D.team].dep;
-                    if (__hip_atomic_load(a.gathered_prefix, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < dep) {
-                        const uint64_t t0 = wall_clock64();
-                        uint32_t it = 0;
-                        while (__hip_atomic_load(a.gathered_prefix, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < dep) {
-                            if ((++it & 7u) == 0) {
-                                if (__hip_atomic_load(a.dev_abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) { cs = 0; break; }
-                                if (wall_clock64() - t0 > a.timeout_ticks) {
-                                    __hip_atomic_store(a.dev_abort, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                                    __hip_atomic_store(a.gpu_status, (uint32_t)kGpuTimeout, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-                                    cs = 0;
-                                    break;
-                                }
-                            }
-                            __builtin_amdgcn_s_sleep(4);
-                        }
-                        stall += wall_clock64() - t0;
-                    }
-                }
-            }
-            s_unit = u;
-            s_slot = cs;
-        }
-        __syncthreads();
-        const uint32_t u = s_unit;
-        if (u >= total_units || s_slot == 0) break;
-        const uint32_t k = u / D.team, part = u % D.team;
-        const uint32_t slot = s_slot - 1;
-        const bool direct = s_slot == kDirect;
-        const DevChunk ch = D.chunks[k];
-        uint8_t *slot_base = direct ? (uint8_t *)(uintptr_t)D.direct_base[k - D.n_staged]
-                                    : D.ring + (size_t)slot * a.slot_bytes;
-
-        const uint32_t n_tiles = (ch.used + kTileBytes - 1) / kTileBytes;
-        for (uint32_t t = part * waves_per_wg + wave; t < n_tiles; t += D.team * waves_per_wg) {
-            const uint32_t t0 = t * kTileBytes;
-            const uint32_t t1 = t0 + kTileBytes < ch.used ? t0 + kTileBytes : ch.used;
-            copy_tile<DIR == 0>(D.segs + ch.seg_begin, ch.seg_count, slot_base, t0, t1, lane);
-        }
-        // Payload before flag, without a release fence.  A system- or device-scope release would
-        // write back the whole L2 (which holds the scatter side's dirty HBM lines) for every work
-        // unit, and measurably slows both directions.  Every store into the ring is a write-through
-        // system-scope store, so it is enough that every wave waits until all of its stores are
-        // acknowledged (vmcnt = 0), that the workgroup then meets at the barrier, and that
-        // thread 0 only afterwards bumps the arrive counter and stores the flag.  The flag is a
-        // later posted write on the same link and cannot pass the payload.
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();   // also: every thread has read s_unit / s_slot before thread 0 overwrites them
-        if (tid == 0) {
-            // (for the outgoing direction the counter also tells the pump that the chunk has left HBM:
-            //  every load of this unit completed before the barrier above)
-            const uint32_t old = __hip_atomic_fetch_add(D.arrive + k, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const bool last = (old == D.team - 1) && !direct;   // nobody waits for a direct chunk's slot
-            if (last) {   // outgoing: "slot holds chunk k"; incoming: "chunk k has left the slot"
-                __hip_atomic_store(D.post_flags + (size_t)slot * kFlagStride, (uint64_t)k + 1u, __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_SYSTEM);
-                __hip_atomic_store(D.stamp + slot, wall_clock64(), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
+        s_unit = u;
+        s_slot = cs;
     }
-    // Leaving.  The pump reports "direction complete" to the host once every workgroup of the
-    // direction has left, and the host may then let the incoming application run while this
-    // kernel is still evicting.  What this workgroup scattered into HBM must therefore be out of
-    // this XCD's L2 before it counts as gone: all waves wait for their stores, and one
-    // device-scope release (an L2 write-back, once per workgroup, not per work unit) precedes the
-    // increment.  The gather side wrote only write-through stores and needs none.
+    __syncthreads();
+    const uint32_t u = s_unit, cs = s_slot;
+    __syncthreads();   // everybody has read the two words before thread 0 can write them again
+    if (u >= total_units || cs == 0) return false;
+    const uint32_t k = u / D.team, part = u % D.team;
+    const uint32_t slot = cs - 1;
+    const bool direct = cs == kDirect;
+    const DevChunk ch = D.chunks[k];
+    uint8_t *slot_base = direct ? (uint8_t *)(uintptr_t)D.direct_base[k - D.n_staged]
+                                : D.ring + (size_t)slot * a.slot_bytes;
+
+    constexpr uint32_t kTile = kTileBytesDir[DIR];
+    const uint32_t n_tiles = (ch.used + kTile - 1) / kTile;
+    for (uint32_t t = part * waves_per_wg + wave; t < n_tiles; t += D.team * waves_per_wg) {
+        const uint32_t t0 = t * kTile;
+        const uint32_t t1 = t0 + kTile < ch.used ? t0 + kTile : ch.used;
+        copy_tile<DIR == 0>(D.segs + ch.seg_begin, ch.seg_count, slot_base, t0, t1, lane);
+    }
+    // Payload before flag, without a release fence.  A system- or device-scope release would
+    // write back the whole L2 (which holds the scatter side's dirty HBM lines) for every work
+    // unit, and measurably slows both directions.  Every store into the ring is a write-through
+    // system-scope store, so it is enough that every wave waits until all of its stores are
+    // acknowledged (vmcnt = 0), that the workgroup then meets at the barrier, and that
+    // thread 0 only afterwards bumps the arrive counter and stores the flag.  The flag is a
+    // later posted write on the same link and cannot pass the payload.
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (tid == 0) {
+        // (for the outgoing direction the counter also tells the pump that the chunk has left HBM:
+        //  every load of this unit completed before the barrier above)
+        const uint32_t old = __hip_atomic_fetch_add(D.arrive + k, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const bool last = (old == D.team - 1) && !direct;   // nobody waits for a direct chunk's slot
+        if (last) {   // outgoing: "slot holds chunk k"; incoming: "chunk k has left the slot"
+            __hip_atomic_store(D.post_flags + (size_t)slot * kFlagStride, (uint64_t)k + 1u, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_SYSTEM);
+            __hip_atomic_store(D.stamp + slot, wall_clock64(), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+    return true;
+}
+
+// This workgroup will take no more units of direction DIR.  The pump reports "direction complete"
+// to the host once every workgroup that could work on the direction has said so, and the host may
+// then let the incoming application run while this kernel is still evicting.  What this workgroup
+// scattered into HBM must therefore be out of this XCD's L2 before it counts as gone: all waves wait
+// for their stores, and one device-scope release (an L2 write-back, once per workgroup, not per work
+// unit) precedes the increment.  The gather side wrote only write-through stores and needs none.
+template <int DIR>
+__device__ void leave_direction(const SwapArgs &a, uint64_t &stall) {
+    const DevDir &D = a.d[DIR];
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0) {
         if (stall) __hip_atomic_fetch_add(D.stall_ticks, stall, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (DIR == 1) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
         __hip_atomic_fetch_add(D.exited, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // on every exit path
+    }
+    stall = 0;
+}
+
+// XCC_ID hardware register, bits 3:0 = the XCD this workgroup runs on
+__device__ __forceinline__ bool sits_out(const SwapArgs &a) {
+    return a.xcd_mask && !((a.xcd_mask >> (__builtin_amdgcn_s_getreg((3 << 11) | 20) & 7u)) & 1u);
+}
+
+// A workgroup with a fixed role: units of one direction until there are none left.
+template <int DIR>
+__device__ void run_direction(const SwapArgs &a) {
+    uint64_t stall = 0;
+    if (!sits_out(a))
+        while (do_unit<DIR>(a, stall)) {}
+    leave_direction<DIR>(a, stall);
+}
+
+// A workgroup without a fixed role: before every unit it looks at how many chunks either direction
+// still has to hand out and takes a unit of the one with more left (the outgoing one on a tie:
+// its stores need more workgroups than the loads of the other).  Two equal working sets therefore
+// finish together whatever the rates of the two directions turn out to be on this machine, and once
+// one direction is done its share of these workgroups goes to the other.
+__device__ void run_either(const SwapArgs &a) {
+    __shared__ int s_dir;
+    uint64_t stall[2] = {0, 0};
+    bool live[2] = {a.d[0].wgs != 0, a.d[1].wgs != 0};
+    if (sits_out(a)) {
+        if (live[0]) leave_direction<0>(a, stall[0]);
+        if (live[1]) leave_direction<1>(a, stall[1]);
+        return;
+    }
+    while (live[0] || live[1]) {
+        if (threadIdx.x == 0) {
+            uint32_t left[2];
+            for (int x = 0; x < 2; x++) {
+                const uint32_t total = a.d[x].n_chunks * a.d[x].team;
+                const uint32_t t = live[x] ? __hip_atomic_load(a.d[x].ticket, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : total;
+                left[x] = t < total ? (total - t + a.d[x].team - 1) / a.d[x].team : 0;
+            }
+            s_dir = !live[0] ? 1 : !live[1] ? 0 : left[1] > left[0] ? 1 : 0;
+        }
+        __syncthreads();
+        const int dir = s_dir;
+        __syncthreads();
+        if (dir == 0) {
+            if (!do_unit<0>(a, stall[0])) { live[0] = false; leave_direction<0>(a, stall[0]); }
+        } else {
+            if (!do_unit<1>(a, stall[1])) { live[1] = false; leave_direction<1>(a, stall[1]); }
+        }
     }
 }
 
@@ -422,17 +479,19 @@ __device__ void leave_kernel(const SwapArgs &a) {
 }
 
 // Block 0 is the pump (first to be dispatched, so it is resident before any worker can wait on
-// it); blocks 1..gather_wgs are gather workers, the rest scatter workers.
+// it); then the gather workers, the scatter workers, and the workgroups that serve either direction.
 __global__ void __launch_bounds__(kWgThreads) nixie_swap_kernel(SwapArgs a) {
     if (blockIdx.x == 0) {
         const uint32_t wave = threadIdx.x >> 6;
         if (threadIdx.x == 0)   // from here on a host thread's wait is a credit wait, not queue delay
             __hip_atomic_store(a.dir_done + kStartedWord, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
         if (wave < 2) run_pump(a, (int)wave);
-    } else if (blockIdx.x - 1 < a.d[0].wgs) {
+    } else if (blockIdx.x - 1 < a.fixed_wgs[0]) {
         run_direction<0>(a);
-    } else {
+    } else if (blockIdx.x - 1 < a.fixed_wgs[0] + a.fixed_wgs[1]) {
         run_direction<1>(a);
+    } else {
+        run_either(a);
     }
     leave_kernel(a);
 }
@@ -444,15 +503,17 @@ __global__ void __launch_bounds__(256) nixie_zero32_kernel(uint32_t *p, uint64_t
 
 // H = mix64(bytes) + sum_k mix64(w_k + G (k+1)).  A tile is up to 4096 words (32 KiB) of one
 // allocation; each workgroup takes a contiguous run of tiles, so it finds its first allocation
-// by binary search once and then only steps forward.  Per tile: 16 B loads, eight in flight per
-// lane, wave-shuffle + LDS reduce, one 64-bit atomic add into the allocation's slot (hashes must
-// be zero on entry).  HBM-read bound: 1 B read per byte hashed.
+// by binary search once and then only steps forward.  Every thread keeps one running sum for the
+// allocation it is in and hands it over only when the run moves on to another allocation (or ends):
+// a wave-shuffle reduction and one 64-bit atomic add per wave into the allocation's slot (hashes
+// must be zero on entry).  No barrier anywhere, so a wave's loads of the next tile are not held up
+// by the slowest wave of the last one.  16 B loads, eight in flight per lane.  HBM-read bound: 1 B
+// read per byte hashed.
 __global__ void __launch_bounds__(256) nixie_hash_kernel(const HashDesc *descs, uint64_t n, uint64_t total_tiles,
                                                          uint64_t *hashes) {
     constexpr uint64_t G = 0x9E3779B97F4A7C15ull;
     typedef uint64_t u64x2 __attribute__((ext_vector_type(2)));
-    __shared__ uint64_t s_part[4];
-    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u;
     const uint64_t per = (total_tiles + gridDim.x - 1) / gridDim.x;
     const uint64_t t_begin = (uint64_t)blockIdx.x * per;
     const uint64_t t_end = t_begin + per < total_tiles ? t_begin + per : total_tiles;
@@ -464,14 +525,22 @@ __global__ void __launch_bounds__(256) nixie_hash_kernel(const HashDesc *descs, 
     }
     uint64_t i = lo - 1;
     HashDesc d = descs[i];
+    uint64_t acc = 0;
+    auto hand_over = [&](uint64_t owner) {   // wave-uniform call
+        for (int off = 32; off > 0; off >>= 1) acc += __shfl_down((unsigned long long)acc, off, 64);
+        if (lane == 0 && acc) atomicAdd((unsigned long long *)&hashes[owner], (unsigned long long)acc);
+        acc = 0;
+    };
     for (uint64_t t = t_begin; t < t_end; t++) {
         // step to the allocation that owns tile t (allocations of zero bytes own no tile)
-        while (i + 1 < n && descs[i + 1].first_tile <= t) d = descs[++i];
+        if (i + 1 < n && descs[i + 1].first_tile <= t) {
+            hand_over(i);
+            while (i + 1 < n && descs[i + 1].first_tile <= t) d = descs[++i];
+        }
         const uint64_t words = (d.bytes + 7) / 8, full = d.bytes / 8;
         const uint64_t w0 = (t - d.first_tile) * kHashTileWords;
         const uint64_t w1 = w0 + kHashTileWords < words ? w0 + kHashTileWords : words;
         const uint8_t *p = (const uint8_t *)(uintptr_t)d.ptr;
-        uint64_t acc = 0;
         if ((d.ptr & 15u) == 0 && w1 - w0 == kHashTileWords && w1 <= full) {   // whole aligned tile
             const u64x2 *v = (const u64x2 *)(p + 8 * w0);
             u64x2 r[8];
@@ -496,13 +565,8 @@ __global__ void __launch_bounds__(256) nixie_hash_kernel(const HashDesc *descs, 
             }
         }
         if (w0 == 0 && tid == 0) acc += mix64_dev(d.bytes);
-        for (int off = 32; off > 0; off >>= 1) acc += __shfl_down((unsigned long long)acc, off, 64);
-        if (lane == 0) s_part[wave] = acc;
-        __syncthreads();
-        if (tid == 0)
-            atomicAdd((unsigned long long *)&hashes[i], (unsigned long long)(s_part[0] + s_part[1] + s_part[2] + s_part[3]));
-        __syncthreads();
     }
+    hand_over(i);
 }
 
 // Plain copy for the link probe: each workgroup moves contiguous 64 KiB tiles, 16 B per lane.
@@ -606,7 +670,7 @@ int nixie_launch_hash_noalloc(const HashDesc *descs, uint32_t n, uint64_t total_
 
 int nixie_launch_swap(const SwapArgs &a, void *stream) {
     if (a.d[0].wgs + a.d[1].wgs == 0) return (int)hipSuccess;
-    const uint32_t grid = a.d[0].wgs + a.d[1].wgs + 1;   // + the pump
+    const uint32_t grid = a.fixed_wgs[0] + a.fixed_wgs[1] + a.flex_wgs + 1;   // + the pump
     nixie_swap_kernel<<<grid, kWgThreads, 0, (hipStream_t)stream>>>(a);
     return (int)hipGetLastError();
 }

@@ -318,25 +318,40 @@ void fill_info(const Layout &L, nixie_plan_info_t *info) {
     info->pinned_ctrl_bytes = (wait_flag_words(L.dir[0].slots) + wait_flag_words(L.dir[1].slots) +
                                (all_slots + 3) * kFlagStride) * 8;
     // Measured on MI355X with both directions active: write-through stores into the ring need
-    // about twice the workgroups that the reads out of it need; beyond 128 + 64 the surplus
-    // only waits for slots.
+    // about twice the workgroups that the reads out of it need; 128 + 64 balance the two directions for
+    // slots up to 512 KiB, and larger slots are within 2 % of their best (144 + 64).
     uint32_t wgs[2] = {L.opts.gather_wgs ? L.opts.gather_wgs : 128u, L.opts.scatter_wgs ? L.opts.scatter_wgs : 64u};
     // Work unit: at most 128 KiB of a slot -- per unit a workgroup pays a ticket, a slot lookup, a
     // store drain and a barrier (4 % of the rate at 64 KiB), while at 256 KiB and more a chunk
     // waits too long for its slowest unit -- and small enough that the units in flight (one per
     // workgroup) occupy no more than a quarter of the direction's share of the ring (where the unit floor allows): the rest is
     // what the host threads drain or fill meanwhile.
-    uint32_t team = L.opts.team;
-    if (team == 0) {
-        const uint32_t max_slots = std::max(L.dir[0].slots, L.dir[1].slots);
-        // Never below 32 KiB: a workgroup's four waves take one 8 KiB tile each per pass, so a smaller
-        // unit would leave waves, or whole units, without a tile while still paying for the unit.
-        constexpr uint64_t kMinUnit = (uint64_t)(kWgThreads / 64) * kTileBytes;
-        uint64_t unit = 128u << 10;
-        while (max_slots && unit > kMinUnit && unit * 4 * std::max(wgs[0], wgs[1]) > (uint64_t)max_slots * L.slot_bytes) unit >>= 1;
-        team = (uint32_t)std::max<uint64_t>(1, L.slot_bytes / unit);
+    // (a team of more than 256 could not be counted by the chunk limits checked in build_layout)
+    uint32_t team[2];
+    for (int x = 0; x < 2; x++) {
+        team[x] = L.opts.team;
+        if (team[x] == 0) {
+            // Never below one tile per wave: a smaller unit would leave waves, or whole units, without a
+            // tile while still paying for the unit.
+            const uint64_t floor_unit = (uint64_t)(kWgThreads / 64) * kTileBytesDir[x];
+            uint64_t unit = 128u << 10;
+            while (L.dir[x].slots && unit > floor_unit && unit * 4 * wgs[x] > (uint64_t)L.dir[x].slots * L.slot_bytes) unit >>= 1;
+            team[x] = (uint32_t)std::max<uint64_t>(1, L.slot_bytes / std::max(unit, floor_unit));
+        }
+        team[x] = std::min(team[x], 256u);
     }
-    team = std::min(team, 256u);
+    // Small rings: every workgroup holds one unit's worth of a slot while the link works it off, and the
+    // flag that hands a finished chunk to the host queues behind whatever the other workgroups have in
+    // flight.  Measured with a 16 MiB ring (8 MiB per direction), 128 + 64 workgroups wait for slots
+    // (570 ms for 24 + 24 GiB) where 48 + 24 to 80 + 40 do not (554 - 560 ms); with a 4 MiB ring 32 + 16
+    // are best and 16 + 8 starve the incoming direction; from 16 MiB per direction on, 128 + 64 are best.
+    // Default: one gather workgroup per 128 KiB of the outgoing share, between 32 and 128; half as many
+    // scatter workgroups.
+    if (L.opts.gather_wgs == 0 && L.opts.scatter_wgs == 0 && L.dir[0].slots && L.dir[1].slots) {
+        const uint64_t share = (uint64_t)std::min(L.dir[0].slots, L.dir[1].slots) * L.slot_bytes;
+        wgs[0] = (uint32_t)std::min<uint64_t>(128, std::max<uint64_t>(32, share >> 17));
+        wgs[1] = wgs[0] / 2;
+    }
     // Host threads busy-poll their slots, so the default never takes more than half the cores for
     // the two directions together (4 + 4 on the 16-core boxes measured; 3 + 3 already saturate the link).
     const uint32_t cores = std::max(1u, std::thread::hardware_concurrency());
@@ -345,7 +360,7 @@ void fill_info(const Layout &L, nixie_plan_info_t *info) {
     for (int x = 0; x < 2; x++) {
         if (L.dir[x].chunks.empty()) { wgs[x] = 0; thr[x] = 0; continue; }
         // more workgroups than slots * team could only spin on credits (direct chunks need none)
-        uint64_t cap = L.dir[x].staged == L.dir[x].chunks.size() ? (uint64_t)L.dir[x].slots * team : ~0ull;
+        uint64_t cap = L.dir[x].staged == L.dir[x].chunks.size() ? (uint64_t)L.dir[x].slots * team[x] : ~0ull;
         wgs[x] = (uint32_t)std::max<uint64_t>(1, std::min<uint64_t>(wgs[x], cap));
         wgs[x] = std::min(wgs[x], 1024u);
         // no host thread where nothing goes through the ring
@@ -353,8 +368,17 @@ void fill_info(const Layout &L, nixie_plan_info_t *info) {
     }
     info->gather_wgs = wgs[0];
     info->scatter_wgs = wgs[1];
-    info->team_out = L.dir[0].chunks.empty() ? 0 : team;
-    info->team_in = L.dir[1].chunks.empty() ? 0 : team;
+    // Workgroups that serve either direction only make sense where both directions run in one launch.
+    // Measured: with 128 + 64 fixed workgroups the incoming direction of two equal sets finishes 5 % ahead of
+    // the outgoing one (more with large slots, less or the other way round with small ones); 16 workgroups
+    // that go where more is left make both finish together and shorten the switch by 1.5 - 2.5 % on every
+    // configuration; beyond 32 they only wait for slots.  Default: an eighth of the gather workgroups.
+    uint32_t flex = (L.opts.flags & (NIXIE_NO_FLEX_WGS | NIXIE_SERIALIZE)) ? 0
+                    : L.opts.flex_wgs ? L.opts.flex_wgs : std::max(4u, wgs[0] / 8);
+    if (wgs[0] == 0 || wgs[1] == 0) flex = 0;
+    info->flex_wgs = std::min(flex, 256u);
+    info->team_out = L.dir[0].chunks.empty() ? 0 : team[0];
+    info->team_in = L.dir[1].chunks.empty() ? 0 : team[1];
     info->drain_threads = thr[0];
     info->fill_threads = thr[1];
 }

@@ -297,8 +297,10 @@ int pass_begin(nixie_plan_t *p, uint32_t mask, hipStream_t stream, nixie_stats_t
         d.n_slots = D.slots;
         d.team = x ? p->info.team_in : p->info.team_out;
         if (d.team == 0) d.team = 1;
-        d.wgs = on ? (x ? p->info.scatter_wgs : p->info.gather_wgs) : 0;
+        a.fixed_wgs[x] = on ? (x ? p->info.scatter_wgs : p->info.gather_wgs) : 0;
     }
+    a.flex_wgs = (a.fixed_wgs[0] && a.fixed_wgs[1]) ? p->info.flex_wgs : 0;
+    for (int x = 0; x < 2; x++) a.d[x].wgs = a.fixed_wgs[x] ? a.fixed_wgs[x] + a.flex_wgs : 0;
     a.slot_bytes = L.slot_bytes;
     a.host_abort = (const uint32_t *)(p->ctrl_d + (size_t)((uint64_t *)p->hs.abort_word - p->ctrl_h));
     a.gpu_status = (uint32_t *)(p->ctrl_d + (size_t)((uint64_t *)p->hs.status_word - p->ctrl_h));
@@ -606,6 +608,13 @@ int nixie_switch_end(nixie_plan_t *p, nixie_stats_t *stats) {
     if (f.ring_lock.owns_lock()) f.ring_lock.unlock();
     f.plan_lock.unlock();
     return rc;
+}
+
+int nixie_abi_check(uint64_t sizeof_opts, uint64_t sizeof_plan_info, uint64_t sizeof_stats) {
+    return sizeof_opts == sizeof(nixie_opts_t) && sizeof_plan_info == sizeof(nixie_plan_info_t) &&
+                   sizeof_stats == sizeof(nixie_stats_t)
+               ? NIXIE_OK
+               : NIXIE_EINVAL;
 }
 
 const char *nixie_strerror(int err) {

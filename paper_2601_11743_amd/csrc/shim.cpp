@@ -153,6 +153,10 @@ void init_once() {
     s.scribble = env_u64("NIXIE_SHIM_SCRIBBLE", 0) != 0;
     s.log = env_u64("NIXIE_SHIM_LOG", 0) != 0;
     g = &s;
+    if (nixie_abi_check(sizeof(nixie_opts_t), sizeof(nixie_plan_info_t), sizeof(nixie_stats_t)) != NIXIE_OK) {
+        std::fprintf(stderr, "nixie-shim: libnixie.so is of another version than this shim; allocations pass through\n");
+        return;
+    }
     int rc = nixie_pool_create(s.capacity, s.block, &s.pool);
     if (rc == NIXIE_EINVAL) {   // the device wants coarser blocks: take the library's default
         say("block of %llu MiB does not suit this device, using the default", (unsigned long long)(s.block >> 20));

@@ -13,6 +13,7 @@ _LIB_PATH = os.path.join(_HERE, "libnixie.so")
 EINVAL, EOVERLAP, ENOMEM, EHIP, ETIMEOUT, EMISMATCH, EBUSY, EUNMAPPED = -1, -2, -3, -4, -5, -6, -7, -8
 ORDER_TABLE, ORDER_LARGE_FIRST, ORDER_ADDRESS, ORDER_REVERSE = 0, 1, 2, 3
 SPLIT_BY_BYTES, SERIALIZE, DIAG_RING_ONLY, DIAG_STALL_DRAIN, HOST_PLAIN_MEMCPY, IN_PLACE, NO_DIRECT, HOST_SPIN = 1, 2, 4, 8, 16, 32, 64, 128
+NO_FLEX_WGS = 256
 
 DECLARED_SYMBOLS = (
     "nixie_layout_create", "nixie_layout_info", "nixie_layout_chunks", "nixie_layout_segments",
@@ -26,7 +27,7 @@ DECLARED_SYMBOLS = (
     "nixie_tier_register", "nixie_tier_unregister", "nixie_host_copy", "nixie_place",
     "nixie_switch_begin", "nixie_switch_wait_in", "nixie_switch_end",
     "nixie_ring_create", "nixie_ring_destroy", "nixie_plan_on_ring",
-    "nixie_hash_buffers_noalloc",
+    "nixie_hash_buffers_noalloc", "nixie_abi_check",
 )
 
 
@@ -42,7 +43,7 @@ class _Opts(C.Structure):
     _fields_ = [("slot_bytes", C.c_uint64), ("out_slots", C.c_uint32), ("order", C.c_uint32),
                 ("gather_wgs", C.c_uint32), ("scatter_wgs", C.c_uint32), ("team", C.c_uint32),
                 ("drain_threads", C.c_uint32), ("fill_threads", C.c_uint32),
-                ("timeout_ms", C.c_uint32), ("flags", C.c_uint32), ("xcd_mask", C.c_uint32)]
+                ("timeout_ms", C.c_uint32), ("flags", C.c_uint32), ("xcd_mask", C.c_uint32), ("flex_wgs", C.c_uint32)]
 
 
 class _Info(C.Structure):
@@ -56,7 +57,7 @@ class _Info(C.Structure):
                 ("team_out", C.c_uint32), ("team_in", C.c_uint32),
                 ("drain_threads", C.c_uint32), ("fill_threads", C.c_uint32),
                 ("direct_chunks_out", C.c_uint64), ("direct_chunks_in", C.c_uint64),
-                ("direct_bytes_out", C.c_uint64), ("direct_bytes_in", C.c_uint64)]
+                ("direct_bytes_out", C.c_uint64), ("direct_bytes_in", C.c_uint64), ("flex_wgs", C.c_uint32)]
 
 
 class _Segment(C.Structure):
@@ -160,6 +161,10 @@ def lib() -> C.CDLL:
     L.nixie_verify.argtypes = [vp, vp, vp, vp, C.POINTER(_Report)]
     L.nixie_hash_buffers.argtypes = [vp, vp, u64, i32, vp, vp]
     L.nixie_hash_buffers_noalloc.argtypes = [vp, vp, u64, vp, vp]
+    L.nixie_abi_check.argtypes = [u64, u64, u64]
+    if L.nixie_abi_check(C.sizeof(_Opts), C.sizeof(_Info), C.sizeof(_Stats)) != 0:
+        raise RuntimeError(f"{_LIB_PATH} was built from another version of include/nixie.h than this binding: "
+                           "rebuild (python -m paper_2601_11743_amd.build)")
     L.nixie_link_peak.argtypes = [u64, i32, C.POINTER(_LinkPeak)]
     L.nixie_sched_create.argtypes = [C.POINTER(_SchedParams), C.POINTER(vp)]
     L.nixie_sched_destroy.argtypes = [vp]

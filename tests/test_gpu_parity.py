@@ -102,6 +102,24 @@ def test_launch_shapes(nx, oracle, team, wgs):
              nx.Opts(slot_bytes=S, team=team, gather_wgs=wgs, scatter_wgs=wgs, drain_threads=2, fill_threads=3))
 
 
+@pytest.mark.parametrize("g,s,flex,flags", [(1, 1, 1, 0), (1, 1, 32, 0), (3, 2, 7, 0), (16, 8, 64, 0), (8, 8, 0, "NO_FLEX_WGS"),
+                                           (2, 5, 9, "IN_ORDER_ADDRESS")])
+def test_workgroups_that_serve_either_direction(nx, oracle, g, s, flex, flags):
+    """Workgroups without a fixed role take units of whichever direction has more left; with one fixed
+    workgroup per direction they do nearly all the work, in both roles, one unit after the other."""
+    sizes_a = [5 * S + 1, 300, 2 * S, 11 * S + 17, 7]
+    sizes_b = [4 * S, 11, 6 * S + 9, 200000, 3 * S - 5, 15 * S]
+    o = nx.Opts(slot_bytes=S, team=4, gather_wgs=g, scatter_wgs=s, flex_wgs=flex, drain_threads=2, fill_threads=2,
+                flags=nx.NO_FLEX_WGS if flags == "NO_FLEX_WGS" else 0, order=nx.ORDER_ADDRESS if flags == "IN_ORDER_ADDRESS" else 0)
+    info, st = run_case(nx, oracle, sizes_a, sizes_b, 8 * S, o, switches=2)
+    assert info["flex_wgs"] == (0 if flags == "NO_FLEX_WGS" else flex)
+    # very unequal sets, and one of them empty: the roles collapse to one
+    run_case(nx, oracle, [30 * S + 1], [100], 8 * S, o)
+    run_case(nx, oracle, [100], [30 * S + 1], 8 * S, o)
+    info, st = run_case(nx, oracle, [9 * S], [], 8 * S, o)
+    assert info["flex_wgs"] == 0
+
+
 def test_uneven_ring_split_and_staged_oracle(nx, oracle):
     sizes_a = [9 * S + 1, 77, 3 * S]
     sizes_b = [5 * S, 3, 2 * S + 2]
@@ -200,7 +218,7 @@ ALIAS_CASES = [
 
 
 @pytest.mark.parametrize("case", range(len(ALIAS_CASES)))
-@pytest.mark.parametrize("mode", ["default", "small_units", "serialized"])
+@pytest.mark.parametrize("mode", ["default", "small_units", "serialized", "either"])
 def test_in_place_switch(nx, oracle, case, mode):
     import torch
     from tests.helpers import AliasedPair
@@ -218,7 +236,7 @@ def test_in_place_switch(nx, oracle, case, mode):
     rows_a = [(base + od, g.host_a.ctypes.data + oh, b) for od, oh, b in zip(g.la.offsets, g.lha.offsets, g.sizes_a)]
     rows_b = [(base + od, g.host_b.ctypes.data + oh, b) for od, oh, b in zip(g.lb.offsets, g.lhb.offsets, g.sizes_b)]
     kw = dict(default={}, small_units=dict(team=8, gather_wgs=16, scatter_wgs=24, drain_threads=2, fill_threads=2),
-              serialized={})[mode]
+              serialized={}, either=dict(team=4, gather_wgs=1, scatter_wgs=1, flex_wgs=24))[mode]
     flags = nx.IN_PLACE | (nx.SERIALIZE if mode == "serialized" else 0)
     with pytest.raises(nx.NixieError):
         nx.Plan(rows_a, rows_b, 8 * S, nx.Opts(slot_bytes=S))     # without the flag aliasing is an error

@@ -171,7 +171,8 @@ def test_planner_ring_split_and_defaults(nx):
     lay = nx.Layout(ra, rb, 16 * MiB)                  # small ring: smaller slots and smaller work units
     i = lay.info()
     assert i["slot_bytes"] == 64 * KiB and i["out_slots"] == 128
-    assert i["team_out"] == 2                          # 32 KiB units, the floor: one 8 KiB tile per wave
+    assert i["team_out"] == 4                          # 16 KiB units, the floor: one 4 KiB tile per wave
+    assert i["gather_wgs"] == 64 and i["scatter_wgs"] == 32   # small ring: one gather workgroup per 128 KiB of a share
     lay = nx.Layout(ra, rb, 4 * MiB)
     assert lay.info()["slot_bytes"] == 64 * KiB and lay.info()["out_slots"] == 32
     lay = nx.Layout(ra, rb, 256 * KiB)

@@ -54,6 +54,10 @@ hipMemAllocationProp device_prop(int device) {
     return prop;
 }
 
+// s->mapped[b]: 0 = not mapped, 1 = mapped and in the registry, kUnmapPending = taken out of the
+// registry by an unmap that the driver refused (see unmap_blocks)
+constexpr uint8_t kUnmapPending = 2;
+
 int block_range(const nixie_space *s, uint64_t offset, uint64_t bytes, uint64_t *first, uint64_t *count) {
     const uint64_t B = s->pool->block_bytes;
     if (offset % B || bytes % B || offset > s->pool->bytes || bytes > s->pool->bytes - offset) return NIXIE_EINVAL;
@@ -69,9 +73,15 @@ int unmap_blocks(nixie_space *s, uint64_t first, uint64_t count) {
         if (!s->mapped[b]) continue;
         // out of the registry first: from here on no switch may count on this block
         space_set_mapped((uint64_t)(uintptr_t)s->base, b, 1, false);
-        s->mapped[b] = 0;
         hipError_t e = hipMemUnmap((char *)s->base + b * B, B);
-        if (e != hipSuccess) return fail(e);
+        if (e != hipSuccess) {
+            // The registry says "not mapped" (no switch will touch the block), the driver may still
+            // have it mapped: remember that, so that the next map or unmap of the block first
+            // finishes this unmap instead of mapping over it.
+            s->mapped[b] = kUnmapPending;
+            return fail(e);
+        }
+        s->mapped[b] = 0;
     }
     return NIXIE_OK;
 }
@@ -227,6 +237,12 @@ int nixie_space_map(nixie_space_t *s, uint64_t offset, uint64_t bytes) {
     acc.location.id = device;
     acc.flags = hipMemAccessFlagsProtReadWrite;
     // map, then open access for each run of newly mapped blocks with one call
+    for (uint64_t q = first; q < first + count; q++)     // finish what an earlier unmap left behind
+        if (s->mapped[q] == kUnmapPending) {
+            e = hipMemUnmap((char *)s->base + q * B, B);
+            if (e != hipSuccess) return fail(e);
+            s->mapped[q] = 0;
+        }
     uint64_t b = first;
     while (b < first + count) {
         if (s->mapped[b]) { b++; continue; }
@@ -287,7 +303,7 @@ int nixie_space_mapped(const nixie_space_t *s, uint64_t offset, uint64_t bytes) 
     int rc = block_range(s, offset, bytes, &first, &count);
     if (rc) return rc;
     for (uint64_t b = first; b < first + count; b++)   // (changed only by the owner's own map / unmap calls)
-        if (!s->mapped[b]) return 0;
+        if (s->mapped[b] != 1) return 0;
     return 1;
 }
 

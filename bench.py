@@ -280,6 +280,11 @@ def main() -> int:
         ring = max(16 << 20, int(ring * args.scale) >> 20 << 20)
         slot = 0 if not slot else max(64 << 10, int(slot * args.scale) >> 12 << 12)
 
+    peak = None
+    if not args.no_link_peak:     # before the working sets exist: the probe pins 2 GiB of its own
+        peak = nx.link_peak(1 << 30, 3)
+        log("[bench] link peak GB/s:", {k: round(v, 2) for k, v in peak.items()})
+
     t0 = time.perf_counter()
     pool = space_a = space_b = None
     if args.spaces:
@@ -309,11 +314,6 @@ def main() -> int:
     log(f"[bench] working sets built in {time.perf_counter() - t0:.1f} s: "
         f"A {A.total_bytes / 2**30:.2f} GiB / {len(A.sizes)} allocations, "
         f"B {B.total_bytes / 2**30:.2f} GiB / {len(B.sizes)} allocations")
-
-    peak = None
-    if not args.no_link_peak:
-        peak = nx.link_peak(1 << 30, 3)
-        log("[bench] link peak GB/s:", {k: round(v, 2) for k, v in peak.items()})
 
     opts = nx.Opts(slot_bytes=slot, gather_wgs=args.gather_wgs, scatter_wgs=args.scatter_wgs, team=args.team,
                    drain_threads=args.drain_threads, fill_threads=args.fill_threads, flags=args.flags,

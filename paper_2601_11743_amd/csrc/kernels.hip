@@ -327,7 +327,10 @@ __device__ void run_either(const SwapArgs &a) {
                 const uint32_t t = live[x] ? __hip_atomic_load(a.d[x].ticket, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : total;
                 left[x] = t < total ? (total - t + a.d[x].team - 1) / a.d[x].team : 0;
             }
-            s_dir = !live[0] ? 1 : !live[1] ? 0 : left[1] > left[0] ? 1 : 0;
+            // In place the incoming direction can never be ahead (a chunk is written only where the old
+            // bytes have left), so "more left" would always point at it, and the help would stand waiting
+            // for the outgoing side: there the help goes to the outgoing direction while it has units.
+            s_dir = !live[0] ? 1 : !live[1] ? 0 : a.track_prefix ? (left[0] ? 0 : 1) : left[1] > left[0] ? 1 : 0;
         }
         __syncthreads();
         const int dir = s_dir;

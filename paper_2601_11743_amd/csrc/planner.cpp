@@ -278,7 +278,8 @@ int build_layout(const nixie_table_t *out_table, const nixie_table_t *in_table, 
                 const nixie_segment_t &sg = L.dir[1].segs[q];
                 c.dep_out = std::max(c.dep_out, dep_of_pieces(osegs, dev_pieces(sg.dev_addr, sg.len, pieces)));
             }
-    } else if (L.table[0].size() + L.table[1].size() > 20000) {   // large tables: one direction per thread
+    } else if (L.table[0].size() + L.table[1].size() > 20000 || (tot[0] + tot[1]) / S > 50000) {
+        // many allocations or many chunks: one direction per thread
         std::thread other([&] { cut(L.table[1], walk1, direct[1], S, L.dir[1]); });
         cut(L.table[0], walk0, direct[0], S, L.dir[0]);
         other.join();

@@ -30,6 +30,7 @@
 
 #include "nixie.h"
 #include "nixie_shim.h"
+#include "blockruns.hpp"
 
 namespace {
 
@@ -98,7 +99,7 @@ struct Shim {
     std::shared_mutex gate;
     std::mutex mu;
     std::map<uint64_t, Alloc> table;          // by device address
-    std::map<uint64_t, uint64_t> free_runs;   // first block -> number of blocks
+    nixie::BlockRuns free_runs;               // blocks of the space that no allocation holds
     uint64_t managed_bytes = 0, passthrough = 0;
     std::atomic<bool> resident{true};
     std::atomic<uint32_t> evictions{0}, restores{0};
@@ -172,7 +173,7 @@ void init_once() {
     }
     s.base = (uint64_t)(uintptr_t)base;
     s.min_bytes = env_u64("NIXIE_SHIM_MIN_BYTES", s.block);
-    s.free_runs[0] = s.capacity / s.block;
+    s.free_runs = nixie::BlockRuns(s.capacity / s.block);
     s.last_return.store(now_ns());
     s.ok = true;
     say("managing %llu MiB in %llu MiB blocks at %p, allocations from %llu bytes", (unsigned long long)(s.capacity >> 20),
@@ -330,13 +331,11 @@ hipError_t hipMalloc(void **ptr, size_t size) {
     Inside in;
     std::lock_guard<std::mutex> lk(s->mu);
     const uint64_t need = (size + s->block - 1) / s->block;
-    for (auto it = s->free_runs.begin(); it != s->free_runs.end(); ++it) {
-        if (it->second < need) continue;
-        const uint64_t first = it->first, rest = it->second - need;
-        // an evicted application's new memory gets its physical blocks when the application comes back
-        if (s->resident.load() && nixie_space_map(s->space, first * s->block, need * s->block) != NIXIE_OK) break;
-        s->free_runs.erase(it);
-        if (rest) s->free_runs[first + need] = rest;
+    const uint64_t first = s->free_runs.find(need);
+    // an evicted application's new memory gets its physical blocks when the application comes back
+    if (first != nixie::BlockRuns::kNone &&
+        (!s->resident.load() || nixie_space_map(s->space, first * s->block, need * s->block) == NIXIE_OK)) {
+        s->free_runs.take(first, need);
         const uint64_t addr = s->base + first * s->block;
         s->table[addr] = Alloc{size, need, nullptr};
         s->managed_bytes += need * s->block;
@@ -365,16 +364,10 @@ hipError_t hipFree(void *ptr) {
                 (void)nixie_space_unmap(s->space, it->first - s->base, a.blocks * s->block);
             }
             if (a.host) munmap(a.host, a.bytes);
-            uint64_t first = (it->first - s->base) / s->block, n = a.blocks;
+            const uint64_t first = (it->first - s->base) / s->block;
             s->table.erase(it);
-            s->managed_bytes -= n * s->block;
-            auto nx = s->free_runs.lower_bound(first);           // merge with the free neighbours
-            if (nx != s->free_runs.end() && nx->first == first + n) { n += nx->second; nx = s->free_runs.erase(nx); }
-            if (nx != s->free_runs.begin()) {
-                auto pv = std::prev(nx);
-                if (pv->first + pv->second == first) { first = pv->first; n += pv->second; s->free_runs.erase(pv); }
-            }
-            s->free_runs[first] = n;
+            s->managed_bytes -= a.blocks * s->block;
+            s->free_runs.give(first, a.blocks);
             s->last_return.store(now_ns());
             return hipSuccess;
         }

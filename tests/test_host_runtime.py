@@ -69,3 +69,16 @@ def test_pinned_tier_allocations_move_directly(fake_gpu, scenario, seed):
 def test_failure_paths_time_out_cleanly(fake_gpu, scenario):
     out = run(fake_gpu, scenario, 1)
     assert "error -5" in out
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_shim_block_allocator_against_a_bitmap(tmp_path_factory, seed):
+    """First fit over whole blocks with merging on release (the shim's address space), checked step by
+    step against a brute-force bitmap."""
+    if shutil.which("g++") is None:
+        pytest.skip("no g++")
+    out = str(tmp_path_factory.mktemp("runs") / "blockruns_test")
+    subprocess.check_call(["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-I" + CSRC,
+                           os.path.join(ROOT, "tests", "fake_device", "blockruns_test.cpp"), "-o", out])
+    r = subprocess.run([out, str(seed)], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0 and "ok seed" in r.stdout, r.stdout + r.stderr

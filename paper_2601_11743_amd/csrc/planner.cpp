@@ -180,6 +180,8 @@ int build_layout(const nixie_table_t *out_table, const nixie_table_t *in_table, 
     std::vector<KeyPiece> pieces;
     dev.reserve(L.table[0].size() + L.table[1].size());
     host.reserve(L.table[0].size() + L.table[1].size());
+    uint64_t n_spaces = 0, n_tier_spans = 0;   // with neither, an address is just an address: no lookups
+    registry_counts(&n_spaces, &n_tier_spans);
     for (int x = 0; x < 2; x++) {
         if (x == 1) { mid = dev.size(); mid_host = host.size(); }
         direct[x].assign(L.table[x].size(), 0);
@@ -187,13 +189,17 @@ int build_layout(const nixie_table_t *out_table, const nixie_table_t *in_table, 
             const nixie_alloc_t &a = L.table[x][i];
             if (a.bytes == 0) continue;
             uint64_t d = (uint64_t)(uintptr_t)a.dev_ptr, h = (uint64_t)(uintptr_t)a.host_ptr;
-            pieces.clear();
-            if (!space_translate(d, a.bytes, &pieces, &L.uses[x])) return NIXIE_EINVAL;   // straddles the edge of a space
-            for (const KeyPiece &p : pieces) dev.push_back({p.key, p.key + p.len});
+            if (n_spaces) {
+                pieces.clear();
+                if (!space_translate(d, a.bytes, &pieces, &L.uses[x])) return NIXIE_EINVAL;   // straddles the edge of a space
+                for (const KeyPiece &p : pieces) dev.push_back({p.key, p.key + p.len});
+            } else {
+                dev.push_back({d, d + a.bytes});
+            }
             host.push_back({h, h + a.bytes});
             tot[x] += a.bytes;
             uint64_t seen_by_gpu = 0, span_id = 0;
-            if (use_tier && tier_translate(h, a.bytes, &seen_by_gpu, &span_id) && ((seen_by_gpu ^ d) & 15) == 0) {
+            if (use_tier && n_tier_spans && tier_translate(h, a.bytes, &seen_by_gpu, &span_id) && ((seen_by_gpu ^ d) & 15) == 0) {
                 direct[x][i] = seen_by_gpu;
                 if (L.tier_ids.empty() || L.tier_ids.back() != span_id) L.tier_ids.push_back(span_id);
             } else staged_tot[x] += a.bytes;

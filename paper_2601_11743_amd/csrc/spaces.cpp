@@ -74,6 +74,12 @@ void tier_release(const std::vector<uint64_t> &span_ids) {
             if (e.id == id && e.users) e.users--;
 }
 
+void registry_counts(uint64_t *spaces, uint64_t *tier_spans) {
+    std::lock_guard<std::mutex> g(g_mu);
+    *spaces = g_spaces.size();
+    *tier_spans = g_tiers.size();
+}
+
 std::shared_mutex &switch_lock() {
     static std::shared_mutex mu;
     return mu;

@@ -74,6 +74,10 @@ bool tier_translate(uint64_t host_addr, uint64_t bytes, uint64_t *dev_addr, uint
 bool tier_acquire(const std::vector<uint64_t> &span_ids);
 void tier_release(const std::vector<uint64_t> &span_ids);
 
+// Number of registered spaces and of registered tier spans right now (one look under the lock, so a
+// planner facing large tables can skip the per-allocation lookups when both are zero).
+void registry_counts(uint64_t *spaces, uint64_t *tier_spans);
+
 // Held shared by a running switch (and by the hash kernels), exclusively by map / unmap.
 std::shared_mutex &switch_lock();
 

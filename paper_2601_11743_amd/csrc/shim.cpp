@@ -219,6 +219,7 @@ int run_switch(Shim &s, const std::vector<nixie_alloc_t> &out, const std::vector
 int evict_locked(Shim &s) {
     if (!s.resident.load()) return NIXIE_OK;
     std::lock_guard<std::mutex> lk(s.mu);
+    if (s.table.empty()) return NIXIE_OK;   // nothing of the application's is managed: nothing to take away
     if (REAL(hipDeviceSynchronize)() != hipSuccess) return NIXIE_EHIP;   // nothing of the application's is running any more
     uint64_t bytes = 0;
     for (auto &kv : s.table) {
@@ -285,8 +286,9 @@ int restore_locked(Shim &s) {
 struct Running {
     Shim *s;
     std::shared_lock<std::shared_mutex> hold;
-    explicit Running(Shim *sh, bool may_block = false) : s(sh), may_block_(may_block) {
+    explicit Running(Shim *sh) : s(sh) {
         if (!s) return;
+        s->blocking++;   // inside a runtime call the application is not idle, however long the call takes
         hold = std::shared_lock<std::shared_mutex>(s->gate);
         while (!s->resident.load()) {          // step 2: not runnable -> ask for the GPU, wait for the memory
             hold.unlock();
@@ -302,16 +304,12 @@ struct Running {
             }
             hold.lock();
         }
-        if (may_block_) s->blocking++;
     }
     ~Running() {
         if (!s) return;
-        if (may_block_) s->blocking--;
         s->last_return.store(now_ns());
+        s->blocking--;
     }
-
-private:
-    bool may_block_;
 };
 
 }  // namespace
@@ -408,10 +406,10 @@ hipError_t hipModuleLaunchKernel(hipFunction_t f, unsigned int gridDimX, unsigne
                                        kernelParams, extra);
 }
 
-// Copies and fills address device memory too: same flag.  The synchronous ones may block.
+// Copies and fills address device memory too: same flag.
 hipError_t hipMemcpy(void *dst, const void *src, size_t sizeBytes, hipMemcpyKind kind) {
     if (t_inside) return REAL(hipMemcpy)(dst, src, sizeBytes, kind);
-    Running r(shim(), true);
+    Running r(shim());
     return REAL(hipMemcpy)(dst, src, sizeBytes, kind);
 }
 
@@ -423,7 +421,7 @@ hipError_t hipMemcpyAsync(void *dst, const void *src, size_t sizeBytes, hipMemcp
 
 hipError_t hipMemset(void *dst, int value, size_t sizeBytes) {
     if (t_inside) return REAL(hipMemset)(dst, value, sizeBytes);
-    Running r(shim(), true);
+    Running r(shim());
     return REAL(hipMemset)(dst, value, sizeBytes);
 }
 

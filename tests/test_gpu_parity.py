@@ -136,6 +136,19 @@ def test_serialized_and_plain_memcpy_modes(nx, oracle):
     run_case(nx, oracle, sizes_a, sizes_b, 8 * S, nx.Opts(slot_bytes=S, flags=nx.HOST_PLAIN_MEMCPY))
 
 
+def test_statistics_are_filled_in(nx, oracle):
+    """Timers and counters of a switch: plausible and complete (every slot is used many times over, so
+    the pump has made rounds and has seen credit round trips in both directions)."""
+    info, st = run_case(nx, oracle, [60 * S + 5, 999], [55 * S, 4], 4 * S, nx.Opts(slot_bytes=S))
+    assert st["bytes_out"] == 60 * S + 5 + 999 and st["bytes_in"] == 55 * S + 4 and st["kernels"] == 1
+    assert 0 < st["ns_launch"] < st["ns_total"] and 0 < st["ns_kernel"] <= st["ns_total"]
+    assert 0 < st["ns_in_done"] <= st["ns_total"] and 0 < st["ns_out_done"] <= st["ns_total"]
+    assert st["pump_rounds_out"] > 10 and st["pump_rounds_in"] > 10
+    for rtt in (st["credit_rtt_ticks_out"], st["credit_rtt_ticks_in"]):
+        assert 50 < rtt < 100_000_000          # between half a microsecond and a second, in 100 MHz ticks
+    assert st["gpu_status"] == 0
+
+
 def test_repeated_switch_same_plan(nx, oracle):
     """A plan is reusable: flags and counters start clean every time."""
     run_case(nx, oracle, [20 * S + 5, 999], [17 * S, 4], 4 * S, nx.Opts(slot_bytes=S), switches=3)

@@ -358,3 +358,37 @@ def test_shim_library_exports_what_its_header_declares():
         assert getattr(lib, name) is not None, name
     info = (ctypes.c_uint64 * 16)()
     assert lib.nixie_shim_info(info) == -1               # NIXIE_EINVAL: no interposed call has been made
+
+
+def test_planner_properties_on_random_tables(nx):
+    """Property test (hypothesis): for random tables, slot sizes, orders, ring splits and skews the
+    planner's output partitions every allocation exactly, fits the slots, keeps the 16-byte congruence and
+    stays inside the ring; the launch geometry it proposes is self-consistent."""
+    from hypothesis import given, settings, strategies as st, HealthCheck
+
+    sizes = st.lists(st.one_of(st.integers(0, 64), st.integers(1, 5000), st.integers(60_000, 300_000),
+                               st.sampled_from([4095, 4096, 4097, 65535, 65536, 65537, 1 << 20])), min_size=0, max_size=24)
+
+    @settings(max_examples=120, deadline=None, suppress_health_check=[HealthCheck.too_slow])
+    @given(sizes, sizes, st.sampled_from([4096, 8192, 65536, 262144]), st.integers(4, 40), st.integers(0, 3),
+           st.integers(0, 15), st.integers(0, 15), st.booleans(), st.integers(0, 200))
+    def run(sa, sb, S, slots, order, skew_d, skew_h, by_bytes, flex):
+        ra = fake_rows(sa, skew_dev=skew_d, skew_host=skew_h)
+        rb = fake_rows(sb, dev_base=0x7F80_0000_0000, host_base=0x1800_0000_0000, skew_dev=skew_h, skew_host=skew_d)
+        ring = slots * S
+        o = nx.Opts(slot_bytes=S, order=order, flags=nx.SPLIT_BY_BYTES if by_bytes else 0, flex_wgs=flex)
+        lay = nx.Layout(ra, rb, ring, o)
+        info = check_layout(lay, ra, rb, ring)
+        n_out, n_in = sum(sa) > 0, sum(sb) > 0
+        assert (info["out_slots"] >= 2) == n_out and (info["in_slots"] >= 2) == n_in
+        assert (info["gather_wgs"] > 0) == n_out and (info["scatter_wgs"] > 0) == n_in
+        assert (info["flex_wgs"] > 0) == (n_out and n_in)               # only where both directions run
+        assert info["flex_wgs"] == (min(flex, 256) if flex else max(4, info["gather_wgs"] // 8)) or not (n_out and n_in)
+        for team, key in ((info["team_out"], "gather_wgs"), (info["team_in"], "scatter_wgs")):
+            if info[key]:
+                assert 1 <= team <= 256 and info[key] <= 1024
+        # a chunk count that follows from the sizes alone: never fewer chunks than bytes / slot
+        assert info["chunks_out"] >= -(-sum(sa) // S) and info["chunks_in"] >= -(-sum(sb) // S)
+        lay.close()
+
+    run()

@@ -264,8 +264,8 @@ def main() -> int:
         if not args.quiet:
             print(*a, file=sys.stderr, flush=True)
 
+    nx.lib()                      # (builds the library first if nothing is built: before the GPU is touched)
     assert torch.cuda.is_available(), "bench.py needs a GPU"
-    nx.lib()
     torch.cuda.set_device(0)
     plain_run = (args.config in (0, 2) and not (args.ring_mib or args.slot_kib or args.gather_wgs or args.scatter_wgs or
                  args.team or args.flags or args.order or args.in_place or args.spaces or args.pinned_tier != "none" or

@@ -134,8 +134,14 @@ def lib() -> C.CDLL:
     if _lib is not None:
         return _lib
     if not os.path.exists(_LIB_PATH):
-        raise RuntimeError(f"{_LIB_PATH} is missing: run paper_2601_11743_amd/build.py "
-                           "(or __graft_entry__.build()) first; there is no CPU fallback")
+        # Nothing built yet: build once (hipcc cross-compiles, no GPU needed).  Callers that are about to
+        # use the GPU load the library before they touch it, since a build starts other programs.
+        try:
+            from . import build as _build
+            _build.build()
+        except Exception as e:   # no compiler, or the build failed: there is no CPU fallback
+            raise RuntimeError(f"{_LIB_PATH} is missing and could not be built ({e}): run "
+                               "paper_2601_11743_amd/build.py (or __graft_entry__.build())") from e
     L = C.CDLL(_LIB_PATH)
     vp, u64, i32 = C.c_void_p, C.c_uint64, C.c_int
     L.nixie_layout_create.argtypes = [C.POINTER(_Table), C.POINTER(_Table), u64, C.POINTER(_Opts), C.POINTER(vp)]

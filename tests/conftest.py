@@ -14,7 +14,13 @@ _spawner = None
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
-    # Started now, before any test can have initialised the GPU in this process: see tests/spawner.py.
+    # Whatever is not built yet is built now, and the helper below is started now: both start other
+    # programs, which a process must not do once it has initialised the GPU (see tests/spawner.py).
+    import oracle
+    oracle.build()
+    from paper_2601_11743_amd import build as lib_build
+    if not all(os.path.exists(p) for p in (lib_build.LIB, lib_build.SHIM, lib_build.SHIM_APP)):
+        lib_build.build()
     global _spawner
     if _spawner is None:
         _spawner = subprocess.Popen([sys.executable, "-u", os.path.join(ROOT, "tests", "spawner.py")],

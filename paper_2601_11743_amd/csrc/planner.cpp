@@ -328,9 +328,10 @@ void fill_info(const Layout &L, nixie_plan_info_t *info) {
     // about twice the workgroups that the reads out of it need; 128 + 64 balance the two directions for
     // slots up to 512 KiB, and larger slots are within 2 % of their best (144 + 64).
     uint32_t wgs[2] = {L.opts.gather_wgs ? L.opts.gather_wgs : 128u, L.opts.scatter_wgs ? L.opts.scatter_wgs : 64u};
-    // Work unit: at most 128 KiB of a slot -- per unit a workgroup pays a ticket, a slot lookup, a
-    // store drain and a barrier (4 % of the rate at 64 KiB), while at 256 KiB and more a chunk
-    // waits too long for its slowest unit -- and small enough that the units in flight (one per
+    // Work unit: at most 64 KiB of a slot -- per unit a workgroup pays a ticket, a slot lookup, a
+    // store drain and a barrier, while with large units a chunk waits too long for its slowest one
+    // (config 2, ms per switch by unit size: 512 KiB 467, 256 KiB 418, 128 KiB 381, 64 KiB 380,
+    // 32 KiB 398) -- and small enough that the units in flight (one per
     // workgroup) occupy no more than a quarter of the direction's share of the ring (where the unit floor allows): the rest is
     // what the host threads drain or fill meanwhile.
     // (a team of more than 256 could not be counted by the chunk limits checked in build_layout)
@@ -341,7 +342,7 @@ void fill_info(const Layout &L, nixie_plan_info_t *info) {
             // Never below one tile per wave: a smaller unit would leave waves, or whole units, without a
             // tile while still paying for the unit.
             const uint64_t floor_unit = (uint64_t)(kWgThreads / 64) * kTileBytesDir[x];
-            uint64_t unit = 128u << 10;
+            uint64_t unit = 64u << 10;
             while (L.dir[x].slots && unit > floor_unit && unit * 4 * wgs[x] > (uint64_t)L.dir[x].slots * L.slot_bytes) unit >>= 1;
             team[x] = (uint32_t)std::max<uint64_t>(1, L.slot_bytes / std::max(unit, floor_unit));
         }

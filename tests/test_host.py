@@ -156,10 +156,10 @@ def test_planner_ring_split_and_defaults(nx):
     lay = nx.Layout(ra, rb, 512 * MiB)
     i = lay.info()
     assert i["slot_bytes"] == 2 * MiB and i["out_slots"] == 128 and i["in_slots"] == 128
-    assert i["team_out"] == 16 and i["gather_wgs"] == 128 and i["scatter_wgs"] == 64   # 128 KiB work units
+    assert i["team_out"] == 32 and i["gather_wgs"] == 128 and i["scatter_wgs"] == 64   # 64 KiB work units
     lay = nx.Layout(ra, rb, 128 * MiB)                 # about 128 slots per direction
     i = lay.info()
-    assert i["slot_bytes"] == 512 * KiB and i["out_slots"] == 128 and i["in_slots"] == 128 and i["team_out"] == 4
+    assert i["slot_bytes"] == 512 * KiB and i["out_slots"] == 128 and i["in_slots"] == 128 and i["team_out"] == 8
     lay = nx.Layout(ra, rb, 128 * MiB, nx.Opts(flags=nx.SPLIT_BY_BYTES))
     i = lay.info()
     assert i["out_slots"] == round(256 * 20 / 26) and i["out_slots"] + i["in_slots"] == 256
@@ -179,7 +179,7 @@ def test_planner_ring_split_and_defaults(nx):
     assert lay.info()["slot_bytes"] == 64 * KiB and lay.info()["out_slots"] == 2
     lay = nx.Layout(ra, rb, 256 * MiB, nx.Opts(slot_bytes=4 * MiB))   # the headline geometry
     i = lay.info()
-    assert i["out_slots"] == 32 and i["team_out"] == 32
+    assert i["out_slots"] == 32 and i["team_out"] == 64
 
 
 def test_planner_errors(nx):

@@ -29,14 +29,20 @@
  *   hipFree          releases such a range (and its host copy, if the application is evicted).
  *   hipMemGetInfo    total = the capacity the shim was given, free = total - the application's
  *                    own managed allocations (in whole blocks).
- *   hipLaunchKernel, hipModuleLaunchKernel
+ *   hipLaunchKernel, hipLaunchKernelExC, hipLaunchCooperativeKernel, hipModuleLaunchKernel,
+ *   hipModuleLaunchCooperativeKernel, hipExtModuleLaunchKernel
  *                    check the execution flag; restore the application first if it is evicted.
  *                    Launches made by the shim's own library calls pass straight through.
- *   hipMemcpy, hipMemcpyAsync, hipMemset, hipMemsetAsync
+ *   hipMemcpy, hipMemcpyAsync, hipMemcpyWithStream, hipMemcpyHtoD, hipMemcpyDtoH, hipMemcpyDtoD,
+ *   hipMemcpyHtoDAsync, hipMemcpyDtoHAsync, hipMemcpyDtoDAsync, hipMemset, hipMemsetAsync,
+ *   hipMemsetD8, hipMemsetD8Async, hipMemsetD32, hipMemsetD32Async
  *                    address device memory as well: the same flag check before they go ahead.
  * Interposed only to time the application's activity (idleness), bracketed as calls that may
- * block: hipDeviceSynchronize, hipStreamSynchronize (and the synchronous hipMemcpy / hipMemset).
- * Graph capture, stream-ordered allocators and the other launch entry points are not interposed.
+ * block: hipDeviceSynchronize, hipStreamSynchronize (the calls above count as activity too, for
+ * as long as they take).
+ * Not interposed: graph capture and launch, stream-ordered allocators (hipMallocAsync), 2-D/3-D
+ * and array copies, peer copies, managed memory.  A program that reaches its managed allocations
+ * only through those must not be run with idle eviction on.
  *
  * Environment (read once, at the first interposed call):
  *   NIXIE_SHIM_POOL_MIB     capacity of the managed GPU memory, MiB (default 1024)

@@ -11,6 +11,7 @@
 // context-switch swap (nixie_plan / nixie_switch).  One process, no daemon: the scheduler's side is
 // nixie_shim_evict / nixie_shim_restore, or the shim's own idleness rule ("Idleness Detection").
 #include <hip/hip_runtime_api.h>
+#include <hip/hip_ext.h>
 
 #include <dlfcn.h>
 #include <sys/mman.h>
@@ -48,13 +49,7 @@ F next_symbol(const char *name) {
 using fn_hipMalloc = hipError_t (*)(void **, size_t);
 using fn_hipFree = hipError_t (*)(void *);
 using fn_hipMemGetInfo = hipError_t (*)(size_t *, size_t *);
-using fn_hipLaunchKernel = hipError_t (*)(const void *, dim3, dim3, void **, size_t, hipStream_t);
-using fn_hipModuleLaunchKernel = hipError_t (*)(hipFunction_t, unsigned int, unsigned int, unsigned int, unsigned int,
-                                                unsigned int, unsigned int, unsigned int, hipStream_t, void **, void **);
-using fn_hipMemcpy = hipError_t (*)(void *, const void *, size_t, hipMemcpyKind);
-using fn_hipMemcpyAsync = hipError_t (*)(void *, const void *, size_t, hipMemcpyKind, hipStream_t);
 using fn_hipMemset = hipError_t (*)(void *, int, size_t);
-using fn_hipMemsetAsync = hipError_t (*)(void *, int, size_t, hipStream_t);
 using fn_hipDeviceSynchronize = hipError_t (*)(void);
 using fn_hipStreamSynchronize = hipError_t (*)(hipStream_t);
 #define REAL(name) ([]() { static fn_##name f = next_symbol<fn_##name>(#name); return f; }())
@@ -388,48 +383,64 @@ hipError_t hipMemGetInfo(size_t *free_bytes, size_t *total_bytes) {
     return hipSuccess;
 }
 
-hipError_t hipLaunchKernel(const void *function_address, dim3 numBlocks, dim3 dimBlocks, void **args, size_t sharedMemBytes,
-                           hipStream_t stream) {
-    if (t_inside) return REAL(hipLaunchKernel)(function_address, numBlocks, dimBlocks, args, sharedMemBytes, stream);
-    Running r(shim());
-    return REAL(hipLaunchKernel)(function_address, numBlocks, dimBlocks, args, sharedMemBytes, stream);
-}
+// Everything that launches work or touches device memory checks the execution flag first (and brings
+// the application back if it is off), and holds the gate shared while the runtime call is in
+// progress.  Same prototypes as the runtime's; the compiler checks them against its header.
+#define NIXIE_GUARDED(name, params, args)                   \
+    hipError_t name params {                                \
+        using fn = hipError_t(*) params;                    \
+        static const fn real = next_symbol<fn>(#name);      \
+        if (t_inside) return real args;                     \
+        Running r(shim());                                  \
+        return real args;                                   \
+    }
 
-hipError_t hipModuleLaunchKernel(hipFunction_t f, unsigned int gridDimX, unsigned int gridDimY, unsigned int gridDimZ,
-                                 unsigned int blockDimX, unsigned int blockDimY, unsigned int blockDimZ,
-                                 unsigned int sharedMemBytes, hipStream_t stream, void **kernelParams, void **extra) {
-    if (t_inside)
-        return REAL(hipModuleLaunchKernel)(f, gridDimX, gridDimY, gridDimZ, blockDimX, blockDimY, blockDimZ, sharedMemBytes,
-                                           stream, kernelParams, extra);
-    Running r(shim());
-    return REAL(hipModuleLaunchKernel)(f, gridDimX, gridDimY, gridDimZ, blockDimX, blockDimY, blockDimZ, sharedMemBytes, stream,
-                                       kernelParams, extra);
-}
+NIXIE_GUARDED(hipLaunchKernel,
+              (const void *function_address, dim3 numBlocks, dim3 dimBlocks, void **args, size_t sharedMemBytes, hipStream_t stream),
+              (function_address, numBlocks, dimBlocks, args, sharedMemBytes, stream))
+NIXIE_GUARDED(hipLaunchCooperativeKernel,
+              (const void *f, dim3 gridDim, dim3 blockDimX, void **kernelParams, unsigned int sharedMemBytes, hipStream_t stream),
+              (f, gridDim, blockDimX, kernelParams, sharedMemBytes, stream))
+NIXIE_GUARDED(hipLaunchKernelExC, (const hipLaunchConfig_t *config, const void *fPtr, void **args), (config, fPtr, args))
+NIXIE_GUARDED(hipModuleLaunchKernel,
+              (hipFunction_t f, unsigned int gridDimX, unsigned int gridDimY, unsigned int gridDimZ, unsigned int blockDimX,
+               unsigned int blockDimY, unsigned int blockDimZ, unsigned int sharedMemBytes, hipStream_t stream,
+               void **kernelParams, void **extra),
+              (f, gridDimX, gridDimY, gridDimZ, blockDimX, blockDimY, blockDimZ, sharedMemBytes, stream, kernelParams, extra))
+NIXIE_GUARDED(hipModuleLaunchCooperativeKernel,
+              (hipFunction_t f, unsigned int gridDimX, unsigned int gridDimY, unsigned int gridDimZ, unsigned int blockDimX,
+               unsigned int blockDimY, unsigned int blockDimZ, unsigned int sharedMemBytes, hipStream_t stream,
+               void **kernelParams),
+              (f, gridDimX, gridDimY, gridDimZ, blockDimX, blockDimY, blockDimZ, sharedMemBytes, stream, kernelParams))
+NIXIE_GUARDED(hipExtModuleLaunchKernel,
+              (hipFunction_t f, uint32_t globalWorkSizeX, uint32_t globalWorkSizeY, uint32_t globalWorkSizeZ,
+               uint32_t localWorkSizeX, uint32_t localWorkSizeY, uint32_t localWorkSizeZ, size_t sharedMemBytes,
+               hipStream_t hStream, void **kernelParams, void **extra, hipEvent_t startEvent, hipEvent_t stopEvent,
+               uint32_t flags),
+              (f, globalWorkSizeX, globalWorkSizeY, globalWorkSizeZ, localWorkSizeX, localWorkSizeY, localWorkSizeZ,
+               sharedMemBytes, hStream, kernelParams, extra, startEvent, stopEvent, flags))
 
-// Copies and fills address device memory too: same flag.
-hipError_t hipMemcpy(void *dst, const void *src, size_t sizeBytes, hipMemcpyKind kind) {
-    if (t_inside) return REAL(hipMemcpy)(dst, src, sizeBytes, kind);
-    Running r(shim());
-    return REAL(hipMemcpy)(dst, src, sizeBytes, kind);
-}
-
-hipError_t hipMemcpyAsync(void *dst, const void *src, size_t sizeBytes, hipMemcpyKind kind, hipStream_t stream) {
-    if (t_inside) return REAL(hipMemcpyAsync)(dst, src, sizeBytes, kind, stream);
-    Running r(shim());
-    return REAL(hipMemcpyAsync)(dst, src, sizeBytes, kind, stream);
-}
-
-hipError_t hipMemset(void *dst, int value, size_t sizeBytes) {
-    if (t_inside) return REAL(hipMemset)(dst, value, sizeBytes);
-    Running r(shim());
-    return REAL(hipMemset)(dst, value, sizeBytes);
-}
-
-hipError_t hipMemsetAsync(void *dst, int value, size_t sizeBytes, hipStream_t stream) {
-    if (t_inside) return REAL(hipMemsetAsync)(dst, value, sizeBytes, stream);
-    Running r(shim());
-    return REAL(hipMemsetAsync)(dst, value, sizeBytes, stream);
-}
+NIXIE_GUARDED(hipMemcpy, (void *dst, const void *src, size_t sizeBytes, hipMemcpyKind kind), (dst, src, sizeBytes, kind))
+NIXIE_GUARDED(hipMemcpyAsync, (void *dst, const void *src, size_t sizeBytes, hipMemcpyKind kind, hipStream_t stream),
+              (dst, src, sizeBytes, kind, stream))
+NIXIE_GUARDED(hipMemcpyWithStream, (void *dst, const void *src, size_t sizeBytes, hipMemcpyKind kind, hipStream_t stream),
+              (dst, src, sizeBytes, kind, stream))
+NIXIE_GUARDED(hipMemcpyHtoD, (hipDeviceptr_t dst, const void *src, size_t sizeBytes), (dst, src, sizeBytes))
+NIXIE_GUARDED(hipMemcpyDtoH, (void *dst, hipDeviceptr_t src, size_t sizeBytes), (dst, src, sizeBytes))
+NIXIE_GUARDED(hipMemcpyDtoD, (hipDeviceptr_t dst, hipDeviceptr_t src, size_t sizeBytes), (dst, src, sizeBytes))
+NIXIE_GUARDED(hipMemcpyHtoDAsync, (hipDeviceptr_t dst, const void *src, size_t sizeBytes, hipStream_t stream),
+              (dst, src, sizeBytes, stream))
+NIXIE_GUARDED(hipMemcpyDtoHAsync, (void *dst, hipDeviceptr_t src, size_t sizeBytes, hipStream_t stream),
+              (dst, src, sizeBytes, stream))
+NIXIE_GUARDED(hipMemcpyDtoDAsync, (hipDeviceptr_t dst, hipDeviceptr_t src, size_t sizeBytes, hipStream_t stream),
+              (dst, src, sizeBytes, stream))
+NIXIE_GUARDED(hipMemset, (void *dst, int value, size_t sizeBytes), (dst, value, sizeBytes))
+NIXIE_GUARDED(hipMemsetAsync, (void *dst, int value, size_t sizeBytes, hipStream_t stream), (dst, value, sizeBytes, stream))
+NIXIE_GUARDED(hipMemsetD8, (hipDeviceptr_t dest, unsigned char value, size_t count), (dest, value, count))
+NIXIE_GUARDED(hipMemsetD8Async, (hipDeviceptr_t dest, unsigned char value, size_t count, hipStream_t stream),
+              (dest, value, count, stream))
+NIXIE_GUARDED(hipMemsetD32, (hipDeviceptr_t dest, int value, size_t count), (dest, value, count))
+NIXIE_GUARDED(hipMemsetD32Async, (hipDeviceptr_t dst, int value, size_t count, hipStream_t stream), (dst, value, count, stream))
 
 // Blocking calls are bracketed so that an application waiting inside the runtime is not taken for idle.
 hipError_t hipDeviceSynchronize(void) {

@@ -5,13 +5,19 @@
 // there it loses its GPU memory while it is silent and must find the same bytes at the same
 // addresses when it wakes up.
 //
-// usage: shim_app <pause_ms> <big_mib> [rounds]
+// With mode "explicit" it plays an application that a scheduler in the same process takes off the
+// GPU at a moment of its choosing: if the process exports nixie_shim_evict (it does only under the
+// shim) that call is made in every pause, and the next runtime call has to bring the memory back.
+//
+// usage: shim_app <pause_ms> <big_mib> [rounds] [idle|explicit]
 #include <hip/hip_runtime.h>
+#include <dlfcn.h>
 
 #include <chrono>
 #include <cstdint>
 #include <cstdio>
 #include <cstdlib>
+#include <cstring>
 #include <thread>
 #include <vector>
 
@@ -51,6 +57,9 @@ int main(int argc, char **argv) {
     const int pause_ms = argc > 1 ? std::atoi(argv[1]) : 500;
     const uint64_t big = (argc > 2 ? std::strtoull(argv[2], nullptr, 10) : 48) << 20;
     const int rounds = argc > 3 ? std::atoi(argv[3]) : 2;
+    const bool explicit_mode = argc > 4 && std::strcmp(argv[4], "explicit") == 0;
+    using evict_fn = int (*)(void);
+    const evict_fn evict = explicit_mode ? (evict_fn)dlsym(RTLD_DEFAULT, "nixie_shim_evict") : nullptr;
     size_t free0 = 0, total0 = 0;
     CHECK(hipMemGetInfo(&free0, &total0));
     // a few buffers of mixed sizes: three large ones and two small ones
@@ -64,6 +73,8 @@ int main(int argc, char **argv) {
     unsigned long long *bad = nullptr;
     CHECK(hipMalloc((void **)&bad, sizeof(*bad)));
     CHECK(hipMemset(bad, 0, sizeof(*bad)));
+    uint32_t *scratch = nullptr;                       // 1 MiB: below the shim's threshold, the runtime's own memory
+    CHECK(hipMalloc((void **)&scratch, 1 << 20));
     for (int b = 0; b < 5; b++) fill<<<256, 256>>>(buf[b], sizes[b] / 4, 100 + b);
     CHECK(hipGetLastError());
     CHECK(hipDeviceSynchronize());
@@ -71,7 +82,18 @@ int main(int argc, char **argv) {
     unsigned long long total_bad = 0;
     for (int r = 0; r < rounds; r++) {
         std::this_thread::sleep_for(std::chrono::milliseconds(pause_ms));   // silence: no runtime call at all
+        if (evict) {
+            const int rc = evict();
+            std::printf("round %d: scheduler took the GPU away, rc %d\n", r, rc);
+            if (rc) return 1;
+        }
+        if (r % 2 == 1) {
+            // this round wakes up with a copy engine call instead of a launch: the scratch buffer gets the
+            // head of buffer 0 device to device, and the check below reads buffer 0 itself as always
+            CHECK(hipMemcpyDtoDAsync((hipDeviceptr_t)scratch, (hipDeviceptr_t)buf[0], 1 << 20, nullptr));
+        }
         for (int b = 0; b < 5; b++) check<<<256, 256>>>(buf[b], sizes[b] / 4, 100 + b, (uint32_t)r, bad);
+        if (r % 2 == 1) check<<<256, 256>>>(scratch, (1 << 20) / 4, 100, (uint32_t)r, bad);
         for (int b = 0; b < 5; b++) bump<<<256, 256>>>(buf[b], sizes[b] / 4);                  // the state moves on
         CHECK(hipGetLastError());
         unsigned long long h = 0;
@@ -84,6 +106,17 @@ int main(int argc, char **argv) {
     std::vector<uint32_t> head(1024);
     CHECK(hipMemcpy(head.data(), buf[0], head.size() * 4, hipMemcpyDeviceToHost));
     for (size_t i = 0; i < head.size(); i++) total_bad += head[i] != pattern(100, i) + (uint32_t)rounds;
+    // and with the driver-style calls: the tail of the second large buffer, then a 32-bit fill read back
+    if (evict && evict()) return 1;
+    const uint64_t n1 = sizes[1] / 4;
+    CHECK(hipMemcpyDtoH(head.data(), (hipDeviceptr_t)(buf[1] + n1 - head.size()), head.size() * 4));
+    for (size_t i = 0; i < head.size(); i++) total_bad += head[i] != pattern(101, n1 - head.size() + i) + (uint32_t)rounds;
+    if (evict && evict()) return 1;
+    CHECK(hipMemsetD32((hipDeviceptr_t)buf[2], 0x5EED5EED, 4096));
+    CHECK(hipMemcpyDtoH(head.data(), (hipDeviceptr_t)buf[2], head.size() * 4));
+    for (size_t i = 0; i < head.size(); i++) total_bad += head[i] != 0x5EED5EEDu;
+    CHECK(hipMemcpyDtoH(head.data(), (hipDeviceptr_t)(buf[2] + 4096), head.size() * 4));
+    for (size_t i = 0; i < head.size(); i++) total_bad += head[i] != pattern(102, 4096 + i) + (uint32_t)rounds;
     CHECK(hipFree(buf[1]));
     size_t free2 = 0, total2 = 0;
     CHECK(hipMemGetInfo(&free2, &total2));
@@ -91,6 +124,7 @@ int main(int argc, char **argv) {
     for (int b = 0; b < 5; b++)
         if (b != 1) CHECK(hipFree(buf[b]));
     CHECK(hipFree(bad));
+    CHECK(hipFree(scratch));
     std::printf(total_bad ? "RESULT wrong %llu\n" : "RESULT ok %llu\n", total_bad);
     return total_bad ? 1 : 0;
 }

@@ -85,3 +85,24 @@ def test_allocation_beyond_the_capacity_fails_cleanly(run_program):
     env = preload_env(NIXIE_SHIM_LOG=1, NIXIE_SHIM_POOL_MIB=64)
     r = run_program([APP, "10", "48", "1"], env=env, timeout=120)      # 48 + 16 + 5 MiB do not fit 64 MiB
     assert r["rc"] == 1 and "FAIL hipMalloc" in r["stdout"], r
+
+
+def test_scheduler_in_the_process_takes_the_gpu_away(run_program):
+    """nixie_shim_evict called by the process itself (the scheduler's side of the paper's step 6), with no
+    idleness rule: every pause ends with an eviction, and whatever the application calls next (a launch,
+    a device-to-device copy, a driver-style copy back, a 32-bit fill) finds its memory again first."""
+    print("shim_app under LD_PRELOAD, explicit evictions", flush=True)
+    env = preload_env(NIXIE_SHIM_SCRIBBLE=1, NIXIE_SHIM_LOG=1, NIXIE_SHIM_POOL_MIB=256, NIXIE_SHIM_RING_MIB=16)
+    r = run_program([APP, "20", "48", "3", "explicit"], env=env, timeout=120)
+    assert r["rc"] == 0 and "RESULT ok" in r["stdout"], r
+    assert parse(r["stdout"])["rounds"] == [0, 0, 0]
+    assert len(re.findall(r"scheduler took the GPU away, rc 0", r["stdout"])) == 3
+    log = r["stderr"]
+    # three rounds and two more before the driver-style calls
+    assert len(re.findall(r"evicted \d+ allocations", log)) == 5, log
+    assert len(re.findall(r"restored \d+ allocations", log)) == 5, log
+
+
+def test_explicit_mode_without_the_shim_is_the_plain_program(run_program):
+    r = run_program([APP, "10", "48", "2", "explicit"], timeout=90)
+    assert r["rc"] == 0 and "RESULT ok" in r["stdout"] and "took the GPU away" not in r["stdout"], r

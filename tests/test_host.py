@@ -350,11 +350,16 @@ def test_shim_library_exports_what_its_header_declares():
     declared = set(re.findall(r"\b(nixie_shim_\w+)\s*\(", header)) - {"nixie_shim_info_t"}
     assert declared == {"nixie_shim_info", "nixie_shim_evict", "nixie_shim_restore"}
     lib = ctypes.CDLL(path, mode=os.RTLD_LOCAL)
-    interposed = ["hipMalloc", "hipFree", "hipMemGetInfo", "hipLaunchKernel", "hipModuleLaunchKernel", "hipMemcpy",
-                  "hipMemcpyAsync", "hipMemset", "hipMemsetAsync", "hipDeviceSynchronize", "hipStreamSynchronize"]
-    for name in interposed:
-        assert name in header, name                      # documented
-    for name in sorted(declared) + interposed:
+    # both ways: every runtime call the library defines is documented, every documented one is defined
+    import subprocess
+    nm = subprocess.run(["nm", "-D", "--defined-only", path], capture_output=True, text=True, check=True).stdout
+    defined = {l.split()[-1] for l in nm.splitlines() if l.split()[-1].startswith("hip")}
+    block = header[header.index("Interposed runtime calls"):header.index("Not interposed")]
+    documented = set(re.findall(r"\bhip[A-Z]\w+", block)) - {"hipErrorOutOfMemory"}
+    assert defined == documented, (sorted(defined - documented), sorted(documented - defined))
+    assert {"hipMalloc", "hipFree", "hipMemGetInfo", "hipLaunchKernel", "hipModuleLaunchKernel", "hipMemcpyAsync",
+            "hipMemsetAsync", "hipDeviceSynchronize", "hipStreamSynchronize"} <= defined
+    for name in sorted(declared | defined):
         assert getattr(lib, name) is not None, name
     info = (ctypes.c_uint64 * 16)()
     assert lib.nixie_shim_info(info) == -1               # NIXIE_EINVAL: no interposed call has been made

@@ -30,17 +30,25 @@
  *   hipMemGetInfo    total = the capacity the shim was given, free = total - the application's
  *                    own managed allocations (in whole blocks).
  *   hipLaunchKernel, hipLaunchKernelExC, hipLaunchCooperativeKernel, hipModuleLaunchKernel,
- *   hipModuleLaunchCooperativeKernel, hipExtModuleLaunchKernel
+ *   hipModuleLaunchCooperativeKernel, hipExtModuleLaunchKernel, hipGraphLaunch
  *                    check the execution flag; restore the application first if it is evicted.
  *                    Launches made by the shim's own library calls pass straight through.
  *   hipMemcpy, hipMemcpyAsync, hipMemcpyWithStream, hipMemcpyHtoD, hipMemcpyDtoH, hipMemcpyDtoD,
  *   hipMemcpyHtoDAsync, hipMemcpyDtoHAsync, hipMemcpyDtoDAsync, hipMemset, hipMemsetAsync,
  *   hipMemsetD8, hipMemsetD8Async, hipMemsetD32, hipMemsetD32Async
  *                    address device memory as well: the same flag check before they go ahead.
+ *   hipStreamBeginCapture, hipStreamBeginCaptureToGraph, hipStreamEndCapture
+ *                    paper, "CUDA graph compatibility": between the start and the end of a stream
+ *                    capture the shim makes no runtime call of its own -- the capture starts with
+ *                    the application resident, the idleness rule is suspended and
+ *                    nixie_shim_evict returns NIXIE_EBUSY.  A graph instantiated from the capture
+ *                    holds the application's pointers, which stay valid across migrations, so it
+ *                    is launched unchanged afterwards.
  * Interposed only to time the application's activity (idleness), bracketed as calls that may
  * block: hipDeviceSynchronize, hipStreamSynchronize (the calls above count as activity too, for
  * as long as they take).
- * Not interposed: graph capture and launch, stream-ordered allocators (hipMallocAsync), 2-D/3-D
+ * Not interposed: graphs built node by node are launched like any other (hipGraphLaunch) but their
+ * construction is not watched; stream-ordered allocators (hipMallocAsync), 2-D/3-D
  * and array copies, peer copies, managed memory.  A program that reaches its managed allocations
  * only through those must not be run with idle eviction on.
  *
@@ -85,7 +93,8 @@ int nixie_shim_info(nixie_shim_info_t *info);
  * launches, waits for the device, moves every managed allocation to pageable host memory with
  * nixie_switch, and unmaps the physical memory; the application keeps its pointers.
  * nixie_shim_restore maps it again and brings the bytes back; any launch does the same on its own.
- * Both return 0 (also when there is nothing to do) or a negative nixie_err code. */
+ * Both return 0 (also when there is nothing to do) or a negative nixie_err code; nixie_shim_evict
+ * returns NIXIE_EBUSY while the application is capturing a stream. */
 int nixie_shim_evict(void);
 int nixie_shim_restore(void);
 

@@ -103,6 +103,9 @@ struct Shim {
     // idleness: time of the last return from a runtime call; calls that may block are bracketed
     std::atomic<uint64_t> last_return{0};
     std::atomic<int> blocking{0};
+    // stream captures in progress: until the last one ends the shim makes no runtime call of its own
+    // (a synchronize or a copy from another thread would break the application's capture)
+    std::atomic<int> captures{0};
     std::thread watcher;
     std::atomic<bool> quit{false};
 };
@@ -128,7 +131,7 @@ void watch_idleness(Shim *s) {
     const timespec nap{0, (long)std::min<uint64_t>(s->idle_ns / 4 + 1, 20000000)};
     while (!s->quit.load()) {
         nanosleep(&nap, nullptr);
-        if (!s->resident.load() || s->blocking.load() > 0) continue;
+        if (!s->resident.load() || s->blocking.load() > 0 || s->captures.load() > 0) continue;
         const uint64_t last = s->last_return.load();
         if (last == 0 || now_ns() - last <= s->idle_ns) continue;
         std::unique_lock<std::shared_mutex> hold(s->gate);
@@ -213,6 +216,7 @@ int run_switch(Shim &s, const std::vector<nixie_alloc_t> &out, const std::vector
 // gate held exclusively, t_inside set
 int evict_locked(Shim &s) {
     if (!s.resident.load()) return NIXIE_OK;
+    if (s.captures.load() > 0) return NIXIE_EBUSY;   // paper, "CUDA graph compatibility": hands off until the capture ends
     std::lock_guard<std::mutex> lk(s.mu);
     if (s.table.empty()) return NIXIE_OK;   // nothing of the application's is managed: nothing to take away
     if (REAL(hipDeviceSynchronize)() != hipSuccess) return NIXIE_EHIP;   // nothing of the application's is running any more
@@ -441,6 +445,53 @@ NIXIE_GUARDED(hipMemsetD8Async, (hipDeviceptr_t dest, unsigned char value, size_
               (dest, value, count, stream))
 NIXIE_GUARDED(hipMemsetD32, (hipDeviceptr_t dest, int value, size_t count), (dest, value, count))
 NIXIE_GUARDED(hipMemsetD32Async, (hipDeviceptr_t dst, int value, size_t count, hipStream_t stream), (dst, value, count, stream))
+
+// A launched graph runs kernels that hold the application's pointers: the addresses stay valid across
+// a migration, so the graph needs no patching, only the same flag check as a launch.
+NIXIE_GUARDED(hipGraphLaunch, (hipGraphExec_t graphExec, hipStream_t stream), (graphExec, stream))
+
+// Paper, "CUDA graph compatibility": the start and the end of a stream capture are interposed so that
+// no migration (which synchronizes the device and launches work of its own) falls into a capture.
+// The capture starts with the application resident, and evictions are refused until it has ended.
+hipError_t hipStreamBeginCapture(hipStream_t stream, hipStreamCaptureMode mode) {
+    using fn = hipError_t (*)(hipStream_t, hipStreamCaptureMode);
+    static const fn real = next_symbol<fn>("hipStreamBeginCapture");
+    if (t_inside) return real(stream, mode);
+    Shim *s = shim();
+    Running r(s);
+    const hipError_t e = real(stream, mode);
+    if (s && e == hipSuccess) s->captures++;
+    return e;
+}
+
+hipError_t hipStreamBeginCaptureToGraph(hipStream_t stream, hipGraph_t graph, const hipGraphNode_t *dependencies,
+                                        const hipGraphEdgeData *dependencyData, size_t numDependencies,
+                                        hipStreamCaptureMode mode) {
+    using fn = hipError_t (*)(hipStream_t, hipGraph_t, const hipGraphNode_t *, const hipGraphEdgeData *, size_t,
+                              hipStreamCaptureMode);
+    static const fn real = next_symbol<fn>("hipStreamBeginCaptureToGraph");
+    if (t_inside) return real(stream, graph, dependencies, dependencyData, numDependencies, mode);
+    Shim *s = shim();
+    Running r(s);
+    const hipError_t e = real(stream, graph, dependencies, dependencyData, numDependencies, mode);
+    if (s && e == hipSuccess) s->captures++;
+    return e;
+}
+
+hipError_t hipStreamEndCapture(hipStream_t stream, hipGraph_t *pGraph) {
+    using fn = hipError_t (*)(hipStream_t, hipGraph_t *);
+    static const fn real = next_symbol<fn>("hipStreamEndCapture");
+    if (t_inside) return real(stream, pGraph);
+    Shim *s = shim();
+    const hipError_t e = real(stream, pGraph);
+    if (s) {
+        // the capture is over whether it produced a graph or not (an invalidated one ends here too)
+        int have = s->captures.load();
+        while (have > 0 && !s->captures.compare_exchange_weak(have, have - 1)) {}
+        s->last_return.store(now_ns());
+    }
+    return e;
+}
 
 // Blocking calls are bracketed so that an application waiting inside the runtime is not taken for idle.
 hipError_t hipDeviceSynchronize(void) {

@@ -9,7 +9,12 @@
 // GPU at a moment of its choosing: if the process exports nixie_shim_evict (it does only under the
 // shim) that call is made in every pause, and the next runtime call has to bring the memory back.
 //
-// usage: shim_app <pause_ms> <big_mib> [rounds] [idle|explicit]
+// With mode "graph" (implies the explicit evictions, where available) the per-round update of the
+// buffers is a graph captured once from a stream and launched after every pause: the graph holds
+// the buffers' addresses, and its launch is the call that finds the application evicted.  An
+// eviction asked for in the middle of the capture must be refused.
+//
+// usage: shim_app <pause_ms> <big_mib> [rounds] [idle|explicit|graph]
 #include <hip/hip_runtime.h>
 #include <dlfcn.h>
 
@@ -57,7 +62,8 @@ int main(int argc, char **argv) {
     const int pause_ms = argc > 1 ? std::atoi(argv[1]) : 500;
     const uint64_t big = (argc > 2 ? std::strtoull(argv[2], nullptr, 10) : 48) << 20;
     const int rounds = argc > 3 ? std::atoi(argv[3]) : 2;
-    const bool explicit_mode = argc > 4 && std::strcmp(argv[4], "explicit") == 0;
+    const bool graph_mode = argc > 4 && std::strcmp(argv[4], "graph") == 0;
+    const bool explicit_mode = graph_mode || (argc > 4 && std::strcmp(argv[4], "explicit") == 0);
     using evict_fn = int (*)(void);
     const evict_fn evict = explicit_mode ? (evict_fn)dlsym(RTLD_DEFAULT, "nixie_shim_evict") : nullptr;
     size_t free0 = 0, total0 = 0;
@@ -79,8 +85,38 @@ int main(int argc, char **argv) {
     CHECK(hipGetLastError());
     CHECK(hipDeviceSynchronize());
     std::fflush(stdout);
+    hipStream_t stream = nullptr;
+    hipGraphExec_t update = nullptr;
+    if (graph_mode) {
+        hipGraph_t graph = nullptr;
+        CHECK(hipStreamCreate(&stream));
+        CHECK(hipStreamBeginCapture(stream, hipStreamCaptureModeGlobal));
+        for (int b = 0; b < 3; b++) bump<<<256, 256, 0, stream>>>(buf[b], sizes[b] / 4);
+        if (evict) std::printf("eviction asked for during the capture: rc %d\n", evict());
+        for (int b = 3; b < 5; b++) bump<<<256, 256, 0, stream>>>(buf[b], sizes[b] / 4);
+        CHECK(hipStreamEndCapture(stream, &graph));
+        CHECK(hipGraphInstantiate(&update, graph, nullptr, nullptr, 0));
+        CHECK(hipGraphDestroy(graph));
+    }
     unsigned long long total_bad = 0;
-    for (int r = 0; r < rounds; r++) {
+    for (int r = 0; r < rounds && graph_mode; r++) {
+        std::this_thread::sleep_for(std::chrono::milliseconds(pause_ms));
+        if (evict) {
+            const int rc = evict();
+            std::printf("round %d: scheduler took the GPU away, rc %d\n", r, rc);
+            if (rc) return 1;
+        }
+        CHECK(hipGraphLaunch(update, stream));                                                  // wakes up with the graph
+        CHECK(hipStreamSynchronize(stream));
+        for (int b = 0; b < 5; b++) check<<<256, 256>>>(buf[b], sizes[b] / 4, 100 + b, (uint32_t)r + 1, bad);
+        CHECK(hipGetLastError());
+        unsigned long long h = 0;
+        CHECK(hipMemcpy(&h, bad, sizeof(h), hipMemcpyDeviceToHost));
+        std::printf("round %d: %llu wrong words\n", r, h);
+        std::fflush(stdout);
+        total_bad = h;
+    }
+    for (int r = 0; r < rounds && !graph_mode; r++) {
         std::this_thread::sleep_for(std::chrono::milliseconds(pause_ms));   // silence: no runtime call at all
         if (evict) {
             const int rc = evict();
@@ -125,6 +161,8 @@ int main(int argc, char **argv) {
         if (b != 1) CHECK(hipFree(buf[b]));
     CHECK(hipFree(bad));
     CHECK(hipFree(scratch));
+    if (update) CHECK(hipGraphExecDestroy(update));
+    if (stream) CHECK(hipStreamDestroy(stream));
     std::printf(total_bad ? "RESULT wrong %llu\n" : "RESULT ok %llu\n", total_bad);
     return total_bad ? 1 : 0;
 }

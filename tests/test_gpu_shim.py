@@ -106,3 +106,34 @@ def test_scheduler_in_the_process_takes_the_gpu_away(run_program):
 def test_explicit_mode_without_the_shim_is_the_plain_program(run_program):
     r = run_program([APP, "10", "48", "2", "explicit"], timeout=90)
     assert r["rc"] == 0 and "RESULT ok" in r["stdout"] and "took the GPU away" not in r["stdout"], r
+
+
+def test_captured_graph_survives_migrations_and_capture_is_left_alone(run_program):
+    """Paper, "CUDA graph compatibility": an eviction asked for in the middle of a stream capture is
+    refused (NIXIE_EBUSY = -7) and the capture still yields a graph; afterwards the graph -- which
+    holds the application's addresses -- is launched after every eviction and updates the right bytes."""
+    print("shim_app under LD_PRELOAD, graph mode", flush=True)
+    env = preload_env(NIXIE_SHIM_SCRIBBLE=1, NIXIE_SHIM_LOG=1, NIXIE_SHIM_POOL_MIB=256, NIXIE_SHIM_RING_MIB=16)
+    r = run_program([APP, "20", "48", "3", "graph"], env=env, timeout=120)
+    assert r["rc"] == 0 and "RESULT ok" in r["stdout"], r
+    assert "eviction asked for during the capture: rc -7" in r["stdout"], r["stdout"]
+    assert parse(r["stdout"])["rounds"] == [0, 0, 0]
+    log = r["stderr"]
+    assert len(re.findall(r"evicted \d+ allocations", log)) == 5, log
+    assert len(re.findall(r"restored \d+ allocations", log)) == 5, log
+
+
+def test_graph_mode_with_idle_eviction(run_program):
+    """The idleness rule around a capturing application: three pauses, three evictions, each undone
+    by the graph launch that follows."""
+    env = preload_env(NIXIE_SHIM_IDLE_MS=100, NIXIE_SHIM_SCRIBBLE=1, NIXIE_SHIM_LOG=1, NIXIE_SHIM_POOL_MIB=256,
+                      NIXIE_SHIM_RING_MIB=16)
+    r = run_program([APP, "600", "48", "3", "graph"], env=env, timeout=120)
+    assert r["rc"] == 0 and "RESULT ok" in r["stdout"], r
+    assert parse(r["stdout"])["rounds"] == [0, 0, 0]
+    assert len(re.findall(r"evicted \d+ allocations", r["stderr"])) >= 3, r["stderr"]
+
+
+def test_graph_mode_without_the_shim_is_the_plain_program(run_program):
+    r = run_program([APP, "10", "48", "2", "graph"], timeout=90)
+    assert r["rc"] == 0 and "RESULT ok" in r["stdout"] and "during the capture" not in r["stdout"], r

@@ -121,6 +121,7 @@ struct SwapArgs {
 struct HashDesc { uint64_t ptr; uint64_t bytes; uint64_t first_tile; };
 constexpr uint32_t kHashTileWords = 4096;   // 32 KiB per tile
 constexpr uint32_t kNoAllocMaxBuffers = 4096;   // nixie_hash_buffers_noalloc: 128 KiB of static device memory
+constexpr uint32_t kNoAllocBatch = 128;         // descriptors handed to the device per launch, as kernel arguments
 
 }  // namespace nixie
 
@@ -132,6 +133,6 @@ int nixie_launch_hash(const nixie::HashDesc *descs, uint64_t n, uint64_t total_t
                       void *stream);
 int nixie_launch_copy16(const void *src, void *dst, uint64_t bytes, uint32_t wgs, void *stream);
 int nixie_noalloc_scratch(void **out);   // this device's address of the static scratch array
-int nixie_launch_hash_noalloc(const nixie::HashDesc *descs, uint32_t n, uint64_t total_tiles, uint64_t *out_d,
-                              void *stream);
+int nixie_noalloc_put_descs(const nixie::HashDesc *batch, uint32_t count, uint32_t first, void *stream);
+int nixie_noalloc_hash(uint32_t n, uint64_t total_tiles, uint64_t *out_d, void *stream);
 }

@@ -600,13 +600,12 @@ struct HashScratch {
 };
 static __device__ __align__(256) unsigned char scratch[sizeof(HashScratch)];
 
-// Descriptors travel as kernel arguments (by value), 128 at a time: no staging copy, nothing for
+// Descriptors travel as kernel arguments (by value), kNoAllocBatch at a time: no staging copy, nothing for
 // the runtime to allocate.  Each launch writes its batch and clears the matching sums.
-constexpr uint32_t kDescBatch = 128;
-struct DescBatch { HashDesc d[kDescBatch]; };
+struct DescBatch { HashDesc d[kNoAllocBatch]; };
 static_assert(sizeof(DescBatch) + 32 <= 4096, "a batch must fit the kernel argument buffer");
 
-__global__ void __launch_bounds__(kDescBatch) nixie_put_descs_kernel(DescBatch b, uint32_t count, HashScratch *hs,
+__global__ void __launch_bounds__(kNoAllocBatch) nixie_put_descs_kernel(DescBatch b, uint32_t count, HashScratch *hs,
                                                                       uint32_t first) {
     const uint32_t i = threadIdx.x;
     if (i < count) {
@@ -644,23 +643,31 @@ int nixie_noalloc_scratch(void **out) {
     return (int)hipSuccess;
 }
 
-// descs: HOST array of n <= kNoAllocMaxBuffers entries with first_tile filled in; out_d: DEVICE
-// array of n.  Enqueues on stream and returns; nothing is allocated, copied or waited for.
-int nixie_launch_hash_noalloc(const HashDesc *descs, uint32_t n, uint64_t total_tiles, uint64_t *out_d, void *stream) {
+// The no-allocation hash in two steps, both only enqueueing on stream.  First the table, a batch at a
+// time: batch = HOST array of count <= kNoAllocBatch descriptors (first_tile filled in) that become
+// entries first .. first + count - 1; the matching sums are cleared.
+int nixie_noalloc_put_descs(const HashDesc *batch, uint32_t count, uint32_t first, void *stream) {
+    if (count == 0) return (int)hipSuccess;
+    if (count > kNoAllocBatch || first + count > kNoAllocMaxBuffers) return (int)hipErrorInvalidValue;
+    void *base = nullptr;
+    const int e = nixie_noalloc_scratch(&base);
+    if (e) return e;
+    DescBatch b;
+    for (uint32_t i = 0; i < count; i++) b.d[i] = batch[i];
+    for (uint32_t i = count; i < kNoAllocBatch; i++) b.d[i] = HashDesc{0, 0, 0};
+    nixie_put_descs_kernel<<<1, kNoAllocBatch, 0, (hipStream_t)stream>>>(b, count, (HashScratch *)base, first);
+    return (int)hipGetLastError();
+}
+
+// Then the hashes of entries 0 .. n - 1 into out_d (DEVICE array of n).
+int nixie_noalloc_hash(uint32_t n, uint64_t total_tiles, uint64_t *out_d, void *stream) {
+    if (n == 0) return (int)hipSuccess;
+    if (n > kNoAllocMaxBuffers) return (int)hipErrorInvalidValue;
     void *base = nullptr;
     int e = nixie_noalloc_scratch(&base);
     if (e) return e;
     HashScratch *hs = (HashScratch *)base;
     hipStream_t st = (hipStream_t)stream;
-    for (uint32_t first = 0; first < n; first += kDescBatch) {
-        DescBatch b;
-        const uint32_t count = n - first < kDescBatch ? n - first : kDescBatch;
-        for (uint32_t i = 0; i < count; i++) b.d[i] = descs[first + i];
-        for (uint32_t i = count; i < kDescBatch; i++) b.d[i] = HashDesc{0, 0, 0};
-        nixie_put_descs_kernel<<<1, kDescBatch, 0, st>>>(b, count, hs, first);
-        e = (int)hipGetLastError();
-        if (e) return e;
-    }
     if (total_tiles) {
         const uint32_t grid = (uint32_t)(total_tiles < 4096 ? total_tiles : 4096);
         nixie_hash_kernel<<<grid, 256, 0, st>>>(hs->descs, n, total_tiles, hs->sums);

@@ -153,17 +153,24 @@ int nixie_hash_buffers_noalloc(const void *const *ptrs, const uint64_t *bytes, u
     if (n == 0) return NIXIE_OK;
     if (!ptrs || !bytes || !hashes_dev) return NIXIE_EINVAL;
     if (n > kNoAllocMaxBuffers) return NIXIE_EINVAL;   // beyond the static scratch memory: use nixie_hash_buffers
-    static thread_local HashDesc hd[kNoAllocMaxBuffers];   // host side of the table: no heap either
     std::shared_lock<std::shared_mutex> maps(switch_lock());
-    uint64_t tiles = 0;
-    for (uint64_t i = 0; i < n; i++) {
+    for (uint64_t i = 0; i < n; i++) {   // everything is checked before anything is enqueued
         if (bytes[i] && !ptrs[i]) return NIXIE_EINVAL;
         const int where = space_range_state((uint64_t)(uintptr_t)ptrs[i], bytes[i]);
         if (where) return where == 1 ? NIXIE_EUNMAPPED : NIXIE_EINVAL;
-        hd[i] = HashDesc{(uint64_t)(uintptr_t)ptrs[i], bytes[i], tiles};
-        tiles += ((bytes[i] + 7) / 8 + kHashTileWords - 1) / kHashTileWords;
     }
-    const int e = nixie_launch_hash_noalloc(hd, (uint32_t)n, tiles, hashes_dev, hip_stream);
+    HashDesc batch[kNoAllocBatch];   // on the stack: no heap, and no thread-local block for the loader to allocate
+    uint64_t tiles = 0;
+    int e = 0;
+    for (uint64_t first = 0; first < n && !e; first += kNoAllocBatch) {
+        const uint32_t count = (uint32_t)std::min<uint64_t>(kNoAllocBatch, n - first);
+        for (uint32_t i = 0; i < count; i++) {
+            batch[i] = HashDesc{(uint64_t)(uintptr_t)ptrs[first + i], bytes[first + i], tiles};
+            tiles += ((bytes[first + i] + 7) / 8 + kHashTileWords - 1) / kHashTileWords;
+        }
+        e = nixie_noalloc_put_descs(batch, count, (uint32_t)first, hip_stream);
+    }
+    if (!e) e = nixie_noalloc_hash((uint32_t)n, tiles, hashes_dev, hip_stream);
     if (e) { set_last_hip_error(e); return NIXIE_EHIP; }
     return NIXIE_OK;
 }

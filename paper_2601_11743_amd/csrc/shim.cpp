@@ -87,6 +87,7 @@ struct Shim {
     bool scribble = false, log = false;
     nixie_pool_t *pool = nullptr;
     nixie_space_t *space = nullptr;
+    nixie_ring_t *staging = nullptr;   // the pinned ring, made at the first migration and kept: every later one reuses it
     uint64_t base = 0;
 
     // Launches hold `gate` shared; eviction and restore hold it exclusively, which is what holds
@@ -204,7 +205,9 @@ int run_switch(Shim &s, const std::vector<nixie_alloc_t> &out, const std::vector
     for (auto &r : in) moved += r.bytes;
     if (moved == 0) return NIXIE_OK;
     nixie_plan_t *plan = nullptr;
-    int rc = nixie_plan(&to, &ti, s.ring, nullptr, &plan);
+    if (!s.staging && nixie_ring_create(s.ring, &s.staging) != NIXIE_OK) s.staging = nullptr;
+    // (without a ring of its own the plan allocates one for this migration only)
+    int rc = s.staging ? nixie_plan_on_ring(&to, &ti, s.staging, nullptr, &plan) : nixie_plan(&to, &ti, s.ring, nullptr, &plan);
     if (rc) return rc;
     nixie_stats_t st{};
     rc = nixie_switch(plan, nullptr, &st);
@@ -238,8 +241,17 @@ int evict_locked(Shim &s) {
             if (u.second.host) { munmap(u.second.host, u.second.bytes); u.second.host = nullptr; }
         return rc;
     }
-    for (auto &kv : s.table)
-        if ((rc = nixie_space_unmap(s.space, kv.first - s.base, kv.second.blocks * s.block)) != 0) return rc;
+    // From here on the host copies are the application's memory.  A block whose unmapping the driver
+    // refuses stays reserved (nobody else can be given it) until the restore, which maps over whatever
+    // state it finds; the eviction itself has happened.
+    int refused = NIXIE_OK;
+    for (auto &kv : s.table) {
+        const int u = nixie_space_unmap(s.space, kv.first - s.base, kv.second.blocks * s.block);
+        if (u && !refused) refused = u;
+    }
+    if (refused)
+        std::fprintf(stderr, "nixie-shim: some blocks could not be unmapped (%s); they stay reserved until the restore\n",
+                     nixie_strerror(refused));
     if (s.scribble) {
         // what another application would do with the physical memory meanwhile
         nixie_space_t *other = nullptr;

@@ -312,7 +312,7 @@ int nixie_space_destroy(nixie_space_t *s) {
     int rc;
     {
         std::unique_lock<std::shared_mutex> lk(switch_lock(), std::try_to_lock);
-    if (!lk.owns_lock()) return NIXIE_EBUSY;   // a switch is running: never wait for it here (it may be the caller's own)
+        if (!lk.owns_lock()) return NIXIE_EBUSY;   // a switch is running: never wait for it here (it may be the caller's own)
         hipError_t e = hipDeviceSynchronize();
         if (e != hipSuccess) return fail(e);
         rc = unmap_blocks(s, 0, s->mapped.size());

@@ -98,7 +98,7 @@ typedef struct {
     uint32_t order;          /* enum nixie_order                                                            */
     uint32_t gather_wgs;     /* workgroups copying HBM -> ring                                              */
     uint32_t scatter_wgs;    /* workgroups copying ring -> HBM                                              */
-    uint32_t team;           /* workgroups that share one chunk; default one per 16-128 KiB of slot, at most 256 */
+    uint32_t team;           /* workgroups that share one chunk; default one per 16-64 KiB of slot, at most 256  */
     uint32_t drain_threads;  /* host threads moving ring -> pageable; default min(4, cores / 4), at least 1   */
     uint32_t fill_threads;   /* host threads moving pageable -> ring; same default                           */
     uint32_t timeout_ms;     /* bound on any single credit wait, host or GPU side; default 30000.  It is a

@@ -340,3 +340,51 @@ def test_pure_eviction_equals_concatenation_copied_to_the_host(nx):
     plan.switch()
     plan.close()
     assert np.array_equal(host, want)
+
+
+def _random_case(seed):
+    """One seeded draw over everything a caller can choose: table shapes, sizes around the slot
+    boundaries, slot and ring size, ring split, order, launch shape, host threads, host-side modes."""
+    rng = np.random.default_rng(1000 + seed)
+    slot = int(rng.choice([4 * KiB, 16 * KiB, 64 * KiB, 256 * KiB]))
+    edge = [0, 1, 15, 16, 17, slot - 1, slot, slot + 1, 2 * slot + 5]
+
+    def sizes(n):
+        out = []
+        for _ in range(n):
+            if rng.random() < 0.3:
+                out.append(int(rng.choice(edge)))
+            else:
+                out.append(int(np.exp(rng.uniform(0, np.log(6 * slot)))))
+        return out
+
+    na, nb = int(rng.integers(0, 40)), int(rng.integers(0, 40))
+    if seed % 8 == 5: na = 0
+    if seed % 8 == 6: nb = 0
+    sa, sb = sizes(na), sizes(nb)
+    n_slots = int(rng.integers(4, 25))
+    o = dict(slot_bytes=slot, order=int(rng.integers(0, 4)), drain_threads=int(rng.integers(1, 5)),
+             fill_threads=int(rng.integers(1, 5)))
+    if rng.random() < 0.5: o["team"] = int(rng.integers(1, 9))
+    if rng.random() < 0.6:
+        o["gather_wgs"], o["scatter_wgs"] = int(rng.integers(1, 33)), int(rng.integers(1, 33))
+    if rng.random() < 0.5: o["flex_wgs"] = int(rng.integers(1, 41))
+    flags = 0
+    for f, pr in (("SPLIT_BY_BYTES", 0.3), ("SERIALIZE", 0.15), ("HOST_PLAIN_MEMCPY", 0.3), ("HOST_SPIN", 0.3),
+                  ("NO_FLEX_WGS", 0.2)):
+        if rng.random() < pr: flags |= {"SPLIT_BY_BYTES": 1, "SERIALIZE": 2, "HOST_PLAIN_MEMCPY": 16, "HOST_SPIN": 128,
+                                        "NO_FLEX_WGS": 256}[f]
+    o["flags"] = flags
+    if not (flags & 1) and sum(sa) and sum(sb) and rng.random() < 0.4:
+        o["out_slots"] = int(rng.integers(2, n_slots - 1))
+    skew = (int(rng.integers(0, 16)), int(rng.integers(0, 16))) if rng.random() < 0.5 else (0, 0)
+    return sa, sb, n_slots * slot, o, skew, int(rng.integers(1, 3))
+
+
+@pytest.mark.parametrize("seed", range(32))
+def test_random_plans(nx, oracle, seed):
+    """Seeded sweep over the option space (no aliasing, no pinned tier: those have sweeps of their own)."""
+    sa, sb, ring, o, skew, switches = _random_case(seed)
+    print(f"seed {seed}: {len(sa)} + {len(sb)} allocations, {sum(sa)} + {sum(sb)} bytes, ring {ring}, {o}, skew {skew}, "
+          f"{switches} switches", flush=True)
+    run_case(nx, oracle, sa, sb, ring, nx.Opts(**o), seed=50 + seed, skew=skew, switches=switches)

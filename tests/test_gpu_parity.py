@@ -230,39 +230,76 @@ ALIAS_CASES = [
 ]
 
 
-@pytest.mark.parametrize("case", range(len(ALIAS_CASES)))
-@pytest.mark.parametrize("mode", ["default", "small_units", "serialized", "either"])
-def test_in_place_switch(nx, oracle, case, mode):
+def run_in_place(nx, oracle, sa, sb, shift, skew_a, skew_b, ring, opts, extra_flags=0):
     import torch
     from tests.helpers import AliasedPair
     from tests.gpu_helpers import first_diff
-    sa, sb, shift = ALIAS_CASES[case]
-    ref = AliasedPair(sa, sb, 31, shift_b=shift, skew_a=case % 3, skew_b=(case * 5) % 16)
+    ref = AliasedPair(sa, sb, 31, shift_b=shift, skew_a=skew_a, skew_b=skew_b)
     h_out_ref = oracle.hash_table(ref.pairs_a(), "dev")
     h_in_ref = oracle.hash_table(ref.pairs_b(), "host")
     oracle.switch_direct(ref.pairs_a(), ref.pairs_b())           # the definition: evict all, then restore
     ref.check()
 
-    g = AliasedPair(sa, sb, 31, shift_b=shift, skew_a=case % 3, skew_b=(case * 5) % 16)
+    g = AliasedPair(sa, sb, 31, shift_b=shift, skew_a=skew_a, skew_b=skew_b)
     dev_t = torch.from_numpy(g.dev).to("cuda:0")
     base = dev_t.data_ptr()
     rows_a = [(base + od, g.host_a.ctypes.data + oh, b) for od, oh, b in zip(g.la.offsets, g.lha.offsets, g.sizes_a)]
     rows_b = [(base + od, g.host_b.ctypes.data + oh, b) for od, oh, b in zip(g.lb.offsets, g.lhb.offsets, g.sizes_b)]
+    plan = nx.Plan(rows_a, rows_b, ring, nx.Opts(flags=nx.IN_PLACE | extra_flags, **opts))
+    try:
+        h_out, h_in = plan.hash_tables()
+        assert np.array_equal(h_out, h_out_ref) and np.array_equal(h_in, h_in_ref)
+        plan.switch()
+        torch.cuda.synchronize()
+        dev_after = dev_t.cpu().numpy()
+        assert np.array_equal(g.host_a, ref.host_a), "evicted set: " + first_diff(g.host_a, ref.host_a)
+        assert np.array_equal(dev_after, ref.dev), "device arena: " + first_diff(dev_after, ref.dev)
+        plan.verify(h_out_ref, h_in_ref)
+    finally:
+        plan.close()
+    return rows_a, rows_b
+
+
+@pytest.mark.parametrize("case", range(len(ALIAS_CASES)))
+@pytest.mark.parametrize("mode", ["default", "small_units", "serialized", "either"])
+def test_in_place_switch(nx, oracle, case, mode):
+    sa, sb, shift = ALIAS_CASES[case]
     kw = dict(default={}, small_units=dict(team=8, gather_wgs=16, scatter_wgs=24, drain_threads=2, fill_threads=2),
               serialized={}, either=dict(team=4, gather_wgs=1, scatter_wgs=1, flex_wgs=24))[mode]
-    flags = nx.IN_PLACE | (nx.SERIALIZE if mode == "serialized" else 0)
+    rows_a, rows_b = run_in_place(nx, oracle, sa, sb, shift, case % 3, (case * 5) % 16, 8 * S, dict(slot_bytes=S, **kw),
+                                  nx.SERIALIZE if mode == "serialized" else 0)
     with pytest.raises(nx.NixieError):
         nx.Plan(rows_a, rows_b, 8 * S, nx.Opts(slot_bytes=S))     # without the flag aliasing is an error
-    plan = nx.Plan(rows_a, rows_b, 8 * S, nx.Opts(slot_bytes=S, flags=flags, **kw))
-    h_out, h_in = plan.hash_tables()
-    assert np.array_equal(h_out, h_out_ref) and np.array_equal(h_in, h_in_ref)
-    plan.switch()
-    torch.cuda.synchronize()
-    dev_after = dev_t.cpu().numpy()
-    assert np.array_equal(g.host_a, ref.host_a), "evicted set: " + first_diff(g.host_a, ref.host_a)
-    assert np.array_equal(dev_after, ref.dev), "device arena: " + first_diff(dev_after, ref.dev)
-    plan.verify(h_out_ref, h_in_ref)
-    plan.close()
+
+
+def _random_alias_case(seed):
+    """Seeded draw of aliased tables: sizes, how far B's ranges are shifted against A's, alignment of either
+    side, slot and ring size, order, launch shape, flags (as names)."""
+    rng = np.random.default_rng(7000 + seed)
+    slot = int(rng.choice([4 * KiB, 16 * KiB, 64 * KiB]))
+    draw = lambda n: [int(rng.choice([1, 16, slot - 1, slot, slot + 1])) if rng.random() < 0.25
+                      else int(np.exp(rng.uniform(0, np.log(8 * slot)))) for _ in range(n)]
+    sa, sb = draw(int(rng.integers(1, 25))), draw(int(rng.integers(1, 25)))
+    shift = int(rng.choice([0, 16, 1000, slot, 3 * slot + 48, int(rng.integers(0, max(1, sum(sa))))]))
+    o = dict(slot_bytes=slot, order=int(rng.integers(0, 4)), drain_threads=int(rng.integers(1, 4)),
+             fill_threads=int(rng.integers(1, 4)))
+    if rng.random() < 0.5: o["team"] = int(rng.integers(1, 9))
+    if rng.random() < 0.6: o["gather_wgs"], o["scatter_wgs"] = int(rng.integers(1, 25)), int(rng.integers(1, 25))
+    if rng.random() < 0.5: o["flex_wgs"] = int(rng.integers(1, 33))
+    extra = 0
+    if rng.random() < 0.2: extra |= 2          # SERIALIZE
+    if rng.random() < 0.3: extra |= 1          # SPLIT_BY_BYTES
+    if rng.random() < 0.2: extra |= 256        # NO_FLEX_WGS
+    ring = int(rng.integers(4, 20)) * slot
+    return sa, sb, shift, int(rng.integers(0, 16)), int(rng.integers(0, 16)), ring, o, extra
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_in_place_plans(nx, oracle, seed):
+    sa, sb, shift, skew_a, skew_b, ring, o, extra = _random_alias_case(seed)
+    print(f"seed {seed}: {len(sa)} + {len(sb)} allocations, {sum(sa)} + {sum(sb)} bytes, shift {shift}, ring {ring}, {o}, "
+          f"extra flags {extra}", flush=True)
+    run_in_place(nx, oracle, sa, sb, shift, skew_a, skew_b, ring, o, extra)
 
 
 # ---- one ring for many plans --------------------------------------------------------------------

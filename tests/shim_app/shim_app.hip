@@ -14,7 +14,11 @@
 // the buffers' addresses, and its launch is the call that finds the application evicted.  An
 // eviction asked for in the middle of the capture must be refused.
 //
-// usage: shim_app <pause_ms> <big_mib> [rounds] [idle|explicit|graph]
+// With mode "threads" three host threads, each with a stream and a buffer of its own, update their
+// buffers `rounds` x 50 times while the main thread asks for an eviction every pause_ms: launches
+// and waits of several threads meet migrations at arbitrary points.
+//
+// usage: shim_app <pause_ms> <big_mib> [rounds] [idle|explicit|graph|threads]
 #include <hip/hip_runtime.h>
 #include <dlfcn.h>
 
@@ -22,6 +26,7 @@
 #include <cstdint>
 #include <cstdio>
 #include <cstdlib>
+#include <atomic>
 #include <cstring>
 #include <thread>
 #include <vector>
@@ -58,14 +63,64 @@ __global__ void check(const uint32_t *p, uint64_t n, uint32_t seed, uint32_t bum
     if (mine) atomicAdd(bad, mine);
 }
 
+// mode "threads"; returns the process's exit code
+int run_threads(int pause_ms, uint64_t big, int iters, int (*evict)(void)) {
+    constexpr int kWorkers = 3;
+    uint32_t *buf[kWorkers];
+    const uint64_t n = big / kWorkers / 4;
+    for (int w = 0; w < kWorkers; w++) CHECK(hipMalloc((void **)&buf[w], n * 4));
+    unsigned long long *bad = nullptr;
+    CHECK(hipMalloc((void **)&bad, sizeof(*bad)));
+    CHECK(hipMemset(bad, 0, sizeof(*bad)));
+    for (int w = 0; w < kWorkers; w++) fill<<<256, 256>>>(buf[w], n, 200 + w);
+    CHECK(hipDeviceSynchronize());
+    std::atomic<int> running{kWorkers}, failed{0};
+    std::vector<std::thread> workers;
+    for (int w = 0; w < kWorkers; w++)
+        workers.emplace_back([&, w] {
+            hipStream_t st = nullptr;
+            bool ok = hipStreamCreate(&st) == hipSuccess;
+            for (int it = 0; ok && it < iters; it++) {
+                bump<<<64, 256, 0, st>>>(buf[w], n);
+                ok = hipGetLastError() == hipSuccess;
+                if (ok && it % 8 == 7) ok = hipStreamSynchronize(st) == hipSuccess;
+                if (ok && it % 16 == 15) std::this_thread::sleep_for(std::chrono::microseconds(300 * (w + 1)));
+            }
+            ok = ok && hipStreamSynchronize(st) == hipSuccess;
+            if (st) (void)hipStreamDestroy(st);
+            if (!ok) failed++;
+            running--;
+        });
+    int asked = 0, refused = 0;
+    while (running.load() > 0) {
+        std::this_thread::sleep_for(std::chrono::milliseconds(pause_ms));
+        if (evict && running.load() > 0) {
+            asked++;
+            if (evict() != 0) refused++;
+        }
+    }
+    for (auto &t : workers) t.join();
+    std::printf("threads: %d evictions asked for, %d refused, %d workers failed\n", asked, refused, failed.load());
+    for (int w = 0; w < kWorkers; w++) check<<<256, 256>>>(buf[w], n, 200 + w, (uint32_t)iters, bad);
+    unsigned long long h = 0;
+    CHECK(hipMemcpy(&h, bad, sizeof(h), hipMemcpyDeviceToHost));
+    for (int w = 0; w < kWorkers; w++) CHECK(hipFree(buf[w]));
+    CHECK(hipFree(bad));
+    const bool good = h == 0 && failed.load() == 0 && refused == 0;
+    std::printf(good ? "RESULT ok %llu\n" : "RESULT wrong %llu\n", h);
+    return good ? 0 : 1;
+}
+
 int main(int argc, char **argv) {
     const int pause_ms = argc > 1 ? std::atoi(argv[1]) : 500;
     const uint64_t big = (argc > 2 ? std::strtoull(argv[2], nullptr, 10) : 48) << 20;
     const int rounds = argc > 3 ? std::atoi(argv[3]) : 2;
     const bool graph_mode = argc > 4 && std::strcmp(argv[4], "graph") == 0;
-    const bool explicit_mode = graph_mode || (argc > 4 && std::strcmp(argv[4], "explicit") == 0);
+    const bool threads_mode = argc > 4 && std::strcmp(argv[4], "threads") == 0;
+    const bool explicit_mode = graph_mode || threads_mode || (argc > 4 && std::strcmp(argv[4], "explicit") == 0);
     using evict_fn = int (*)(void);
     const evict_fn evict = explicit_mode ? (evict_fn)dlsym(RTLD_DEFAULT, "nixie_shim_evict") : nullptr;
+    if (threads_mode) return run_threads(pause_ms, big, rounds * 50, evict);
     size_t free0 = 0, total0 = 0;
     CHECK(hipMemGetInfo(&free0, &total0));
     // a few buffers of mixed sizes: three large ones and two small ones

@@ -137,3 +137,23 @@ def test_graph_mode_with_idle_eviction(run_program):
 def test_graph_mode_without_the_shim_is_the_plain_program(run_program):
     r = run_program([APP, "10", "48", "2", "graph"], timeout=90)
     assert r["rc"] == 0 and "RESULT ok" in r["stdout"] and "during the capture" not in r["stdout"], r
+
+
+def test_threads_launching_while_evictions_come_in(run_program):
+    """Three host threads with a stream each keep launching and waiting while evictions are asked for every
+    3 ms: every launch finds the memory resident (or brings it back first), no eviction starts under a call
+    in progress, and at the end every buffer has received exactly its updates."""
+    print("shim_app under LD_PRELOAD, three launching threads against explicit evictions", flush=True)
+    env = preload_env(NIXIE_SHIM_SCRIBBLE=1, NIXIE_SHIM_LOG=1, NIXIE_SHIM_POOL_MIB=256, NIXIE_SHIM_RING_MIB=16)
+    r = run_program([APP, "3", "24", "20", "threads"], env=env, timeout=120)
+    assert r["rc"] == 0 and "RESULT ok" in r["stdout"], r
+    m = re.search(r"threads: (\d+) evictions asked for, (\d+) refused, (\d+) workers failed", r["stdout"])
+    assert m and int(m.group(1)) >= 3 and int(m.group(2)) == 0 and int(m.group(3)) == 0, r["stdout"]
+    n_ev = len(re.findall(r"evicted \d+ allocations", r["stderr"]))
+    n_re = len(re.findall(r"restored \d+ allocations", r["stderr"]))
+    assert n_ev >= 3 and n_re == n_ev, (n_ev, n_re)    # the final check kernels wake the application up once more if need be
+
+
+def test_threads_mode_without_the_shim_is_the_plain_program(run_program):
+    r = run_program([APP, "3", "24", "4", "threads"], timeout=90)
+    assert r["rc"] == 0 and "RESULT ok" in r["stdout"], r

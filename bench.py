@@ -359,6 +359,20 @@ def main() -> int:
     elapsed = time.perf_counter() - t_begin
     host_cpu_s = (time.process_time() - cpu_begin) / args.steps   # all threads of this process
 
+    # What a scheduler pays that makes a fresh plan for every switch (the tables change) but keeps its
+    # pinned ring: descriptors, counters, control block and host threads, without the ring's allocation.
+    plan_on_ring_ms = None
+    if pool is None and not args.in_place:
+        keep = nx.Ring(ring)
+        took = []
+        for _ in range(3):
+            t0 = time.perf_counter()
+            nx.Plan(rows_a, rows_b, keep, opts).close()
+            took.append((time.perf_counter() - t0) * 1e3)
+        keep.close()
+        plan_on_ring_ms = round(sorted(took)[1], 2)
+        log(f"[bench] nixie_plan_on_ring + destroy: {took} ms")
+
     serialized = None
     if not args.no_serialized and not args.in_place and not (args.flags & nx.SERIALIZE) and info["bytes_out"] and info["bytes_in"]:
         # self-baseline: the same library with the overlap switched off (one link direction at a time)
@@ -524,7 +538,7 @@ def main() -> int:
                    "direct_bytes_out": info["direct_bytes_out"], "direct_bytes_in": info["direct_bytes_in"]},
         "switch_latency_ms": {"min": round(lat[0], 3), "median": round(med(lat), 3), "max": round(lat[-1], 3)},
         "b_ready_ms": round(med(sorted(s["ns_in_done"] / 1e6 for s in stats)), 3),
-        "plan_ms": round(plan_ms, 2),
+        "plan_ms": round(plan_ms, 2), "plan_on_shared_ring_ms": plan_on_ring_ms,
         "host_cpu_s_per_step": round(host_cpu_s, 4),
         "pinned_bytes": {"ring": info["pinned_ring_bytes"], "control": info["pinned_ctrl_bytes"]},
         "verified": {"hash_mismatches": rep["mismatched_out"] + rep["mismatched_in"], "full_buffer_equal": arenas_ok},

@@ -19,6 +19,11 @@
  * rule (paper, "Idleness Detection": idle = no runtime call has returned for longer than a
  * threshold), after which the application is evicted as if another one had been scheduled.
  *
+ * Application threads: the shim's own state is safe against calls from several threads (checked on a
+ * CPU model under ThreadSanitizer), but on the GPU only applications that make their runtime calls
+ * from one thread at a time are validated; with several launching threads a migration's own runtime
+ * calls overlap those of the other threads, and that combination is not supported yet.
+ *
  * Use:  LD_PRELOAD=/path/to/libnixie_shim.so  ./application      (set before the process starts)
  *
  * Interposed runtime calls (same prototypes as the HIP runtime's; everything else passes through):
@@ -44,9 +49,14 @@
  *                    nixie_shim_evict returns NIXIE_EBUSY.  A graph instantiated from the capture
  *                    holds the application's pointers, which stay valid across migrations, so it
  *                    is launched unchanged afterwards.
+ *   hipStreamCreate, hipStreamCreateWithFlags, hipStreamDestroy
+ *                    never overlap a migration (the paper's shim intercepts stream creation too, as
+ *                    a call that allocates implicitly); they do not bring an evicted application back.
  * Interposed only to time the application's activity (idleness), bracketed as calls that may
- * block: hipDeviceSynchronize, hipStreamSynchronize (the calls above count as activity too, for
- * as long as they take).
+ * block: hipDeviceSynchronize, hipStreamSynchronize, hipEventSynchronize (the calls above count as
+ * activity too, for as long as they take).  They are not held back during a migration: a thread
+ * waiting for work that another thread has yet to submit must not block the migration that holds
+ * that other thread back.
  * Not interposed: graphs built node by node are launched like any other (hipGraphLaunch) but their
  * construction is not watched; stream-ordered allocators (hipMallocAsync), 2-D/3-D
  * and array copies, peer copies, managed memory.  A program that reaches its managed allocations

@@ -505,6 +505,24 @@ hipError_t hipStreamEndCapture(hipStream_t stream, hipGraph_t *pGraph) {
     return e;
 }
 
+// Creating and destroying streams changes runtime state that a migration's own calls walk through
+// (the paper's shim intercepts stream creation as well, as a call that allocates implicitly): such a
+// call never overlaps a migration, but it needs no memory behind the application's pointers.
+#define NIXIE_NOT_DURING_MIGRATION(name, params, args)      \
+    hipError_t name params {                                \
+        using fn = hipError_t(*) params;                    \
+        static const fn real = next_symbol<fn>(#name);      \
+        Shim *s = t_inside ? nullptr : shim();              \
+        if (!s) return real args;                           \
+        std::shared_lock<std::shared_mutex> hold(s->gate);  \
+        const hipError_t e = real args;                     \
+        s->last_return.store(now_ns());                     \
+        return e;                                           \
+    }
+NIXIE_NOT_DURING_MIGRATION(hipStreamCreate, (hipStream_t * stream), (stream))
+NIXIE_NOT_DURING_MIGRATION(hipStreamCreateWithFlags, (hipStream_t * stream, unsigned int flags), (stream, flags))
+NIXIE_NOT_DURING_MIGRATION(hipStreamDestroy, (hipStream_t stream), (stream))
+
 // Blocking calls are bracketed so that an application waiting inside the runtime is not taken for idle.
 hipError_t hipDeviceSynchronize(void) {
     if (t_inside) return REAL(hipDeviceSynchronize)();
@@ -520,6 +538,17 @@ hipError_t hipStreamSynchronize(hipStream_t stream) {
     Shim *s = shim();
     if (s) s->blocking++;
     const hipError_t e = REAL(hipStreamSynchronize)(stream);
+    if (s) { s->blocking--; s->last_return.store(now_ns()); }
+    return e;
+}
+
+hipError_t hipEventSynchronize(hipEvent_t event) {
+    using fn = hipError_t (*)(hipEvent_t);
+    static const fn real = next_symbol<fn>("hipEventSynchronize");
+    if (t_inside) return real(event);
+    Shim *s = shim();
+    if (s) s->blocking++;
+    const hipError_t e = real(event);
     if (s) { s->blocking--; s->last_return.store(now_ns()); }
     return e;
 }

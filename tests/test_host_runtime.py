@@ -82,3 +82,47 @@ def test_shim_block_allocator_against_a_bitmap(tmp_path_factory, seed):
                            os.path.join(ROOT, "tests", "fake_device", "blockruns_test.cpp"), "-o", out])
     r = subprocess.run([out, str(seed)], capture_output=True, text=True, timeout=120)
     assert r.returncode == 0 and "ok seed" in r.stdout, r.stdout + r.stderr
+
+
+# ---- the transparent shim's logic against a CPU model of the runtime -----------------------------
+
+CLANG = "/opt/rocm/lib/llvm/bin/clang++"      # g++ does not get through the runtime's hip_ext.h
+
+
+@pytest.fixture(scope="module")
+def shim_model(tmp_path_factory):
+    """shim.cpp itself, compiled into a test program in front of tests/fake_device/fake_runtime.cpp (a
+    CPU stand-in for the HIP calls it forwards to and the libnixie calls it makes), all under
+    ThreadSanitizer."""
+    if not os.path.exists(CLANG):
+        pytest.skip("no clang++ with the HIP headers")
+    d = str(tmp_path_factory.mktemp("shim_model"))
+    flags = ["-std=c++17", "-O1", "-g", "-fsanitize=thread", "-D__HIP_PLATFORM_AMD__", "-w", "-I/opt/rocm/include",
+             "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
+    fake = os.path.join(ROOT, "tests", "fake_device")
+    subprocess.check_call([CLANG, *flags, "-shared", "-fPIC", os.path.join(fake, "fake_runtime.cpp"),
+                           "-o", os.path.join(d, "libfake_runtime.so")])
+    out = os.path.join(d, "shim_model_test")
+    subprocess.check_call([CLANG, *flags, os.path.join(CSRC, "shim.cpp"), os.path.join(fake, "shim_model_test.cpp"),
+                           "-L" + d, "-lfake_runtime", "-Wl,-rpath," + d, "-ldl", "-pthread", "-o", out])
+    return out
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_shim_with_three_application_threads_against_constant_evictions(shim_model, seed):
+    """Launches, waits, copies, allocations and memory reports of three threads while the main thread evicts
+    every 150 us: no update is lost or doubled (a launch past the execution flag would die on unmapped
+    memory, a migration before the kernels have finished would be a race), and no data race in the shim."""
+    out = run(shim_model, "threads", seed)
+    assert "ok" in out.splitlines()[-1], out
+
+
+@pytest.mark.parametrize("seed", [1, 2])
+def test_shim_idleness_rule_with_several_threads(shim_model, seed):
+    out = run(shim_model, "idle", seed)
+    assert "ok" in out.splitlines()[-1], out
+
+
+def test_shim_refuses_to_migrate_inside_a_stream_capture(shim_model):
+    out = run(shim_model, "capture", 1)
+    assert "evict during capture -7" in out

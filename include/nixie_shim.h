@@ -72,7 +72,14 @@
  *                           this long (default 0 = never; the paper's threshold is 100)
  *   NIXIE_SHIM_SCRIBBLE     1: after an eviction the freed physical memory is overwritten through
  *                           a second address space, as another application would (test aid)
+ *   NIXIE_SHIM_SYNC_UNMAP   1: an eviction unmaps the application's blocks before it returns.  By default
+ *                           that is left to a background thread (a driver call per block, 0.25 ms each on
+ *                           MI355X, that nobody has to wait for: the evicted application cannot run, and
+ *                           an application that comes back first keeps what is still mapped)
  *   NIXIE_SHIM_LOG          1: one line per eviction / restore on stderr
+ * Host memory: the pageable copy of an allocation keeps its address range from one eviction to the
+ * next; after a restore its pages are released lazily (MADV_FREE), so a later eviction usually pays
+ * no page faults for them.  hipFree gives the range back.
  */
 #ifndef NIXIE_SHIM_H
 #define NIXIE_SHIM_H
@@ -91,7 +98,7 @@ typedef struct {
     uint64_t passthrough_allocs;/* live allocations below the threshold                   */
     uint32_t resident;          /* the execution flag: 1 = the application's memory is in HBM */
     uint32_t evictions, restores;
-    uint64_t last_switch_ns;    /* duration of the last eviction or restore               */
+    uint64_t last_switch_ns;    /* duration of the last eviction (device wait, swap, unmapping) or restore */
     uint64_t launches_held;     /* launches that found the flag off and waited for a restore */
 } nixie_shim_info_t;
 
@@ -101,7 +108,7 @@ int nixie_shim_info(nixie_shim_info_t *info);
 
 /* The scheduler's two actions, for a caller inside the process.  nixie_shim_evict holds back new
  * launches, waits for the device, moves every managed allocation to pageable host memory with
- * nixie_switch, and unmaps the physical memory; the application keeps its pointers.
+ * nixie_switch, and has the physical memory unmapped; the application keeps its pointers.
  * nixie_shim_restore maps it again and brings the bytes back; any launch does the same on its own.
  * Both return 0 (also when there is nothing to do) or a negative nixie_err code; nixie_shim_evict
  * returns NIXIE_EBUSY while the application is capturing a stream. */

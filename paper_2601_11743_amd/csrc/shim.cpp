@@ -19,6 +19,8 @@
 
 #include <algorithm>
 #include <atomic>
+#include <chrono>
+#include <condition_variable>
 #include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
@@ -76,9 +78,15 @@ uint64_t env_u64(const char *name, uint64_t dflt) {
 }
 
 struct Alloc {
-    uint64_t bytes = 0;    // as the application asked
-    uint64_t blocks = 0;   // what it occupies
-    void *host = nullptr;  // pageable copy while evicted (exactly one copy: freed on restore)
+    uint64_t bytes = 0;      // as the application asked
+    uint64_t blocks = 0;     // what it occupies
+    void *host = nullptr;    // the pageable copy while evicted (exactly one copy of the bytes at any time), else null
+    // The mapping behind `host` is kept from one eviction to the next: after a restore its pages are
+    // handed back lazily (MADV_FREE: the kernel may take them when it needs memory), so the next
+    // eviction usually finds them still there and pays neither page faults nor zeroing -- with fresh
+    // memory every time those cost three times what the transfer itself does.
+    void *backing = nullptr;
+    uint64_t unmapped = 0;   // leading blocks whose physical memory has been taken away since the last eviction
 };
 
 struct Shim {
@@ -109,6 +117,17 @@ struct Shim {
     std::atomic<int> captures{0};
     std::thread watcher;
     std::atomic<bool> quit{false};
+
+    // Unmapping costs a driver call per block (0.25 ms each on MI355X) and nobody waits for it: the
+    // evicted application cannot run, and whoever gets the physical blocks maps them at addresses of
+    // its own.  It is done by this thread after the eviction, a few blocks at a time; an application
+    // that comes back first simply keeps what is still mapped.
+    bool sync_unmap = false;
+    std::atomic<int> wanted_back{0};   // threads waiting to bring the application back: the background work gives way to them
+    std::thread reaper;
+    std::mutex reap_mu;
+    std::condition_variable reap_cv;
+    bool reap_pending = false;
 };
 
 Shim *g = nullptr;
@@ -142,6 +161,53 @@ void watch_idleness(Shim *s) {
     }
 }
 
+// Unmap up to `budget` blocks of evicted allocations; returns how many.  Gate held exclusively, mu held.
+uint64_t unmap_some(Shim &s, uint64_t budget) {
+    uint64_t done = 0;
+    for (auto &kv : s.table) {
+        Alloc &a = kv.second;
+        if (a.unmapped >= a.blocks) continue;
+        const uint64_t n = std::min(budget - done, a.blocks - a.unmapped);
+        const int u = nixie_space_unmap(s.space, kv.first - s.base + a.unmapped * s.block, n * s.block);
+        if (u == NIXIE_EBUSY) break;            // a switch of somebody else's is running: later
+        if (u)   // a block the driver refuses to unmap stays reserved until the restore maps over whatever state it finds
+            std::fprintf(stderr, "nixie-shim: some blocks could not be unmapped (%s)\n", nixie_strerror(u));
+        a.unmapped += n;
+        done += n;
+        if (done >= budget) break;
+    }
+    return done;
+}
+
+void reap_unmapped(Shim *s) {
+    for (;;) {
+        {
+            std::unique_lock<std::mutex> lk(s->reap_mu);
+            s->reap_cv.wait(lk, [&] { return s->quit.load() || s->reap_pending; });
+            if (s->quit.load()) return;
+            s->reap_pending = false;
+        }
+        const uint64_t t0 = now_ns();
+        uint64_t total = 0;
+        bool came_back = false;
+        for (;;) {
+            // (the lock has no queue: without this the loop could take it again and again ahead of a waiting restore)
+            while (s->wanted_back.load() > 0 && !s->quit.load()) std::this_thread::sleep_for(std::chrono::microseconds(50));
+            std::unique_lock<std::shared_mutex> hold(s->gate);   // short slices: a launch that wants the application back waits 4 ms at most
+            if (s->quit.load()) return;
+            if (s->resident.load()) { came_back = true; break; }
+            Inside in;
+            std::lock_guard<std::mutex> lk(s->mu);
+            const uint64_t n = unmap_some(*s, 16);
+            total += n;
+            if (n == 0) break;
+        }
+        if (total || came_back)
+            say("unmapped %llu blocks in the background in %.3f ms%s", (unsigned long long)total, (now_ns() - t0) / 1e6,
+                came_back ? "; the application came back first and keeps the rest" : "");
+    }
+}
+
 void init_once() {
     static Shim shim;
     Inside in;
@@ -152,6 +218,7 @@ void init_once() {
     s.idle_ns = env_u64("NIXIE_SHIM_IDLE_MS", 0) * 1000000ull;
     s.scribble = env_u64("NIXIE_SHIM_SCRIBBLE", 0) != 0;
     s.log = env_u64("NIXIE_SHIM_LOG", 0) != 0;
+    s.sync_unmap = env_u64("NIXIE_SHIM_SYNC_UNMAP", 0) != 0;
     g = &s;
     if (nixie_abi_check(sizeof(nixie_opts_t), sizeof(nixie_plan_info_t), sizeof(nixie_stats_t)) != NIXIE_OK) {
         std::fprintf(stderr, "nixie-shim: libnixie.so is of another version than this shim; allocations pass through\n");
@@ -178,10 +245,16 @@ void init_once() {
     say("managing %llu MiB in %llu MiB blocks at %p, allocations from %llu bytes", (unsigned long long)(s.capacity >> 20),
         (unsigned long long)(s.block >> 20), base, (unsigned long long)s.min_bytes);
     if (s.idle_ns) s.watcher = std::thread(watch_idleness, &s);
+    if (!s.sync_unmap) s.reaper = std::thread(reap_unmapped, &s);
     std::atexit([] {
         if (!g) return;
-        g->quit.store(true);
+        {
+            std::lock_guard<std::mutex> lk(g->reap_mu);
+            g->quit.store(true);
+        }
+        g->reap_cv.notify_all();
         if (g->watcher.joinable()) g->watcher.join();
+        if (g->reaper.joinable()) g->reaper.join();
     });
 }
 
@@ -212,7 +285,6 @@ int run_switch(Shim &s, const std::vector<nixie_alloc_t> &out, const std::vector
     nixie_stats_t st{};
     rc = nixie_switch(plan, nullptr, &st);
     nixie_plan_destroy(plan);
-    s.last_switch_ns.store(st.ns_total);
     return rc;
 }
 
@@ -222,36 +294,32 @@ int evict_locked(Shim &s) {
     if (s.captures.load() > 0) return NIXIE_EBUSY;   // paper, "CUDA graph compatibility": hands off until the capture ends
     std::lock_guard<std::mutex> lk(s.mu);
     if (s.table.empty()) return NIXIE_OK;   // nothing of the application's is managed: nothing to take away
+    const uint64_t t_begin = now_ns();
     if (REAL(hipDeviceSynchronize)() != hipSuccess) return NIXIE_EHIP;   // nothing of the application's is running any more
+    const uint64_t t_quiet = now_ns();
     uint64_t bytes = 0;
+    auto give_up = [&]() {   // the application stays resident, its bytes are still in HBM
+        for (auto &u : s.table) u.second.host = nullptr;
+    };
     for (auto &kv : s.table) {
         Alloc &a = kv.second;
-        a.host = mmap(nullptr, a.bytes, PROT_READ | PROT_WRITE, MAP_PRIVATE | MAP_ANONYMOUS, -1, 0);
-        if (a.host == MAP_FAILED) {
-            a.host = nullptr;
-            for (auto &u : s.table)
-                if (u.second.host) { munmap(u.second.host, u.second.bytes); u.second.host = nullptr; }
-            return NIXIE_ENOMEM;
+        if (!a.backing) {
+            void *m = mmap(nullptr, a.bytes, PROT_READ | PROT_WRITE, MAP_PRIVATE | MAP_ANONYMOUS, -1, 0);
+            if (m == MAP_FAILED) { give_up(); return NIXIE_ENOMEM; }
+            (void)madvise(m, a.bytes, MADV_HUGEPAGE);   // fewer, larger faults the first time, where the kernel offers them
+            a.backing = m;
         }
+        a.host = a.backing;
         bytes += a.bytes;
     }
     int rc = run_switch(s, rows_with_host_copy(s), {});
-    if (rc) {            // the application stays resident, its bytes are still in HBM
-        for (auto &u : s.table)
-            if (u.second.host) { munmap(u.second.host, u.second.bytes); u.second.host = nullptr; }
-        return rc;
-    }
-    // From here on the host copies are the application's memory.  A block whose unmapping the driver
-    // refuses stays reserved (nobody else can be given it) until the restore, which maps over whatever
-    // state it finds; the eviction itself has happened.
-    int refused = NIXIE_OK;
-    for (auto &kv : s.table) {
-        const int u = nixie_space_unmap(s.space, kv.first - s.base, kv.second.blocks * s.block);
-        if (u && !refused) refused = u;
-    }
-    if (refused)
-        std::fprintf(stderr, "nixie-shim: some blocks could not be unmapped (%s); they stay reserved until the restore\n",
-                     nixie_strerror(refused));
+    if (rc) { give_up(); return rc; }
+    const uint64_t t_moved = now_ns();
+    // From here on the host copies are the application's memory; its blocks are unmapped behind its back.
+    for (auto &kv : s.table) kv.second.unmapped = 0;
+    if (s.sync_unmap)
+        while (unmap_some(s, ~0ull)) {}
+    const uint64_t t_end = now_ns();
     if (s.scribble) {
         // what another application would do with the physical memory meanwhile
         nixie_space_t *other = nullptr;
@@ -266,7 +334,17 @@ int evict_locked(Shim &s) {
     }
     s.resident.store(false);
     s.evictions++;
-    say("evicted %zu allocations, %llu bytes, in %.3f ms", s.table.size(), (unsigned long long)bytes, s.last_switch_ns.load() / 1e6);
+    s.last_switch_ns.store(t_end - t_begin);
+    say("evicted %zu allocations, %llu bytes, in %.3f ms (waiting for the device %.3f, swap %.3f, unmapping %.3f%s)", s.table.size(),
+        (unsigned long long)bytes, (t_end - t_begin) / 1e6, (t_quiet - t_begin) / 1e6, (t_moved - t_quiet) / 1e6,
+        (t_end - t_moved) / 1e6, s.sync_unmap ? "" : ": left to the background");
+    if (!s.sync_unmap) {
+        {
+            std::lock_guard<std::mutex> lk(s.reap_mu);
+            s.reap_pending = true;
+        }
+        s.reap_cv.notify_one();
+    }
     return NIXIE_OK;
 }
 
@@ -274,21 +352,31 @@ int restore_locked(Shim &s) {
     if (s.resident.load()) return NIXIE_OK;
     std::lock_guard<std::mutex> lk(s.mu);
     int rc = NIXIE_OK;
+    const uint64_t t_begin = now_ns();
     for (auto &kv : s.table)
         if ((rc = nixie_space_map(s.space, kv.first - s.base, kv.second.blocks * s.block)) != 0) return rc;
+    const uint64_t t_mapped = now_ns();
     const std::vector<nixie_alloc_t> rows = rows_with_host_copy(s);   // allocations made while evicted have nothing to bring back
     rc = run_switch(s, {}, rows);
     if (rc) return rc;
     uint64_t bytes = 0;
-    for (auto &kv : s.table)
-        if (kv.second.host) {
-            munmap(kv.second.host, kv.second.bytes);
-            kv.second.host = nullptr;
-            bytes += kv.second.bytes;
+    for (auto &kv : s.table) {
+        Alloc &a = kv.second;
+        a.unmapped = 0;
+        if (!a.host) continue;
+        a.host = nullptr;                                        // one copy: the bytes are in HBM again
+        if (madvise(a.backing, a.bytes, MADV_FREE) != 0) {       // no lazy release on this kernel: give the memory back now
+            munmap(a.backing, a.bytes);
+            a.backing = nullptr;
         }
+        bytes += a.bytes;
+    }
     s.resident.store(true);
     s.restores++;
-    say("restored %zu allocations, %llu bytes, in %.3f ms", rows.size(), (unsigned long long)bytes, s.last_switch_ns.load() / 1e6);
+    const uint64_t t_end = now_ns();
+    s.last_switch_ns.store(t_end - t_begin);
+    say("restored %zu allocations, %llu bytes, in %.3f ms (mapping %.3f, swap and release of the host copies %.3f)", rows.size(),
+        (unsigned long long)bytes, (t_end - t_begin) / 1e6, (t_mapped - t_begin) / 1e6, (t_end - t_mapped) / 1e6);
     return NIXIE_OK;
 }
 
@@ -305,7 +393,9 @@ struct Running {
             hold.unlock();
             s->launches_held++;
             {
+                s->wanted_back++;
                 std::unique_lock<std::shared_mutex> x(s->gate);
+                s->wanted_back--;
                 Inside in;
                 const int rc = restore_locked(*s);
                 if (rc) {
@@ -346,7 +436,11 @@ hipError_t hipMalloc(void **ptr, size_t size) {
         (!s->resident.load() || nixie_space_map(s->space, first * s->block, need * s->block) == NIXIE_OK)) {
         s->free_runs.take(first, need);
         const uint64_t addr = s->base + first * s->block;
-        s->table[addr] = Alloc{size, need, nullptr};
+        Alloc fresh;
+        fresh.bytes = size;
+        fresh.blocks = need;
+        fresh.unmapped = s->resident.load() ? 0 : need;   // made while evicted: nothing behind it yet
+        s->table[addr] = fresh;
         s->managed_bytes += need * s->block;
         *ptr = (void *)(uintptr_t)addr;
         s->last_return.store(now_ns());
@@ -370,9 +464,10 @@ hipError_t hipFree(void *ptr) {
                 lk.unlock();
                 (void)REAL(hipDeviceSynchronize)();   // as the runtime's hipFree does: nothing may still use it
                 lk.lock();
-                (void)nixie_space_unmap(s->space, it->first - s->base, a.blocks * s->block);
             }
-            if (a.host) munmap(a.host, a.bytes);
+            // (of an evicted application some blocks may still be mapped: the background has not got to them)
+            (void)nixie_space_unmap(s->space, it->first - s->base, a.blocks * s->block);
+            if (a.backing) munmap(a.backing, a.bytes);
             const uint64_t first = (it->first - s->base) / s->block;
             s->table.erase(it);
             s->managed_bytes -= a.blocks * s->block;
@@ -581,7 +676,9 @@ int nixie_shim_evict(void) {
 int nixie_shim_restore(void) {
     Shim *s = shim();
     if (!s) return NIXIE_EINVAL;
+    s->wanted_back++;
     std::unique_lock<std::shared_mutex> hold(s->gate);
+    s->wanted_back--;
     Inside in;
     return restore_locked(*s);
 }

@@ -164,3 +164,23 @@ def test_threads_launching_while_evictions_come_in(run_program):
 def test_threads_mode_without_the_shim_is_the_plain_program(run_program):
     r = run_program([APP, "3", "24", "4", "threads"], timeout=90)
     assert r["rc"] == 0 and "RESULT ok" in r["stdout"], r
+
+
+def test_gigabyte_application_is_evicted_at_link_rate(run_program):
+    """1.3 GiB in three large buffers, idle eviction: from the second eviction on the host copies' pages are
+    there already, the blocks are unmapped in the background (685 driver calls nobody waits for), and what
+    the application waits for when it wakes up is mapping plus the transfer."""
+    print("shim_app under LD_PRELOAD, 1.3 GiB, idle eviction", flush=True)
+    env = preload_env(NIXIE_SHIM_IDLE_MS=100, NIXIE_SHIM_LOG=1, NIXIE_SHIM_POOL_MIB=2048, NIXIE_SHIM_RING_MIB=64)
+    r = run_program([APP, "700", "1024", "3"], env=env, timeout=120)
+    assert r["rc"] == 0 and "RESULT ok" in r["stdout"], r
+    log = r["stderr"]
+    ev = [(int(b), float(ms)) for b, ms in re.findall(r"evicted \d+ allocations, (\d+) bytes, in ([\d.]+) ms", log)]
+    re_ = [(int(b), float(ms)) for b, ms in re.findall(r"restored \d+ allocations, (\d+) bytes, in ([\d.]+) ms", log)]
+    bg = [int(n) for n in re.findall(r"unmapped (\d+) blocks in the background", log)]
+    assert len(ev) == 3 and len(re_) == 3, log
+    assert all(b > 1.3 * 2**30 for b, _ in ev)
+    # the one-direction link rate is about 57 GB/s; a third of it is asked for, from the second eviction on
+    assert all(b / (ms * 1e6) > 19 for b, ms in ev[1:]), ev
+    assert all(b / (ms * 1e6) > 12 for b, ms in re_), re_        # includes mapping 685 blocks again
+    assert sum(bg) >= 2 * 685, log                                # nobody waited for these

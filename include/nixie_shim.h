@@ -31,7 +31,9 @@
  *                    (first fit), entered in the application's allocation table; smaller ones go
  *                    to the runtime unchanged (the paper leaves allocations under one block to the
  *                    plain allocator).  hipErrorOutOfMemory when the space is full.
- *   hipFree          releases such a range (and its host copy, if the application is evicted).
+ *   hipFree          releases such a range (and its host copy, if the application is evicted).  The
+ *                    range's blocks stay mapped for the next allocation at these addresses (an
+ *                    eviction unmaps them): a use after free is not caught by a fault.
  *   hipMemGetInfo    total = the capacity the shim was given, free = total - the application's
  *                    own managed allocations (in whole blocks).
  *   hipLaunchKernel, hipLaunchKernelExC, hipLaunchCooperativeKernel, hipModuleLaunchKernel,

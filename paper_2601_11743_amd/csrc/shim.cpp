@@ -86,7 +86,6 @@ struct Alloc {
     // eviction usually finds them still there and pays neither page faults nor zeroing -- with fresh
     // memory every time those cost three times what the transfer itself does.
     void *backing = nullptr;
-    uint64_t unmapped = 0;   // leading blocks whose physical memory has been taken away since the last eviction
 };
 
 struct Shim {
@@ -104,6 +103,12 @@ struct Shim {
     std::mutex mu;
     std::map<uint64_t, Alloc> table;          // by device address
     nixie::BlockRuns free_runs;               // blocks of the space that no allocation holds
+    // Which blocks of the space have physical memory mapped behind them.  A block is mapped when an
+    // allocation first covers it and stays mapped when that allocation is freed (every block of the space
+    // has its own physical block, so nothing is gained by taking it away, and the next allocation there
+    // costs no driver call); only an eviction unmaps, everything, in the background, from block 0 up.
+    std::vector<uint8_t> mapped;
+    uint64_t reap_cursor = 0;                 // blocks below it have been dealt with since the last eviction
     uint64_t managed_bytes = 0, passthrough = 0;
     std::atomic<bool> resident{true};
     std::atomic<uint32_t> evictions{0}, restores{0};
@@ -161,22 +166,32 @@ void watch_idleness(Shim *s) {
     }
 }
 
-// Unmap up to `budget` blocks of evicted allocations; returns how many.  Gate held exclusively, mu held.
+// Unmap the next run of mapped blocks, `budget` at most; returns how many (0: none left).  Gate held
+// exclusively, mu held.
 uint64_t unmap_some(Shim &s, uint64_t budget) {
-    uint64_t done = 0;
-    for (auto &kv : s.table) {
-        Alloc &a = kv.second;
-        if (a.unmapped >= a.blocks) continue;
-        const uint64_t n = std::min(budget - done, a.blocks - a.unmapped);
-        const int u = nixie_space_unmap(s.space, kv.first - s.base + a.unmapped * s.block, n * s.block);
-        if (u == NIXIE_EBUSY) break;            // a switch of somebody else's is running: later
-        if (u)   // a block the driver refuses to unmap stays reserved until the restore maps over whatever state it finds
-            std::fprintf(stderr, "nixie-shim: some blocks could not be unmapped (%s)\n", nixie_strerror(u));
-        a.unmapped += n;
-        done += n;
-        if (done >= budget) break;
-    }
-    return done;
+    const uint64_t n_blocks = s.mapped.size();
+    while (s.reap_cursor < n_blocks && !s.mapped[s.reap_cursor]) s.reap_cursor++;
+    uint64_t n = 0;
+    while (s.reap_cursor + n < n_blocks && n < budget && s.mapped[s.reap_cursor + n]) n++;
+    if (n == 0) return 0;
+    const int u = nixie_space_unmap(s.space, s.reap_cursor * s.block, n * s.block);
+    if (u == NIXIE_EBUSY) return 0;   // a switch of somebody else's is running: the next eviction starts over
+    if (u)   // a block the driver refuses to unmap stays reserved until a restore maps over whatever state it finds
+        std::fprintf(stderr, "nixie-shim: some blocks could not be unmapped (%s)\n", nixie_strerror(u));
+    for (uint64_t b = 0; b < n; b++) s.mapped[s.reap_cursor + b] = 0;
+    s.reap_cursor += n;
+    return n;
+}
+
+// Map the blocks of one allocation that are not mapped yet.  mu held.
+int map_range(Shim &s, uint64_t first, uint64_t count) {
+    bool all = true;
+    for (uint64_t b = first; b < first + count; b++) all = all && s.mapped[b];
+    if (all) return NIXIE_OK;
+    const int rc = nixie_space_map(s.space, first * s.block, count * s.block);   // skips what is mapped already
+    if (rc == NIXIE_OK)
+        for (uint64_t b = first; b < first + count; b++) s.mapped[b] = 1;
+    return rc;
 }
 
 void reap_unmapped(Shim *s) {
@@ -240,6 +255,7 @@ void init_once() {
     s.base = (uint64_t)(uintptr_t)base;
     s.min_bytes = env_u64("NIXIE_SHIM_MIN_BYTES", s.block);
     s.free_runs = nixie::BlockRuns(s.capacity / s.block);
+    s.mapped.assign(s.capacity / s.block, 0);
     s.last_return.store(now_ns());
     s.ok = true;
     say("managing %llu MiB in %llu MiB blocks at %p, allocations from %llu bytes", (unsigned long long)(s.capacity >> 20),
@@ -316,7 +332,7 @@ int evict_locked(Shim &s) {
     if (rc) { give_up(); return rc; }
     const uint64_t t_moved = now_ns();
     // From here on the host copies are the application's memory; its blocks are unmapped behind its back.
-    for (auto &kv : s.table) kv.second.unmapped = 0;
+    s.reap_cursor = 0;
     if (s.sync_unmap)
         while (unmap_some(s, ~0ull)) {}
     const uint64_t t_end = now_ns();
@@ -354,7 +370,7 @@ int restore_locked(Shim &s) {
     int rc = NIXIE_OK;
     const uint64_t t_begin = now_ns();
     for (auto &kv : s.table)
-        if ((rc = nixie_space_map(s.space, kv.first - s.base, kv.second.blocks * s.block)) != 0) return rc;
+        if ((rc = map_range(s, (kv.first - s.base) / s.block, kv.second.blocks)) != 0) return rc;
     const uint64_t t_mapped = now_ns();
     const std::vector<nixie_alloc_t> rows = rows_with_host_copy(s);   // allocations made while evicted have nothing to bring back
     rc = run_switch(s, {}, rows);
@@ -362,7 +378,6 @@ int restore_locked(Shim &s) {
     uint64_t bytes = 0;
     for (auto &kv : s.table) {
         Alloc &a = kv.second;
-        a.unmapped = 0;
         if (!a.host) continue;
         a.host = nullptr;                                        // one copy: the bytes are in HBM again
         if (madvise(a.backing, a.bytes, MADV_FREE) != 0) {       // no lazy release on this kernel: give the memory back now
@@ -432,14 +447,12 @@ hipError_t hipMalloc(void **ptr, size_t size) {
     const uint64_t need = (size + s->block - 1) / s->block;
     const uint64_t first = s->free_runs.find(need);
     // an evicted application's new memory gets its physical blocks when the application comes back
-    if (first != nixie::BlockRuns::kNone &&
-        (!s->resident.load() || nixie_space_map(s->space, first * s->block, need * s->block) == NIXIE_OK)) {
+    if (first != nixie::BlockRuns::kNone && (!s->resident.load() || map_range(*s, first, need) == NIXIE_OK)) {
         s->free_runs.take(first, need);
         const uint64_t addr = s->base + first * s->block;
         Alloc fresh;
         fresh.bytes = size;
         fresh.blocks = need;
-        fresh.unmapped = s->resident.load() ? 0 : need;   // made while evicted: nothing behind it yet
         s->table[addr] = fresh;
         s->managed_bytes += need * s->block;
         *ptr = (void *)(uintptr_t)addr;
@@ -465,8 +478,7 @@ hipError_t hipFree(void *ptr) {
                 (void)REAL(hipDeviceSynchronize)();   // as the runtime's hipFree does: nothing may still use it
                 lk.lock();
             }
-            // (of an evicted application some blocks may still be mapped: the background has not got to them)
-            (void)nixie_space_unmap(s->space, it->first - s->base, a.blocks * s->block);
+            // (its blocks stay mapped for whoever is given these addresses next; an eviction takes them away)
             if (a.backing) munmap(a.backing, a.bytes);
             const uint64_t first = (it->first - s->base) / s->block;
             s->table.erase(it);

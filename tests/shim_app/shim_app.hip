@@ -18,7 +18,11 @@
 // buffers `rounds` x 50 times while the main thread asks for an eviction every pause_ms: launches
 // and waits of several threads meet migrations at arbitrary points.
 //
-// usage: shim_app <pause_ms> <big_mib> [rounds] [idle|explicit|graph|threads]
+// With mode "overhead" it measures what the paper's "Runtime Overheads" and "Memory Overheads" measure:
+// the time of a small kernel launch (asynchronous, and with a wait after each) and of an allocation
+// followed by a fill and a free, by size.  Run once alone and once under the shim.
+//
+// usage: shim_app <pause_ms> <big_mib> [rounds] [idle|explicit|graph|threads|overhead]
 #include <hip/hip_runtime.h>
 #include <dlfcn.h>
 
@@ -26,6 +30,7 @@
 #include <cstdint>
 #include <cstdio>
 #include <cstdlib>
+#include <algorithm>
 #include <atomic>
 #include <cstring>
 #include <thread>
@@ -61,6 +66,57 @@ __global__ void check(const uint32_t *p, uint64_t n, uint32_t seed, uint32_t bum
     for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (uint64_t)gridDim.x * blockDim.x)
         mine += p[i] != pattern(seed, i) + bumps;
     if (mine) atomicAdd(bad, mine);
+}
+
+__global__ void tiny(uint32_t *p) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) p[0] += 1;
+}
+
+// mode "overhead"
+int run_overhead(uint64_t big) {
+    using clk = std::chrono::steady_clock;
+    auto us = [](clk::time_point a, clk::time_point b) { return std::chrono::duration<double, std::micro>(b - a).count(); };
+    uint32_t *buf = nullptr;
+    CHECK(hipMalloc((void **)&buf, big));            // a managed allocation for the kernels to touch
+    CHECK(hipMemset(buf, 0, 4096));
+    for (int i = 0; i < 2000; i++) tiny<<<1, 64>>>(buf);
+    CHECK(hipDeviceSynchronize());
+    const int n = 20000;
+    auto t0 = clk::now();
+    for (int i = 0; i < n; i++) tiny<<<1, 64>>>(buf);
+    auto t1 = clk::now();
+    CHECK(hipDeviceSynchronize());
+    auto t2 = clk::now();
+    std::printf("launch: %.3f us per asynchronous launch, %.3f us per kernel with the queue draining\n", us(t0, t1) / n, us(t0, t2) / n);
+    t0 = clk::now();
+    for (int i = 0; i < n / 4; i++) { tiny<<<1, 64>>>(buf); CHECK(hipDeviceSynchronize()); }
+    t1 = clk::now();
+    std::printf("launch+wait: %.3f us\n", us(t0, t1) / (n / 4));
+    uint32_t count = 0;
+    CHECK(hipMemcpy(&count, buf, 4, hipMemcpyDeviceToHost));
+    const uint64_t sizes[] = {64ull << 10, 1ull << 20, 2ull << 20, 16ull << 20, 128ull << 20, 512ull << 20};
+    for (uint64_t sz : sizes) {
+        double best_alloc = 1e30, best_free = 1e30, first_alloc = 0, first_free = 0;
+        for (int rep = 0; rep < 5; rep++) {
+            void *p = nullptr;
+            t0 = clk::now();
+            CHECK(hipMalloc(&p, sz));
+            CHECK(hipMemset(p, 1, sz));              // as the paper does: takes lazy initialisation out of the comparison
+            CHECK(hipDeviceSynchronize());
+            t1 = clk::now();
+            CHECK(hipFree(p));
+            t2 = clk::now();
+            best_alloc = std::min(best_alloc, us(t0, t1));
+            best_free = std::min(best_free, us(t1, t2));
+            if (rep == 0) { first_alloc = us(t0, t1); first_free = us(t1, t2); }
+        }
+        std::printf("malloc+fill %llu KiB: first %.1f us, best of 5 %.1f us; free: first %.1f us, best %.1f us\n",
+                    (unsigned long long)(sz >> 10), first_alloc, best_alloc, first_free, best_free);
+    }
+    CHECK(hipFree(buf));
+    const bool good = count == 2000u + n + n / 4;
+    std::printf(good ? "RESULT ok 0\n" : "RESULT wrong 1\n");
+    return good ? 0 : 1;
 }
 
 // mode "threads"; returns the process's exit code
@@ -121,6 +177,7 @@ int main(int argc, char **argv) {
     using evict_fn = int (*)(void);
     const evict_fn evict = explicit_mode ? (evict_fn)dlsym(RTLD_DEFAULT, "nixie_shim_evict") : nullptr;
     if (threads_mode) return run_threads(pause_ms, big, rounds * 50, evict);
+    if (argc > 4 && std::strcmp(argv[4], "overhead") == 0) return run_overhead(big);
     size_t free0 = 0, total0 = 0;
     CHECK(hipMemGetInfo(&free0, &total0));
     // a few buffers of mixed sizes: three large ones and two small ones

@@ -184,3 +184,18 @@ def test_gigabyte_application_is_evicted_at_link_rate(run_program):
     assert all(b / (ms * 1e6) > 19 for b, ms in ev[1:]), ev
     assert all(b / (ms * 1e6) > 12 for b, ms in re_), re_        # includes mapping 685 blocks again
     assert sum(bg) >= 2 * 685, log                                # nobody waited for these
+
+
+def test_overheads_of_launch_and_allocation(run_program):
+    """Paper, "Runtime Overheads" / "Memory Overheads": a resident application's launches go straight to the
+    runtime (one flag check and a shared lock on the way), allocations below one block are the runtime's
+    own.  The figures are printed for the record; asserted is only that a launch costs no more than a few
+    microseconds extra."""
+    plain = run_program([APP, "0", "64", "1", "overhead"], timeout=120)
+    assert plain["rc"] == 0 and "RESULT ok" in plain["stdout"], plain
+    env = preload_env(NIXIE_SHIM_POOL_MIB=2048)
+    under = run_program([APP, "0", "64", "1", "overhead"], env=env, timeout=120)
+    assert under["rc"] == 0 and "RESULT ok" in under["stdout"], under
+    print("without the shim:\n" + plain["stdout"] + "under the shim:\n" + under["stdout"], flush=True)
+    get = lambda out: float(re.search(r"launch: ([\d.]+) us per asynchronous launch", out).group(1))
+    assert get(under["stdout"]) < get(plain["stdout"]) + 3.0

@@ -27,7 +27,7 @@
  * Use:  LD_PRELOAD=/path/to/libnixie_shim.so  ./application      (set before the process starts)
  *
  * Interposed runtime calls (same prototypes as the HIP runtime's; everything else passes through):
- *   hipMalloc        size >= NIXIE_SHIM_MIN_BYTES: whole blocks of the shim's address space
+ *   hipMalloc        size >= NIXIE_SHIM_MIN_BYTES: whole units of the shim's address space
  *                    (first fit), entered in the application's allocation table; smaller ones go
  *                    to the runtime unchanged (the paper leaves allocations under one block to the
  *                    plain allocator).  hipErrorOutOfMemory when the space is full.
@@ -35,7 +35,7 @@
  *                    range's blocks stay mapped for the next allocation at these addresses (an
  *                    eviction unmaps them): a use after free is not caught by a fault.
  *   hipMemGetInfo    total = the capacity the shim was given, free = total - the application's
- *                    own managed allocations (in whole blocks).
+ *                    own managed allocations (in whole units).
  *   hipLaunchKernel, hipLaunchKernelExC, hipLaunchCooperativeKernel, hipModuleLaunchKernel,
  *   hipModuleLaunchCooperativeKernel, hipExtModuleLaunchKernel, hipGraphLaunch
  *                    check the execution flag; restore the application first if it is evicted.
@@ -66,9 +66,11 @@
  *
  * Environment (read once, at the first interposed call):
  *   NIXIE_SHIM_POOL_MIB     capacity of the managed GPU memory, MiB (default 1024)
- *   NIXIE_SHIM_BLOCK_MIB    block size, MiB (default 2: the paper's block; must suit the device's
- *                           allocation granularity)
- *   NIXIE_SHIM_MIN_BYTES    smallest managed allocation (default: one block)
+ *   NIXIE_SHIM_UNIT_MIB     allocation granularity, MiB (default 2: the paper's block)
+ *   NIXIE_SHIM_BLOCK_MIB    what the driver maps and unmaps at a time, MiB: a multiple of the unit that
+ *                           suits the device's allocation granularity (default 32; a driver call per
+ *                           block is on the way of an application that comes back, 0.03-0.05 ms each)
+ *   NIXIE_SHIM_MIN_BYTES    smallest managed allocation (default: one unit)
  *   NIXIE_SHIM_RING_MIB     pinned staging ring of the swap, MiB (default 64)
  *   NIXIE_SHIM_IDLE_MS      > 0: a watcher thread evicts the application once it has been idle
  *                           this long (default 0 = never; the paper's threshold is 100)
@@ -94,8 +96,9 @@ extern "C" {
 
 typedef struct {
     uint64_t capacity_bytes;    /* managed GPU memory                                     */
-    uint64_t block_bytes;
-    uint64_t managed_bytes;     /* live managed allocations, in whole blocks              */
+    uint64_t block_bytes;       /* what is mapped and unmapped at a time                  */
+    uint64_t unit_bytes;        /* what allocations are rounded to                        */
+    uint64_t managed_bytes;     /* live managed allocations, in whole units               */
     uint64_t managed_allocs;
     uint64_t passthrough_allocs;/* live allocations below the threshold                   */
     uint32_t resident;          /* the execution flag: 1 = the application's memory is in HBM */

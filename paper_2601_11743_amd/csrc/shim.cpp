@@ -79,7 +79,7 @@ uint64_t env_u64(const char *name, uint64_t dflt) {
 
 struct Alloc {
     uint64_t bytes = 0;      // as the application asked
-    uint64_t blocks = 0;     // what it occupies
+    uint64_t units = 0;      // what it occupies, in allocation units
     void *host = nullptr;    // the pageable copy while evicted (exactly one copy of the bytes at any time), else null
     // The mapping behind `host` is kept from one eviction to the next: after a restore its pages are
     // handed back lazily (MADV_FREE: the kernel may take them when it needs memory), so the next
@@ -90,7 +90,11 @@ struct Alloc {
 
 struct Shim {
     bool ok = false;
-    uint64_t capacity = 0, block = 0, min_bytes = 0, ring = 0, idle_ns = 0;
+    // Two granularities.  `unit` is what allocations are rounded to and the smallest managed allocation
+    // (the paper's 2 MB block).  `block` is what the driver maps and unmaps at a time: it costs 0.03 - 0.05 ms
+    // to map and 0.25 ms to unmap whatever its size, so it is larger (the paper, too, backs its 2 MB blocks
+    // with physical chunks of up to 128 MB), and neighbouring allocations share one.
+    uint64_t capacity = 0, unit = 0, block = 0, min_bytes = 0, ring = 0, idle_ns = 0;
     bool scribble = false, log = false;
     nixie_pool_t *pool = nullptr;
     nixie_space_t *space = nullptr;
@@ -102,7 +106,7 @@ struct Shim {
     std::shared_mutex gate;
     std::mutex mu;
     std::map<uint64_t, Alloc> table;          // by device address
-    nixie::BlockRuns free_runs;               // blocks of the space that no allocation holds
+    nixie::BlockRuns free_runs;               // units of the space that no allocation holds
     // Which blocks of the space have physical memory mapped behind them.  A block is mapped when an
     // allocation first covers it and stays mapped when that allocation is freed (every block of the space
     // has its own physical block, so nothing is gained by taking it away, and the next allocation there
@@ -183,8 +187,10 @@ uint64_t unmap_some(Shim &s, uint64_t budget) {
     return n;
 }
 
-// Map the blocks of one allocation that are not mapped yet.  mu held.
-int map_range(Shim &s, uint64_t first, uint64_t count) {
+// Map the blocks under units [first_unit, first_unit + n_units) that are not mapped yet.  mu held.
+int map_range(Shim &s, uint64_t first_unit, uint64_t n_units) {
+    const uint64_t first = first_unit * s.unit / s.block;
+    const uint64_t count = ((first_unit + n_units) * s.unit + s.block - 1) / s.block - first;
     bool all = true;
     for (uint64_t b = first; b < first + count; b++) all = all && s.mapped[b];
     if (all) return NIXIE_OK;
@@ -228,7 +234,13 @@ void init_once() {
     Inside in;
     Shim &s = shim;
     s.capacity = env_u64("NIXIE_SHIM_POOL_MIB", 1024) << 20;
-    s.block = env_u64("NIXIE_SHIM_BLOCK_MIB", 2) << 20;
+    s.unit = env_u64("NIXIE_SHIM_UNIT_MIB", 2) << 20;
+    s.block = env_u64("NIXIE_SHIM_BLOCK_MIB", 32) << 20;
+    if (s.unit == 0 || s.block % s.unit) {
+        std::fprintf(stderr, "nixie-shim: the block size must be a multiple of the unit; allocations pass through\n");
+        g = &s;
+        return;
+    }
     s.ring = env_u64("NIXIE_SHIM_RING_MIB", 64) << 20;
     s.idle_ns = env_u64("NIXIE_SHIM_IDLE_MS", 0) * 1000000ull;
     s.scribble = env_u64("NIXIE_SHIM_SCRIBBLE", 0) != 0;
@@ -246,6 +258,7 @@ void init_once() {
     }
     void *base = nullptr;
     if (!rc) rc = nixie_pool_info(s.pool, &s.capacity, &s.block);
+    if (!rc && s.block % s.unit) rc = NIXIE_EINVAL;
     if (!rc) rc = nixie_space_create(s.pool, &s.space, &base);
     if (rc) {
         std::fprintf(stderr, "nixie-shim: cannot set up %llu MiB of managed GPU memory (%s); allocations pass through\n",
@@ -253,13 +266,14 @@ void init_once() {
         return;
     }
     s.base = (uint64_t)(uintptr_t)base;
-    s.min_bytes = env_u64("NIXIE_SHIM_MIN_BYTES", s.block);
-    s.free_runs = nixie::BlockRuns(s.capacity / s.block);
+    s.min_bytes = env_u64("NIXIE_SHIM_MIN_BYTES", s.unit);
+    s.free_runs = nixie::BlockRuns(s.capacity / s.unit);
     s.mapped.assign(s.capacity / s.block, 0);
     s.last_return.store(now_ns());
     s.ok = true;
-    say("managing %llu MiB in %llu MiB blocks at %p, allocations from %llu bytes", (unsigned long long)(s.capacity >> 20),
-        (unsigned long long)(s.block >> 20), base, (unsigned long long)s.min_bytes);
+    say("managing %llu MiB in units of %llu MiB, mapped in blocks of %llu MiB, at %p, allocations from %llu bytes",
+        (unsigned long long)(s.capacity >> 20), (unsigned long long)(s.unit >> 20), (unsigned long long)(s.block >> 20), base,
+        (unsigned long long)s.min_bytes);
     if (s.idle_ns) s.watcher = std::thread(watch_idleness, &s);
     if (!s.sync_unmap) s.reaper = std::thread(reap_unmapped, &s);
     std::atexit([] {
@@ -370,7 +384,7 @@ int restore_locked(Shim &s) {
     int rc = NIXIE_OK;
     const uint64_t t_begin = now_ns();
     for (auto &kv : s.table)
-        if ((rc = map_range(s, (kv.first - s.base) / s.block, kv.second.blocks)) != 0) return rc;
+        if ((rc = map_range(s, (kv.first - s.base) / s.unit, kv.second.units)) != 0) return rc;
     const uint64_t t_mapped = now_ns();
     const std::vector<nixie_alloc_t> rows = rows_with_host_copy(s);   // allocations made while evicted have nothing to bring back
     rc = run_switch(s, {}, rows);
@@ -444,17 +458,17 @@ hipError_t hipMalloc(void **ptr, size_t size) {
     std::shared_lock<std::shared_mutex> hold(s->gate);   // not in the middle of a migration
     Inside in;
     std::lock_guard<std::mutex> lk(s->mu);
-    const uint64_t need = (size + s->block - 1) / s->block;
+    const uint64_t need = (size + s->unit - 1) / s->unit;
     const uint64_t first = s->free_runs.find(need);
     // an evicted application's new memory gets its physical blocks when the application comes back
     if (first != nixie::BlockRuns::kNone && (!s->resident.load() || map_range(*s, first, need) == NIXIE_OK)) {
         s->free_runs.take(first, need);
-        const uint64_t addr = s->base + first * s->block;
+        const uint64_t addr = s->base + first * s->unit;
         Alloc fresh;
         fresh.bytes = size;
-        fresh.blocks = need;
+        fresh.units = need;
         s->table[addr] = fresh;
-        s->managed_bytes += need * s->block;
+        s->managed_bytes += need * s->unit;
         *ptr = (void *)(uintptr_t)addr;
         s->last_return.store(now_ns());
         return hipSuccess;
@@ -480,10 +494,10 @@ hipError_t hipFree(void *ptr) {
             }
             // (its blocks stay mapped for whoever is given these addresses next; an eviction takes them away)
             if (a.backing) munmap(a.backing, a.bytes);
-            const uint64_t first = (it->first - s->base) / s->block;
+            const uint64_t first = (it->first - s->base) / s->unit;
             s->table.erase(it);
-            s->managed_bytes -= a.blocks * s->block;
-            s->free_runs.give(first, a.blocks);
+            s->managed_bytes -= a.units * s->unit;
+            s->free_runs.give(first, a.units);
             s->last_return.store(now_ns());
             return hipSuccess;
         }
@@ -666,6 +680,7 @@ int nixie_shim_info(nixie_shim_info_t *info) {
     std::lock_guard<std::mutex> lk(s.mu);
     info->capacity_bytes = s.capacity;
     info->block_bytes = s.block;
+    info->unit_bytes = s.unit;
     info->managed_bytes = s.managed_bytes;
     info->managed_allocs = s.table.size();
     info->passthrough_allocs = s.passthrough;

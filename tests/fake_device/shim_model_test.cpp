@@ -27,7 +27,7 @@
 
 namespace {
 
-constexpr uint64_t kWords = (4u << 20) / 4;   // a managed buffer: 4 MiB, two blocks
+constexpr uint64_t kWords = (4u << 20) / 4;   // a managed buffer: 4 MiB, two units
 
 // "kernels": three 64-bit arguments each
 void k_fill(uint64_t p, uint64_t n, uint64_t v) {
@@ -173,7 +173,8 @@ int main(int argc, char **argv) {
     const char *scenario = argc > 1 ? argv[1] : "threads";
     const int seed = argc > 2 ? std::atoi(argv[2]) : 1;
     setenv("NIXIE_SHIM_POOL_MIB", "32", 1);
-    setenv("NIXIE_SHIM_BLOCK_MIB", "2", 1);
+    setenv("NIXIE_SHIM_UNIT_MIB", "2", 1);
+    setenv("NIXIE_SHIM_BLOCK_MIB", "6", 1);    // three units to a block: allocations share blocks and straddle them
     setenv("NIXIE_SHIM_RING_MIB", "1", 1);
     setenv("NIXIE_SHIM_SCRIBBLE", "1", 1);
     if (!std::strcmp(scenario, "idle")) setenv("NIXIE_SHIM_IDLE_MS", "1", 1);

@@ -51,9 +51,12 @@ def test_idle_application_is_evicted_and_comes_back_at_the_same_addresses(run_pr
     r = run_program([APP, "600", "48", "3"], env=env, timeout=120)
     assert r["rc"] == 0 and "RESULT ok" in r["stdout"], r
     log = r["stderr"]
-    m = re.search(r"managing (\d+) MiB in (\d+) MiB blocks at (0x[0-9a-f]+), allocations from (\d+) bytes", log)
+    m = re.search(r"managing (\d+) MiB in units of (\d+) MiB, mapped in blocks of (\d+) MiB, at (0x[0-9a-f]+), "
+                  r"allocations from (\d+) bytes", log)
     assert m, log
-    cap, block, base = int(m.group(1)) * MiB, int(m.group(2)) * MiB, int(m.group(3), 16)
+    # (`block` below is the allocation unit: what addresses and the memory report are rounded to)
+    cap, block, base = int(m.group(1)) * MiB, int(m.group(2)) * MiB, int(m.group(4), 16)
+    assert int(m.group(3)) == 32 and int(m.group(2)) == 2
     info = parse(r["stdout"])
     assert info["rounds"] == [0, 0, 0]
     # three pauses -> three evictions, each undone by the first launch after it
@@ -168,7 +171,7 @@ def test_threads_mode_without_the_shim_is_the_plain_program(run_program):
 
 def test_gigabyte_application_is_evicted_at_link_rate(run_program):
     """1.3 GiB in three large buffers, idle eviction: from the second eviction on the host copies' pages are
-    there already, the blocks are unmapped in the background (685 driver calls nobody waits for), and what
+    there already, the blocks are unmapped in the background (driver calls nobody waits for), and what
     the application waits for when it wakes up is mapping plus the transfer."""
     print("shim_app under LD_PRELOAD, 1.3 GiB, idle eviction", flush=True)
     env = preload_env(NIXIE_SHIM_IDLE_MS=100, NIXIE_SHIM_LOG=1, NIXIE_SHIM_POOL_MIB=2048, NIXIE_SHIM_RING_MIB=64)
@@ -182,8 +185,8 @@ def test_gigabyte_application_is_evicted_at_link_rate(run_program):
     assert all(b > 1.3 * 2**30 for b, _ in ev)
     # the one-direction link rate is about 57 GB/s; a third of it is asked for, from the second eviction on
     assert all(b / (ms * 1e6) > 19 for b, ms in ev[1:]), ev
-    assert all(b / (ms * 1e6) > 12 for b, ms in re_), re_        # includes mapping 685 blocks again
-    assert sum(bg) >= 2 * 685, log                                # nobody waited for these
+    assert all(b / (ms * 1e6) > 12 for b, ms in re_), re_        # includes mapping the blocks again
+    assert sum(bg) >= 2 * 43, log                                 # 1372 MiB in 32 MiB blocks, at least twice: nobody waited for these
 
 
 def test_overheads_of_launch_and_allocation(run_program):

@@ -56,7 +56,8 @@
  *                    a call that allocates implicitly); they do not bring an evicted application back.
  * Interposed only to time the application's activity (idleness), bracketed as calls that may
  * block: hipDeviceSynchronize, hipStreamSynchronize, hipEventSynchronize (the calls above count as
- * activity too, for as long as they take).  They are not held back during a migration: a thread
+ * activity too, for as long as they take); and as plain signs of life the calls a program polls
+ * with or feeds a stream with: hipEventQuery, hipStreamQuery, hipEventRecord, hipStreamWaitEvent.  They are not held back during a migration: a thread
  * waiting for work that another thread has yet to submit must not block the migration that holds
  * that other thread back.
  * Not interposed: graphs built node by node are launched like any other (hipGraphLaunch) but their

@@ -644,6 +644,24 @@ NIXIE_NOT_DURING_MIGRATION(hipStreamCreate, (hipStream_t * stream), (stream))
 NIXIE_NOT_DURING_MIGRATION(hipStreamCreateWithFlags, (hipStream_t * stream, unsigned int flags), (stream, flags))
 NIXIE_NOT_DURING_MIGRATION(hipStreamDestroy, (hipStream_t stream), (stream))
 
+// Calls that neither block nor touch device memory, but with which an application polls or keeps a
+// stream busy: their return counts as a sign of life (paper, "Idleness Detection": idle = no runtime
+// call has returned for longer than the threshold), or a program that waits by polling would be evicted
+// in the middle of its work.
+#define NIXIE_SEEN(name, params, args)                          \
+    hipError_t name params {                                    \
+        using fn = hipError_t(*) params;                        \
+        static const fn real = next_symbol<fn>(#name);          \
+        const hipError_t e = real args;                         \
+        if (!t_inside)                                          \
+            if (Shim *s = shim()) s->last_return.store(now_ns()); \
+        return e;                                               \
+    }
+NIXIE_SEEN(hipEventQuery, (hipEvent_t event), (event))
+NIXIE_SEEN(hipStreamQuery, (hipStream_t stream), (stream))
+NIXIE_SEEN(hipEventRecord, (hipEvent_t event, hipStream_t stream), (event, stream))
+NIXIE_SEEN(hipStreamWaitEvent, (hipStream_t stream, hipEvent_t event, unsigned int flags), (stream, event, flags))
+
 // Blocking calls are bracketed so that an application waiting inside the runtime is not taken for idle.
 hipError_t hipDeviceSynchronize(void) {
     if (t_inside) return REAL(hipDeviceSynchronize)();

@@ -22,7 +22,10 @@
 // the time of a small kernel launch (asynchronous, and with a wait after each) and of an allocation
 // followed by a fill and a free, by size.  Run once alone and once under the shim.
 //
-// usage: shim_app <pause_ms> <big_mib> [rounds] [idle|explicit|graph|threads|overhead]
+// With mode "poll" it queues `rounds` x 100 ms of kernels and waits for them by polling hipStreamQuery:
+// busy all the time, but never inside a blocking call.
+//
+// usage: shim_app <pause_ms> <big_mib> [rounds] [idle|explicit|graph|threads|overhead|poll]
 #include <hip/hip_runtime.h>
 #include <dlfcn.h>
 
@@ -70,6 +73,32 @@ __global__ void check(const uint32_t *p, uint64_t n, uint32_t seed, uint32_t bum
 
 __global__ void tiny(uint32_t *p) {
     if (threadIdx.x == 0 && blockIdx.x == 0) p[0] += 1;
+}
+
+__global__ void spin(uint32_t *p, uint64_t ticks) {   // ticks of the 100 MHz wall clock; bounded by construction
+    const uint64_t t0 = wall_clock64();
+    while (wall_clock64() - t0 < ticks) __builtin_amdgcn_s_sleep(32);
+    if (threadIdx.x == 0) p[0] += 1;
+}
+
+// mode "poll"
+int run_poll(uint64_t big, int rounds) {
+    uint32_t *buf = nullptr;
+    CHECK(hipMalloc((void **)&buf, big));
+    CHECK(hipMemset(buf, 0, 4096));
+    const int n = rounds * 50;
+    for (int i = 0; i < n; i++) spin<<<1, 64>>>(buf, 200000);   // 2 ms each
+    CHECK(hipGetLastError());
+    uint64_t polls = 0;
+    hipError_t q;
+    while ((q = hipStreamQuery(nullptr)) == hipErrorNotReady) polls++;
+    CHECK(q);
+    uint32_t count = 0;
+    CHECK(hipMemcpy(&count, buf, 4, hipMemcpyDeviceToHost));
+    CHECK(hipFree(buf));
+    std::printf("polled %llu times, %u kernels done\n", (unsigned long long)polls, count);
+    std::printf(count == (uint32_t)n ? "RESULT ok 0\n" : "RESULT wrong 1\n");
+    return count == (uint32_t)n ? 0 : 1;
 }
 
 // mode "overhead"
@@ -178,6 +207,7 @@ int main(int argc, char **argv) {
     const evict_fn evict = explicit_mode ? (evict_fn)dlsym(RTLD_DEFAULT, "nixie_shim_evict") : nullptr;
     if (threads_mode) return run_threads(pause_ms, big, rounds * 50, evict);
     if (argc > 4 && std::strcmp(argv[4], "overhead") == 0) return run_overhead(big);
+    if (argc > 4 && std::strcmp(argv[4], "poll") == 0) return run_poll(big, rounds);
     size_t free0 = 0, total0 = 0;
     CHECK(hipMemGetInfo(&free0, &total0));
     // a few buffers of mixed sizes: three large ones and two small ones

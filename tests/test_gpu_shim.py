@@ -202,3 +202,13 @@ def test_overheads_of_launch_and_allocation(run_program):
     print("without the shim:\n" + plain["stdout"] + "under the shim:\n" + under["stdout"], flush=True)
     get = lambda out: float(re.search(r"launch: ([\d.]+) us per asynchronous launch", out).group(1))
     assert get(under["stdout"]) < get(plain["stdout"]) + 3.0
+
+
+def test_polling_application_is_not_taken_for_idle(run_program):
+    """300 ms of queued kernels waited for with hipStreamQuery in a loop, idle threshold 50 ms: the
+    returns of the polling call are signs of life, nothing is evicted."""
+    env = preload_env(NIXIE_SHIM_IDLE_MS=50, NIXIE_SHIM_LOG=1, NIXIE_SHIM_POOL_MIB=256)
+    r = run_program([APP, "0", "48", "3", "poll"], env=env, timeout=120)
+    assert r["rc"] == 0 and "RESULT ok" in r["stdout"], r
+    assert "evicted" not in r["stderr"], r["stderr"]
+    assert int(re.search(r"polled (\d+) times", r["stdout"]).group(1)) > 100

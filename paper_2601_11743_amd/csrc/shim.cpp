@@ -230,7 +230,9 @@ void reap_unmapped(Shim *s) {
 }
 
 void init_once() {
-    static Shim shim;
+    // Never destroyed: the application's own static destructors may still free memory through the
+    // wrappers after this library's have run.
+    static Shim &shim = *new Shim;
     Inside in;
     Shim &s = shim;
     s.capacity = env_u64("NIXIE_SHIM_POOL_MIB", 1024) << 20;

@@ -107,44 +107,49 @@ __device__ __forceinline__ void store_to_host(u32x4 *p, u32x4 v) {
 
 // Copy n bytes between a device range and its image in a ring slot.  The two addresses are
 // congruent modulo 16 (the planner guarantees it), so one head/tail peel serves both sides.
+// Both sides are addressed as global memory (address space 1): the addresses arrive as integers in
+// the descriptors, and through a generic pointer every access would be a flat instruction that
+// also has to be checked against the LDS and scratch apertures.
+typedef __attribute__((address_space(1))) u32x4 GVec;
+typedef __attribute__((address_space(1))) uint8_t GByte;
 template <bool TO_RING>
 __device__ __forceinline__ void copy_span(uint8_t *dev, uint8_t *ring, uint32_t n, uint32_t lane) {
-    const uint8_t *src = TO_RING ? dev : ring;
-    uint8_t *dst = TO_RING ? ring : dev;
+    GByte *gdev = (GByte *)(uintptr_t)dev, *gring = (GByte *)(uintptr_t)ring;
     uint32_t head = (16u - ((uint32_t)(uintptr_t)ring & 15u)) & 15u;
     if (head > n) head = n;
     if (lane < head) {   // byte accesses to the ring are system-scope atomics: same write-through / no-cache rule
-        if (TO_RING) __hip_atomic_store(dst + lane, src[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-        else dst[lane] = __hip_atomic_load(src + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        if (TO_RING) __hip_atomic_store(gring + lane, gdev[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        else gdev[lane] = __hip_atomic_load(gring + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     }
     const uint32_t nvec = (n - head) >> 4;
-    const u32x4 *s4 = (const u32x4 *)(src + head);
-    u32x4 *d4 = (u32x4 *)(dst + head);
+    GVec *dev4 = (GVec *)(gdev + head);
+    const u32x4 *ring4_in = (const u32x4 *)(ring + head);   // the ring side goes through the asm loads and stores
+    u32x4 *ring4_out = (u32x4 *)(ring + head);
     constexpr uint32_t kU = TO_RING ? kUnrollOut : kUnrollIn;
     for (uint32_t j = lane; j - lane < nvec; j += 64 * kU) {   // wave-uniform trip count
         u32x4 v[kU];
         if constexpr (TO_RING) {
 #pragma unroll
             for (uint32_t u = 0; u < kU; u++)
-                if (j + 64 * u < nvec) v[u] = s4[j + 64 * u];
+                if (j + 64 * u < nvec) v[u] = dev4[j + 64 * u];
         } else {
             // out-of-range lanes re-read the last vector of the span (one extra line) and drop it
             const u32x4 *a[kU];
 #pragma unroll
-            for (uint32_t u = 0; u < kU; u++) a[u] = s4 + (j + 64 * u < nvec ? j + 64 * u : nvec - 1);
+            for (uint32_t u = 0; u < kU; u++) a[u] = ring4_in + (j + 64 * u < nvec ? j + 64 * u : nvec - 1);
             load_from_host(v, a);
         }
 #pragma unroll
         for (uint32_t u = 0; u < kU; u++)
             if (j + 64 * u < nvec) {
-                if (TO_RING) store_to_host(d4 + j + 64 * u, v[u]);
-                else d4[j + 64 * u] = v[u];
+                if (TO_RING) store_to_host(ring4_out + j + 64 * u, v[u]);
+                else dev4[j + 64 * u] = v[u];
             }
     }
     const uint32_t done = head + (nvec << 4);
     if (lane < n - done) {
-        if (TO_RING) __hip_atomic_store(dst + done + lane, src[done + lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-        else dst[done + lane] = __hip_atomic_load(src + done + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        if (TO_RING) __hip_atomic_store(gring + done + lane, gdev[done + lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        else gdev[done + lane] = __hip_atomic_load(gring + done + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     }
 }
 
@@ -516,6 +521,7 @@ __global__ void __launch_bounds__(256) nixie_hash_kernel(const HashDesc *descs, 
                                                          uint64_t *hashes) {
     constexpr uint64_t G = 0x9E3779B97F4A7C15ull;
     typedef uint64_t u64x2 __attribute__((ext_vector_type(2)));
+    typedef __attribute__((address_space(1))) u64x2 GlobalU64x2;
     const uint32_t tid = threadIdx.x, lane = tid & 63u;
     const uint64_t per = (total_tiles + gridDim.x - 1) / gridDim.x;
     const uint64_t t_begin = (uint64_t)blockIdx.x * per;
@@ -545,7 +551,7 @@ __global__ void __launch_bounds__(256) nixie_hash_kernel(const HashDesc *descs, 
         const uint64_t w1 = w0 + kHashTileWords < words ? w0 + kHashTileWords : words;
         const uint8_t *p = (const uint8_t *)(uintptr_t)d.ptr;
         if ((d.ptr & 15u) == 0 && w1 - w0 == kHashTileWords && w1 <= full) {   // whole aligned tile
-            const u64x2 *v = (const u64x2 *)(p + 8 * w0);
+            const GlobalU64x2 *v = (const GlobalU64x2 *)(d.ptr + 8 * w0);   // a device address: global, not generic, loads
             u64x2 r[8];
 #pragma unroll
             for (uint32_t u = 0; u < 8; u++) r[u] = __builtin_nontemporal_load(v + tid + 256 * u);

@@ -425,3 +425,19 @@ def test_random_plans(nx, oracle, seed):
     print(f"seed {seed}: {len(sa)} + {len(sb)} allocations, {sum(sa)} + {sum(sb)} bytes, ring {ring}, {o}, skew {skew}, "
           f"{switches} switches", flush=True)
     run_case(nx, oracle, sa, sb, ring, nx.Opts(**o), seed=50 + seed, skew=skew, switches=switches)
+
+
+def test_link_peak_probe_is_plausible(nx):
+    """nixie_link_peak (the roofline's denominator): every figure is a rate this link can have, one direction
+    alone is never slower than the same direction with the other one busy, and bad arguments are refused."""
+    p = nx.link_peak(64 * MiB, 2)
+    for k in ("sdma_d2h", "sdma_h2d", "sdma_d2h_both", "sdma_h2d_both", "kernel_d2h", "kernel_h2d", "kernel_d2h_both",
+              "kernel_h2d_both"):
+        assert 5.0 < p[k] < 70.0, (k, p)
+    assert p["sdma_d2h_both"] <= 1.05 * p["sdma_d2h"] and p["sdma_h2d_both"] <= 1.05 * p["sdma_h2d"], p
+    for bad in ((1 << 20) - 16, (1 << 20) + 8):
+        with pytest.raises(nx.NixieError) as e:
+            nx.link_peak(bad, 1)
+        assert e.value.code == nx.EINVAL
+    with pytest.raises(nx.NixieError):
+        nx.link_peak(1 << 20, 0)

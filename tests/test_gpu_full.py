@@ -219,6 +219,37 @@ def test_allocation_larger_than_4gib(nx, oracle):
     torch.cuda.empty_cache()
 
 
+def test_largest_slot(nx, oracle):
+    """The largest slot the planner accepts (1 GiB), two per direction: a chunk of 2^30 bytes, a team capped
+    at 256 workgroups with 4 MiB units, slot offsets up to the 32-bit limit of a segment."""
+    import torch
+    from workloads.device import BigSet
+    A = BigSet([("a", 2 * GiB + GiB // 2 + 5), ("a2", 100)], 21, "dev", "splitmix")
+    B = BigSet([("b", GiB + 5), ("b2", 3 * MiB + 1)], 22, "host", "splitmix")
+    src_a = [A.dev_view(i).cpu().numpy().copy() for i in range(2)]
+    src_b = [B.host_view(i).copy() for i in range(2)]
+    exp_a = [np.zeros_like(x) for x in src_a]
+    exp_b = [np.zeros_like(x) for x in src_b]
+    oracle.switch_direct(list(zip(src_a, exp_a)), list(zip(exp_b, src_b)))
+    plan = nx.Plan(A.rows_np(), B.rows_np(), 4 * GiB, nx.Opts(slot_bytes=GiB))
+    info = plan.info()
+    assert info["slot_bytes"] == GiB and info["out_slots"] == 2 and info["in_slots"] == 2
+    assert info["team_out"] == 256 and info["chunks_out"] == 3 and info["chunks_in"] == 2
+    h_out, h_in = plan.hash_tables()
+    plan.switch()
+    for i in range(2):
+        assert np.array_equal(A.host_view(i), exp_a[i]), f"evicted allocation {i}"
+        assert np.array_equal(B.dev_view(i).cpu().numpy(), exp_b[i]), f"restored allocation {i}"
+    assert A.arenas_equal() and B.arenas_equal()
+    plan.verify(h_out, h_in)
+    with pytest.raises(nx.NixieError) as e:
+        nx.Plan(A.rows_np(), B.rows_np(), 8 * GiB, nx.Opts(slot_bytes=2 * GiB))       # beyond the largest slot
+    assert e.value.code == nx.EINVAL
+    plan.close()
+    del A, B
+    torch.cuda.empty_cache()
+
+
 def test_pingpong_stress_small_ring(nx, oracle):
     """Twelve back-to-back switches A<->B of a 2 GiB-class pair through a 16 MiB ring, whole-arena
     compare after every one: the flag / slot protocol is exercised ~400k times."""

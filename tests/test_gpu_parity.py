@@ -441,3 +441,20 @@ def test_link_peak_probe_is_plausible(nx):
         assert e.value.code == nx.EINVAL
     with pytest.raises(nx.NixieError):
         nx.link_peak(1 << 20, 0)
+
+
+@pytest.mark.parametrize("slots,threads", [(1024, 4), (640, 3), (2048, 1)])
+def test_more_slots_than_the_pump_keeps_in_registers(nx, oracle, slots, threads):
+    """A direction with more than 256 slots: the pump wave keeps the last-seen flag values of the first 256 in
+    registers and the others in device memory.  4 KiB slots, several turns of the ring, both directions; then
+    one direction alone with all the slots."""
+    slot = 4 * KiB
+    sizes_a = [700 * slot + 1, 3, 555 * slot, 17 * slot - 9] + [slot + 1] * 40
+    sizes_b = [900 * slot - 5, slot, 311 * slot + 77] + [3 * slot - 1] * 30
+    o = nx.Opts(slot_bytes=slot, drain_threads=threads, fill_threads=threads)
+    info, st = run_case(nx, oracle, sizes_a, sizes_b, slots * slot, o, seed=91, switches=2)
+    assert info["out_slots"] == slots // 2 and info["in_slots"] == slots // 2 and info["out_slots"] > 256
+    info, st = run_case(nx, oracle, sizes_a, [], slots * slot, o, seed=92)
+    assert info["out_slots"] == slots and info["in_slots"] == 0
+    info, st = run_case(nx, oracle, [], sizes_b, slots * slot, o, seed=93)
+    assert info["in_slots"] == slots

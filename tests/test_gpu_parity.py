@@ -458,3 +458,25 @@ def test_more_slots_than_the_pump_keeps_in_registers(nx, oracle, slots, threads)
     assert info["out_slots"] == slots and info["in_slots"] == 0
     info, st = run_case(nx, oracle, [], sizes_b, slots * slot, o, seed=93)
     assert info["in_slots"] == slots
+
+
+@pytest.mark.parametrize("mask", [0x01, 0xAA, 0xF0, 0xFF])
+def test_workgroups_restricted_to_some_xcds(nx, oracle, mask):
+    """xcd_mask (a tuning aid): workgroups that land on an XCD outside the mask leave at once, the others do
+    all the work; 64 + 64 + 16 workgroups are dealt over the 8 XCDs, so every mask keeps some."""
+    sizes_a = [5 * S + 1, 300, 2 * S, 11 * S + 17, 7]
+    sizes_b = [4 * S, 11, 6 * S + 9, 200000, 3 * S - 5]
+    o = nx.Opts(slot_bytes=S, gather_wgs=64, scatter_wgs=64, flex_wgs=16, xcd_mask=mask, timeout_ms=5000)
+    run_case(nx, oracle, sizes_a, sizes_b, 8 * S, o, seed=70 + mask % 7)
+
+
+def test_ring_only_diagnostic_mode_completes(nx):
+    """NIXIE_DIAG_RING_ONLY (measurement: the host threads recycle credits without touching pageable memory):
+    the switch completes and reports its figures; the incoming bytes are whatever the ring held."""
+    from tests.gpu_helpers import GpuSet
+    gA, gB = GpuSet([20 * S + 3, 77], 1, "dev"), GpuSet([9 * S, 5], 2, "host")
+    plan = nx.Plan(gA.rows(), gB.rows(), 8 * S, nx.Opts(slot_bytes=S, flags=nx.DIAG_RING_ONLY))
+    st = plan.switch()
+    assert st["bytes_out"] == 20 * S + 80 and st["bytes_in"] == 9 * S + 5 and st["kernels"] == 1
+    assert st["ns_total"] > 0 and st["gpu_status"] == 0
+    plan.close()

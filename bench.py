@@ -11,7 +11,8 @@ Without --config the same line also carries a "configs" list: the metric taken l
 64 x 256 MiB each way), the asymmetric (3), fragmented (4) and tiny (1) configs, and config 5's
 pinned-budget sweep (rings of 16 / 64 / 256 / 1024 MiB, 10 ping-pong switches each), every one
 in the library's default launch configuration, verified by per-allocation hashes and, except for the
-sweep, a whole-arena compare.
+sweep, a whole-arena compare; and a "shim" object: an unmodified HIP program (tests/shim_app, 2.7 GiB)
+evicted and restored three times under the LD_PRELOAD shim, as the shim itself reports it.
 """
 from __future__ import annotations
 
@@ -200,6 +201,43 @@ def extra_config(nx, W, torch, cfg_id: int, peak, log) -> dict:
     return res
 
 
+def shim_leg(log) -> dict | None:
+    """The transparent shim at GiB scale: tests/shim_app (an ordinary HIP program) as a child process under
+    LD_PRELOAD=libnixie_shim.so with the paper's idleness rule, 2.7 GiB in three buffers, three pauses.  Reports
+    what the shim logs about each eviction and restore.  Must run before this process touches the GPU (a
+    process that has initialised the GPU may not start another program here)."""
+    import re
+    import subprocess
+    root = os.path.dirname(os.path.abspath(__file__))
+    app = os.path.join(root, "tests", "shim_app", "shim_app")
+    shim = os.path.join(root, "paper_2601_11743_amd", "libnixie_shim.so")
+    if not (os.path.exists(app) and os.path.exists(shim)):
+        from paper_2601_11743_amd import build
+        build.build()
+    env = dict(os.environ)
+    have = env.get("LD_PRELOAD", "")
+    env.update(LD_PRELOAD=(have + ":" if have else "") + shim, NIXIE_SHIM_LOG="1", NIXIE_SHIM_IDLE_MS="100",
+               NIXIE_SHIM_POOL_MIB="4096", NIXIE_SHIM_RING_MIB="64")
+    try:
+        r = subprocess.run([app, "500", "2048", "3"], env=env, capture_output=True, text=True, timeout=120)
+    except (OSError, subprocess.TimeoutExpired) as e:
+        log("[bench] shim leg did not run:", e)
+        return None
+    ev = [(int(b), float(ms)) for b, ms in re.findall(r"evicted \d+ allocations, (\d+) bytes, in ([\d.]+) ms", r.stderr)]
+    rs = [(int(b), float(ms)) for b, ms in re.findall(r"restored \d+ allocations, (\d+) bytes, in ([\d.]+) ms", r.stderr)]
+    bg = [(int(n), float(ms)) for n, ms in re.findall(r"unmapped (\d+) blocks in the background in ([\d.]+) ms", r.stderr)]
+    out = {"workload": "tests/shim_app 500 2048 3 under LD_PRELOAD=libnixie_shim.so, idle eviction after 100 ms, "
+                       "2 MiB units in 32 MiB blocks, 64 MiB ring",
+           "ok": r.returncode == 0 and "RESULT ok" in r.stdout,
+           "bytes": ev[0][0] if ev else 0,
+           "evict_ms": [ms for _, ms in ev], "restore_ms": [ms for _, ms in rs],
+           "evict_GBps": round(max((b / ms / 1e6 for b, ms in ev), default=0.0), 2),
+           "restore_GBps": round(max((b / ms / 1e6 for b, ms in rs), default=0.0), 2),
+           "background_unmap": [{"blocks": n, "ms": ms} for n, ms in bg]}
+    log("[bench] shim:", out)
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -265,6 +303,9 @@ def main() -> int:
             print(*a, file=sys.stderr, flush=True)
 
     nx.lib()                      # (builds the library first if nothing is built: before the GPU is touched)
+    shim = None
+    if args.config == 0 and not args.no_extras:
+        shim = shim_leg(log)      # a child process: also before the GPU is touched
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     plain_run = (args.config in (0, 2) and not (args.ring_mib or args.slot_kib or args.gather_wgs or args.scatter_wgs or
@@ -572,6 +613,8 @@ def main() -> int:
     torch.cuda.empty_cache()
     if with_extras:
         res["configs"] = [extra_config(nx, W, torch, c, peak, log) for c in (6, 3, 4, 1, 5)]
+    if shim is not None:
+        res["shim"] = shim
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(cf, int(args.cpu_sample_gib * 2**30))
     print(json.dumps(res), flush=True)

@@ -28,6 +28,9 @@
 // usage: shim_app <pause_ms> <big_mib> [rounds] [idle|explicit|graph|threads|overhead|poll]
 #include <hip/hip_runtime.h>
 #include <dlfcn.h>
+#include <execinfo.h>
+#include <signal.h>
+#include <unistd.h>
 
 #include <chrono>
 #include <cstdint>
@@ -196,7 +199,19 @@ int run_threads(int pause_ms, uint64_t big, int iters, int (*evict)(void)) {
     return good ? 0 : 1;
 }
 
+// Should the program ever die on a signal, say where: the test harness only sees the exit status.
+void say_where(int sig) {
+    void *frames[64];
+    const int n = backtrace(frames, 64);
+    const char msg[] = "shim_app: fatal signal, backtrace follows\n";
+    (void)!write(2, msg, sizeof(msg) - 1);
+    backtrace_symbols_fd(frames, n, 2);
+    signal(sig, SIG_DFL);
+    raise(sig);
+}
+
 int main(int argc, char **argv) {
+    for (int sig : {SIGSEGV, SIGBUS, SIGABRT, SIGFPE}) signal(sig, say_where);
     const int pause_ms = argc > 1 ? std::atoi(argv[1]) : 500;
     const uint64_t big = (argc > 2 ? std::strtoull(argv[2], nullptr, 10) : 48) << 20;
     const int rounds = argc > 3 ? std::atoi(argv[3]) : 2;

@@ -43,7 +43,11 @@ enum nixie_err {
 
 /* One allocation of a working set.  Memory is caller-owned on both sides.
  * dev_ptr:  DEVICE address of the allocation (any alignment).
- * host_ptr: HOST address of its pageable backing (any alignment, >= bytes long).
+ * host_ptr: HOST address of its pageable backing (any alignment, >= bytes long).  For an outgoing
+ *           allocation the range is written by the host threads inside the switch: memory that has
+ *           never been touched costs a page fault and a zeroed page per 4 KiB there (measured: three
+ *           times the transfer itself), so keep backing memory from one eviction to the next, or
+ *           touch it beforehand.
  * bytes:    length; 0 is legal and the entry is skipped. */
 typedef struct {
     void *dev_ptr;

@@ -106,6 +106,9 @@ typedef struct {
     uint32_t evictions, restores;
     uint64_t last_switch_ns;    /* duration of the last eviction (device wait, swap, unmapping) or restore */
     uint64_t launches_held;     /* launches that found the flag off and waited for a restore */
+    uint64_t mapped_blocks;     /* blocks of the space with physical memory behind them right now */
+    uint64_t host_backing_bytes;/* pageable address ranges kept for this application's copies (their pages are the
+                                   kernel's to reclaim while the application is resident)  */
 } nixie_shim_info_t;
 
 /* HOST out.  Returns 0, or NIXIE_EINVAL when the shim has not been initialised yet (no interposed

@@ -709,6 +709,11 @@ int nixie_shim_info(nixie_shim_info_t *info) {
     info->restores = s.restores.load();
     info->last_switch_ns = s.last_switch_ns.load();
     info->launches_held = s.launches_held.load();
+    info->mapped_blocks = 0;
+    for (uint8_t m : s.mapped) info->mapped_blocks += m;
+    info->host_backing_bytes = 0;
+    for (auto &kv : s.table)
+        if (kv.second.backing) info->host_backing_bytes += kv.second.bytes;
     return NIXIE_OK;
 }
 

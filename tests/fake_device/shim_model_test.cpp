@@ -137,9 +137,12 @@ int run_threads(int seed, bool by_idleness) {
             wrong += back[i] != (uint32_t)(1000 * (w + 1) + i) + (i % 512 == 0 ? (uint32_t)iters : 0u);
         MUST(hipFree(buf[w]));
     }
-    std::printf("evictions %u restores %u held %llu asked %d failed %d wrong %llu bad %d\n", info.evictions, info.restores,
-                (unsigned long long)info.launches_held, asked, failed, (unsigned long long)wrong, (int)bad.load());
-    const bool ok = wrong == 0 && !bad.load() && failed == 0 && info.evictions >= (by_idleness ? 2u : 3u) && info.restores >= info.evictions - 1;
+    std::printf("evictions %u restores %u held %llu asked %d failed %d wrong %llu bad %d, %llu blocks mapped, %llu bytes of host backing\n",
+                info.evictions, info.restores, (unsigned long long)info.launches_held, asked, failed, (unsigned long long)wrong,
+                (int)bad.load(), (unsigned long long)info.mapped_blocks, (unsigned long long)info.host_backing_bytes);
+    const bool ok = wrong == 0 && !bad.load() && failed == 0 && info.evictions >= (by_idleness ? 2u : 3u) &&
+                    info.restores >= info.evictions - 1 && info.host_backing_bytes == kWorkers * kWords * 4 &&
+                    info.mapped_blocks <= info.capacity_bytes / info.block_bytes;
     std::printf(ok ? "ok\n" : "FAIL\n");
     return ok ? 0 : 1;
 }

@@ -145,12 +145,13 @@ std::once_flag g_once;
 void say(const char *fmt, ...) __attribute__((format(printf, 1, 2)));
 void say(const char *fmt, ...) {
     if (!g || !g->log) return;
+    char line[512];   // one write per line: several threads log
     va_list ap;
     va_start(ap, fmt);
-    std::fputs("nixie-shim: ", stderr);
-    std::vfprintf(stderr, fmt, ap);
-    std::fputc('\n', stderr);
+    const int n = std::vsnprintf(line, sizeof(line) - 1, fmt, ap);
     va_end(ap);
+    if (n < 0) return;
+    std::fprintf(stderr, "nixie-shim: %s\n", line);
 }
 
 int evict_locked(Shim &s);

@@ -80,7 +80,7 @@ uint64_t env_u64(const char *name, uint64_t dflt) {
 struct Alloc {
     uint64_t bytes = 0;      // as the application asked
     uint64_t units = 0;      // what it occupies, in allocation units
-    void *host = nullptr;    // the pageable copy while evicted (exactly one copy of the bytes at any time), else null
+    void *host = nullptr;    // the pageable copy while evicted (exactly one live copy of the bytes at any time), else null
     // The mapping behind `host` is kept from one eviction to the next: after a restore its pages are
     // handed back lazily (MADV_FREE: the kernel may take them when it needs memory), so the next
     // eviction usually finds them still there and pays neither page faults nor zeroing -- with fresh

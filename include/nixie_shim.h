@@ -81,6 +81,8 @@
  *                           that is left to a background thread (a driver call per block, 0.25 ms each on
  *                           MI355X, that nobody has to wait for: the evicted application cannot run, and
  *                           an application that comes back first keeps what is still mapped)
+ *   NIXIE_SHIM_HOST_RELEASE what a restore does with the pages of the host copies: 0 (default) releases them
+ *                           lazily, 1 keeps them (the memory stays the process's), 2 returns the range at once
  *   NIXIE_SHIM_LOG          1: one line per eviction / restore on stderr
  * Host memory: the pageable copy of an allocation keeps its address range from one eviction to the
  * next; after a restore its pages are released lazily (MADV_FREE), so a later eviction usually pays

@@ -131,6 +131,7 @@ struct Shim {
     // evicted application cannot run, and whoever gets the physical blocks maps them at addresses of
     // its own.  It is done by this thread after the eviction, a few blocks at a time; an application
     // that comes back first simply keeps what is still mapped.
+    int host_release = 0;   // what a restore does with the host copies' pages: 0 lazy release, 1 keep them, 2 return them at once
     bool sync_unmap = false;
     std::atomic<int> wanted_back{0};   // threads waiting to bring the application back: the background work gives way to them
     std::thread reaper;
@@ -249,6 +250,7 @@ void init_once() {
     s.scribble = env_u64("NIXIE_SHIM_SCRIBBLE", 0) != 0;
     s.log = env_u64("NIXIE_SHIM_LOG", 0) != 0;
     s.sync_unmap = env_u64("NIXIE_SHIM_SYNC_UNMAP", 0) != 0;
+    s.host_release = (int)std::min<uint64_t>(2, env_u64("NIXIE_SHIM_HOST_RELEASE", 0));
     g = &s;
     if (nixie_abi_check(sizeof(nixie_opts_t), sizeof(nixie_plan_info_t), sizeof(nixie_stats_t)) != NIXIE_OK) {
         std::fprintf(stderr, "nixie-shim: libnixie.so is of another version than this shim; allocations pass through\n");
@@ -397,7 +399,9 @@ int restore_locked(Shim &s) {
         Alloc &a = kv.second;
         if (!a.host) continue;
         a.host = nullptr;                                        // one copy: the bytes are in HBM again
-        if (madvise(a.backing, a.bytes, MADV_FREE) != 0) {       // no lazy release on this kernel: give the memory back now
+        if (s.host_release == 1) {
+            // kept as they are: the memory stays this process's
+        } else if (s.host_release == 2 || madvise(a.backing, a.bytes, MADV_FREE) != 0) {   // (or no lazy release on this kernel)
             munmap(a.backing, a.bytes);
             a.backing = nullptr;
         }

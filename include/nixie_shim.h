@@ -35,7 +35,7 @@
  *                    range's blocks stay mapped for the next allocation at these addresses (an
  *                    eviction unmaps them): a use after free is not caught by a fault.
  *   hipMemGetInfo    total = the capacity the shim was given, free = total - the application's
- *                    own managed allocations (in whole units).
+ *                    own allocations: the managed ones in whole units, the small ones as asked for.
  *   hipLaunchKernel, hipLaunchKernelExC, hipLaunchCooperativeKernel, hipModuleLaunchKernel,
  *   hipModuleLaunchCooperativeKernel, hipExtModuleLaunchKernel, hipGraphLaunch
  *                    check the execution flag; restore the application first if it is evicted.
@@ -109,6 +109,7 @@ typedef struct {
     uint64_t last_switch_ns;    /* duration of the last eviction (device wait, swap, unmapping) or restore */
     uint64_t launches_held;     /* launches that found the flag off and waited for a restore */
     uint64_t mapped_blocks;     /* blocks of the space with physical memory behind them right now */
+    uint64_t passthrough_bytes; /* their sum, as asked for                                */
     uint64_t host_backing_bytes;/* pageable address ranges kept for this application's copies (their pages are the
                                    kernel's to reclaim while the application is resident)  */
 } nixie_shim_info_t;

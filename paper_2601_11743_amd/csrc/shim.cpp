@@ -29,6 +29,7 @@
 #include <mutex>
 #include <shared_mutex>
 #include <thread>
+#include <unordered_map>
 #include <vector>
 
 #include "nixie.h"
@@ -113,7 +114,11 @@ struct Shim {
     // costs no driver call); only an eviction unmaps, everything, in the background, from block 0 up.
     std::vector<uint8_t> mapped;
     uint64_t reap_cursor = 0;                 // blocks below it have been dealt with since the last eviction
-    uint64_t managed_bytes = 0, passthrough = 0;
+    uint64_t managed_bytes = 0;
+    // Allocations below the threshold are the runtime's own, but they count in the process's memory
+    // report like the others (paper, "GPU Memory information": the sum of the process's own allocations).
+    std::unordered_map<const void *, uint64_t> small;
+    uint64_t small_bytes = 0;
     std::atomic<bool> resident{true};
     std::atomic<uint32_t> evictions{0}, restores{0};
     std::atomic<uint64_t> last_switch_ns{0}, launches_held{0};
@@ -458,7 +463,11 @@ hipError_t hipMalloc(void **ptr, size_t size) {
     Shim *s = shim();
     if (!s || !ptr || size < s->min_bytes) {
         const hipError_t e = REAL(hipMalloc)(ptr, size);
-        if (s && e == hipSuccess && ptr && *ptr) { std::lock_guard<std::mutex> lk(s->mu); s->passthrough++; }
+        if (s && e == hipSuccess && ptr && *ptr) {
+            std::lock_guard<std::mutex> lk(s->mu);
+            s->small[*ptr] = size;
+            s->small_bytes += size;
+        }
         if (s) s->last_return.store(now_ns());
         return e;
     }
@@ -508,7 +517,11 @@ hipError_t hipFree(void *ptr) {
             s->last_return.store(now_ns());
             return hipSuccess;
         }
-        if (s->passthrough) s->passthrough--;
+        auto sm = s->small.find(ptr);
+        if (sm != s->small.end()) {
+            s->small_bytes -= sm->second;
+            s->small.erase(sm);
+        }
     }
     const hipError_t e = REAL(hipFree)(ptr);
     if (s) s->last_return.store(now_ns());
@@ -522,7 +535,8 @@ hipError_t hipMemGetInfo(size_t *free_bytes, size_t *total_bytes) {
     if (!free_bytes || !total_bytes) return hipErrorInvalidValue;
     std::lock_guard<std::mutex> lk(s->mu);
     *total_bytes = s->capacity;
-    *free_bytes = s->capacity - s->managed_bytes;
+    const uint64_t used = s->managed_bytes + s->small_bytes;
+    *free_bytes = used < s->capacity ? s->capacity - used : 0;
     s->last_return.store(now_ns());
     return hipSuccess;
 }
@@ -708,7 +722,8 @@ int nixie_shim_info(nixie_shim_info_t *info) {
     info->unit_bytes = s.unit;
     info->managed_bytes = s.managed_bytes;
     info->managed_allocs = s.table.size();
-    info->passthrough_allocs = s.passthrough;
+    info->passthrough_allocs = s.small.size();
+    info->passthrough_bytes = s.small_bytes;
     info->resident = s.resident.load() ? 1u : 0u;
     info->evictions = s.evictions.load();
     info->restores = s.restores.load();

@@ -84,7 +84,10 @@ enum nixie_flags {
                                          outgoing one gives up; paper, "Maintaining consistent virtual memory
                                          addresses").  A chunk is scattered only after every outgoing chunk that
                                          covers GPU bytes it overwrites has left HBM.  Ranges inside one table must
-                                         still be disjoint, and so must all host ranges. */
+                                         still be disjoint, and so must all host ranges.  The outgoing allocations
+                                         whose GPU memory the incoming table reuses are evicted first (among
+                                         themselves, and the others after them, in the order asked for), so that the
+                                         incoming application is ready as early as its own size allows. */
     NIXIE_HOST_SPIN = 1u << 7,        /* host threads with nothing to do spin.  By default they sleep for 1/16 of the time
                                          their direction's share of the ring lasts at link rate (at most 50 us, never
                                          when that is under 4 us): same latency, less than half the CPU time */

@@ -317,6 +317,7 @@ __device__ void run_direction(const SwapArgs &a) {
 // one direction is done its share of these workgroups goes to the other.
 __device__ void run_either(const SwapArgs &a) {
     __shared__ int s_dir;
+    __shared__ uint32_t s_none_left;   // bit x: direction x has handed out its last unit
     uint64_t stall[2] = {0, 0};
     bool live[2] = {a.d[0].wgs != 0, a.d[1].wgs != 0};
     if (sits_out(a)) {
@@ -335,11 +336,19 @@ __device__ void run_either(const SwapArgs &a) {
             // In place the incoming direction can never be ahead (a chunk is written only where the old
             // bytes have left), so "more left" would always point at it, and the help would stand waiting
             // for the outgoing side: there the help goes to the outgoing direction while it has units.
-            s_dir = !live[0] ? 1 : !live[1] ? 0 : a.track_prefix ? (left[0] ? 0 : 1) : left[1] > left[0] ? 1 : 0;
+            s_dir = !left[0] ? 1 : !left[1] ? 0 : a.track_prefix ? 0 : left[1] > left[0] ? 1 : 0;
+            s_none_left = (left[0] ? 0u : 1u) | (left[1] ? 0u : 2u);
         }
         __syncthreads();
         const int dir = s_dir;
+        const uint32_t none_left = s_none_left;
         __syncthreads();
+        // A direction without units left is left at once, not when the other one runs dry too: the pump
+        // reports "direction complete" only after every workgroup that could have worked on it has said
+        // goodbye, and the host may be waiting for exactly that to let the incoming application run.
+        if (live[0] && (none_left & 1u)) { live[0] = false; leave_direction<0>(a, stall[0]); }
+        if (live[1] && (none_left & 2u)) { live[1] = false; leave_direction<1>(a, stall[1]); }
+        if (!live[dir]) continue;   // (then the other one has units, or the loop ends)
         if (dir == 0) {
             if (!do_unit<0>(a, stall[0])) { live[0] = false; leave_direction<0>(a, stall[0]); }
         } else {

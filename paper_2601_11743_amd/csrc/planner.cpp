@@ -258,9 +258,31 @@ int build_layout(const nixie_table_t *out_table, const nixie_table_t *in_table, 
     L.slot_bytes = S;
     L.dir[0].slots = (uint32_t)n_out;
     L.dir[1].slots = (uint32_t)(staged_tot[1] ? n_slots - n_out : 0);
-    const std::vector<uint64_t> walk0 = walk_order(L.table[0], L.opts.order);
+    std::vector<uint64_t> walk0 = walk_order(L.table[0], L.opts.order);
     std::vector<uint64_t> walk1 = walk_order(L.table[1], L.opts.order);
     if (in_place && tot[0] && tot[1]) {
+        // The incoming application is ready when its last chunk is in HBM, and a chunk can only be written
+        // where the old bytes have left: the outgoing allocations whose GPU memory the incoming table reuses
+        // are walked first (in the given order among themselves), so that what the incoming side waits for
+        // is a short prefix of the eviction and not, at worst, all of it.
+        {
+            std::vector<Range> in_pieces;
+            for (const nixie_alloc_t &a : L.table[1])
+                for (const KeyPiece &q : dev_pieces((uint64_t)(uintptr_t)a.dev_ptr, a.bytes, pieces))
+                    in_pieces.push_back({q.key, q.key + q.len});
+            std::sort(in_pieces.begin(), in_pieces.end(), [](const Range &a, const Range &b) { return a.lo < b.lo; });
+            // (incoming ranges are pairwise disjoint, so sorted by lo they are sorted by hi as well)
+            auto reused = [&](uint64_t i) {
+                const nixie_alloc_t &a = L.table[0][i];
+                for (const KeyPiece &q : dev_pieces((uint64_t)(uintptr_t)a.dev_ptr, a.bytes, pieces)) {
+                    auto it = std::upper_bound(in_pieces.begin(), in_pieces.end(), q.key,
+                                               [](uint64_t v, const Range &r) { return v < r.hi; });
+                    if (it != in_pieces.end() && it->lo < q.key + q.len) return true;
+                }
+                return false;
+            };
+            std::stable_partition(walk0.begin(), walk0.end(), reused);
+        }
         cut(L.table[0], walk0, direct[0], S, L.dir[0]);
         std::vector<OutSpan> osegs;
         osegs.reserve(L.dir[0].segs.size());

@@ -249,7 +249,7 @@ def run_in_place(nx, oracle, sa, sb, shift, skew_a, skew_b, ring, opts, extra_fl
     try:
         h_out, h_in = plan.hash_tables()
         assert np.array_equal(h_out, h_out_ref) and np.array_equal(h_in, h_in_ref)
-        plan.switch()
+        st = plan.switch()
         torch.cuda.synchronize()
         dev_after = dev_t.cpu().numpy()
         assert np.array_equal(g.host_a, ref.host_a), "evicted set: " + first_diff(g.host_a, ref.host_a)
@@ -257,7 +257,7 @@ def run_in_place(nx, oracle, sa, sb, shift, skew_a, skew_b, ring, opts, extra_fl
         plan.verify(h_out_ref, h_in_ref)
     finally:
         plan.close()
-    return rows_a, rows_b
+    return rows_a, rows_b, st
 
 
 @pytest.mark.parametrize("case", range(len(ALIAS_CASES)))
@@ -266,8 +266,8 @@ def test_in_place_switch(nx, oracle, case, mode):
     sa, sb, shift = ALIAS_CASES[case]
     kw = dict(default={}, small_units=dict(team=8, gather_wgs=16, scatter_wgs=24, drain_threads=2, fill_threads=2),
               serialized={}, either=dict(team=4, gather_wgs=1, scatter_wgs=1, flex_wgs=24))[mode]
-    rows_a, rows_b = run_in_place(nx, oracle, sa, sb, shift, case % 3, (case * 5) % 16, 8 * S, dict(slot_bytes=S, **kw),
-                                  nx.SERIALIZE if mode == "serialized" else 0)
+    rows_a, rows_b, _ = run_in_place(nx, oracle, sa, sb, shift, case % 3, (case * 5) % 16, 8 * S, dict(slot_bytes=S, **kw),
+                                     nx.SERIALIZE if mode == "serialized" else 0)
     with pytest.raises(nx.NixieError):
         nx.Plan(rows_a, rows_b, 8 * S, nx.Opts(slot_bytes=S))     # without the flag aliasing is an error
 
@@ -300,6 +300,21 @@ def test_random_in_place_plans(nx, oracle, seed):
     print(f"seed {seed}: {len(sa)} + {len(sb)} allocations, {sum(sa)} + {sum(sb)} bytes, shift {shift}, ring {ring}, {o}, "
           f"extra flags {extra}", flush=True)
     run_in_place(nx, oracle, sa, sb, shift, skew_a, skew_b, ring, o, extra)
+
+
+def test_in_place_small_incoming_set_is_ready_early(nx, oracle):
+    """768 MiB leave, 128 MiB come in where the LAST eight outgoing allocations are: the planner evicts those
+    first, so the incoming application is ready after a fraction of the switch (it would be ready only at the
+    very end if the outgoing table were walked as listed)."""
+    import workloads as W
+    sa = [16 * MiB] * 48
+    sb = [16 * MiB - 4096] * 8
+    la, lb = W.make_layout(sa, redzone=256), W.make_layout(sb, redzone=256)
+    shift = la.offsets[40] - lb.offsets[0]
+    _, _, st = run_in_place(nx, oracle, sa, sb, shift, 0, 0, 64 * MiB, {})
+    print(f"in-place 768 MiB out / 128 MiB in over the tail: B ready after {st['ns_in_done'] / 1e6:.2f} ms of "
+          f"{st['ns_total'] / 1e6:.2f} ms", flush=True)
+    assert 0 < st["ns_in_done"] < 0.5 * st["ns_total"], st
 
 
 # ---- one ring for many plans --------------------------------------------------------------------

@@ -271,6 +271,30 @@ def test_in_place_dependencies(nx):
         nx.Layout(ra, [(r[0], ra[0][1], r[2]) for r in rb[:1]], 16 * S, nx.Opts(slot_bytes=S, flags=nx.IN_PLACE))
 
 
+@pytest.mark.parametrize("order", [0, 1, 2, 3])
+def test_in_place_evicts_first_what_the_incoming_table_reuses(nx, order):
+    """A large outgoing table, a small incoming one that reuses the GPU memory of the LAST outgoing
+    allocations: those are walked first (in the given order among themselves), so the incoming chunks
+    depend on a short prefix of the eviction, not on nearly all of it."""
+    S = 64 * KiB
+    sizes_a = [3 * S + 5] * 40
+    ra = fake_rows(sizes_a, gap=64)
+    reused = ra[-6:]                                                   # B sits exactly where A's last six allocations are
+    rb = [(d, 0x1800_0000_0000 + i * (1 << 24), b - 7) for i, (d, _, b) in enumerate(reused)]
+    lay = nx.Layout(ra, rb, 16 * S, nx.Opts(slot_bytes=S, flags=nx.IN_PLACE, order=order))
+    check_layout(lay, ra, rb, 16 * S)
+    co, so, ci = lay.chunks(0), lay.segments(0), lay.chunks(1)
+    n_first = int(np.ceil(6 * (3 * S + 5) / S)) + 1                    # chunks that can hold the six reused allocations
+    assert int(ci["dep_out"].max()) <= n_first < len(co) // 4
+    first_addrs = {int(a) for a in so["dev_addr"][: int(co["seg_begin"][min(n_first, len(co) - 1)])]}
+    assert {d for d, _, _ in reused} <= first_addrs                    # they lead the walk
+    # the other allocations keep the order asked for among themselves
+    rest = [int(a) for a in so["dev_addr"] if int(a) in {d for d, _, _ in ra[:-6]}]
+    want = {0: [d for d, _, _ in ra[:-6]], 1: [d for d, _, _ in ra[:-6]], 2: sorted(d for d, _, _ in ra[:-6]),
+            3: [d for d, _, _ in ra[:-6]][::-1]}[order]
+    assert rest == want
+
+
 def test_plan_without_gpu_fails_loudly(nx):
     """No CPU fallback: without a GPU the product path reports a HIP error instead of doing the work."""
     import torch

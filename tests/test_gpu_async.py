@@ -54,7 +54,9 @@ def test_incoming_application_is_ready_before_the_eviction_ends(nx, oracle):
     assert np.array_equal(gA.hs.host, rA.host), "evicted set: " + first_diff(gA.hs.host, rA.host)
     assert st["rc"] == 0 and st["bytes_out"] == sum(sizes_a)
     assert 0 < st["ns_in_done"] < st["ns_total"]
-    assert t_in < 0.7 * t_all, f"B ready after {t_in * 1e3:.2f} ms of {t_all * 1e3:.2f} ms"
+    # 6 MiB against 512 MiB: a small fraction of the switch (workgroups that serve either direction must leave
+    # the incoming one when its units run out, or this wait lasts until the outgoing units run out too)
+    assert t_in < 0.4 * t_all, f"B ready after {t_in * 1e3:.2f} ms of {t_all * 1e3:.2f} ms"
     print(f"B ready after {t_in * 1e3:.2f} ms, switch complete after {t_all * 1e3:.2f} ms")
     # a second time with the same plan, without the early wait
     plan.switch_begin(swap_stream.cuda_stream)

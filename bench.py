@@ -186,6 +186,14 @@ def extra_config(nx, W, torch, cfg_id: int, peak, log) -> dict:
         t1 = time.perf_counter()
         stats = [step() for _ in range(steps)]
         ms = (time.perf_counter() - t1) / steps * 1e3
+        wait_in_ms = None
+        if cfg_id == 3:
+            # the same switch once more in three steps: when does nixie_switch_wait_in let the incoming application run?
+            t2 = time.perf_counter()
+            plan.switch_begin()
+            plan.switch_wait_in()
+            wait_in_ms = round((time.perf_counter() - t2) * 1e3, 3)
+            plan.switch_end()
         rep = plan.verify(h_out, h_in, check=False)
         equal = bool(A.arenas_equal() and B.arenas_equal())
         plan.close()
@@ -194,6 +202,7 @@ def extra_config(nx, W, torch, cfg_id: int, peak, log) -> dict:
                    pinned_bytes=info["pinned_ring_bytes"] + info["pinned_ctrl_bytes"],
                    traffic=read_traffic(cfg_id, ring, True),
                    algorithmic_bytes_per_launch=info["bytes_out"] + info["bytes_in"],
+                   **({"wait_in_returned_ms": wait_in_ms} if wait_in_ms is not None else {}),
                    verified={"hash_mismatches": rep["mismatched_out"] + rep["mismatched_in"], "full_buffer_equal": equal})
     del A, B
     torch.cuda.empty_cache()
